@@ -1,0 +1,130 @@
+/*
+ * dwconv.h -- C ABI of the MI355X (gfx950) depthwise 1-D convolution library.
+ *
+ * The operator is the depthwise convolution of S4ConvD as the paper states it
+ * in Sec. IV-A ("Common Problem Definition and Memory Layout"): one length-K
+ * filter per channel slid along the time axis of a [B, C, L] tensor (the paper
+ * writes H for the channel count C and k for the filter w), with the three
+ * execution paths the paper measures separately: forward (eq. (dwconv)),
+ * input gradient (eq. (dx_def)) and kernel/weight gradient (eq. (dk_def)).
+ *
+ * Common conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers (HIP global memory on the current
+ *     device).  The caller owns every buffer; the library never allocates,
+ *     frees or synchronises.  Work is enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL is the default stream) and the call returns at once.
+ *   - x, y, dy, dx are dense row-major [B, C, L] with t the stride-1 index;
+ *     w, dw are dense row-major [C, K] (Sec. IV-A, last paragraph).  No strides.
+ *   - dtype is the STORAGE type of every tensor of the call (DWCONV_F32 as in
+ *     the paper, or DWCONV_BF16).  Products and sums are always fp32; bf16
+ *     outputs are rounded to nearest-even once, at the final store.
+ *   - Padding: the output length is L.  x~ is x extended by zeros; pad_left in
+ *     [0, K-1] zeros are implied on the left and K-1-pad_left on the right.
+ *     pad_left = K/2 is the paper's p (eq. (padding_width)), pad_left = K-1 is
+ *     causal, (K-1)/2 is 'same' for odd K.  pad_left is the FORWARD pad in all
+ *     calls; the library derives the gradient offsets itself.
+ *   - Inputs are never written.  Outputs are overwritten, never accumulated.
+ *     Inputs and outputs must not overlap.  Tensor base pointers must be aligned
+ *     to the element size.
+ *   - Same inputs give bitwise-identical outputs from run to run: the weight
+ *     gradient is reduced in two ordered levels, never with atomics (the
+ *     structure the paper describes in Sec. IV-C/D for its second-stage
+ *     reduction).
+ *   - Arguments are validated before any HIP call is made; a failed validation
+ *     launches nothing.  Return value: a DWCONV_* status, DWCONV_OK (0) on
+ *     success.  The library never throws and never aborts.
+ *   - K = 1 and K > L are legal.  B*C*L must fit 2^40 elements.
+ */
+#ifndef DWCONV_H
+#define DWCONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum dwconv_dtype {
+    DWCONV_F32  = 0,  /* IEEE binary32 storage (the paper's precision) */
+    DWCONV_BF16 = 1   /* bfloat16 storage, fp32 accumulate             */
+};
+
+enum dwconv_status {
+    DWCONV_OK            = 0,
+    DWCONV_ERR_NULL      = 1,  /* a required pointer is NULL                       */
+    DWCONV_ERR_SHAPE     = 2,  /* B, C, L or K < 1, or B*C*L too large             */
+    DWCONV_ERR_PAD       = 3,  /* pad_left < 0 or pad_left > K-1                   */
+    DWCONV_ERR_DTYPE     = 4,  /* dtype is not a dwconv_dtype                      */
+    DWCONV_ERR_WORKSPACE = 5,  /* workspace NULL, too small or not 16-byte aligned */
+    DWCONV_ERR_ALIGN     = 6,  /* a tensor pointer is not element-aligned          */
+    DWCONV_ERR_LAUNCH    = 7   /* HIP reported an error when launching             */
+};
+
+/*
+ * Forward, Sec. IV-A eq. (dwconv):
+ *     y[b,c,t] = sum_{j=0}^{K-1} x~[b,c,t+j-pad_left] * w[c,j]
+ * (cross-correlation, the filter is not flipped).
+ * x [B,C,L] in, w [C,K] in, y [B,C,L] out; all device, all of `dtype`.
+ */
+int dwconv_fwd(const void *x, const void *w, void *y,
+               int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/*
+ * Input gradient, Sec. IV-A eq. (dx_def), computed as the adjoint of
+ * eq. (dwconv) with respect to x:
+ *     dx[b,c,s] = sum_{j=0}^{K-1} dy~[b,c,s-j+pad_left] * w[c,j]
+ * (equal to the printed eq. (dx_def) whenever K = 2*pad_left + 1).
+ * dy [B,C,L] in, w [C,K] in, dx [B,C,L] out.
+ */
+int dwconv_bwd_input(const void *dy, const void *w, void *dx,
+                     int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/*
+ * Weight (kernel) gradient, Sec. IV-A eq. (dk_def):
+ *     dw[c,j] = sum_b sum_t dy[b,c,t] * x~[b,c,t+j-pad_left]
+ * x, dy [B,C,L] in; dw [C,K] out (storage dtype).  Runs the two stages below
+ * back to back on `stream`.  `workspace` is device memory of at least
+ * dwconv_bwd_weight_workspace_bytes(...) bytes, 16-byte aligned; its contents
+ * on entry are ignored and it may be reused once the call's work has finished.
+ */
+int dwconv_bwd_weight(const void *x, const void *dy, void *dw,
+                      void *workspace, size_t workspace_bytes,
+                      int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/*
+ * Stage 1 of the weight gradient (Sec. IV-C/D: per-block partial sums written
+ * to an intermediate tensor):
+ *     part[s,c,j] = sum over the (b,t) of slice s of dy[b,c,t] * x~[b,c,t+j-pad_left]
+ * part is fp32 [S, C, K] in `workspace`, S = dwconv_bwd_weight_slices(...).
+ * Within a block the sum runs over wave-level and then LDS-level reductions in
+ * a fixed order.
+ */
+int dwconv_bwd_weight_partial(const void *x, const void *dy,
+                              void *workspace, size_t workspace_bytes,
+                              int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/*
+ * Stage 2 of the weight gradient (Sec. IV-C/D: "second reduction stage"):
+ *     dw[c,j] = sum_{s=0}^{S-1} part[s,c,j], in increasing s.
+ * Reads the fp32 partials stage 1 left in `workspace`, writes dw [C,K] in
+ * `dtype`.  Shape arguments must equal those given to stage 1.
+ */
+int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw,
+                               int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/* Number S of partial slices per coefficient stage 1 writes for this shape; 0 on bad arguments. */
+int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype);
+
+/* Bytes of workspace dwconv_bwd_weight needs for this shape (S*C*K*4 rounded up); 0 on bad arguments. */
+size_t dwconv_bwd_weight_workspace_bytes(int B, int C, int L, int K, int pad_left, int dtype);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *dwconv_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int dwconv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DWCONV_H */

@@ -1,0 +1,52 @@
+"""Roofline bookkeeping and the parity metric (no operator arithmetic).
+
+Operation counts follow the paper's roofline construction (Sec. III-G,
+eqs. (flops_fwd_bwdin), (flops_bwdk), (roofline_metrics)); the byte counts are
+the operator's own minimal traffic: every input read once, every output
+written once.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3    # dense fp32 matrix
+VALU_F32_PEAK_TFLOPS = 157.3    # 256 CU x 4 SIMD x 16 lanes x 2 (fma) x 2 (packed) x 2.4 GHz
+VALU_F32_NONPACKED_TFLOPS = 78.6
+
+
+def algorithmic_bytes(B, C, L, K, elem_size, path):
+    """Bytes one path must move: two [B,C,L] tensors plus one [C,K] tensor."""
+    n = B * C * L
+    if path in ("fwd", "dx", "dw"):
+        return (2 * n + C * K) * elem_size
+    if path == "dw_partial":
+        return 2 * n * elem_size
+    if path == "step":
+        return 3 * (2 * n + C * K) * elem_size
+    raise ValueError(path)
+
+
+def dense_flops(B, C, L, K):
+    """Paper's count, eq. (flops_fwd_bwdin) = eq. (flops_bwdk): 2*K per output, padded taps included."""
+    return 2 * B * C * L * K
+
+
+def in_range_flops(B, C, L, K, pad_left):
+    """2 flops per multiply-add whose input index falls inside [0, L)."""
+    taps = 0
+    for j in range(K):
+        taps += max(0, L - abs(j - pad_left))
+    return 2 * B * C * taps
+
+
+def normalised_error(got, ref, ref_abs, floor=2.0 ** -100):
+    """max_i |got_i - ref_i| / max(sum_i|terms|, floor).  Returns (err, argmax)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.maximum(np.asarray(ref_abs, dtype=np.float64), floor)
+    e = np.abs(got - ref) / den
+    if not np.all(np.isfinite(got)):
+        return float("inf"), int(np.argmin(np.isfinite(got).ravel()))
+    i = int(np.argmax(e))
+    return float(e.ravel()[i]), i
