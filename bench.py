@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the depthwise-convolution hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: forward,
+input gradient, and weight gradient (stage 1 + stage 2), through the C ABI, at the
+headline training-step shape (fp32 B32 C256 L4096 K64 causal) unless --workload says
+otherwise.  Inputs are resident in HBM before the timed region; buffers rotate over
+several sets so that no step finds its operands in the 256 MB Infinity Cache.
+
+Prints ONE JSON line:  metric / value = effective HBM GB/s of the full step (algorithmic
+bytes: each path reads two [B,C,L] tensors' worth and one [C,K], i.e. reads two and
+writes one), ms_per_step, per-path microseconds, a `roofline` object for the kernel that
+dominates the step, and a `cpu_baseline` object (the fp64 CPU oracle timed on host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=1, help="index into workloads.WORKLOADS (1 = headline)")
+    ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, inputs):
+    """The oracle as it stands, timed on the host cores: one full step of the same workload
+    (or, for workloads whose step exceeds ~30 s of CPU work, a bounded slice of it)."""
+    import numpy as np
+    import oracle
+    from paper_2604_25422_amd.roofline import algorithmic_bytes
+    from paper_2604_25422_amd.workloads import as_f32_numpy
+    oracle.build()
+    macs_step = 3.0 * wl.B * wl.C * wl.L * min(wl.K, wl.L)
+    # ~3e9 fp64 MAC/s on 8 cores; keep the sample to roughly 10-30 s of CPU work
+    Bs, Cs = wl.B, wl.C
+    while 3.0 * Bs * Cs * wl.L * min(wl.K, wl.L) > 4.0e10 and Cs > 1:
+        Cs = max(1, Cs // 2)
+    x = np.ascontiguousarray(as_f32_numpy(inputs["x"])[:Bs, :Cs])
+    dy = np.ascontiguousarray(as_f32_numpy(inputs["dy"])[:Bs, :Cs])
+    w = np.ascontiguousarray(as_f32_numpy(inputs["w"])[:Cs])
+    t0 = time.perf_counter()
+    oracle.fwd(x, w, wl.pad_left)
+    oracle.bwd_input(dy, w, wl.pad_left)
+    oracle.bwd_weight(x, dy, wl.K, wl.pad_left)
+    dt = time.perf_counter() - t0
+    nbytes = algorithmic_bytes(Bs, Cs, wl.L, wl.K, wl.elem_size, "step")
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "seconds": dt,
+            "sample": f"one full fwd+dX+dW step of B{Bs} C{Cs} L{wl.L} K{wl.K} "
+                      f"({'the whole workload' if (Bs, Cs) == (wl.B, wl.C) else 'a channel slice of the workload'}), "
+                      f"fp64 accumulate, OpenMP over rows/coefficients"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists, "
+              "see DESIGN.md for how the operator would shard)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2604_25422_amd import binding, workloads
+    from paper_2604_25422_amd.roofline import HBM_PEAK_GBPS, algorithmic_bytes, dense_flops, in_range_flops
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.lib()   # fail loudly if the HIP library is missing
+    wl = workloads.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    inputs = workloads.make_inputs(wl)
+    K, p = wl.K, wl.pad_left
+
+    sets = []
+    for i in range(args.sets):
+        s = {"x": inputs["x"].to(dev), "w": inputs["w"].to(dev), "dy": inputs["dy"].to(dev)}
+        if i:   # distinct contents per set; values do not change the work done
+            s["x"] = s["x"].roll(i, dims=2).contiguous()
+            s["dy"] = s["dy"].roll(-i, dims=2).contiguous()
+        s["y"] = torch.empty_like(s["x"]); s["dx"] = torch.empty_like(s["x"])
+        s["dw"] = torch.empty_like(s["w"])
+        s["ws"] = binding.new_workspace(s["x"], K, p)
+        sets.append(s)
+    tdt = workloads.torch_dtype(wl)
+
+    def step(s, ev=None):
+        if ev: ev[0].record()
+        binding.dwconv_fwd(s["x"], s["w"], p, out=s["y"])
+        if ev: ev[1].record()
+        binding.dwconv_bwd_input(s["dy"], s["w"], p, out=s["dx"])
+        if ev: ev[2].record()
+        binding.dwconv_bwd_weight_partial(s["x"], s["dy"], K, p, workspace=s["ws"])
+        if ev: ev[3].record()
+        binding.dwconv_bwd_weight_finalize(s["ws"], wl.B, wl.C, wl.L, K, p, tdt, out=s["dw"])
+        if ev: ev[4].record()
+
+    for i in range(args.warmup):
+        step(sets[i % args.sets])
+    torch.cuda.synchronize()
+
+    # timed region 1: exactly `steps` steps back to back (the headline number)
+    start = torch.cuda.Event(enable_timing=True); end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(args.steps):
+        step(sets[i % args.sets])
+    end.record()
+    torch.cuda.synchronize()
+    ms_per_step = start.elapsed_time(end) / args.steps
+
+    # timed region 2: the same steps with HIP events between the launches, for per-kernel durations
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        step(sets[i % args.sets], evs[i])
+    torch.cuda.synchronize()
+    names = ["fwd", "dx", "dw_partial", "dw_finalize"]
+    us = {n: 1e3 * sum(e[k].elapsed_time(e[k + 1]) for e in evs) / args.steps for k, n in enumerate(names)}
+
+    es = wl.elem_size
+    step_bytes = algorithmic_bytes(wl.B, wl.C, wl.L, K, es, "step")
+    path_bytes = algorithmic_bytes(wl.B, wl.C, wl.L, K, es, "fwd")
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    dom = max(("fwd", "dx", "dw_partial"), key=lambda n: us[n])
+    achieved = path_bytes / (us[dom] * 1e-6) / 1e9
+    flops = in_range_flops(wl.B, wl.C, wl.L, K, p)
+    out = {
+        "metric": "effective HBM GB/s per fwd+dX+dW step (and us per step), B32 C256 L4096 K64 fp32"
+                  if args.workload == 1 else f"effective HBM GB/s per fwd+dX+dW step, {wl.name}",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "C": wl.C, "L": wl.L, "K": K, "pad_left": p,
+                   "storage": wl.dtype, "buffer_sets": args.sets,
+                   "step_algorithmic_bytes": step_bytes, "path_algorithmic_bytes": path_bytes,
+                   "path_flops_in_range": flops, "path_flops_dense": dense_flops(wl.B, wl.C, wl.L, K)},
+        "paths_us": {n: round(v, 2) for n, v in us.items()},
+        "paths_gbps": {"fwd": round(path_bytes / us["fwd"] / 1e3, 1), "dx": round(path_bytes / us["dx"] / 1e3, 1),
+                       "dw": round(path_bytes / (us["dw_partial"] + us["dw_finalize"]) / 1e3, 1)},
+        "paths_frac_of_hbm_peak": {"fwd": round(path_bytes / us["fwd"] / 1e3 / HBM_PEAK_GBPS, 4),
+                                   "dx": round(path_bytes / us["dx"] / 1e3 / HBM_PEAK_GBPS, 4),
+                                   "dw": round(path_bytes / (us["dw_partial"] + us["dw_finalize"]) / 1e3 / HBM_PEAK_GBPS, 4)},
+        "paths_tflops": {n: round(flops / us[n] / 1e6, 2) for n in ("fwd", "dx", "dw_partial")},
+        "roofline": {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel_us": round(us[dom], 2), "algorithmic_bytes": path_bytes},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, inputs)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

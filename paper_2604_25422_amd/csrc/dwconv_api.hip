@@ -1,0 +1,251 @@
+// C ABI of the gfx950 depthwise 1-D convolution library: argument validation,
+// kernel selection and launch.  Declarations and argument contracts are in
+// include/dwconv.h; the operator is the one of the paper's Sec. IV-A.
+#include "../../include/dwconv.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dwconv_common.hip.h"
+#include "dwconv_valu.hip.h"
+
+namespace {
+
+using dwconv::bf16_t;
+
+constexpr int kVersion = 100;   // 0.1.0
+
+struct Shape {
+    int B, C, L, K, pad, dtype;
+};
+
+int check_shape(int B, int C, int L, int K, int pad, int dtype)
+{
+    if (B < 1 || C < 1 || L < 1 || K < 1) return DWCONV_ERR_SHAPE;
+    const unsigned long long n = (unsigned long long)B * (unsigned long long)C;
+    if (n > (1ull << 40) || n * (unsigned long long)L > (1ull << 40)) return DWCONV_ERR_SHAPE;
+    if ((unsigned long long)C * (unsigned long long)K > (1ull << 40)) return DWCONV_ERR_SHAPE;
+    if (pad < 0 || pad > K - 1) return DWCONV_ERR_PAD;
+    if (dtype != DWCONV_F32 && dtype != DWCONV_BF16) return DWCONV_ERR_DTYPE;
+    return DWCONV_OK;
+}
+
+bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+size_t elem_size(int dtype) { return dtype == DWCONV_F32 ? 4 : 2; }
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------ forward / input gradient
+// out = correlate(in, f_eff, pad_eff): the forward is (x, w, pad); the input gradient is
+// (dy, reversed w, K-1-pad).
+template <typename T>
+int launch_corr(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    constexpr int R = 4, THREADS = 256, KCH = 512;
+    constexpr int TILE = R * THREADS;
+    const long long tiles_per_row = ((long long)s.L + TILE - 1) / TILE;
+    const long long blocks = (long long)s.B * s.C * tiles_per_row;
+    if (blocks > 0x7fffffffLL) return DWCONV_ERR_SHAPE;
+    hipLaunchKernelGGL((dwconv::corr_valu_kernel<T, R, THREADS, KCH>), dim3((unsigned)blocks), dim3(THREADS), 0, st,
+                       static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), s.C, s.L, s.K,
+                       pad_eff, reverse, (int)tiles_per_row);
+    return launch_status();
+}
+
+int corr_entry(const void *in, const void *f, void *out, int B, int C, int L, int K, int pad, int dtype, void *stream,
+               bool is_dx)
+{
+    if (!in || !f || !out) return DWCONV_ERR_NULL;
+    const int rc = check_shape(B, C, L, K, pad, dtype);
+    if (rc != DWCONV_OK) return rc;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(in, es) || !aligned_to(f, es) || !aligned_to(out, es)) return DWCONV_ERR_ALIGN;
+    const Shape s{B, C, L, K, pad, dtype};
+    const int pad_eff = is_dx ? (K - 1 - pad) : pad;
+    const int reverse = is_dx ? 1 : 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == DWCONV_F32) return launch_corr<float>(in, f, out, s, pad_eff, reverse, st);
+    return launch_corr<bf16_t>(in, f, out, s, pad_eff, reverse, st);
+}
+
+// ------------------------------------------------------------------ weight gradient
+enum DwKernel { DW_VALU_K8, DW_VALU_K32, DW_VALU_K64, DW_VALU_K256 };
+
+struct DwPlan {
+    DwKernel kernel;
+    int S;                 // partial slices per coefficient
+    int tiles_per_row;     // tiles along L
+    int items_per_slice;   // (b, tile) items each slice owns
+};
+
+constexpr int kDwTT = 1024;       // positions per staged tile (generic kernel)
+constexpr int kDwThreads = 256;
+
+DwPlan plan_dw(const Shape &s)
+{
+    DwPlan p;
+    p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
+    const long long tiles = ((long long)s.L + kDwTT - 1) / kDwTT;
+    const long long items = (long long)s.B * tiles;
+    long long want = (2048 + s.C - 1) / s.C;          // about 2048 blocks in flight over the chip
+    if (want < 1) want = 1;
+    if (want > items) want = items;
+    if (want > 65535) want = 65535;
+    const long long per = (items + want - 1) / want;
+    p.items_per_slice = (int)per;
+    p.S = (int)((items + per - 1) / per);
+    p.tiles_per_row = (int)tiles;
+    return p;
+}
+
+size_t dw_workspace_bytes(const Shape &s, const DwPlan &p)
+{
+    const size_t bytes = (size_t)p.S * (size_t)s.C * (size_t)s.K * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int check_dw_shape(int B, int C, int L, int K, int pad, int dtype)
+{
+    const int rc = check_shape(B, C, L, K, pad, dtype);
+    if (rc != DWCONV_OK) return rc;
+    // the slice bookkeeping of stage 1 is 32-bit
+    const long long tiles = ((long long)L + kDwTT - 1) / kDwTT;
+    if ((long long)B * tiles > 0x7fffffffLL || C > 0x7fffffff / 2) return DWCONV_ERR_SHAPE;
+    return DWCONV_OK;
+}
+
+template <typename T, int KCH>
+void launch_dw_partial_valu(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    hipLaunchKernelGGL((dwconv::dw_partial_valu_kernel<T, kDwThreads, kDwTT, KCH>), dim3((unsigned)s.C, (unsigned)p.S),
+                       dim3(kDwThreads), 0, st, static_cast<const T *>(x), static_cast<const T *>(dy), part, s.B, s.C,
+                       s.L, s.K, s.pad, p.tiles_per_row, p.items_per_slice);
+}
+
+template <typename T>
+int launch_dw_partial(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    switch (p.kernel) {
+    case DW_VALU_K8: launch_dw_partial_valu<T, 8>(x, dy, part, s, p, st); break;
+    case DW_VALU_K32: launch_dw_partial_valu<T, 32>(x, dy, part, s, p, st); break;
+    case DW_VALU_K64: launch_dw_partial_valu<T, 64>(x, dy, part, s, p, st); break;
+    case DW_VALU_K256: launch_dw_partial_valu<T, 256>(x, dy, part, s, p, st); break;
+    }
+    return launch_status();
+}
+
+template <typename T>
+int launch_dw_finalize(const float *part, void *dw, const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    const size_t CK = (size_t)s.C * (size_t)s.K;
+    const size_t blocks = (CK + 255) / 256;
+    if (blocks > 0x7fffffffull) return DWCONV_ERR_SHAPE;
+    hipLaunchKernelGGL((dwconv::dw_finalize_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, st, part,
+                       static_cast<T *>(dw), p.S, CK);
+    return launch_status();
+}
+
+int check_workspace(const void *ws, size_t ws_bytes, const Shape &s, const DwPlan &p)
+{
+    if (!ws || !aligned_to(ws, 16) || ws_bytes < dw_workspace_bytes(s, p)) return DWCONV_ERR_WORKSPACE;
+    return DWCONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dwconv_fwd(const void *x, const void *w, void *y, int B, int C, int L, int K, int pad_left, int dtype, void *stream)
+{
+    return corr_entry(x, w, y, B, C, L, K, pad_left, dtype, stream, false);
+}
+
+int dwconv_bwd_input(const void *dy, const void *w, void *dx, int B, int C, int L, int K, int pad_left, int dtype,
+                     void *stream)
+{
+    return corr_entry(dy, w, dx, B, C, L, K, pad_left, dtype, stream, true);
+}
+
+int dwconv_bwd_weight_partial(const void *x, const void *dy, void *workspace, size_t workspace_bytes, int B, int C,
+                              int L, int K, int pad_left, int dtype, void *stream)
+{
+    if (!x || !dy) return DWCONV_ERR_NULL;
+    int rc = check_dw_shape(B, C, L, K, pad_left, dtype);
+    if (rc != DWCONV_OK) return rc;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(x, es) || !aligned_to(dy, es)) return DWCONV_ERR_ALIGN;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    const DwPlan p = plan_dw(s);
+    rc = check_workspace(workspace, workspace_bytes, s, p);
+    if (rc != DWCONV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *part = static_cast<float *>(workspace);
+    if (dtype == DWCONV_F32) return launch_dw_partial<float>(x, dy, part, s, p, st);
+    return launch_dw_partial<bf16_t>(x, dy, part, s, p, st);
+}
+
+int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw, int B, int C, int L, int K,
+                               int pad_left, int dtype, void *stream)
+{
+    if (!dw) return DWCONV_ERR_NULL;
+    int rc = check_dw_shape(B, C, L, K, pad_left, dtype);
+    if (rc != DWCONV_OK) return rc;
+    if (!aligned_to(dw, elem_size(dtype))) return DWCONV_ERR_ALIGN;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    const DwPlan p = plan_dw(s);
+    rc = check_workspace(workspace, workspace_bytes, s, p);
+    if (rc != DWCONV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float *part = static_cast<const float *>(workspace);
+    if (dtype == DWCONV_F32) return launch_dw_finalize<float>(part, dw, s, p, st);
+    return launch_dw_finalize<bf16_t>(part, dw, s, p, st);
+}
+
+int dwconv_bwd_weight(const void *x, const void *dy, void *dw, void *workspace, size_t workspace_bytes, int B, int C,
+                      int L, int K, int pad_left, int dtype, void *stream)
+{
+    if (!x || !dy || !dw) return DWCONV_ERR_NULL;
+    int rc = check_dw_shape(B, C, L, K, pad_left, dtype);
+    if (rc != DWCONV_OK) return rc;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(x, es) || !aligned_to(dy, es) || !aligned_to(dw, es)) return DWCONV_ERR_ALIGN;
+    rc = dwconv_bwd_weight_partial(x, dy, workspace, workspace_bytes, B, C, L, K, pad_left, dtype, stream);
+    if (rc != DWCONV_OK) return rc;
+    return dwconv_bwd_weight_finalize(workspace, workspace_bytes, dw, B, C, L, K, pad_left, dtype, stream);
+}
+
+int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype)
+{
+    if (check_dw_shape(B, C, L, K, pad_left, dtype) != DWCONV_OK) return 0;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    return plan_dw(s).S;
+}
+
+size_t dwconv_bwd_weight_workspace_bytes(int B, int C, int L, int K, int pad_left, int dtype)
+{
+    if (check_dw_shape(B, C, L, K, pad_left, dtype) != DWCONV_OK) return 0;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    return dw_workspace_bytes(s, plan_dw(s));
+}
+
+const char *dwconv_status_string(int status)
+{
+    switch (status) {
+    case DWCONV_OK: return "ok";
+    case DWCONV_ERR_NULL: return "a required pointer is NULL";
+    case DWCONV_ERR_SHAPE: return "B, C, L and K must be >= 1 and B*C*L must fit 2^40 elements";
+    case DWCONV_ERR_PAD: return "pad_left must lie in [0, K-1]";
+    case DWCONV_ERR_DTYPE: return "dtype must be DWCONV_F32 or DWCONV_BF16";
+    case DWCONV_ERR_WORKSPACE: return "workspace is NULL, smaller than dwconv_bwd_weight_workspace_bytes() or not 16-byte aligned";
+    case DWCONV_ERR_ALIGN: return "a tensor pointer is not aligned to its element size";
+    case DWCONV_ERR_LAUNCH: return "HIP reported an error at kernel launch";
+    default: return "unknown status";
+    }
+}
+
+int dwconv_version(void) { return kVersion; }
+
+}  // extern "C"

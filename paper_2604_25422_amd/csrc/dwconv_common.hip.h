@@ -1,0 +1,45 @@
+// Shared device helpers of the gfx950 depthwise-convolution kernels:
+// storage-type load/store (fp32 and bfloat16 with fp32 arithmetic).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dwconv {
+
+// bfloat16 storage element: the upper 16 bits of an IEEE binary32.
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 (NaN stays a quiet NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float ld_elem(const float *p) { return *p; }
+__device__ __forceinline__ float ld_elem(const bf16_t *p) { return bf16_bits_to_f32(p->bits); }
+__device__ __forceinline__ void st_elem(float *p, float v) { *p = v; }
+__device__ __forceinline__ void st_elem(bf16_t *p, float v) { p->bits = (uint16_t)f32_to_bf16_bits(v); }
+
+// Four consecutive elements, p aligned to 4 elements.
+__device__ __forceinline__ float4 ld_elem4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 ld_elem4(const bf16_t *p)
+{
+    uint2 u = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+}
+__device__ __forceinline__ void st_elem4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ void st_elem4(bf16_t *p, float4 v)
+{
+    uint2 u;
+    u.x = f32_to_bf16_bits(v.x) | (f32_to_bf16_bits(v.y) << 16);
+    u.y = f32_to_bf16_bits(v.z) | (f32_to_bf16_bits(v.w) << 16);
+    *reinterpret_cast<uint2 *>(p) = u;
+}
+
+}  // namespace dwconv

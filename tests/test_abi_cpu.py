@@ -1,0 +1,120 @@
+"""CPU-only checks of the C ABI: the shared library loads, exports every symbol the header
+declares, and validates its arguments before touching HIP (so error paths run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2604_25422_amd import _build, binding
+    if _build.is_stale():
+        _build.build()
+    return binding.lib()
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "dwconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dwconv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2604_25422_amd import binding
+    syms = header_symbols()
+    assert len(syms) >= 9
+    assert set(syms) == set(binding.SYMBOLS)
+    for s in syms:
+        assert hasattr(lib, s), s
+
+
+def test_version_and_status_strings(lib):
+    assert lib.dwconv_version() >= 100
+    seen = set()
+    for code in range(0, 8):
+        s = lib.dwconv_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert lib.dwconv_status_string(99).decode() == "unknown status"
+
+
+P = 0x1000  # any non-NULL, aligned, never-dereferenced address: validation fails before a launch
+
+
+@pytest.mark.parametrize("fn", ["dwconv_fwd", "dwconv_bwd_input"])
+def test_corr_argument_validation(lib, fn):
+    f = getattr(lib, fn)
+    assert f(None, P, P, 1, 1, 8, 3, 1, 0, None) == 1
+    assert f(P, None, P, 1, 1, 8, 3, 1, 0, None) == 1
+    assert f(P, P, None, 1, 1, 8, 3, 1, 0, None) == 1
+    assert f(P, P, P, 0, 1, 8, 3, 1, 0, None) == 2
+    assert f(P, P, P, 1, 0, 8, 3, 1, 0, None) == 2
+    assert f(P, P, P, 1, 1, 0, 3, 1, 0, None) == 2
+    assert f(P, P, P, 1, 1, 8, 0, 0, 0, None) == 2
+    assert f(P, P, P, 1 << 20, 1 << 20, 8, 3, 1, 0, None) == 2
+    assert f(P, P, P, 1, 1, 8, 3, 3, 0, None) == 3
+    assert f(P, P, P, 1, 1, 8, 3, -1, 0, None) == 3
+    assert f(P, P, P, 1, 1, 8, 3, 1, 2, None) == 4
+    assert f(P + 2, P, P, 1, 1, 8, 3, 1, 0, None) == 6
+    assert f(P, P, P + 1, 1, 1, 8, 3, 1, 1, None) == 6
+
+
+def test_weight_gradient_argument_validation(lib):
+    need = lib.dwconv_bwd_weight_workspace_bytes(2, 3, 100, 5, 2, 0)
+    assert need >= lib.dwconv_bwd_weight_slices(2, 3, 100, 5, 2, 0) * 3 * 5 * 4 > 0
+    f = lib.dwconv_bwd_weight
+    assert f(None, P, P, P, need, 2, 3, 100, 5, 2, 0, None) == 1
+    assert f(P, P, None, P, need, 2, 3, 100, 5, 2, 0, None) == 1
+    assert f(P, P, P, P, need, 2, 3, 100, 0, 0, 0, None) == 2
+    assert f(P, P, P, P, need, 2, 3, 100, 5, 5, 0, None) == 3
+    assert f(P, P, P, P, need, 2, 3, 100, 5, 2, 7, None) == 4
+    assert f(P, P, P, None, need, 2, 3, 100, 5, 2, 0, None) == 5
+    assert f(P, P, P, P, need - 1, 2, 3, 100, 5, 2, 0, None) == 5
+    assert f(P, P, P, P + 4, need, 2, 3, 100, 5, 2, 0, None) == 5
+    assert f(P + 1, P, P, P, need, 2, 3, 100, 5, 2, 0, None) == 6
+    assert lib.dwconv_bwd_weight_partial(P, P, P, need - 1, 2, 3, 100, 5, 2, 0, None) == 5
+    assert lib.dwconv_bwd_weight_finalize(P, need - 1, P, 2, 3, 100, 5, 2, 0, None) == 5
+    assert lib.dwconv_bwd_weight_finalize(P, need, None, 2, 3, 100, 5, 2, 0, None) == 1
+
+
+def test_workspace_query_rejects_bad_shapes(lib):
+    assert lib.dwconv_bwd_weight_workspace_bytes(0, 3, 100, 5, 2, 0) == 0
+    assert lib.dwconv_bwd_weight_workspace_bytes(2, 3, 100, 5, 9, 0) == 0
+    assert lib.dwconv_bwd_weight_slices(2, 3, 100, 5, 2, 3) == 0
+    for (B, C, L, K, p, dt) in [(32, 256, 4096, 64, 63, 0), (64, 512, 2048, 7, 3, 0), (8, 256, 8192, 8192, 8191, 0),
+                                (128, 768, 1024, 32, 31, 1), (1, 1, 1, 1, 0, 0)]:
+        S = lib.dwconv_bwd_weight_slices(B, C, L, K, p, dt)
+        n = lib.dwconv_bwd_weight_workspace_bytes(B, C, L, K, p, dt)
+        assert S >= 1 and n >= S * C * K * 4 and n % 16 == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    from paper_2604_25422_amd import binding
+    x = torch.zeros(1, 2, 8); w = torch.zeros(2, 3)
+    with pytest.raises(ValueError):
+        binding.dwconv_fwd(x, w, 1)
+    with pytest.raises(ValueError):
+        binding.dwconv_bwd_input(x, w, 1)
+    with pytest.raises(ValueError):
+        binding.dwconv_bwd_weight(x, x, 3, 1)
+
+
+def test_workloads_are_seeded_and_shaped():
+    import torch
+    from paper_2604_25422_amd import workloads
+    assert len(workloads.WORKLOADS) == 5 and workloads.HEADLINE.K == 64
+    wl = workloads.WORKLOADS[0]
+    a = workloads.make_inputs(wl); b = workloads.make_inputs(wl)
+    for k in ("x", "w", "dy"):
+        assert torch.equal(a[k], b[k])
+    assert a["x"].shape == (4, 64, 1024) and a["w"].shape == (64, 16) and a["x"].dtype == torch.float32
+    assert not torch.equal(a["x"], a["dy"])
+    w3 = workloads.make_filter(workloads.WORKLOADS[3].with_shape(C=4))
+    assert w3.shape == (4, 8192) and float(w3[:, 0].min()) == 1.0 and float(w3.abs().max()) <= 1.0
+    w4 = workloads.make_filter(workloads.WORKLOADS[4])
+    assert w4.dtype == torch.bfloat16

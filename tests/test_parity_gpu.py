@@ -1,0 +1,104 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs.  Tolerances: max |gpu - oracle| / sum|terms| <= 1e-5 (fp32 fwd, dX),
+1e-4 (fp32 dW), 2e-2 (bf16 storage)."""
+import numpy as np
+import pytest
+import torch
+
+from _parity import TOL, check_case, gpu_all, oracle_all, seeded
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2604_25422_amd import binding
+    binding.lib()
+
+
+# (B, C, L, K, pad_left): ragged tails, L not a multiple of 4/16/64, K = 1, K > L, every pad class
+SMALL = [
+    (1, 1, 1, 1, 0), (1, 1, 5, 3, 1), (2, 3, 7, 4, 2), (1, 2, 4, 6, 5), (3, 2, 33, 1, 0),
+    (2, 3, 100, 5, 0), (2, 3, 100, 5, 2), (2, 3, 100, 5, 4),
+    (2, 5, 257, 7, 3), (1, 4, 1023, 16, 15), (2, 4, 1025, 16, 8), (1, 3, 2050, 9, 4),
+    (3, 7, 333, 31, 30), (2, 2, 48, 48, 24), (2, 2, 48, 48, 47), (5, 3, 48, 48, 0),
+    (1, 2, 40, 100, 99), (1, 2, 40, 100, 50), (2, 2, 130, 260, 129),
+    (2, 3, 600, 64, 63), (1, 2, 4100, 64, 32), (2, 2, 1500, 300, 299), (1, 1, 3000, 700, 350),
+    (1, 2, 1100, 1030, 1029),
+]
+
+
+@pytest.mark.parametrize("B,C,L,K,p", SMALL)
+def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
+    print(f"case f32 B{B} C{C} L{L} K{K} p{p}", flush=True)
+    check_case(oracle_mod, B, C, L, K, p, "f32", seed=B + C + L + K)
+
+
+@pytest.mark.parametrize("B,C,L,K,p", SMALL[::2] + [(4, 6, 1024, 32, 31), (3, 5, 1000, 32, 16)])
+def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
+    print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
+    check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
+
+
+@pytest.mark.parametrize("B,C,L,K,p,dtype", [
+    (4, 64, 1024, 16, 15, "f32"),          # configuration 0, whole
+    (4, 16, 4096, 64, 63, "f32"),          # headline geometry, fewer rows
+    (8, 32, 2048, 7, 3, "f32"),            # short-filter geometry
+    (16, 24, 1024, 32, 31, "bf16"),        # bf16 geometry
+    (2, 4, 2048, 2048, 2047, "f32"),       # filter as long as the sequence
+])
+def test_config_geometries_reduced(oracle_mod, B, C, L, K, p, dtype):
+    print(f"case {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    check_case(oracle_mod, B, C, L, K, p, dtype, seed=7)
+
+
+def test_weight_gradient_is_run_to_run_deterministic_and_two_stage_matches():
+    from paper_2604_25422_amd import binding
+    B, C, L, K, p = 6, 10, 3000, 48, 24
+    x = seeded((B, C, L), 1, torch.float32).cuda(); dy = seeded((B, C, L), 2, torch.float32).cuda()
+    a = binding.dwconv_bwd_weight(x, dy, K, p)
+    b = binding.dwconv_bwd_weight(x, dy, K, p)
+    ws = binding.dwconv_bwd_weight_partial(x, dy, K, p)
+    c = binding.dwconv_bwd_weight_finalize(ws, B, C, L, K, p, torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    S = binding.dwconv_bwd_weight_slices(B, C, L, K, p, binding.F32)
+    part = ws.view(torch.float32)[: S * C * K].view(S, C, K)
+    seq = torch.zeros(C, K, device="cuda")
+    for s in range(S):
+        seq = seq + part[s]
+    assert torch.equal(seq, a)             # stage 2 is the ordered sum of the stage-1 slices
+
+
+def test_inputs_are_not_written_and_outputs_are_overwritten():
+    from paper_2604_25422_amd import binding
+    B, C, L, K, p = 2, 3, 500, 9, 4
+    x = seeded((B, C, L), 3, torch.float32).cuda(); w = seeded((C, K), 4, torch.float32).cuda()
+    x0, w0 = x.clone(), w.clone()
+    y = torch.full_like(x, float("nan"))
+    binding.dwconv_fwd(x, w, p, out=y)
+    dx = torch.full_like(x, float("nan"))
+    binding.dwconv_bwd_input(x, w, p, out=dx)
+    dw = torch.full((C, K), float("nan"), device="cuda")
+    ws = binding.new_workspace(x, K, p); ws.fill_(0xFF)
+    binding.dwconv_bwd_weight(x, x, K, p, workspace=ws, out=dw)
+    torch.cuda.synchronize()
+    assert torch.equal(x, x0) and torch.equal(w, w0)
+    assert torch.isfinite(y).all() and torch.isfinite(dx).all() and torch.isfinite(dw).all()
+
+
+def test_runs_on_a_non_default_stream(oracle_mod):
+    from paper_2604_25422_amd import binding
+    from paper_2604_25422_amd.roofline import normalised_error
+    B, C, L, K, p = 2, 4, 777, 12, 11
+    x = seeded((B, C, L), 5, torch.float32); w = seeded((C, K), 6, torch.float32)
+    st = torch.cuda.Stream()
+    xd, wd = x.cuda(), w.cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        y = binding.dwconv_fwd(xd, wd, p)
+    st.synchronize()
+    r, ra = oracle_mod.fwd(x.numpy(), w.numpy(), p)
+    e, _ = normalised_error(y.cpu().numpy(), r, ra)
+    assert e <= 1e-5
