@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "dwconv_common.hip.h"
+#include "dwconv_mfma.hip.h"
 #include "dwconv_valu.hip.h"
 
 namespace {
@@ -41,8 +42,16 @@ int launch_status()
 // ------------------------------------------------------------------ forward / input gradient
 // out = correlate(in, f_eff, pad_eff): the forward is (x, w, pad); the input gradient is
 // (dy, reversed w, K-1-pad).
+
+// Block offsets d of the 16-blocked Toeplitz form that can hold a tap: d in [dmin, dmax].
+int toeplitz_dmin(int pad) { return -((pad + 15) / 16); }
+int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
+
+constexpr int kMfmaMinK = 8;      // shorter filters stay on the vector ALU
+constexpr int kMfmaMaxND = 6;
+
 template <typename T>
-int launch_corr(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
     constexpr int R = 4, THREADS = 256, KCH = 512;
     constexpr int TILE = R * THREADS;
@@ -53,6 +62,56 @@ int launch_corr(const void *in, const void *f, void *out, const Shape &s, int pa
                        static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), s.C, s.L, s.K,
                        pad_eff, reverse, (int)tiles_per_row);
     return launch_status();
+}
+
+template <typename T, int ND>
+void launch_corr_mfma_nd(const void *in, const void *f, void *out, const dwconv::CorrGeom &g, unsigned blocks,
+                         hipStream_t st)
+{
+    hipLaunchKernelGGL((dwconv::corr_mfma_kernel<T, ND, 4, 64>), dim3(blocks), dim3(256), 0, st,
+                       static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), g);
+}
+
+// Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
+template <typename T>
+int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    constexpr int WAVES = 4, SEGLEN = 64 * 16;
+    const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
+    const int nd = dmax - dmin + 1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return -1;
+    if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    dwconv::CorrGeom g;
+    g.C = s.C; g.L = s.L; g.K = s.K; g.B = s.B;
+    g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
+    g.segs_per_row = (s.L + SEGLEN - 1) / SEGLEN;
+    if (g.segs_per_row >= WAVES) {
+        g.rows_per_block = 1;
+        g.groups_per_row = (g.segs_per_row + WAVES - 1) / WAVES;
+    } else {
+        g.rows_per_block = WAVES / g.segs_per_row;
+        g.groups_per_row = 1;
+    }
+    const long long b_groups = ((long long)s.B + g.rows_per_block - 1) / g.rows_per_block;
+    const long long blocks = b_groups * s.C * g.groups_per_row;
+    if (blocks > 0x7fffffffLL) return -1;
+    switch (nd) {
+    case 2: launch_corr_mfma_nd<T, 2>(in, f, out, g, (unsigned)blocks, st); break;
+    case 3: launch_corr_mfma_nd<T, 3>(in, f, out, g, (unsigned)blocks, st); break;
+    case 4: launch_corr_mfma_nd<T, 4>(in, f, out, g, (unsigned)blocks, st); break;
+    case 5: launch_corr_mfma_nd<T, 5>(in, f, out, g, (unsigned)blocks, st); break;
+    case 6: launch_corr_mfma_nd<T, 6>(in, f, out, g, (unsigned)blocks, st); break;
+    default: return -1;
+    }
+    return launch_status();
+}
+
+template <typename T>
+int launch_corr(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    const int rc = launch_corr_mfma<T>(in, f, out, s, pad_eff, reverse, st);
+    if (rc >= 0) return rc;
+    return launch_corr_valu<T>(in, f, out, s, pad_eff, reverse, st);
 }
 
 int corr_entry(const void *in, const void *f, void *out, int B, int C, int L, int K, int pad, int dtype, void *stream,
@@ -81,7 +140,7 @@ struct DwPlan {
     int items_per_slice;   // (b, tile) items each slice owns
 };
 
-constexpr int kDwTT = 1024;       // positions per staged tile (generic kernel)
+constexpr int kDwTT = 2048;       // positions per staged tile (every stage-1 kernel)
 constexpr int kDwThreads = 256;
 
 DwPlan plan_dw(const Shape &s)
@@ -125,9 +184,39 @@ void launch_dw_partial_valu(const void *x, const void *dy, float *part, const Sh
                        s.L, s.K, s.pad, p.tiles_per_row, p.items_per_slice);
 }
 
+template <typename T, int ND>
+void launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, int dmin,
+                               hipStream_t st)
+{
+    hipLaunchKernelGGL((dwconv::dw_partial_mfma_kernel<T, ND, 4, kDwTT>), dim3((unsigned)s.C, (unsigned)p.S), dim3(256),
+                       0, st, static_cast<const T *>(x), static_cast<const T *>(dy), part, s.B, s.C, s.L, s.K, s.pad,
+                       dmin, p.tiles_per_row, p.items_per_slice);
+}
+
+// Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
+template <typename T>
+int launch_dw_partial_mfma(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
+    const int nd = dmax - dmin + 1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return -1;
+    if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
+    switch (nd) {
+    case 2: launch_dw_partial_mfma_nd<T, 2>(x, dy, part, s, p, dmin, st); break;
+    case 3: launch_dw_partial_mfma_nd<T, 3>(x, dy, part, s, p, dmin, st); break;
+    case 4: launch_dw_partial_mfma_nd<T, 4>(x, dy, part, s, p, dmin, st); break;
+    case 5: launch_dw_partial_mfma_nd<T, 5>(x, dy, part, s, p, dmin, st); break;
+    case 6: launch_dw_partial_mfma_nd<T, 6>(x, dy, part, s, p, dmin, st); break;
+    default: return -1;
+    }
+    return launch_status();
+}
+
 template <typename T>
 int launch_dw_partial(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
 {
+    const int rc = launch_dw_partial_mfma<T>(x, dy, part, s, p, st);
+    if (rc >= 0) return rc;
     switch (p.kernel) {
     case DW_VALU_K8: launch_dw_partial_valu<T, 8>(x, dy, part, s, p, st); break;
     case DW_VALU_K32: launch_dw_partial_valu<T, 32>(x, dy, part, s, p, st); break;
