@@ -64,11 +64,13 @@ int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, i
     return launch_status();
 }
 
+constexpr long long kTargetWaves = 4096;   // 256 CUs x 16 resident waves
+
 template <typename T, int ND>
 void launch_corr_mfma_nd(const void *in, const void *f, void *out, const dwconv::CorrGeom &g, unsigned blocks,
                          hipStream_t st)
 {
-    hipLaunchKernelGGL((dwconv::corr_mfma_kernel<T, ND, 4, 64>), dim3(blocks), dim3(256), 0, st,
+    hipLaunchKernelGGL((dwconv::corr_mfma_kernel<T, ND>), dim3(blocks), dim3(64 * dwconv::kCorrWavesPerBlock), 0, st,
                        static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), g);
 }
 
@@ -76,25 +78,26 @@ void launch_corr_mfma_nd(const void *in, const void *f, void *out, const dwconv:
 template <typename T>
 int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
-    constexpr int WAVES = 4, SEGLEN = 64 * 16;
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
     const int nd = dmax - dmin + 1;
     if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    const long long rows = (long long)s.B * s.C;
+    const long long segs_per_row = (s.L + dwconv::kSegLen - 1) / dwconv::kSegLen;
+    const long long total_segs = rows * segs_per_row;
+    if (total_segs > 0x3fffffffLL) return -1;           // the kernel's segment walk is 32-bit
     dwconv::CorrGeom g;
-    g.C = s.C; g.L = s.L; g.K = s.K; g.B = s.B;
+    g.C = s.C; g.L = s.L; g.K = s.K; g.rows = (int)rows;
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
-    g.segs_per_row = (s.L + SEGLEN - 1) / SEGLEN;
-    if (g.segs_per_row >= WAVES) {
-        g.rows_per_block = 1;
-        g.groups_per_row = (g.segs_per_row + WAVES - 1) / WAVES;
-    } else {
-        g.rows_per_block = WAVES / g.segs_per_row;
-        g.groups_per_row = 1;
-    }
-    const long long b_groups = ((long long)s.B + g.rows_per_block - 1) / g.rows_per_block;
-    const long long blocks = b_groups * s.C * g.groups_per_row;
-    if (blocks > 0x7fffffffLL) return -1;
+    g.segs_per_row = (int)segs_per_row;
+    long long spw = total_segs / kTargetWaves;          // segments per wave, rounded down: at least kTargetWaves waves
+    if (spw < 1) spw = 1;
+    const long long waves = (total_segs + spw - 1) / spw;
+    const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+    g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
+    g.step_rows = g.n_waves / g.segs_per_row;
+    g.step_seg = g.n_waves % g.segs_per_row;
+    g.step_c = g.step_rows % s.C;
     switch (nd) {
     case 2: launch_corr_mfma_nd<T, 2>(in, f, out, g, (unsigned)blocks, st); break;
     case 3: launch_corr_mfma_nd<T, 3>(in, f, out, g, (unsigned)blocks, st); break;
@@ -136,24 +139,28 @@ enum DwKernel { DW_VALU_K8, DW_VALU_K32, DW_VALU_K64, DW_VALU_K256 };
 struct DwPlan {
     DwKernel kernel;
     int S;                 // partial slices per coefficient
-    int tiles_per_row;     // tiles along L
-    int items_per_slice;   // (b, tile) items each slice owns
+    int tiles_per_row;     // segments (tiles of kDwTT positions) along L
+    int segs_per_wave;     // consecutive (b, segment) items a wave of the matrix-core kernel walks
+    int items_per_slice;   // (b, segment) items each slice owns = 4 * segs_per_wave
 };
 
-constexpr int kDwTT = 2048;       // positions per staged tile (every stage-1 kernel)
+constexpr int kDwTT = dwconv::kSegLen;   // positions per staged tile (every stage-1 kernel)
 constexpr int kDwThreads = 256;
 
+// Depends on the shape only, so stage 1, stage 2 and the workspace query always agree.
 DwPlan plan_dw(const Shape &s)
 {
     DwPlan p;
     p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
     const long long tiles = ((long long)s.L + kDwTT - 1) / kDwTT;
-    const long long items = (long long)s.B * tiles;
-    long long want = (2048 + s.C - 1) / s.C;          // about 2048 blocks in flight over the chip
+    const long long items = (long long)s.B * tiles;                  // per channel
+    long long want = (kTargetWaves / dwconv::kWavesPerBlock + s.C - 1) / s.C;   // blocks per channel
     if (want < 1) want = 1;
-    if (want > items) want = items;
     if (want > 65535) want = 65535;
-    const long long per = (items + want - 1) / want;
+    long long spw = (items + want * dwconv::kWavesPerBlock - 1) / (want * dwconv::kWavesPerBlock);
+    if (spw < 1) spw = 1;
+    const long long per = spw * dwconv::kWavesPerBlock;
+    p.segs_per_wave = (int)spw;
     p.items_per_slice = (int)per;
     p.S = (int)((items + per - 1) / per);
     p.tiles_per_row = (int)tiles;
@@ -172,7 +179,7 @@ int check_dw_shape(int B, int C, int L, int K, int pad, int dtype)
     if (rc != DWCONV_OK) return rc;
     // the slice bookkeeping of stage 1 is 32-bit
     const long long tiles = ((long long)L + kDwTT - 1) / kDwTT;
-    if ((long long)B * tiles > 0x7fffffffLL || C > 0x7fffffff / 2) return DWCONV_ERR_SHAPE;
+    if ((long long)B * tiles > 0x3fffffffLL || C > 0x7fffffff / 2) return DWCONV_ERR_SHAPE;
     return DWCONV_OK;
 }
 
@@ -188,9 +195,9 @@ template <typename T, int ND>
 void launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, int dmin,
                                hipStream_t st)
 {
-    hipLaunchKernelGGL((dwconv::dw_partial_mfma_kernel<T, ND, 4, kDwTT>), dim3((unsigned)s.C, (unsigned)p.S), dim3(256),
-                       0, st, static_cast<const T *>(x), static_cast<const T *>(dy), part, s.B, s.C, s.L, s.K, s.pad,
-                       dmin, p.tiles_per_row, p.items_per_slice);
+    hipLaunchKernelGGL((dwconv::dw_partial_mfma_kernel<T, ND>), dim3((unsigned)s.C, (unsigned)p.S),
+                       dim3(64 * dwconv::kWavesPerBlock), 0, st, static_cast<const T *>(x), static_cast<const T *>(dy),
+                       part, s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.segs_per_wave);
 }
 
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.

@@ -30,198 +30,310 @@ __device__ __forceinline__ floatx4 mfma16x16x4(float a, float b, floatx4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-constexpr int kLdsBlockStride = 20;   // floats per staged 16-block: 16 + 4 pad (bank spread for strided b128 reads)
+constexpr int kLdsBlockStride = 24;   // floats per staged 16-block: 16 + 8 pad, measured conflict-free for the strided b128 reads
+constexpr int kSegBlocks = 64;        // 16-blocks per segment: one segment = 1024 positions
+constexpr int kSegLen = kSegBlocks * 16;
+constexpr int kWavesPerBlock = 4;        // weight-gradient kernel (block-level final reduction)
+constexpr int kMfmaWavesPerSimd = 4;      // register budget both kernels are compiled for (512 / 4 = 128 per lane)
+constexpr int kCorrWavesPerBlock = 1;    // correlate kernel: waves are independent
+
+// Orders LDS traffic of one wave: everything before is visible to every lane after.
+// The LDS regions below are private to a wave, so no workgroup barrier is needed.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 // Geometry the host computes once per call for the correlate kernel.
 struct CorrGeom {
-    int C, L, K, B;
+    int C, L, K;
+    int rows;           // B * C
     int pad;            // effective pad of this correlation
     int reverse;        // filter index reversed (input gradient)
     int dmin;           // first block offset
-    int segs_per_row;   // segments of SEGBLK*16 outputs per row
-    int rows_per_block; // rows a block covers when a row has fewer segments than the block has waves
-    int groups_per_row; // blocks per row otherwise
+    int segs_per_row;   // segments of kSegLen outputs per row
+    int n_waves;        // waves launched; wave w walks segments w, w + n_waves, ... of the memory order (row, seg)
+    int step_rows;      // n_waves / segs_per_row
+    int step_seg;       // n_waves % segs_per_row
+    int step_c;         // step_rows % C
 };
 
-// out[row, t] = sum_j in~[row, t + j - pad] * f_eff[c, j]
-// One wave = one segment of SEGBLK*16 consecutive outputs of one (b,c) row; the waves of a
-// block share the channel.  Each wave stages its segment plus halo into its own LDS region.
-template <typename T, int ND, int WAVES, int SEGBLK>
-__global__ __launch_bounds__(64 * WAVES) void corr_mfma_kernel(const T *__restrict__ in, const T *__restrict__ f,
-                                                                T *__restrict__ out, const CorrGeom g)
+// Prefetch of four consecutive elements that may fall outside the row [0, L): the load is always
+// issued, from a clamped in-range address, and the value is masked only when it is consumed
+// (mask4), so that nothing waits on the load where it is issued.  Needs L >= 4, L % 4 == 0, u % 4 == 0.
+template <typename T>
+__device__ __forceinline__ float4 ld4_clamped(const T *row, int u, int L)
 {
-    constexpr int NIB = SEGBLK + ND - 1;           // input blocks staged per segment
-    constexpr int NDT = SEGBLK / 16;               // D tiles (16 blocks = 256 outputs) per segment
-    static_assert(SEGBLK % 16 == 0, "segment is a whole number of D tiles");
-    __shared__ __align__(16) float s_in[WAVES][NIB * kLdsBlockStride];
+    return ld_elem4(row + min(max(u, 0), L - 4));
+}
+__device__ __forceinline__ float4 mask4(float4 v, int u, int L)
+{
+    return (u >= 0 && u + 3 < L) ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// out[row, t] = sum_j in~[row, t + j - pad] * f_eff[c, j]
+//
+// Every wave walks segments wave, wave + n_waves, ... of the memory order (b, c, seg) and keeps the
+// Toeplitz operands of the current channel in registers (reloaded when the channel changes).
+// Per segment it
+//   (1) issues the global loads of the NEXT segment plus halo into registers,
+//   (2) contracts the 4 D tiles (16 blocks = 256 outputs each) of the current segment out of its
+//       private LDS region (16-blocks padded to 20 floats, zeros outside the row),
+//   (3) drains the prefetch registers into the same LDS region, and
+//   (4) stores 16 bytes per lane per D tile,
+// so loads are in flight during (2) and the stores of a segment have the whole of the next
+// segment's (2) to retire before the next wait on the memory counter.
+template <typename T, int ND>
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_mfma_kernel(const T *__restrict__ in,
+                                                                         const T *__restrict__ f, T *__restrict__ out,
+                                                                         const CorrGeom g)
+{
+    constexpr int NIB = kSegBlocks + ND - 1;       // input blocks staged per segment
+    constexpr int NG = NIB * 4;                    // 16-byte granules staged per segment
+    constexpr int NLD = (NG + 63) / 64;            // granules per lane
+    constexpr int NDT = kSegBlocks / 16;           // D tiles per segment
+    __shared__ __align__(16) float s_in[kCorrWavesPerBlock][NIB * kLdsBlockStride];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int i16 = lane & 15;      // A: output position r;  B/D: block j
     const int k4 = lane >> 4;       // contraction sub-index;  D: row group
 
-    // ---- which segment is this wave's
-    const unsigned bx = blockIdx.x;
-    const int grp = (int)(bx % (unsigned)g.groups_per_row);
-    const int c = (int)((bx / (unsigned)g.groups_per_row) % (unsigned)g.C);
-    const int bg = (int)(bx / ((unsigned)g.groups_per_row * (unsigned)g.C));
-    int b, seg;
-    if (g.segs_per_row >= WAVES) {
-        b = bg;
-        seg = grp * WAVES + wave;
-    } else {
-        const int sub = wave / g.segs_per_row;
-        b = bg * g.rows_per_block + sub;
-        seg = wave % g.segs_per_row;
-        if (sub >= g.rows_per_block) b = g.B;   // idle wave
-    }
-    const bool active = (b < g.B) && (seg < g.segs_per_row);
+    // Wave w walks segments w, w + n_waves, ...: at any moment the waves of the chip read one
+    // contiguous stretch of memory, which spreads the traffic evenly over the HBM channels.
+    // (row, seg, c) are wave-uniform and advanced without divisions.
+    const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    int row = wg / g.segs_per_row;                 // b * C + c
+    int seg = wg % g.segs_per_row;
+    int c = row % g.C;
+    if (row >= g.rows) return;
+    int row_n, seg_n, c_n;                         // the segment after (row, seg)
+    auto advance = [&]() {
+        seg_n = seg + g.step_seg;
+        const int carry = seg_n >= g.segs_per_row ? 1 : 0;
+        seg_n -= carry ? g.segs_per_row : 0;
+        row_n = row + g.step_rows + carry;
+        c_n = c + g.step_c + carry;
+        c_n -= c_n >= g.C ? g.C : 0;
+        c_n -= c_n >= g.C ? g.C : 0;
+    };
 
-    // ---- Toeplitz operands: A[d][v] (lane (r, k)) = f_eff[16 (dmin + d) + 4k + v - r + pad]
-    float A[ND][4];
-    {
-        const T *f_c = f + (size_t)c * (size_t)g.K;
+    float4 pre[NLD];
+    auto prefetch = [&](int prow, int pseg) {
+        const T *in_row = in + (size_t)prow * (size_t)g.L;
+        const int u0 = pseg * kSegLen + 16 * g.dmin;
 #pragma unroll
-        for (int d = 0; d < ND; ++d)
+        for (int i = 0; i < NLD; ++i) pre[i] = ld4_clamped(in_row, u0 + 4 * (lane + 64 * i), g.L);
+    };
+    float *sw = s_in[wave];
+    // LDS block lb holds in~[seg*kSegLen + 16 (dmin + lb) + 0..15]
+    auto drain = [&](int pseg) {
+        const int u0 = pseg * kSegLen + 16 * g.dmin;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int j = 16 * (g.dmin + d) + 4 * k4 + v - i16 + g.pad;
-                float a = 0.f;
-                if (j >= 0 && j < g.K) a = ld_elem(f_c + (g.reverse ? (g.K - 1 - j) : j));
-                A[d][v] = a;
-            }
-    }
-
-    const size_t row = (size_t)(active ? b : 0) * (size_t)g.C + (size_t)c;
-    const T *in_row = in + row * (size_t)g.L;
-    const int t0 = seg * (SEGBLK * 16);
-
-    // ---- stage the segment: LDS block lb holds in~[16 (t0/16 + dmin + lb) + 0..15]
-    if (active) {
-        const int u0 = t0 + 16 * g.dmin;
-        float *sw = s_in[wave];
-        for (int gi = lane; gi < NIB * 4; gi += 64) {
-            const int u = u0 + 4 * gi;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (u >= 0 && u + 3 < g.L) v = ld_elem4(in_row + u);
-            *reinterpret_cast<float4 *>(sw + (gi >> 2) * kLdsBlockStride + (gi & 3) * 4) = v;
+        for (int i = 0; i < NLD; ++i) {
+            const int gi = lane + 64 * i;
+            if (gi < NG)
+                *reinterpret_cast<float4 *>(sw + (gi >> 2) * kLdsBlockStride + (gi & 3) * 4) =
+                    mask4(pre[i], u0 + 4 * gi, g.L);
         }
-    }
-    __syncthreads();
-    if (!active) return;
+    };
+    prefetch(row, seg);
+    drain(seg);
+    wave_lds_fence();
 
-    // ---- contraction: NDT independent accumulators
-    floatx4 acc[NDT];
+    float A[ND][4];
+    int cur_c = -1;
+    const float *sp = sw + i16 * kLdsBlockStride + 4 * k4;
+
+    for (;;) {
+        advance();
+        const bool more = row_n < g.rows;
+        // (1)
+        if (more) prefetch(row_n, seg_n);
+        if (c != cur_c) {
+            // Toeplitz operands: A[d][v] (lane (r, k)) = f_eff[16 (dmin + d) + 4k + v - r + pad]
+            const T *f_c = f + (size_t)c * (size_t)g.K;
 #pragma unroll
-    for (int dt = 0; dt < NDT; ++dt) acc[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const float *sp = s_in[wave] + i16 * kLdsBlockStride + 4 * k4;
+            for (int d = 0; d < ND; ++d)
 #pragma unroll
-    for (int d = 0; d < ND; ++d) {
-        float4 bv[NDT];
+                for (int v = 0; v < 4; ++v) {
+                    const int j = 16 * (g.dmin + d) + 4 * k4 + v - i16 + g.pad;
+                    const bool ok = j >= 0 && j < g.K;
+                    const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
+                    const float a = ld_elem(f_c + jc);
+                    A[d][v] = ok ? a : 0.f;
+                }
+            cur_c = c;
+        }
+        // (2) one dependent chain of 4*ND matrix instructions per D tile.  Group g = (dt, d) is one
+        // 16-byte LDS read feeding four matrix instructions; reads run PF groups ahead of their use.
+        floatx4 acc[NDT];
+        {
+            constexpr int NGRP = NDT * ND;
+            constexpr int PF = 4;
+            float4 bv[PF];
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-            bv[dt] = *reinterpret_cast<const float4 *>(sp + (16 * dt + d) * kLdsBlockStride);
+            for (int q = 0; q < PF; ++q)
+                bv[q] = *reinterpret_cast<const float4 *>(sp + (16 * (q / ND) + (q % ND)) * kLdsBlockStride);
+#pragma unroll
+            for (int q = 0; q < NGRP; ++q) {
+                const int dt = q / ND, d = q % ND;
+                const float4 cur = bv[q % PF];
+                floatx4 a4 = (d == 0) ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[dt];
+                a4 = mfma16x16x4(A[d][0], cur.x, a4);
+                a4 = mfma16x16x4(A[d][1], cur.y, a4);
+                a4 = mfma16x16x4(A[d][2], cur.z, a4);
+                a4 = mfma16x16x4(A[d][3], cur.w, a4);
+                acc[dt] = a4;
+                if (q + PF < NGRP) {
+                    const int n = q + PF;
+                    bv[q % PF] = *reinterpret_cast<const float4 *>(sp + (16 * (n / ND) + (n % ND)) * kLdsBlockStride);
+                }
+            }
+            // pin the interleaving: PF reads, then (4 matrix instructions, 1 read) per group
+#pragma unroll
+            for (int q = 0; q < PF; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+            for (int q = 0; q < NGRP; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                if (q + PF < NGRP) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        wave_lds_fence();
+        // (3)
+        if (more) drain(seg_n);
+        // (4) lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile
+        T *out_row = out + (size_t)row * (size_t)g.L;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
-            acc[dt] = mfma16x16x4(A[d][0], bv[dt].x, acc[dt]);
-            acc[dt] = mfma16x16x4(A[d][1], bv[dt].y, acc[dt]);
-            acc[dt] = mfma16x16x4(A[d][2], bv[dt].z, acc[dt]);
-            acc[dt] = mfma16x16x4(A[d][3], bv[dt].w, acc[dt]);
+            const int t = seg * kSegLen + 256 * dt + 16 * i16 + 4 * k4;
+            if (t + 3 < g.L) st_elem4(out_row + t, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
         }
-    }
-
-    // ---- store: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile
-    T *out_row = out + row * (size_t)g.L;
-#pragma unroll
-    for (int dt = 0; dt < NDT; ++dt) {
-        const int t = t0 + 256 * dt + 16 * i16 + 4 * k4;
-        if (t + 3 < g.L) st_elem4(out_row + t, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+        wave_lds_fence();
+        if (!more) break;
+        row = row_n; seg = seg_n; c = c_n;
     }
 }
 
 // Stage 1 of the weight gradient on the matrix cores.
-// grid = (C, S).  A block walks the (b, tile) items of its slice; a tile is TT positions.
-// Wave w takes the 64-position chunks w, w+WAVES, ... of every tile and keeps ND 16x16
-// accumulators G_d for its whole life; at the end the diagonals of all G_d of all waves are
-// summed through LDS in a fixed order.
-template <typename T, int ND, int WAVES, int TT>
-__global__ __launch_bounds__(64 * WAVES) void dw_partial_mfma_kernel(const T *__restrict__ x, const T *__restrict__ dy,
-                                                                      float *__restrict__ part, int B, int C, int L,
-                                                                      int K, int pad, int dmin, int tiles_per_row,
-                                                                      int items_per_slice)
+// grid = (C, S).  The segments of a channel are ordered (b, seg); wave w of slice s takes segments
+// 4 s + w, 4 s + w + 4 S, ...  A wave keeps ND 16x16
+// accumulators G_d for its whole life.  Per segment: the loads of the next segment are issued,
+// the current one is contracted out of the wave's private LDS region (x window with halo, then
+// dY; both operands of a 64-position chunk are 64 consecutive floats), then the prefetch
+// registers are drained into LDS.  At the end every wave sums the diagonals of its own G_d, and
+// the four per-wave results are added in wave order.
+template <typename T, int ND>
+__global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_partial_mfma_kernel(
+    const T *__restrict__ x, const T *__restrict__ dy, float *__restrict__ part, int B, int C, int L, int K, int pad,
+    int dmin, int segs_per_row, int segs_per_wave)
 {
-    constexpr int XW = TT + 16 * ND;                      // staged x window (floats)
-    constexpr int STAGE = XW + TT;
-    constexpr int RED = WAVES * ND * 256;
-    constexpr int LDSF = STAGE > RED ? STAGE : RED;
-    static_assert(TT % (64 * WAVES) == 0, "tile is a whole number of chunk rounds");
-    __shared__ __align__(16) float s_mem[LDSF];
-    float *s_x = s_mem;
-    float *s_dy = s_mem + XW;
+    constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
+    constexpr int NGX = XW / 4;
+    constexpr int NLX = (NGX + 63) / 64;
+    constexpr int NLG = kSegLen / 256;             // dY granules per lane
+    constexpr int NCH = kSegLen / 64;              // 64-position chunks per segment
+    constexpr int GF = ND * 256;                   // floats of one wave's G
+    constexpr int STAGE = XW + kSegLen;
+    constexpr int WREG = STAGE > GF ? STAGE : GF;  // per-wave LDS region
+    __shared__ __align__(16) float s_mem[kWavesPerBlock][WREG];
+    __shared__ float s_dw[kWavesPerBlock][16 * ND];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int c = blockIdx.x;
-    const int s = blockIdx.y;
-    const int items = B * tiles_per_row;
-    const int it_begin = s * items_per_slice;
-    const int it_end = min(items, it_begin + items_per_slice);
+    const int nseg_c = B * segs_per_row;
+    // wave-slice ws of the channel walks segments ws, ws + stride, ...: at any moment the chip reads
+    // whole rows of a few batches, contiguous over the channels
+    const int stride = (int)gridDim.y * kWavesPerBlock;
+    const int sid_begin = min(nseg_c, (int)blockIdx.y * kWavesPerBlock + wave);
+    const int sid_end = nseg_c;
+    float *sx = s_mem[wave];            // sx[i] = x~[t0 + 16 dmin + i]
+    float *sg = s_mem[wave] + XW;       // sg[i] = dy[t0 + i]
 
     floatx4 G[ND];
 #pragma unroll
     for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int it = it_begin; it < it_end; ++it) {
-        const int b = it / tiles_per_row;
-        const int t0 = (it % tiles_per_row) * TT;
+    float4 pre_x[NLX], pre_g[NLG];
+    auto prefetch = [&](int sid) {
+        const int b = sid / segs_per_row;
+        const int t0 = (sid % segs_per_row) * kSegLen;
         const size_t row = ((size_t)b * (size_t)C + (size_t)c) * (size_t)L;
-        const T *x_row = x + row;
-        const T *dy_row = dy + row;
-        __syncthreads();
-        // s_dy[i] = dy[t0 + i];  s_x[i] = x~[t0 + 16 dmin + i]   (16-byte granules, zero outside the row)
-        for (int gi = tid; gi < TT / 4; gi += 64 * WAVES) {
-            const int t = t0 + 4 * gi;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t + 3 < L) v = ld_elem4(dy_row + t);
-            *reinterpret_cast<float4 *>(s_dy + 4 * gi) = v;
-        }
         const int u0 = t0 + 16 * dmin;
-        for (int gi = tid; gi < XW / 4; gi += 64 * WAVES) {
-            const int u = u0 + 4 * gi;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (u >= 0 && u + 3 < L) v = ld_elem4(x_row + u);
-            *reinterpret_cast<float4 *>(s_x + 4 * gi) = v;
-        }
-        __syncthreads();
-        const int nch = min(TT, L - t0 + 63) / 64;        // chunks that hold at least one position < L
-        for (int ch = wave; ch < nch; ch += WAVES) {
-            const float gq = s_dy[64 * ch + lane];        // B operand: dY[n0 + k][q]
 #pragma unroll
-            for (int d = 0; d < ND; ++d)                  // A operand: X[n0 + k + dmin + d][q']
-                G[d] = mfma16x16x4(s_x[64 * ch + 16 * d + lane], gq, G[d]);
+        for (int i = 0; i < NLX; ++i) pre_x[i] = ld4_clamped(x + row, u0 + 4 * (lane + 64 * i), L);
+#pragma unroll
+        for (int i = 0; i < NLG; ++i) pre_g[i] = ld4_clamped(dy + row, t0 + 4 * (lane + 64 * i), L);
+    };
+    auto drain = [&](int sid) {
+        const int t0 = (sid % segs_per_row) * kSegLen;
+        const int u0 = t0 + 16 * dmin;
+#pragma unroll
+        for (int i = 0; i < NLX; ++i) {
+            const int gi = lane + 64 * i;
+            if (gi < NGX) *reinterpret_cast<float4 *>(sx + 4 * gi) = mask4(pre_x[i], u0 + 4 * gi, L);
         }
+#pragma unroll
+        for (int i = 0; i < NLG; ++i) {
+            const int gi = lane + 64 * i;
+            *reinterpret_cast<float4 *>(sg + 4 * gi) = mask4(pre_g[i], t0 + 4 * gi, L);
+        }
+    };
+    if (sid_begin < sid_end) {
+        prefetch(sid_begin);
+        drain(sid_begin);
+    }
+    wave_lds_fence();
+
+    for (int sid = sid_begin; sid < sid_end; sid += stride) {
+        const bool more = sid + stride < sid_end;
+        if (more) prefetch(sid + stride);
+        // A operand: X[n0 + k + dmin + d][q'] = sx[64 ch + 16 d + lane];  B operand: dY[n0 + k][q] = sg[64 ch + lane]
+        float gq[NCH];
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) gq[ch] = sg[64 * ch + lane];
+#pragma unroll
+        for (int d = 0; d < ND; ++d) {
+            float xa[NCH];
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) xa[ch] = sx[64 * ch + 16 * d + lane];
+            floatx4 a4 = G[d];
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) a4 = mfma16x16x4(xa[ch], gq[ch], a4);
+            G[d] = a4;
+        }
+        wave_lds_fence();
+        if (more) drain(sid + stride);
+        wave_lds_fence();
     }
 
-    // ---- ordered reduction: red[w][d][q'][q]; lane (q = lane%16, k = lane/16) holds q' = 4k + v
-    __syncthreads();
-    float *red = s_mem;
+    // ---- per-wave diagonal sums: sx as g[d][q'][q]; lane (q = lane%16, k = lane/16) holds q' = 4k + v
+    float *sw = s_mem[wave];
 #pragma unroll
     for (int d = 0; d < ND; ++d)
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            red[((wave * ND + d) * 16 + 4 * (lane >> 4) + v) * 16 + (lane & 15)] = G[d][v];
-    __syncthreads();
-    for (int j = tid; j < K; j += 64 * WAVES) {
+        for (int v = 0; v < 4; ++v) sw[(d * 16 + 4 * (lane >> 4) + v) * 16 + (lane & 15)] = G[d][v];
+    wave_lds_fence();
+    for (int j = lane; j < K; j += 64) {
         float sum = 0.f;
         for (int d = 0; d < ND; ++d) {
             const int e = j - pad - 16 * (dmin + d);      // q' - q on this diagonal
             if (e < -15 || e > 15) continue;
             const int q_lo = e > 0 ? e : 0, q_hi = e > 0 ? 15 : 15 + e;
-            for (int qp = q_lo; qp <= q_hi; ++qp)
-                for (int w = 0; w < WAVES; ++w) sum += red[((w * ND + d) * 16 + qp) * 16 + (qp - e)];
+            for (int qp = q_lo; qp <= q_hi; ++qp) sum += sw[(d * 16 + qp) * 16 + (qp - e)];
         }
-        part[((size_t)s * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
+        s_dw[wave][j] = sum;
+    }
+    __syncthreads();
+    for (int j = tid; j < K; j += 64 * kWavesPerBlock) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) sum += s_dw[w][j];
+        part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
     }
 }
 
