@@ -245,12 +245,20 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int c = blockIdx.x;
-    const int nseg_c = B * segs_per_row;
     // wave-slice ws of the channel walks segments ws, ws + stride, ...: at any moment the chip reads
-    // whole rows of a few batches, contiguous over the channels
+    // whole rows of a few batches, contiguous over the channels.  (b, seg) are wave-uniform and
+    // advanced without divisions.
     const int stride = (int)gridDim.y * kWavesPerBlock;
-    const int sid_begin = min(nseg_c, (int)blockIdx.y * kWavesPerBlock + wave);
-    const int sid_end = nseg_c;
+    const int ws = (int)blockIdx.y * kWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    const int step_b = stride / segs_per_row, step_seg = stride % segs_per_row;
+    int b = ws / segs_per_row, seg = ws % segs_per_row;
+    int b_n, seg_n;
+    auto advance = [&]() {
+        seg_n = seg + step_seg;
+        const int carry = seg_n >= segs_per_row ? 1 : 0;
+        seg_n -= carry ? segs_per_row : 0;
+        b_n = b + step_b + carry;
+    };
     float *sx = s_mem[wave];            // sx[i] = x~[t0 + 16 dmin + i]
     float *sg = s_mem[wave] + XW;       // sg[i] = dy[t0 + i]
 
@@ -259,18 +267,17 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
     for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     float4 pre_x[NLX], pre_g[NLG];
-    auto prefetch = [&](int sid) {
-        const int b = sid / segs_per_row;
-        const int t0 = (sid % segs_per_row) * kSegLen;
-        const size_t row = ((size_t)b * (size_t)C + (size_t)c) * (size_t)L;
+    auto prefetch = [&](int pb, int pseg) {
+        const size_t row = ((size_t)pb * (size_t)C + (size_t)c) * (size_t)L;
+        const int t0 = pseg * kSegLen;
         const int u0 = t0 + 16 * dmin;
 #pragma unroll
         for (int i = 0; i < NLX; ++i) pre_x[i] = ld4_clamped(x + row, u0 + 4 * (lane + 64 * i), L);
 #pragma unroll
         for (int i = 0; i < NLG; ++i) pre_g[i] = ld4_clamped(dy + row, t0 + 4 * (lane + 64 * i), L);
     };
-    auto drain = [&](int sid) {
-        const int t0 = (sid % segs_per_row) * kSegLen;
+    auto drain = [&](int pseg) {
+        const int t0 = pseg * kSegLen;
         const int u0 = t0 + 16 * dmin;
 #pragma unroll
         for (int i = 0; i < NLX; ++i) {
@@ -283,32 +290,50 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
             *reinterpret_cast<float4 *>(sg + 4 * gi) = mask4(pre_g[i], t0 + 4 * gi, L);
         }
     };
-    if (sid_begin < sid_end) {
-        prefetch(sid_begin);
-        drain(sid_begin);
+    if (b < B) {
+        prefetch(b, seg);
+        drain(seg);
     }
     wave_lds_fence();
 
-    for (int sid = sid_begin; sid < sid_end; sid += stride) {
-        const bool more = sid + stride < sid_end;
-        if (more) prefetch(sid + stride);
-        // A operand: X[n0 + k + dmin + d][q'] = sx[64 ch + 16 d + lane];  B operand: dY[n0 + k][q] = sg[64 ch + lane]
-        float gq[NCH];
+    while (b < B) {
+        advance();
+        const bool more = b_n < B;
+        if (more) prefetch(b_n, seg_n);
+        // 64-position chunk ch, block offset d:  G_d += X[n0 + k + dmin + d][q'] * dY[n0 + k][q]
+        //   A operand sx[64 ch + 16 d + lane],  B operand sg[64 ch + lane].
+        // LDS reads run ahead of the matrix instructions in two small rings.
+        {
+            constexpr int NQ = NCH * ND;
+            constexpr int PFX = 6, PFG = 2;
+            float xr[PFX], gr[PFG];
 #pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) gq[ch] = sg[64 * ch + lane];
+            for (int ch = 0; ch < PFG; ++ch) gr[ch] = sg[64 * ch + lane];
 #pragma unroll
-        for (int d = 0; d < ND; ++d) {
-            float xa[NCH];
+            for (int q = 0; q < PFX; ++q) xr[q] = sx[64 * (q / ND) + 16 * (q % ND) + lane];
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) xa[ch] = sx[64 * ch + 16 * d + lane];
-            floatx4 a4 = G[d];
+            for (int q = 0; q < NQ; ++q) {
+                const int ch = q / ND, d = q % ND;
+                G[d] = mfma16x16x4(xr[q % PFX], gr[ch % PFG], G[d]);
+                if (q + PFX < NQ) {
+                    const int n = q + PFX;
+                    xr[q % PFX] = sx[64 * (n / ND) + 16 * (n % ND) + lane];
+                }
+                if (d == ND - 1 && ch + PFG < NCH) gr[ch % PFG] = sg[64 * (ch + PFG) + lane];
+            }
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) a4 = mfma16x16x4(xa[ch], gq[ch], a4);
-            G[d] = a4;
+            for (int q = 0; q < PFX + PFG; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (q + PFX < NQ) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (q % ND == ND - 1 && q / ND + PFG < NCH) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
         wave_lds_fence();
-        if (more) drain(sid + stride);
+        if (more) drain(seg_n);
         wave_lds_fence();
+        b = b_n; seg = seg_n;
     }
 
     // ---- per-wave diagonal sums: sx as g[d][q'][q]; lane (q = lane%16, k = lane/16) holds q' = 4k + v
