@@ -108,6 +108,9 @@ def main():
         binding.dwconv_bwd_weight_finalize(s["ws"], wl.B, wl.C, wl.L, K, p, tdt, out=s["dw"])
         if ev: ev[4].record()
 
+    # One plain device copy of a known size (x -> y of set 0) before anything is timed: under
+    # rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate those counters.
+    sets[0]["y"].copy_(sets[0]["x"])
     for i in range(args.warmup):
         step(sets[i % args.sets])
     torch.cuda.synchronize()

@@ -47,7 +47,7 @@ int launch_status()
 int toeplitz_dmin(int pad) { return -((pad + 15) / 16); }
 int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
 
-constexpr int kMfmaMinK = 8;      // shorter filters stay on the vector ALU
+constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;
 
 template <typename T>
