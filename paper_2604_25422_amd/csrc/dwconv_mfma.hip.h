@@ -104,7 +104,11 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     // Wave w walks segments w, w + n_waves, ...: at any moment the waves of the chip read one
     // contiguous stretch of memory, which spreads the traffic evenly over the HBM channels.
     // (row, seg, c) are wave-uniform and advanced without divisions.
-    const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): wave index
+    // (id % 8) * (n_waves / 8) + id / 8 gives every XCD a contiguous run of segments, so the halo a
+    // segment shares with its neighbour is found in that XCD's L2.
+    const int id = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    const int wg = (g.n_waves % 8 == 0) ? (id % 8) * (g.n_waves / 8) + id / 8 : id;
     int row = wg / g.segs_per_row;                 // b * C + c
     int seg = wg % g.segs_per_row;
     int c = row % g.C;
