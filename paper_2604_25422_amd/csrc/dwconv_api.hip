@@ -6,6 +6,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <map>
+#include <mutex>
+
 #include "dwconv_common.hip.h"
 #include "dwconv_mfma.hip.h"
 #include "dwconv_valu.hip.h"
@@ -64,14 +67,34 @@ int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, i
     return launch_status();
 }
 
-constexpr long long kTargetWaves = 4096;   // 256 CUs x 16 resident waves
+constexpr long long kTargetWaves = 4096;   // 256 CUs x 16 resident waves (weight-gradient plan; shape-only)
 
-template <typename T, int ND>
-void launch_corr_mfma_nd(const void *in, const void *f, void *out, const dwconv::CorrGeom &g, unsigned blocks,
-                         hipStream_t st)
+// Waves of `kernel` that are resident on the current device at once (one full round), from the
+// occupancy the runtime reports; falls back to kTargetWaves if the query fails.
+template <typename Kernel>
+long long resident_waves(Kernel kernel, int block_threads)
 {
-    hipLaunchKernelGGL((dwconv::corr_mfma_kernel<T, ND>), dim3(blocks), dim3(64 * dwconv::kCorrWavesPerBlock), 0, st,
-                       static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), g);
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, long long> cache;      // (device, kernel) -> waves
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return kTargetWaves;
+    }
+    const std::pair<int, const void *> key(dev, reinterpret_cast<const void *>(kernel));
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int cus = 0, blocks_per_cu = 0;
+    long long waves = kTargetWaves;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, kernel, block_threads, 0) == hipSuccess &&
+        cus >= 1 && blocks_per_cu >= 1)
+        waves = (long long)cus * blocks_per_cu * (block_threads / 64);
+    else
+        (void)hipGetLastError();
+    cache[key] = waves;
+    return waves;
 }
 
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
@@ -90,23 +113,47 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     g.C = s.C; g.L = s.L; g.K = s.K; g.rows = (int)rows;
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
     g.segs_per_row = (int)segs_per_row;
-    long long spw = total_segs / kTargetWaves;          // segments per wave, rounded down: at least kTargetWaves waves
-    if (spw < 1) spw = 1;
-    const long long waves = (total_segs + spw - 1) / spw;
-    const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
-    g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
-    g.step_rows = g.n_waves / g.segs_per_row;
-    g.step_seg = g.n_waves % g.segs_per_row;
-    g.step_c = g.step_rows % s.C;
+    constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
+    // One resident round of waves, each walking segments wave, wave + n_waves, ...
+    auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po) -> int {
+        const long long resident = resident_waves(kernel, kThreads);
+        long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
+        if (spw < 1) spw = 1;
+        const long long waves = (total_segs + spw - 1) / spw;
+        long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+        blocks = (blocks + 7) / 8 * 8;                               // whole rounds of the 8 XCDs
+        g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
+        g.step_rows = g.n_waves / g.segs_per_row;
+        g.step_seg = g.n_waves % g.segs_per_row;
+        g.step_c = g.step_rows % s.C;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g);
+        return launch_status();
+    };
+    if constexpr (sizeof(T) == 2) {
+        // bf16 storage: the bf16 matrix instruction when 16-byte granules of 8 elements line up
+        if ((s.L % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
+            const bf16_t *pi = static_cast<const bf16_t *>(in), *pf = static_cast<const bf16_t *>(f);
+            bf16_t *po = static_cast<bf16_t *>(out);
+            switch (nd) {
+            case 2: return launch(dwconv::corr_mfma_bf16_kernel<2>, pi, pf, po);
+            case 3: return launch(dwconv::corr_mfma_bf16_kernel<3>, pi, pf, po);
+            case 4: return launch(dwconv::corr_mfma_bf16_kernel<4>, pi, pf, po);
+            case 5: return launch(dwconv::corr_mfma_bf16_kernel<5>, pi, pf, po);
+            case 6: return launch(dwconv::corr_mfma_bf16_kernel<6>, pi, pf, po);
+            default: return -1;
+            }
+        }
+    }
+    const T *pi = static_cast<const T *>(in), *pf = static_cast<const T *>(f);
+    T *po = static_cast<T *>(out);
     switch (nd) {
-    case 2: launch_corr_mfma_nd<T, 2>(in, f, out, g, (unsigned)blocks, st); break;
-    case 3: launch_corr_mfma_nd<T, 3>(in, f, out, g, (unsigned)blocks, st); break;
-    case 4: launch_corr_mfma_nd<T, 4>(in, f, out, g, (unsigned)blocks, st); break;
-    case 5: launch_corr_mfma_nd<T, 5>(in, f, out, g, (unsigned)blocks, st); break;
-    case 6: launch_corr_mfma_nd<T, 6>(in, f, out, g, (unsigned)blocks, st); break;
+    case 2: return launch(dwconv::corr_mfma_kernel<T, 2>, pi, pf, po);
+    case 3: return launch(dwconv::corr_mfma_kernel<T, 3>, pi, pf, po);
+    case 4: return launch(dwconv::corr_mfma_kernel<T, 4>, pi, pf, po);
+    case 5: return launch(dwconv::corr_mfma_kernel<T, 5>, pi, pf, po);
+    case 6: return launch(dwconv::corr_mfma_kernel<T, 6>, pi, pf, po);
     default: return -1;
     }
-    return launch_status();
 }
 
 template <typename T>

@@ -221,6 +221,122 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     }
 }
 
+// bf16 storage on the bf16 matrix instruction (v_mfma_f32_16x16x16_bf16): the same blocked-Toeplitz
+// contraction as corr_mfma_kernel, but the staged tile stays in bf16 (no conversion on the way in),
+// one instruction covers a whole 16-block of the contraction (lane (i, kg) holds k = 4 kg + 0..3),
+// products of two bf16 are exact in fp32 and the accumulators are fp32; one rounding to bf16 at the
+// store.  Needs L % 8 == 0 and 16-byte aligned tensors (16-byte granules of 8 elements).
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+constexpr int kBf16BlockBytes = 48;      // staged 16-block: 32 bytes + 16 pad
+
+template <int ND>
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_mfma_bf16_kernel(
+    const bf16_t *__restrict__ in, const bf16_t *__restrict__ f, bf16_t *__restrict__ out, const CorrGeom g)
+{
+    constexpr int NIB = kSegBlocks + ND - 1;       // input blocks staged per segment
+    constexpr int NG = NIB * 2;                    // 16-byte granules (8 elements) staged per segment
+    constexpr int NLD = (NG + 63) / 64;            // granules per lane
+    constexpr int NDT = kSegBlocks / 16;           // D tiles per segment
+    __shared__ __align__(16) unsigned char s_in[kCorrWavesPerBlock][NIB * kBf16BlockBytes];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i16 = lane & 15;      // A: output position r;  B/D: block j
+    const int k4 = lane >> 4;       // contraction group (k = 4 k4 + e);  D: row group
+
+    const int id = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    const int wg = (g.n_waves % 8 == 0) ? (id % 8) * (g.n_waves / 8) + id / 8 : id;
+    int row = wg / g.segs_per_row;                 // b * C + c
+    int seg = wg % g.segs_per_row;
+    int c = row % g.C;
+    if (row >= g.rows) return;
+    int row_n, seg_n, c_n;                         // the segment after (row, seg)
+    auto advance = [&]() {
+        seg_n = seg + g.step_seg;
+        const int carry = seg_n >= g.segs_per_row ? 1 : 0;
+        seg_n -= carry ? g.segs_per_row : 0;
+        row_n = row + g.step_rows + carry;
+        c_n = c + g.step_c + carry;
+        c_n -= c_n >= g.C ? g.C : 0;
+        c_n -= c_n >= g.C ? g.C : 0;
+    };
+
+    uint4 pre[NLD];
+    auto prefetch = [&](int prow, int pseg) {
+        const bf16_t *in_row = in + (size_t)prow * (size_t)g.L;
+        const int u0 = pseg * kSegLen + 16 * g.dmin;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int u = min(max(u0 + 8 * (lane + 64 * i), 0), g.L - 8);
+            pre[i] = *reinterpret_cast<const uint4 *>(in_row + u);
+        }
+    };
+    unsigned char *sw = s_in[wave];
+    // LDS block lb holds in~[seg*kSegLen + 16 (dmin + lb) + 0..15] as raw bf16
+    auto drain = [&](int pseg) {
+        const int u0 = pseg * kSegLen + 16 * g.dmin;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int gi = lane + 64 * i;
+            const int u = u0 + 8 * gi;
+            const uint4 v = (u >= 0 && u + 7 < g.L) ? pre[i] : make_uint4(0u, 0u, 0u, 0u);
+            if (gi < NG) *reinterpret_cast<uint4 *>(sw + (gi >> 1) * kBf16BlockBytes + (gi & 1) * 16) = v;
+        }
+    };
+    prefetch(row, seg);
+    drain(seg);
+    wave_lds_fence();
+
+    shortx4 A[ND];
+    int cur_c = -1;
+    const unsigned char *sp = sw + i16 * kBf16BlockBytes + 8 * k4;
+
+    for (;;) {
+        advance();
+        const bool more = row_n < g.rows;
+        if (more) prefetch(row_n, seg_n);
+        if (c != cur_c) {
+            // Toeplitz operands: A[d][e] (lane (r, kg)) = f_eff[16 (dmin + d) + 4 kg + e - r + pad]
+            const bf16_t *f_c = f + (size_t)c * (size_t)g.K;
+#pragma unroll
+            for (int d = 0; d < ND; ++d)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = 16 * (g.dmin + d) + 4 * k4 + e - i16 + g.pad;
+                    const bool ok = j >= 0 && j < g.K;
+                    const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
+                    const uint16_t bits = f_c[jc].bits;
+                    A[d][e] = ok ? (short)bits : (short)0;
+                }
+            cur_c = c;
+        }
+        floatx4 acc[NDT];
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+            shortx4 bv[ND];
+#pragma unroll
+            for (int d = 0; d < ND; ++d)
+                bv[d] = *reinterpret_cast<const shortx4 *>(sp + (16 * dt + d) * kBf16BlockBytes);
+            floatx4 a4 = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int d = 0; d < ND; ++d) a4 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A[d], bv[d], a4, 0, 0, 0);
+            acc[dt] = a4;
+        }
+        wave_lds_fence();
+        if (more) drain(seg_n);
+        // lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile
+        bf16_t *out_row = out + (size_t)row * (size_t)g.L;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+            const int t = seg * kSegLen + 256 * dt + 16 * i16 + 4 * k4;
+            if (t + 3 < g.L) st_elem4(out_row + t, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+        }
+        wave_lds_fence();
+        if (!more) break;
+        row = row_n; seg = seg_n; c = c_n;
+    }
+}
+
 // Stage 1 of the weight gradient on the matrix cores.
 // grid = (C, S).  The segments of a channel are ordered (b, seg); wave w of slice s takes segments
 // 4 s + w, 4 s + w + 4 S, ...  A wave keeps ND 16x16
