@@ -60,18 +60,75 @@ struct CorrGeom {
     int step_c;         // step_rows % C
 };
 
-// Prefetch of four consecutive elements that may fall outside the row [0, L): the load is always
-// issued, from a clamped in-range address, and the value is masked only when it is consumed
-// (mask4), so that nothing waits on the load where it is issued.  Needs L >= 4, L % 4 == 0, u % 4 == 0.
+// Row access through buffer instructions.  A buffer resource describes (the tail of) ONE row
+// (base, num_records in bytes, stride 0); the hardware range check makes a load whose byte offset
+// lies outside [0, num_records) return zero, so the zero padding of the operator costs no
+// instructions: an offset before the row start is a negative number, i.e. a huge unsigned one.
+//
+// The prefetch loads are issued through inline assembly on purpose.  They stay in flight across the
+// whole matrix phase of a segment, and the compiler's own wait-count bookkeeping, which has to be
+// conservative across the loop back edge, otherwise splits a round of loads with waits on its own
+// members (a full memory latency per segment).  Untracked loads need exactly one manual wait, where
+// their registers are drained into LDS: s_waitcnt vmcnt(0).  The counter retires in order, so any
+// wait the compiler inserts for its own loads and stores only becomes stricter, never wrong.
+// On this part every vector-ALU instruction also takes issue time away from the matrix instructions of
+// the same SIMD (measured: about 5.5 cycles each), so a window that starts inside the row folds its
+// start into the resource (scalar work) and uses per-lane offsets that are loop constants.
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+constexpr unsigned kBufferFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 family)
+constexpr int kOutOfRow = 0x40000000;            // byte offset no row reaches (rows are shorter than 2^28 elements): load gives 0
+
+// Resource for the bytes [start, L * sizeof(T)) of a row; start >= 0.  All operands are wave-uniform.
 template <typename T>
-__device__ __forceinline__ float4 ld4_clamped(const T *row, int u, int L)
+__device__ __forceinline__ uintx4 row_tail_resource(const T *row, int L, int start)
 {
-    return ld_elem4(row + min(max(u, 0), L - 4));
+    const unsigned long long a = reinterpret_cast<unsigned long long>(row) + (unsigned long long)start;
+    const uintx4 r = {(unsigned)a, (unsigned)(a >> 32) & 0xffffu, (unsigned)(L * (int)sizeof(T) - start), kBufferFlags};
+    return r;
 }
-__device__ __forceinline__ float4 mask4(float4 v, int u, int L)
+
+__device__ __forceinline__ uintx4 buffer_load_x4_untracked(uintx4 rsrc, int byte_off)
 {
-    return (u >= 0 && u + 3 < L) ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+    uintx4 v;
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(v) : "v"(byte_off), "s"(rsrc) : "memory");
+    return v;
 }
+__device__ __forceinline__ uintx2 buffer_load_x2_untracked(uintx4 rsrc, int byte_off)
+{
+    uintx2 v;
+    asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "=v"(v) : "v"(byte_off), "s"(rsrc) : "memory");
+    return v;
+}
+// Wait for every outstanding vector-memory operation of the wave, then hand the prefetch registers
+// back to the compiler (the empty statements keep their uses below the wait).
+__device__ __forceinline__ void wait_untracked_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <typename V, int N>
+__device__ __forceinline__ void release_after_wait(V (&regs)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(regs[i]));
+}
+
+// Raw bits of 4 consecutive elements (a "granule").
+template <typename T> struct Raw4;
+template <> struct Raw4<float> {
+    typedef uintx4 type;
+    static __device__ __forceinline__ type load(uintx4 r, int byte_off) { return buffer_load_x4_untracked(r, byte_off); }
+    static __device__ __forceinline__ float4 widen(type v)
+    {
+        return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3]));
+    }
+};
+template <> struct Raw4<bf16_t> {
+    typedef uintx2 type;
+    static __device__ __forceinline__ type load(uintx4 r, int byte_off) { return buffer_load_x2_untracked(r, byte_off); }
+    static __device__ __forceinline__ float4 widen(type v)
+    {
+        return make_float4(__uint_as_float(v[0] << 16), __uint_as_float(v[0] & 0xffff0000u),
+                           __uint_as_float(v[1] << 16), __uint_as_float(v[1] & 0xffff0000u));
+    }
+};
 
 // out[row, t] = sum_j in~[row, t + j - pad] * f_eff[c, j]
 //
@@ -124,27 +181,37 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
         c_n -= c_n >= g.C ? g.C : 0;
     };
 
-    float4 pre[NLD];
+    // per-lane constants: byte offset of the lane's i-th granule inside the staged window, and its LDS slot
+    constexpr int ES = (int)sizeof(T);
+    typename Raw4<T>::type pre[NLD];
+    int ld_off[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) ld_off[i] = (lane + 64 * i < NG) ? 4 * ES * (lane + 64 * i) : kOutOfRow;
     auto prefetch = [&](int prow, int pseg) {
-        const T *in_row = in + (size_t)prow * (size_t)g.L;
-        const int u0 = pseg * kSegLen + 16 * g.dmin;
+        const int u0 = ES * (pseg * kSegLen + 16 * g.dmin);          // may be negative: before the row start
+        const int start = u0 > 0 ? u0 : 0;
+        const uintx4 r = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, start);
+        if (u0 >= 0) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) pre[i] = ld4_clamped(in_row, u0 + 4 * (lane + 64 * i), g.L);
-    };
-    float *sw = s_in[wave];
-    // LDS block lb holds in~[seg*kSegLen + 16 (dmin + lb) + 0..15]
-    auto drain = [&](int pseg) {
-        const int u0 = pseg * kSegLen + 16 * g.dmin;
+            for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int gi = lane + 64 * i;
-            if (gi < NG)
-                *reinterpret_cast<float4 *>(sw + (gi >> 2) * kLdsBlockStride + (gi & 3) * 4) =
-                    mask4(pre[i], u0 + 4 * gi, g.L);
+            for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i] + u0);
         }
     };
+    float *sw = s_in[wave];
+    float *sw_lane = sw + (lane >> 2) * kLdsBlockStride + (lane & 3) * 4;
+    // LDS block lb holds in~[seg*kSegLen + 16 (dmin + lb) + 0..15]; granule lane + 64 i is block 16 i + lane/4
+    auto drain = [&]() {
+        wait_untracked_loads();
+        release_after_wait(pre);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            if (64 * (i + 1) <= NG || lane + 64 * i < NG)       // only the last round is partial
+                *reinterpret_cast<float4 *>(sw_lane + 16 * i * kLdsBlockStride) = Raw4<T>::widen(pre[i]);
+    };
     prefetch(row, seg);
-    drain(seg);
+    drain();
     wave_lds_fence();
 
     float A[ND][4];
@@ -207,13 +274,20 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
         }
         wave_lds_fence();
         // (3)
-        if (more) drain(seg_n);
-        // (4) lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile
-        T *out_row = out + (size_t)row * (size_t)g.L;
+        if (more) drain();
+        // (4) lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile;
+        // stores past the end of the row are dropped by the range check
+        T *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+        const int lane_t = 16 * i16 + 4 * k4;
+        if ((seg + 1) * kSegLen <= g.L) {
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt) {
-            const int t = seg * kSegLen + 256 * dt + 16 * i16 + 4 * k4;
-            if (t + 3 < g.L) st_elem4(out_row + t, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+            for (int dt = 0; dt < NDT; ++dt)
+                st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+        } else {
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+                if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
+                    st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
         }
         wave_lds_fence();
         if (!more) break;
@@ -261,30 +335,35 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
         c_n -= c_n >= g.C ? g.C : 0;
     };
 
-    uint4 pre[NLD];
-    auto prefetch = [&](int prow, int pseg) {
-        const bf16_t *in_row = in + (size_t)prow * (size_t)g.L;
-        const int u0 = pseg * kSegLen + 16 * g.dmin;
+    uintx4 pre[NLD];
+    int ld_off[NLD];
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int u = min(max(u0 + 8 * (lane + 64 * i), 0), g.L - 8);
-            pre[i] = *reinterpret_cast<const uint4 *>(in_row + u);
+    for (int i = 0; i < NLD; ++i) ld_off[i] = (lane + 64 * i < NG) ? 16 * (lane + 64 * i) : kOutOfRow;
+    auto prefetch = [&](int prow, int pseg) {
+        const int u0 = 2 * (pseg * kSegLen + 16 * g.dmin);           // bytes; may be negative
+        const int start = u0 > 0 ? u0 : 0;
+        const uintx4 r = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, start);
+        if (u0 >= 0) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) pre[i] = buffer_load_x4_untracked(r, ld_off[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) pre[i] = buffer_load_x4_untracked(r, ld_off[i] + u0);
         }
     };
     unsigned char *sw = s_in[wave];
-    // LDS block lb holds in~[seg*kSegLen + 16 (dmin + lb) + 0..15] as raw bf16
-    auto drain = [&](int pseg) {
-        const int u0 = pseg * kSegLen + 16 * g.dmin;
+    unsigned char *sw_lane = sw + (lane >> 1) * kBf16BlockBytes + (lane & 1) * 16;
+    // LDS block lb holds in~[seg*kSegLen + 16 (dmin + lb) + 0..15] as raw bf16; granule lane + 64 i is block 32 i + lane/2
+    auto drain = [&]() {
+        wait_untracked_loads();
+        release_after_wait(pre);
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int gi = lane + 64 * i;
-            const int u = u0 + 8 * gi;
-            const uint4 v = (u >= 0 && u + 7 < g.L) ? pre[i] : make_uint4(0u, 0u, 0u, 0u);
-            if (gi < NG) *reinterpret_cast<uint4 *>(sw + (gi >> 1) * kBf16BlockBytes + (gi & 1) * 16) = v;
-        }
+        for (int i = 0; i < NLD; ++i)
+            if (64 * (i + 1) <= NG || lane + 64 * i < NG)       // only the last round is partial
+                *reinterpret_cast<uintx4 *>(sw_lane + 32 * i * kBf16BlockBytes) = pre[i];
     };
     prefetch(row, seg);
-    drain(seg);
+    drain();
     wave_lds_fence();
 
     shortx4 A[ND];
@@ -323,13 +402,19 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             acc[dt] = a4;
         }
         wave_lds_fence();
-        if (more) drain(seg_n);
+        if (more) drain();
         // lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile
-        bf16_t *out_row = out + (size_t)row * (size_t)g.L;
+        bf16_t *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+        const int lane_t = 16 * i16 + 4 * k4;
+        if ((seg + 1) * kSegLen <= g.L) {
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt) {
-            const int t = seg * kSegLen + 256 * dt + 16 * i16 + 4 * k4;
-            if (t + 3 < g.L) st_elem4(out_row + t, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+            for (int dt = 0; dt < NDT; ++dt)
+                st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+        } else {
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+                if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
+                    st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
         }
         wave_lds_fence();
         if (!more) break;
@@ -386,33 +471,42 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
 #pragma unroll
     for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    float4 pre_x[NLX], pre_g[NLG];
+    constexpr int ES = (int)sizeof(T);
+    typename Raw4<T>::type pre_x[NLX], pre_g[NLG];
+    int ld_off[NLX];                      // byte offset of the lane's i-th granule inside a staged window
+#pragma unroll
+    for (int i = 0; i < NLX; ++i) ld_off[i] = 4 * ES * (lane + 64 * i);
+    const int ld_off_last = (lane + 64 * (NLX - 1) < NGX) ? ld_off[NLX - 1] : kOutOfRow;
     auto prefetch = [&](int pb, int pseg) {
         const size_t row = ((size_t)pb * (size_t)C + (size_t)c) * (size_t)L;
-        const int t0 = pseg * kSegLen;
-        const int u0 = t0 + 16 * dmin;
+        const int t0 = ES * pseg * kSegLen;
+        const int u0 = t0 + ES * 16 * dmin;                            // may be negative: before the row start
+        const int start = u0 > 0 ? u0 : 0;
+        const uintx4 rx = row_tail_resource(x + row, L, start), rg = row_tail_resource(dy + row, L, t0);
+        if (u0 >= 0) {
 #pragma unroll
-        for (int i = 0; i < NLX; ++i) pre_x[i] = ld4_clamped(x + row, u0 + 4 * (lane + 64 * i), L);
+            for (int i = 0; i < NLX; ++i) pre_x[i] = Raw4<T>::load(rx, i == NLX - 1 ? ld_off_last : ld_off[i]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < NLG; ++i) pre_g[i] = ld4_clamped(dy + row, t0 + 4 * (lane + 64 * i), L);
+            for (int i = 0; i < NLX; ++i) pre_x[i] = Raw4<T>::load(rx, (i == NLX - 1 ? ld_off_last : ld_off[i]) + u0);
+        }
+#pragma unroll
+        for (int i = 0; i < NLG; ++i) pre_g[i] = Raw4<T>::load(rg, ld_off[i]);
     };
-    auto drain = [&](int pseg) {
-        const int t0 = pseg * kSegLen;
-        const int u0 = t0 + 16 * dmin;
+    auto drain = [&]() {
+        wait_untracked_loads();
+        release_after_wait(pre_x);
+        release_after_wait(pre_g);
 #pragma unroll
-        for (int i = 0; i < NLX; ++i) {
-            const int gi = lane + 64 * i;
-            if (gi < NGX) *reinterpret_cast<float4 *>(sx + 4 * gi) = mask4(pre_x[i], u0 + 4 * gi, L);
-        }
+        for (int i = 0; i < NLX; ++i)
+            if (64 * (i + 1) <= NGX || lane + 64 * i < NGX)     // only the last round is partial
+                *reinterpret_cast<float4 *>(sx + 4 * (lane + 64 * i)) = Raw4<T>::widen(pre_x[i]);
 #pragma unroll
-        for (int i = 0; i < NLG; ++i) {
-            const int gi = lane + 64 * i;
-            *reinterpret_cast<float4 *>(sg + 4 * gi) = mask4(pre_g[i], t0 + 4 * gi, L);
-        }
+        for (int i = 0; i < NLG; ++i) *reinterpret_cast<float4 *>(sg + 4 * (lane + 64 * i)) = Raw4<T>::widen(pre_g[i]);
     };
     if (b < B) {
         prefetch(b, seg);
-        drain(seg);
+        drain();
     }
     wave_lds_fence();
 
@@ -451,7 +545,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
             }
         }
         wave_lds_fence();
-        if (more) drain(seg_n);
+        if (more) drain();
         wave_lds_fence();
         b = b_n; seg = seg_n;
     }
