@@ -422,6 +422,19 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     }
 }
 
+// Prefetch of four consecutive elements that may fall outside the row [0, L): the load is always
+// issued, from a clamped in-range address, and the value is masked only when it is consumed
+// (mask4), so that nothing waits on the load where it is issued.  Needs L >= 4, L % 4 == 0, u % 4 == 0.
+template <typename T>
+__device__ __forceinline__ float4 ld4_clamped(const T *row, int u, int L)
+{
+    return ld_elem4(row + min(max(u, 0), L - 4));
+}
+__device__ __forceinline__ float4 mask4(float4 v, int u, int L)
+{
+    return (u >= 0 && u + 3 < L) ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 // Stage 1 of the weight gradient on the matrix cores.
 // grid = (C, S).  The segments of a channel are ordered (b, seg); wave w of slice s takes segments
 // 4 s + w, 4 s + w + 4 S, ...  A wave keeps ND 16x16
@@ -471,42 +484,33 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
 #pragma unroll
     for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int ES = (int)sizeof(T);
-    typename Raw4<T>::type pre_x[NLX], pre_g[NLG];
-    int ld_off[NLX];                      // byte offset of the lane's i-th granule inside a staged window
-#pragma unroll
-    for (int i = 0; i < NLX; ++i) ld_off[i] = 4 * ES * (lane + 64 * i);
-    const int ld_off_last = (lane + 64 * (NLX - 1) < NGX) ? ld_off[NLX - 1] : kOutOfRow;
+    float4 pre_x[NLX], pre_g[NLG];
     auto prefetch = [&](int pb, int pseg) {
         const size_t row = ((size_t)pb * (size_t)C + (size_t)c) * (size_t)L;
-        const int t0 = ES * pseg * kSegLen;
-        const int u0 = t0 + ES * 16 * dmin;                            // may be negative: before the row start
-        const int start = u0 > 0 ? u0 : 0;
-        const uintx4 rx = row_tail_resource(x + row, L, start), rg = row_tail_resource(dy + row, L, t0);
-        if (u0 >= 0) {
+        const int t0 = pseg * kSegLen;
+        const int u0 = t0 + 16 * dmin;
 #pragma unroll
-            for (int i = 0; i < NLX; ++i) pre_x[i] = Raw4<T>::load(rx, i == NLX - 1 ? ld_off_last : ld_off[i]);
-        } else {
+        for (int i = 0; i < NLX; ++i) pre_x[i] = ld4_clamped(x + row, u0 + 4 * (lane + 64 * i), L);
 #pragma unroll
-            for (int i = 0; i < NLX; ++i) pre_x[i] = Raw4<T>::load(rx, (i == NLX - 1 ? ld_off_last : ld_off[i]) + u0);
+        for (int i = 0; i < NLG; ++i) pre_g[i] = ld4_clamped(dy + row, t0 + 4 * (lane + 64 * i), L);
+    };
+    auto drain = [&](int pseg) {
+        const int t0 = pseg * kSegLen;
+        const int u0 = t0 + 16 * dmin;
+#pragma unroll
+        for (int i = 0; i < NLX; ++i) {
+            const int gi = lane + 64 * i;
+            if (gi < NGX) *reinterpret_cast<float4 *>(sx + 4 * gi) = mask4(pre_x[i], u0 + 4 * gi, L);
         }
 #pragma unroll
-        for (int i = 0; i < NLG; ++i) pre_g[i] = Raw4<T>::load(rg, ld_off[i]);
-    };
-    auto drain = [&]() {
-        wait_untracked_loads();
-        release_after_wait(pre_x);
-        release_after_wait(pre_g);
-#pragma unroll
-        for (int i = 0; i < NLX; ++i)
-            if (64 * (i + 1) <= NGX || lane + 64 * i < NGX)     // only the last round is partial
-                *reinterpret_cast<float4 *>(sx + 4 * (lane + 64 * i)) = Raw4<T>::widen(pre_x[i]);
-#pragma unroll
-        for (int i = 0; i < NLG; ++i) *reinterpret_cast<float4 *>(sg + 4 * (lane + 64 * i)) = Raw4<T>::widen(pre_g[i]);
+        for (int i = 0; i < NLG; ++i) {
+            const int gi = lane + 64 * i;
+            *reinterpret_cast<float4 *>(sg + 4 * gi) = mask4(pre_g[i], t0 + 4 * gi, L);
+        }
     };
     if (b < B) {
         prefetch(b, seg);
-        drain();
+        drain(seg);
     }
     wave_lds_fence();
 
@@ -545,7 +549,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
             }
         }
         wave_lds_fence();
-        if (more) drain();
+        if (more) drain(seg_n);
         wave_lds_fence();
         b = b_n; seg = seg_n;
     }
