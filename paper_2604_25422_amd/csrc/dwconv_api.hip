@@ -10,6 +10,7 @@
 #include <mutex>
 
 #include "dwconv_common.hip.h"
+#include "dwconv_longk.hip.h"
 #include "dwconv_mfma.hip.h"
 #include "dwconv_valu.hip.h"
 
@@ -156,10 +157,54 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     }
 }
 
+constexpr size_t kMaxLdsBytes = 160 * 1024;
+
+// Lets `kernel` use more than the default 64 KiB of dynamic LDS (once per kernel and process).
+template <typename Kernel>
+bool allow_large_lds(Kernel kernel)
+{
+    static std::mutex mu;
+    static std::map<const void *, bool> done;
+    std::lock_guard<std::mutex> lock(mu);
+    const void *key = reinterpret_cast<const void *>(kernel);
+    auto it = done.find(key);
+    if (it != done.end()) return it->second;
+    const bool ok = hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLdsBytes) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    done[key] = ok;
+    return ok;
+}
+
+// Filters too long for the register-resident Toeplitz form: whole rows and the whole filter in LDS.
+// Returns -1 when the shape or the pointers do not fit.
+template <typename T>
+int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
+    if (dmax - dmin + 1 <= kMfmaMaxND || s.K > dwconv::kLkMaxK || (s.L % 4) != 0) return -1;
+    const int NB = (s.L + 15) / 16;
+    if (NB > dwconv::kLkMaxBlocks) return -1;
+    if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    const size_t lds = dwconv::longk_corr_lds_bytes(s.K, NB);
+    const long long row_groups = ((long long)s.B + dwconv::kLkRows - 1) / dwconv::kLkRows;
+    if (lds > kMaxLdsBytes || row_groups > 65535) return -1;
+    if (!allow_large_lds(dwconv::corr_longk_kernel<T>)) return -1;
+    dwconv::LongKGeom g;
+    g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K;
+    g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin; g.dmax = dmax;
+    g.NB = NB; g.NT = (NB + 15) / 16;
+    hipLaunchKernelGGL((dwconv::corr_longk_kernel<T>), dim3((unsigned)s.C, (unsigned)row_groups),
+                       dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(in), static_cast<const T *>(f),
+                       static_cast<T *>(out), g);
+    return launch_status();
+}
+
 template <typename T>
 int launch_corr(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
-    const int rc = launch_corr_mfma<T>(in, f, out, s, pad_eff, reverse, st);
+    int rc = launch_corr_mfma<T>(in, f, out, s, pad_eff, reverse, st);
+    if (rc >= 0) return rc;
+    rc = launch_corr_longk<T>(in, f, out, s, pad_eff, reverse, st);
     if (rc >= 0) return rc;
     return launch_corr_valu<T>(in, f, out, s, pad_eff, reverse, st);
 }

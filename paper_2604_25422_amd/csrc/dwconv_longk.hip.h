@@ -1,0 +1,142 @@
+// Matrix-core kernels for filters whose length is of the order of the sequence (K up to 8192,
+// L up to 8192): the blocked-Toeplitz form of dwconv_mfma.hip.h with a long loop over block offsets.
+//
+//   Y[n][r] = sum_{d = dmin..dmax} sum_q Toep_d[r][q] X[n + d][q],   Toep_d[r][q] = w[16 d + q - r + pad]
+//
+// Here neither the Toeplitz operands (4 registers per offset, hundreds of offsets) nor the inputs fit
+// in registers, so a workgroup keeps the whole filter of its channel and whole rows in LDS:
+//   forward / input gradient:  grid (C, ceil(B/2)); a workgroup of 16 waves stages w[c,:] (with zero
+//       margins) and two rows x[b,c,:], x[b+1,c,:] (16-blocks padded to 24 floats, 15 zero blocks on
+//       both sides).  A wave owns D tiles (16 blocks = 256 outputs) t and NT-1-t, which balances the
+//       triangular cost of a causal filter, and for each walks d over the offsets that touch the row:
+//       4 LDS dwords of Toeplitz operand, one 16-byte LDS read per row, 4 matrix instructions per row.
+//   weight gradient: see dw_longk_kernel below.
+// Sums are fp32; a chain never runs longer than 64 offsets (1024 terms) before it is folded into a
+// second accumulator.
+#pragma once
+#include "dwconv_common.hip.h"
+#include "dwconv_mfma.hip.h"
+
+namespace dwconv {
+
+constexpr int kLkWaves = 16;            // waves per workgroup (1024 threads)
+constexpr int kLkRows = 2;              // rows staged together
+constexpr int kLkMaxBlocks = 512;       // 16-blocks per row: L <= 8192
+constexpr int kLkMaxK = 8192;
+constexpr int kLkMargin = 15;           // zero 16-blocks on both sides of a staged row
+constexpr int kLkWMargin = 48;          // zero taps on both sides of the staged filter
+constexpr int kLkFold = 64;             // offsets per inner accumulation chain
+
+struct LongKGeom {
+    int B, C, L, K;
+    int pad;        // effective pad of this correlation
+    int reverse;    // filter index reversed (input gradient)
+    int dmin, dmax; // block offsets that can hold a tap
+    int NB;         // 16-blocks per row, ceil(L / 16)
+    int NT;         // D tiles per row, ceil(NB / 16)
+};
+
+__host__ __device__ inline int longk_filter_floats(int K) { return (K + 2 * kLkWMargin + 3) & ~3; }
+__host__ __device__ inline int longk_row_floats(int NB) { return (NB + 2 * kLkMargin) * kLdsBlockStride; }
+inline size_t longk_corr_lds_bytes(int K, int NB)
+{
+    return sizeof(float) * ((size_t)longk_filter_floats(K) + (size_t)kLkRows * longk_row_floats(NB));
+}
+
+// out[row, t] = sum_j in~[row, t + j - pad] * f_eff[c, j]
+template <typename T>
+__global__ __launch_bounds__(64 * kLkWaves) void corr_longk_kernel(const T *__restrict__ in, const T *__restrict__ f,
+                                                                    T *__restrict__ out, const LongKGeom g)
+{
+    extern __shared__ __align__(16) float lk_smem[];
+    float *fw = lk_smem;                                     // fw[kLkWMargin + j] = f_eff[j], zero outside [0, K)
+    float *xr = lk_smem + longk_filter_floats(g.K);
+    const int XR = longk_row_floats(g.NB);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i16 = lane & 15;
+    const int k4 = lane >> 4;
+    const int c = blockIdx.x;
+    const int b0 = blockIdx.y * kLkRows;
+
+    // ---- stage the filter and the rows
+    {
+        const T *f_c = f + (size_t)c * (size_t)g.K;
+        const int FW = longk_filter_floats(g.K);
+        for (int i = tid; i < FW; i += 64 * kLkWaves) {
+            const int j = i - kLkWMargin;
+            float v = 0.f;
+            if (j >= 0 && j < g.K) v = ld_elem(f_c + (g.reverse ? (g.K - 1 - j) : j));
+            fw[i] = v;
+        }
+        for (int rb = 0; rb < kLkRows; ++rb) {
+            float *xrow = xr + rb * XR;
+            const int b = b0 + rb;
+            // zero margins (16 useful floats of each of the 15 + 15 blocks)
+            for (int i = tid; i < 2 * kLkMargin * 16; i += 64 * kLkWaves) {
+                const int blk = i >> 4, q = i & 15;
+                const int lb = blk < kLkMargin ? blk : g.NB + blk;
+                xrow[lb * kLdsBlockStride + q] = 0.f;
+            }
+            const T *in_row = in + ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            for (int gi = tid; gi < g.NB * 4; gi += 64 * kLkWaves) {
+                const int u = 4 * gi;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (b < g.B && u + 3 < g.L) v = ld_elem4(in_row + u);
+                *reinterpret_cast<float4 *>(xrow + (kLkMargin + (gi >> 2)) * kLdsBlockStride + (gi & 3) * 4) = v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- D tiles of this wave: w, 2*16-1-w, 2*16+w, ...
+    for (int base = 0; base < g.NT; base += 2 * kLkWaves) {
+        for (int half = 0; half < 2; ++half) {
+            const int t = half == 0 ? base + wave : base + 2 * kLkWaves - 1 - wave;
+            if (t >= g.NT) continue;
+            // offsets d for which some block 16 t + j + d of the tile lies inside the row
+            const int dlo = max(g.dmin, -(16 * t + 15));
+            const int dhi = min(g.dmax, g.NB - 1 - 16 * t);
+            floatx4 tot0 = floatx4{0.f, 0.f, 0.f, 0.f}, tot1 = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (dlo <= dhi) {
+                // A: lane (r = i16, k4) reads f_eff[16 d + 4 k4 + v - r + pad];  B: lane (j = i16, k4) reads X[16 t + j + d][4 k4 ..]
+                const float *ap = fw + kLkWMargin + 16 * dlo + 4 * k4 - i16 + g.pad;
+                const float *bp = xr + (kLkMargin + 16 * t + i16 + dlo) * kLdsBlockStride + 4 * k4;
+                for (int d0 = dlo; d0 <= dhi; d0 += kLkFold) {
+                    const int n = min(kLkFold, dhi - d0 + 1);
+                    floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                    for (int i = 0; i < n; ++i) {
+                        const float a0 = ap[0], a1 = ap[1], a2 = ap[2], a3 = ap[3];
+                        const float4 x0 = *reinterpret_cast<const float4 *>(bp);
+                        const float4 x1 = *reinterpret_cast<const float4 *>(bp + XR);
+                        acc0 = mfma16x16x4(a0, x0.x, acc0);
+                        acc1 = mfma16x16x4(a0, x1.x, acc1);
+                        acc0 = mfma16x16x4(a1, x0.y, acc0);
+                        acc1 = mfma16x16x4(a1, x1.y, acc1);
+                        acc0 = mfma16x16x4(a2, x0.z, acc0);
+                        acc1 = mfma16x16x4(a2, x1.z, acc1);
+                        acc0 = mfma16x16x4(a3, x0.w, acc0);
+                        acc1 = mfma16x16x4(a3, x1.w, acc1);
+                        ap += 16;
+                        bp += kLdsBlockStride;
+                    }
+                    tot0 += acc0;
+                    tot1 += acc1;
+                }
+            }
+            // lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of the tile
+            const int to = 256 * t + 16 * i16 + 4 * k4;
+            if (to + 3 < g.L) {
+                T *o0 = out + ((size_t)b0 * (size_t)g.C + (size_t)c) * (size_t)g.L + to;
+                st_elem4(o0, make_float4(tot0[0], tot0[1], tot0[2], tot0[3]));
+                if (b0 + 1 < g.B)
+                    st_elem4(o0 + (size_t)g.C * (size_t)g.L, make_float4(tot1[0], tot1[1], tot1[2], tot1[3]));
+            }
+        }
+    }
+}
+
+}  // namespace dwconv
