@@ -230,6 +230,8 @@ enum DwKernel { DW_VALU_K8, DW_VALU_K32, DW_VALU_K64, DW_VALU_K256 };
 
 struct DwPlan {
     DwKernel kernel;
+    bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
+    int lk_wgs, lk_gd, lk_groups;   // its workgroups per channel, offsets per group, number of groups
     int S;                 // partial slices per coefficient
     int tiles_per_row;     // segments (tiles of kDwTT positions) along L
     int segs_per_wave;     // consecutive (b, segment) items a wave of the matrix-core kernel walks
@@ -256,6 +258,26 @@ DwPlan plan_dw(const Shape &s)
     p.items_per_slice = (int)per;
     p.S = (int)((items + per - 1) / per);
     p.tiles_per_row = (int)tiles;
+    // long filters: offsets are split over waves instead, partials land in exactly two slices
+    p.longk = false;
+    p.lk_wgs = p.lk_gd = p.lk_groups = 0;
+    const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
+    const int NCH = (s.L + 63) / 64;
+    if (nd > kMfmaMaxND && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
+        dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
+        const int per_wg = 2 * dwconv::kLkWaves * dwconv::kLkDwMaxGD;
+        p.lk_wgs = (nd + per_wg - 1) / per_wg;
+        const int slots2 = 2 * dwconv::kLkWaves * p.lk_wgs;
+        const int need = (nd + slots2 - 1) / slots2;
+        static const int kGd[] = {1, 2, 3, 4, 6, 9};
+        p.lk_gd = 9;
+        for (int gd : kGd)
+            if (gd >= need) { p.lk_gd = gd; break; }
+        p.lk_groups = (nd + p.lk_gd - 1) / p.lk_gd;
+        p.longk = true;
+        p.S = 2;
+        p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
+    }
     return p;
 }
 
@@ -311,9 +333,59 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, const Sha
     return launch_status();
 }
 
+template <typename T, int GD>
+void launch_dw_longk_gd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p,
+                        const dwconv::LongKDwGeom &g, size_t lds, hipStream_t st)
+{
+    hipLaunchKernelGGL((dwconv::dw_longk_kernel<T, GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
+                       dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(x), static_cast<const T *>(dy),
+                       part, g);
+}
+
+// Returns -1 when the pointers do not fit the long-filter matrix-core kernel.
+template <typename T>
+int launch_dw_partial_longk(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
+    dwconv::LongKDwGeom g;
+    g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K; g.pad = s.pad;
+    g.dmin = toeplitz_dmin(s.pad); g.dmax = toeplitz_dmax(s.K, s.pad);
+    g.NCH = (s.L + 63) / 64;
+    g.groups = p.lk_groups;
+    const size_t lds = dwconv::longk_dw_lds_bytes(s.L, g.NCH);
+    bool ok = true;
+    switch (p.lk_gd) {
+    case 1: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 1>); break;
+    case 2: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 2>); break;
+    case 3: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 3>); break;
+    case 4: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 4>); break;
+    case 6: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 6>); break;
+    default: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 9>); break;
+    }
+    if (!ok) return -1;
+    // both slices start at zero: a group stores only the taps it owns
+    const size_t n = (size_t)2 * (size_t)s.C * (size_t)s.K;
+    size_t fill_blocks = (n + 256 * 8 - 1) / (256 * 8);
+    if (fill_blocks > 65536) fill_blocks = 65536;
+    hipLaunchKernelGGL(dwconv::fill_zero_kernel, dim3((unsigned)fill_blocks), dim3(256), 0, st, part, n);
+    switch (p.lk_gd) {
+    case 1: launch_dw_longk_gd<T, 1>(x, dy, part, s, p, g, lds, st); break;
+    case 2: launch_dw_longk_gd<T, 2>(x, dy, part, s, p, g, lds, st); break;
+    case 3: launch_dw_longk_gd<T, 3>(x, dy, part, s, p, g, lds, st); break;
+    case 4: launch_dw_longk_gd<T, 4>(x, dy, part, s, p, g, lds, st); break;
+    case 6: launch_dw_longk_gd<T, 6>(x, dy, part, s, p, g, lds, st); break;
+    default: launch_dw_longk_gd<T, 9>(x, dy, part, s, p, g, lds, st); break;
+    }
+    return launch_status();
+}
+
 template <typename T>
 int launch_dw_partial(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
 {
+    if (p.longk) {
+        const int rc = launch_dw_partial_longk<T>(x, dy, part, s, p, st);
+        if (rc >= 0) return rc;
+    }
     const int rc = launch_dw_partial_mfma<T>(x, dy, part, s, p, st);
     if (rc >= 0) return rc;
     switch (p.kernel) {

@@ -139,4 +139,156 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_kernel(const T *__re
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Stage 1 of the weight gradient for long filters (eq. (dk_def)):
+//     G_d[q'][q] = sum_b sum_n X[n + d][q'] dY[n][q],      dw[j] = sum over 16 d + q' - q + pad = j.
+// There are hundreds of offsets d, each with a 16x16 accumulator, so the offsets are what is split
+// over waves: with W = 16 * gridDim.y waves per channel the offsets are cut into 2 W groups of GD and
+// wave slot s owns groups s and 2 W - 1 - s (a causal filter makes the work of a group fall linearly
+// with |d|, the pairing evens it out).  A workgroup stages two rows of x (256 zero floats on both
+// sides) and of dY at a time; a wave walks the 64-position chunks that its groups can touch: one LDS
+// dword of dY and, per offset, one of x feed one matrix instruction.  At the end each wave sums the
+// diagonals of its accumulators into the taps of its groups and stores them into slice (group & 1)
+// of the partial tensor: groups of equal parity own disjoint taps, so nothing is added in memory;
+// the slices are zero-filled beforehand by fill_zero_kernel and summed by the ordinary stage 2.
+constexpr int kLkDwMargin = 256;        // zero floats on both sides of a staged x row
+constexpr int kLkDwMaxGD = 9;           // offsets per group (4 accumulator registers each, two groups per wave)
+
+struct LongKDwGeom {
+    int B, C, L, K, pad;
+    int dmin, dmax;
+    int NCH;        // 64-position chunks per row
+    int groups;     // number of offset groups, ceil((dmax - dmin + 1) / GD)
+};
+
+inline size_t longk_dw_lds_bytes(int L, int NCH)
+{
+    const size_t stage = sizeof(float) * (size_t)kLkRows * ((size_t)((L + 2 * kLkDwMargin + 3) & ~3) + (size_t)NCH * 64);
+    const size_t reduce = sizeof(float) * (size_t)kLkWaves * (256 + 16 * kLkDwMaxGD + 32);   // epilogue scratch of every wave
+    return stage > reduce ? stage : reduce;
+}
+
+__device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
+__device__ __forceinline__ int ceil_div(int a, int b) { return -floor_div(-a, b); }
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+template <typename T, int GD>
+__global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__restrict__ x, const T *__restrict__ dy,
+                                                                     float *__restrict__ part, const LongKDwGeom g)
+{
+    extern __shared__ __align__(16) float lk_smem[];
+    const int XW = (g.L + 2 * kLkDwMargin + 3) & ~3;        // floats of one staged x row
+    const int GW = g.NCH * 64;                              // floats of one staged dY row
+    float *sx = lk_smem;                                    // sx[rb * XW + kLkDwMargin + u] = x[u]
+    float *sg = lk_smem + kLkRows * XW;                     // sg[rb * GW + t] = dy[t]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = blockIdx.x;
+    const int W = (int)gridDim.y * kLkWaves;                // wave slots of this channel
+    const int slot = (int)blockIdx.y * kLkWaves + wave;
+
+    // the two groups of this wave: [da, db] inclusive, empty if da > db
+    int grp[2], da[2], db[2], ch_lo[2], ch_hi[2];
+    grp[0] = slot;
+    grp[1] = 2 * W - 1 - slot;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const bool valid = grp[k] < g.groups;
+        da[k] = g.dmin + grp[k] * GD;
+        db[k] = valid ? min(g.dmax, da[k] + GD - 1) : da[k] - 1;
+        // chunks in which some offset of the group reaches the row
+        ch_lo[k] = max(0, ceil_div(-63 - 16 * db[k], 64));
+        ch_hi[k] = valid ? min(g.NCH - 1, floor_div(g.L - 1 - 16 * da[k], 64)) : -1;
+    }
+
+    floatx4 G0[GD], G1[GD];
+#pragma unroll
+    for (int i = 0; i < GD; ++i) {
+        G0[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        G1[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int b0 = 0; b0 < g.B; b0 += kLkRows) {
+        __syncthreads();
+        for (int rb = 0; rb < kLkRows; ++rb) {
+            const int b = b0 + rb;
+            float *xrow = sx + rb * XW;
+            float *grow = sg + rb * GW;
+            const size_t row = ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            for (int i = tid; i < 2 * kLkDwMargin; i += 64 * kLkWaves)
+                xrow[i < kLkDwMargin ? i : g.L + i] = 0.f;
+            for (int gi = tid; gi < g.NCH * 16; gi += 64 * kLkWaves) {
+                const int u = 4 * gi;
+                float4 vx = make_float4(0.f, 0.f, 0.f, 0.f), vg = vx;
+                if (b < g.B && u + 3 < g.L) {
+                    vx = ld_elem4(x + row + u);
+                    vg = ld_elem4(dy + row + u);
+                }
+                if (u + 3 < g.L) *reinterpret_cast<float4 *>(xrow + kLkDwMargin + u) = vx;
+                *reinterpret_cast<float4 *>(grow + u) = vg;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            for (int rb = 0; rb < kLkRows; ++rb) {
+                // A operand: X[n0 + kk + d][q'] = sx[64 ch + 16 d + lane];  B operand: dY[n0 + kk][q] = sg[64 ch + lane]
+                const float *xp = sx + rb * XW + kLkDwMargin + 16 * da[k] + lane;
+                const float *gp = sg + rb * GW + lane;
+#pragma unroll 2
+                for (int ch = ch_lo[k]; ch <= ch_hi[k]; ++ch) {
+                    const float gq = gp[64 * ch];
+#pragma unroll
+                    for (int i = 0; i < GD; ++i) {
+                        const float xa = xp[64 * ch + 16 * i];
+                        if (k == 0) G0[i] = mfma16x16x4(xa, gq, G0[i]);
+                        else G1[i] = mfma16x16x4(xa, gq, G1[i]);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- diagonal sums.  Wave-private scratch in the (now free) x region: 256 floats of one
+    // accumulator plus the taps of one group, tap T = 16 i + e + 15 for offset da + i, e = q' - q.
+    __syncthreads();
+    constexpr int NTAP = 16 * GD + 32;
+    float *scr = lk_smem + wave * (256 + NTAP);
+    float *tap = scr + 256;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (da[k] > db[k]) continue;
+        for (int i = lane; i < NTAP; i += 64) tap[i] = 0.f;
+        wave_lds_fence();
+#pragma unroll
+        for (int i = 0; i < GD; ++i) {
+            const floatx4 Gi = (k == 0) ? G0[i] : G1[i];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) scr[(4 * (lane >> 4) + v) * 16 + (lane & 15)] = Gi[v];
+            wave_lds_fence();
+            if (lane < 31) {
+                const int e = lane - 15;
+                const int q_lo = e > 0 ? e : 0, q_hi = e > 0 ? 15 : 15 + e;
+                float sum = 0.f;
+                for (int qp = q_lo; qp <= q_hi; ++qp) sum += scr[qp * 16 + (qp - e)];
+                if (da[k] + i <= db[k]) tap[16 * i + lane] += sum;     // a short last group owns fewer offsets
+            }
+            wave_lds_fence();
+        }
+        const int ntap = 16 * (db[k] - da[k]) + 31;
+        float *dst = part + ((size_t)(grp[k] & 1) * (size_t)g.C + (size_t)c) * (size_t)g.K;
+        for (int i = lane; i < ntap; i += 64) {
+            const int j = 16 * da[k] + (i - 15) + g.pad;
+            if (j >= 0 && j < g.K) dst[j] = tap[i];
+        }
+        wave_lds_fence();
+    }
+}
+
 }  // namespace dwconv
