@@ -26,6 +26,12 @@ SMALL = [
     (1, 2, 40, 100, 99), (1, 2, 40, 100, 50), (2, 2, 130, 260, 129),
     (2, 3, 600, 64, 63), (1, 2, 4100, 64, 32), (2, 2, 1500, 300, 299), (1, 1, 3000, 700, 350),
     (1, 2, 1100, 1030, 1029),
+    # long-filter matrix-core kernels: odd batch (row pairing), paper-style and anti-causal pads, every group size
+    (3, 2, 256, 200, 100), (2, 3, 512, 512, 511), (1, 2, 2048, 1500, 700), (2, 2, 1024, 130, 129),
+    (1, 1, 1024, 90, 0), (3, 1, 640, 640, 320), (1, 2, 4096, 4096, 4095), (2, 1, 1000, 2500, 1200),
+    (1, 1, 8192, 300, 299), (1, 2, 72, 67, 66),
+    # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
+    (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
 
 
@@ -35,7 +41,8 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
     check_case(oracle_mod, B, C, L, K, p, "f32", seed=B + C + L + K)
 
 
-@pytest.mark.parametrize("B,C,L,K,p", SMALL[::2] + [(4, 6, 1024, 32, 31), (3, 5, 1000, 32, 16)])
+@pytest.mark.parametrize("B,C,L,K,p", SMALL[::2] + [(4, 6, 1024, 32, 31), (3, 5, 1000, 32, 16), (2, 3, 1004, 32, 31),
+                                                   (3, 2, 256, 200, 100), (1, 2, 2048, 1500, 700), (2, 2, 2056, 64, 0)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
