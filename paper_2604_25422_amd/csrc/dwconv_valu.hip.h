@@ -187,7 +187,13 @@ __global__ __launch_bounds__(256) void dw_finalize_kernel(const float *__restric
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= CK) return;
     float sum = 0.f;
-    for (int s = 0; s < S; ++s) sum += part[(size_t)s * CK + i];
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {           // four independent loads in flight, added in slice order
+        const float p0 = part[(size_t)s * CK + i], p1 = part[(size_t)(s + 1) * CK + i];
+        const float p2 = part[(size_t)(s + 2) * CK + i], p3 = part[(size_t)(s + 3) * CK + i];
+        sum = (((sum + p0) + p1) + p2) + p3;
+    }
+    for (; s < S; ++s) sum += part[(size_t)s * CK + i];
     st_elem(dw + i, sum);
 }
 
