@@ -8,8 +8,10 @@
 
 #include <map>
 #include <mutex>
+#include <type_traits>
 
 #include "dwconv_common.hip.h"
+#include "dwconv_dw_direct.hip.h"
 #include "dwconv_longk.hip.h"
 #include "dwconv_mfma.hip.h"
 #include "dwconv_valu.hip.h"
@@ -53,6 +55,7 @@ int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
 
 constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;
+constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
 template <typename T>
 int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
@@ -104,7 +107,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
 {
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
     const long long rows = (long long)s.B * s.C;
     const long long segs_per_row = (s.L + dwconv::kSegLen - 1) / dwconv::kSegLen;
@@ -309,9 +312,18 @@ template <typename T, int ND>
 void launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, int dmin,
                                hipStream_t st)
 {
-    hipLaunchKernelGGL((dwconv::dw_partial_mfma_kernel<T, ND>), dim3((unsigned)s.C, (unsigned)p.S),
-                       dim3(64 * dwconv::kWavesPerBlock), 0, st, static_cast<const T *>(x), static_cast<const T *>(dy),
-                       part, s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.segs_per_wave);
+    if constexpr (std::is_same<T, float>::value) {
+        // fp32 rows go from memory straight into LDS
+        hipLaunchKernelGGL((dwconv::dw_partial_direct_kernel<ND>), dim3((unsigned)s.C, (unsigned)p.S),
+                           dim3(64 * dwconv::kWavesPerBlock), 0, st, static_cast<const float *>(x),
+                           static_cast<const float *>(dy), part, s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row,
+                           p.segs_per_wave);
+    } else {
+        hipLaunchKernelGGL((dwconv::dw_partial_mfma_kernel<T, ND>), dim3((unsigned)s.C, (unsigned)p.S),
+                           dim3(64 * dwconv::kWavesPerBlock), 0, st, static_cast<const T *>(x),
+                           static_cast<const T *>(dy), part, s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row,
+                           p.segs_per_wave);
+    }
 }
 
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
@@ -320,7 +332,7 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, const Sha
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
     switch (nd) {
     case 2: launch_dw_partial_mfma_nd<T, 2>(x, dy, part, s, p, dmin, st); break;

@@ -435,6 +435,41 @@ __device__ __forceinline__ float4 mask4(float4 v, int u, int L)
     return (u >= 0 && u + 3 < L) ? v : make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
+// Sums the diagonals of one wave's ND accumulators:
+//     dw_wave[j] = sum of G_d[q'][q] over 16 (dmin + d) + q' - q + pad = j.
+// Lane (q = lane % 16, k = lane / 16) holds G_d[4 k + v][q] in element v.  The accumulators are scattered into
+// a skewed LDS image M[jl][q], jl = 16 d + q' - q + 15, rows padded to 17 floats, in which every diagonal is a
+// row: cell (jl, q) is written by at most one (d, q'), the cells nothing maps to stay zero, and lane j adds the
+// 16 cells of its row in q order (independent reads, conflict-free at stride 17).  sw: the wave's private LDS
+// region, at least (16 ND + 15) * 17 floats, 16-byte aligned.
+template <int ND>
+__device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], float *sw, float *dw_wave, int lane, int K,
+                                                      int pad, int dmin)
+{
+    constexpr int ROWS = 16 * ND + 15, RS = 17;
+    constexpr int N4 = (ROWS * RS + 3) / 4;
+    for (int i = lane; i < N4; i += 64) *reinterpret_cast<float4 *>(sw + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    wave_lds_fence();
+    const int q = lane & 15, k4 = lane >> 4;
+#pragma unroll
+    for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sw[(16 * d + 4 * k4 + v - q + 15) * RS + q] = G[d][v];
+    wave_lds_fence();
+    for (int j = lane; j < K; j += 64) {
+        const int jl = j - pad - 16 * dmin + 15;
+        float sum = 0.f;
+        if (jl >= 0 && jl < ROWS) {
+            float t[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[i] = sw[jl * RS + i];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += t[i];
+        }
+        dw_wave[j] = sum;
+    }
+}
+
 // Stage 1 of the weight gradient on the matrix cores.
 // grid = (C, S).  The segments of a channel are ordered (b, seg); wave w of slice s takes segments
 // 4 s + w, 4 s + w + 4 S, ...  A wave keeps ND 16x16
@@ -554,23 +589,9 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
         b = b_n; seg = seg_n;
     }
 
-    // ---- per-wave diagonal sums: sx as g[d][q'][q]; lane (q = lane%16, k = lane/16) holds q' = 4k + v
-    float *sw = s_mem[wave];
-#pragma unroll
-    for (int d = 0; d < ND; ++d)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) sw[(d * 16 + 4 * (lane >> 4) + v) * 16 + (lane & 15)] = G[d][v];
-    wave_lds_fence();
-    for (int j = lane; j < K; j += 64) {
-        float sum = 0.f;
-        for (int d = 0; d < ND; ++d) {
-            const int e = j - pad - 16 * (dmin + d);      // q' - q on this diagonal
-            if (e < -15 || e > 15) continue;
-            const int q_lo = e > 0 ? e : 0, q_hi = e > 0 ? 15 : 15 + e;
-            for (int qp = q_lo; qp <= q_hi; ++qp) sum += sw[(d * 16 + qp) * 16 + (qp - e)];
-        }
-        s_dw[wave][j] = sum;
-    }
+    // ---- per-wave diagonal sums, then the four waves in wave order
+    static_assert(WREG >= ((16 * ND + 15) * 17 + 3) / 4 * 4, "diagonal image fits the wave's region");
+    dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, K, pad, dmin);
     __syncthreads();
     for (int j = tid; j < K; j += 64 * kWavesPerBlock) {
         float sum = 0.f;
