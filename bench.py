@@ -104,15 +104,24 @@ def main():
         sets.append(s)
     tdt = workloads.torch_dtype(wl)
 
+    # The weight gradient runs as one kernel when a whole channel is reduced inside one workgroup; otherwise
+    # its two stages are launched (and timed) separately.
+    code = binding.F32 if wl.dtype == "f32" else binding.BF16
+    single = binding.dwconv_bwd_weight_single_pass(wl.B, wl.C, wl.L, K, p, code)
+
     def step(s, ev=None):
         if ev: ev[0].record()
         binding.dwconv_fwd(s["x"], s["w"], p, out=s["y"])
         if ev: ev[1].record()
         binding.dwconv_bwd_input(s["dy"], s["w"], p, out=s["dx"])
         if ev: ev[2].record()
-        binding.dwconv_bwd_weight_partial(s["x"], s["dy"], K, p, workspace=s["ws"])
-        if ev: ev[3].record()
-        binding.dwconv_bwd_weight_finalize(s["ws"], wl.B, wl.C, wl.L, K, p, tdt, out=s["dw"])
+        if single:
+            binding.dwconv_bwd_weight(s["x"], s["dy"], K, p, workspace=s["ws"], out=s["dw"])
+            if ev: ev[3].record()
+        else:
+            binding.dwconv_bwd_weight_partial(s["x"], s["dy"], K, p, workspace=s["ws"])
+            if ev: ev[3].record()
+            binding.dwconv_bwd_weight_finalize(s["ws"], wl.B, wl.C, wl.L, K, p, tdt, out=s["dw"])
         if ev: ev[4].record()
 
     # One plain device copy of a known size (x -> y of set 0) before anything is timed: under
@@ -140,6 +149,8 @@ def main():
     torch.cuda.synchronize()
     names = ["fwd", "dx", "dw_partial", "dw_finalize"]
     us = {n: 1e3 * sum(e[k].elapsed_time(e[k + 1]) for e in evs) / args.steps for k, n in enumerate(names)}
+    if single:
+        us["dw_finalize"] = 0.0          # no second stage: "dw_partial" is the whole weight-gradient kernel
 
     es = wl.elem_size
     step_bytes = algorithmic_bytes(wl.B, wl.C, wl.L, K, es, "step")
@@ -156,7 +167,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "C": wl.C, "L": wl.L, "K": K, "pad_left": p,
-                   "storage": wl.dtype, "buffer_sets": args.sets,
+                   "storage": wl.dtype, "buffer_sets": args.sets, "dw_single_kernel": bool(single),
                    "step_algorithmic_bytes": step_bytes, "path_algorithmic_bytes": path_bytes,
                    "path_flops_in_range": flops, "path_flops_dense": dense_flops(wl.B, wl.C, wl.L, K)},
         "paths_us": {n: round(v, 2) for n, v in us.items()},

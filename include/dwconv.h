@@ -83,7 +83,10 @@ int dwconv_bwd_input(const void *dy, const void *w, void *dx,
  * Weight (kernel) gradient, Sec. IV-A eq. (dk_def):
  *     dw[c,j] = sum_b sum_t dy[b,c,t] * x~[b,c,t+j-pad_left]
  * x, dy [B,C,L] in; dw [C,K] out (storage dtype).  Runs the two stages below
- * back to back on `stream`.  `workspace` is device memory of at least
+ * back to back on `stream`; when a whole channel is reduced inside one
+ * workgroup (dwconv_bwd_weight_single_pass(...) == 1) the block-level sums are
+ * the gradient and the first stage writes dw itself: one kernel, workspace
+ * untouched.  `workspace` is device memory of at least
  * dwconv_bwd_weight_workspace_bytes(...) bytes, 16-byte aligned; its contents
  * on entry are ignored and it may be reused once the call's work has finished.
  */
@@ -114,6 +117,12 @@ int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, vo
 
 /* Number S of partial slices per coefficient stage 1 writes for this shape; 0 on bad arguments. */
 int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype);
+
+/*
+ * 1 when, for this shape and 16-byte aligned tensors, dwconv_bwd_weight runs as a single kernel
+ * (one workgroup per channel, S = 1, no second stage); 0 otherwise or on bad arguments.
+ */
+int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype);
 
 /* Bytes of workspace dwconv_bwd_weight needs for this shape (S*C*K*4 rounded up); 0 on bad arguments. */
 size_t dwconv_bwd_weight_workspace_bytes(int B, int C, int L, int K, int pad_left, int dtype);

@@ -21,7 +21,8 @@ _lib = None
 
 SYMBOLS = (
     "dwconv_fwd", "dwconv_bwd_input", "dwconv_bwd_weight", "dwconv_bwd_weight_partial",
-    "dwconv_bwd_weight_finalize", "dwconv_bwd_weight_slices", "dwconv_bwd_weight_workspace_bytes",
+    "dwconv_bwd_weight_finalize", "dwconv_bwd_weight_slices", "dwconv_bwd_weight_single_pass",
+    "dwconv_bwd_weight_workspace_bytes",
     "dwconv_status_string", "dwconv_version",
 )
 
@@ -53,6 +54,8 @@ def lib():
             getattr(l, n).restype = i
         l.dwconv_bwd_weight_slices.argtypes = shape
         l.dwconv_bwd_weight_slices.restype = i
+        l.dwconv_bwd_weight_single_pass.argtypes = shape
+        l.dwconv_bwd_weight_single_pass.restype = i
         l.dwconv_bwd_weight_workspace_bytes.argtypes = shape
         l.dwconv_bwd_weight_workspace_bytes.restype = sz
         l.dwconv_status_string.argtypes = [i]
@@ -128,6 +131,11 @@ def dwconv_bwd_input(dy: torch.Tensor, w: torch.Tensor, pad_left: int, out: torc
 
 def dwconv_bwd_weight_slices(B, C, L, K, pad_left, dtype_code) -> int:
     return int(lib().dwconv_bwd_weight_slices(B, C, L, K, pad_left, dtype_code))
+
+
+def dwconv_bwd_weight_single_pass(B, C, L, K, pad_left, dtype_code) -> bool:
+    """True when dwconv_bwd_weight runs as one kernel for this shape (no second stage)."""
+    return bool(lib().dwconv_bwd_weight_single_pass(B, C, L, K, pad_left, dtype_code))
 
 
 def dwconv_bwd_weight_workspace_bytes(B, C, L, K, pad_left, dtype_code) -> int:

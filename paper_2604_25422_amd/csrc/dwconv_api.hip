@@ -55,6 +55,7 @@ int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
 
 constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;
+constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
 template <typename T>
@@ -236,6 +237,8 @@ struct DwPlan {
     bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
     int lk_wgs, lk_gd, lk_groups;   // its workgroups per channel, offsets per group, number of groups
     int S;                 // partial slices per coefficient
+    int wpb;               // waves per block of the matrix-core stage-1 kernels
+    bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
     int tiles_per_row;     // segments (tiles of kDwTT positions) along L
     int segs_per_wave;     // consecutive (b, segment) items a wave of the matrix-core kernel walks
     int items_per_slice;   // (b, segment) items each slice owns = 4 * segs_per_wave
@@ -251,12 +254,23 @@ DwPlan plan_dw(const Shape &s)
     p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
     const long long tiles = ((long long)s.L + kDwTT - 1) / kDwTT;
     const long long items = (long long)s.B * tiles;                  // per channel
-    long long want = (kTargetWaves / dwconv::kWavesPerBlock + s.C - 1) / s.C;   // blocks per channel
+    const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
+    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
+    // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
+    // waves takes a whole channel: no slices, no second stage.
+    p.wpb = dwconv::kWavesPerBlock;
+    p.single = false;
+    if (mfma_shape && s.C % kComputeUnits == 0 && s.C / kComputeUnits <= 3) {
+        const int wpb = 16 / (s.C / kComputeUnits);
+        if (items >= 2 * wpb) { p.wpb = wpb; p.single = true; }
+    }
+    long long want = (kTargetWaves / p.wpb + s.C - 1) / s.C;   // blocks per channel
+    if (p.single) want = 1;
     if (want < 1) want = 1;
     if (want > 65535) want = 65535;
-    long long spw = (items + want * dwconv::kWavesPerBlock - 1) / (want * dwconv::kWavesPerBlock);
+    long long spw = (items + want * p.wpb - 1) / (want * p.wpb);
     if (spw < 1) spw = 1;
-    const long long per = spw * dwconv::kWavesPerBlock;
+    const long long per = spw * p.wpb;
     p.segs_per_wave = (int)spw;
     p.items_per_slice = (int)per;
     p.S = (int)((items + per - 1) / per);
@@ -264,7 +278,6 @@ DwPlan plan_dw(const Shape &s)
     // long filters: offsets are split over waves instead, partials land in exactly two slices
     p.longk = false;
     p.lk_wgs = p.lk_gd = p.lk_groups = 0;
-    const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     const int NCH = (s.L + 63) / 64;
     if (nd > kMfmaMaxND && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
@@ -308,41 +321,62 @@ void launch_dw_partial_valu(const void *x, const void *dy, float *part, const Sh
                        s.L, s.K, s.pad, p.tiles_per_row, p.items_per_slice);
 }
 
-template <typename T, int ND>
-void launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, int dmin,
-                               hipStream_t st)
+// One stage-1 launch on the matrix cores.  dw_out != nullptr only for single-slice plans.
+template <typename T, int ND, int W>
+int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                               int dmin, hipStream_t st)
 {
     if constexpr (std::is_same<T, float>::value) {
         // fp32 rows go from memory straight into LDS
-        hipLaunchKernelGGL((dwconv::dw_partial_direct_kernel<ND>), dim3((unsigned)s.C, (unsigned)p.S),
-                           dim3(64 * dwconv::kWavesPerBlock), 0, st, static_cast<const float *>(x),
-                           static_cast<const float *>(dy), part, s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row,
-                           p.segs_per_wave);
+        auto kernel = dwconv::dw_partial_direct_kernel<ND, W>;
+        constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
+        static_assert(lds <= kMaxLdsBytes, "LDS budget");
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const float *>(x), static_cast<const float *>(dy), part,
+                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
     } else {
-        hipLaunchKernelGGL((dwconv::dw_partial_mfma_kernel<T, ND>), dim3((unsigned)s.C, (unsigned)p.S),
-                           dim3(64 * dwconv::kWavesPerBlock), 0, st, static_cast<const T *>(x),
-                           static_cast<const T *>(dy), part, s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row,
-                           p.segs_per_wave);
+        auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W>;
+        constexpr size_t lds = dwconv::dw_mfma_lds_bytes(ND, W);
+        static_assert(lds <= kMaxLdsBytes, "LDS budget");
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const T *>(x),
+                           static_cast<const T *>(dy), part, static_cast<T *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin,
+                           p.tiles_per_row);
+    }
+    return launch_status();
+}
+
+template <typename T, int ND>
+int launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                              int dmin, hipStream_t st)
+{
+    switch (p.wpb) {
+    case 4: return launch_dw_partial_mfma_ndw<T, ND, 4>(x, dy, part, dw_out, s, p, dmin, st);
+    case 5: return launch_dw_partial_mfma_ndw<T, ND, 5>(x, dy, part, dw_out, s, p, dmin, st);
+    case 8: return launch_dw_partial_mfma_ndw<T, ND, 8>(x, dy, part, dw_out, s, p, dmin, st);
+    case 16: return launch_dw_partial_mfma_ndw<T, ND, 16>(x, dy, part, dw_out, s, p, dmin, st);
+    default: return -1;
     }
 }
 
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
 template <typename T>
-int launch_dw_partial_mfma(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
+int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                           hipStream_t st)
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
     if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
     switch (nd) {
-    case 2: launch_dw_partial_mfma_nd<T, 2>(x, dy, part, s, p, dmin, st); break;
-    case 3: launch_dw_partial_mfma_nd<T, 3>(x, dy, part, s, p, dmin, st); break;
-    case 4: launch_dw_partial_mfma_nd<T, 4>(x, dy, part, s, p, dmin, st); break;
-    case 5: launch_dw_partial_mfma_nd<T, 5>(x, dy, part, s, p, dmin, st); break;
-    case 6: launch_dw_partial_mfma_nd<T, 6>(x, dy, part, s, p, dmin, st); break;
+    case 2: return launch_dw_partial_mfma_nd<T, 2>(x, dy, part, dw_out, s, p, dmin, st);
+    case 3: return launch_dw_partial_mfma_nd<T, 3>(x, dy, part, dw_out, s, p, dmin, st);
+    case 4: return launch_dw_partial_mfma_nd<T, 4>(x, dy, part, dw_out, s, p, dmin, st);
+    case 5: return launch_dw_partial_mfma_nd<T, 5>(x, dy, part, dw_out, s, p, dmin, st);
+    case 6: return launch_dw_partial_mfma_nd<T, 6>(x, dy, part, dw_out, s, p, dmin, st);
     default: return -1;
     }
-    return launch_status();
 }
 
 template <typename T, int GD>
@@ -392,14 +426,22 @@ int launch_dw_partial_longk(const void *x, const void *dy, float *part, const Sh
 }
 
 template <typename T>
-int launch_dw_partial(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
+int launch_dw_partial(const void *x, const void *dy, float *part, void *dw_out, bool *wrote_dw, const Shape &s,
+                      const DwPlan &p, hipStream_t st)
 {
+    // dw_out: where a single-slice matrix-core launch may put the gradient itself (nullptr: always write part);
+    // *wrote_dw tells the caller whether it did.
+    if (wrote_dw) *wrote_dw = false;
     if (p.longk) {
         const int rc = launch_dw_partial_longk<T>(x, dy, part, s, p, st);
         if (rc >= 0) return rc;
     }
-    const int rc = launch_dw_partial_mfma<T>(x, dy, part, s, p, st);
-    if (rc >= 0) return rc;
+    void *direct = (p.single && p.S == 1) ? dw_out : nullptr;
+    const int rc = launch_dw_partial_mfma<T>(x, dy, part, direct, s, p, st);
+    if (rc >= 0) {
+        if (wrote_dw && direct && rc == DWCONV_OK) *wrote_dw = true;
+        return rc;
+    }
     switch (p.kernel) {
     case DW_VALU_K8: launch_dw_partial_valu<T, 8>(x, dy, part, s, p, st); break;
     case DW_VALU_K32: launch_dw_partial_valu<T, 32>(x, dy, part, s, p, st); break;
@@ -455,8 +497,8 @@ int dwconv_bwd_weight_partial(const void *x, const void *dy, void *workspace, si
     if (rc != DWCONV_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(workspace);
-    if (dtype == DWCONV_F32) return launch_dw_partial<float>(x, dy, part, s, p, st);
-    return launch_dw_partial<bf16_t>(x, dy, part, s, p, st);
+    if (dtype == DWCONV_F32) return launch_dw_partial<float>(x, dy, part, nullptr, nullptr, s, p, st);
+    return launch_dw_partial<bf16_t>(x, dy, part, nullptr, nullptr, s, p, st);
 }
 
 int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw, int B, int C, int L, int K,
@@ -484,9 +526,26 @@ int dwconv_bwd_weight(const void *x, const void *dy, void *dw, void *workspace, 
     if (rc != DWCONV_OK) return rc;
     const size_t es = elem_size(dtype);
     if (!aligned_to(x, es) || !aligned_to(dy, es) || !aligned_to(dw, es)) return DWCONV_ERR_ALIGN;
-    rc = dwconv_bwd_weight_partial(x, dy, workspace, workspace_bytes, B, C, L, K, pad_left, dtype, stream);
+    const Shape s{B, C, L, K, pad_left, dtype};
+    const DwPlan p = plan_dw(s);
+    rc = check_workspace(workspace, workspace_bytes, s, p);
     if (rc != DWCONV_OK) return rc;
-    return dwconv_bwd_weight_finalize(workspace, workspace_bytes, dw, B, C, L, K, pad_left, dtype, stream);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *part = static_cast<float *>(workspace);
+    bool wrote_dw = false;
+    rc = (dtype == DWCONV_F32) ? launch_dw_partial<float>(x, dy, part, dw, &wrote_dw, s, p, st)
+                               : launch_dw_partial<bf16_t>(x, dy, part, dw, &wrote_dw, s, p, st);
+    if (rc != DWCONV_OK || wrote_dw) return rc;
+    if (dtype == DWCONV_F32) return launch_dw_finalize<float>(part, dw, s, p, st);
+    return launch_dw_finalize<bf16_t>(part, dw, s, p, st);
+}
+
+int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype)
+{
+    if (check_dw_shape(B, C, L, K, pad_left, dtype) != DWCONV_OK) return 0;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    const DwPlan p = plan_dw(s);
+    return (p.single && p.S == 1 && !p.longk) ? 1 : 0;
 }
 
 int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype)

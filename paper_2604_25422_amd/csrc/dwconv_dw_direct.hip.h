@@ -89,10 +89,20 @@ struct DirectSchedule {
 
 constexpr int kDirectSlackFloats = 256;   // x4 writes a full 1 KiB: the tail of the window, then zeros
 
-template <int ND>
-__global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_partial_direct_kernel(
-    const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, int B, int C, int L, int K,
-    int pad, int dmin, int segs_per_row, int segs_per_wave)
+// Per-wave LDS region (floats) and dynamic LDS bytes of a block of W waves.
+constexpr int dw_direct_wave_floats(int ND)
+{
+    const int stage = 5 * 256 + kSegLen, gf = ND * 256;
+    return stage > gf ? stage : gf;
+}
+constexpr size_t dw_direct_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_direct_wave_floats(ND) + 16 * ND) * sizeof(float); }
+
+// W waves per block.  dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (one
+// block per channel, gridDim.y == 1) they are the weight gradient itself and go to dw_out.
+template <int ND, int W>
+__global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_kernel(
+    const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row)
 {
     constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
     constexpr int NGX = XW / 4;                    // its 16-byte granules: 4 full loads and a tail
@@ -103,15 +113,17 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
     constexpr int GF = ND * 256;                   // floats of one wave's G
     constexpr int STAGE = XREG + kSegLen;
     constexpr int WREG = STAGE > GF ? STAGE : GF;  // per-wave LDS region
-    __shared__ __align__(16) float s_mem[kWavesPerBlock][WREG];
-    __shared__ float s_dw[kWavesPerBlock][16 * ND];
+    static_assert(WREG == dw_direct_wave_floats(ND), "host and kernel agree on the LDS layout");
+    extern __shared__ __align__(16) float dyn_lds[];
+    float (*s_mem)[WREG] = reinterpret_cast<float (*)[WREG]>(dyn_lds);
+    float (*s_dw)[16 * ND] = reinterpret_cast<float (*)[16 * ND]>(dyn_lds + W * WREG);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int c = blockIdx.x;
-    const int stride = (int)gridDim.y * kWavesPerBlock;
-    const int ws = (int)blockIdx.y * kWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    const int stride = (int)gridDim.y * W;
+    const int ws = (int)blockIdx.y * W + __builtin_amdgcn_readfirstlane(wave);
     const int step_b = stride / segs_per_row, step_seg = stride % segs_per_row;
     int b = ws / segs_per_row, seg = ws % segs_per_row;
     float *sx = s_mem[wave];            // sx[i] = x~[t0 + 16 dmin + i]
@@ -219,15 +231,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     wave_lds_fence();
 
-    // ---- per-wave diagonal sums, then the four waves in wave order
+    // ---- per-wave diagonal sums, then the waves of the block in wave order
     static_assert(WREG >= ((16 * ND + 15) * 17 + 3) / 4 * 4, "diagonal image fits the wave's region");
     dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, K, pad, dmin);
     __syncthreads();
-    for (int j = tid; j < K; j += 64 * kWavesPerBlock) {
+    for (int j = tid; j < K; j += 64 * W) {
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWavesPerBlock; ++w) sum += s_dw[w][j];
-        part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
+        for (int w = 0; w < W; ++w) sum += s_dw[w][j];
+        if (dw_out) dw_out[(size_t)c * (size_t)K + (size_t)j] = sum;
+        else part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
     }
 }
 

@@ -472,16 +472,25 @@ __device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], fl
 
 // Stage 1 of the weight gradient on the matrix cores.
 // grid = (C, S).  The segments of a channel are ordered (b, seg); wave w of slice s takes segments
-// 4 s + w, 4 s + w + 4 S, ...  A wave keeps ND 16x16
+// W s + w, W s + w + W S, ...  A wave keeps ND 16x16
 // accumulators G_d for its whole life.  Per segment: the loads of the next segment are issued,
 // the current one is contracted out of the wave's private LDS region (x window with halo, then
 // dY; both operands of a 64-position chunk are 64 consecutive floats), then the prefetch
 // registers are drained into LDS.  At the end every wave sums the diagonals of its own G_d, and
-// the four per-wave results are added in wave order.
-template <typename T, int ND>
-__global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_partial_mfma_kernel(
-    const T *__restrict__ x, const T *__restrict__ dy, float *__restrict__ part, int B, int C, int L, int K, int pad,
-    int dmin, int segs_per_row, int segs_per_wave)
+// the W per-wave results are added in wave order.
+constexpr int dw_mfma_wave_floats(int ND)
+{
+    const int stage = kSegLen + 16 * ND + kSegLen, gf = ND * 256;
+    return stage > gf ? stage : gf;
+}
+constexpr size_t dw_mfma_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_mfma_wave_floats(ND) + 16 * ND) * sizeof(float); }
+
+// W waves per block.  dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (one
+// block per channel, gridDim.y == 1) they are the weight gradient itself and go to dw_out.
+template <typename T, int ND, int W>
+__global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_mfma_kernel(
+    const T *__restrict__ x, const T *__restrict__ dy, float *__restrict__ part, T *__restrict__ dw_out, int B, int C,
+    int L, int K, int pad, int dmin, int segs_per_row)
 {
     constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
     constexpr int NGX = XW / 4;
@@ -491,8 +500,10 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
     constexpr int GF = ND * 256;                   // floats of one wave's G
     constexpr int STAGE = XW + kSegLen;
     constexpr int WREG = STAGE > GF ? STAGE : GF;  // per-wave LDS region
-    __shared__ __align__(16) float s_mem[kWavesPerBlock][WREG];
-    __shared__ float s_dw[kWavesPerBlock][16 * ND];
+    static_assert(WREG == dw_mfma_wave_floats(ND), "host and kernel agree on the LDS layout");
+    extern __shared__ __align__(16) float dyn_lds[];
+    float (*s_mem)[WREG] = reinterpret_cast<float (*)[WREG]>(dyn_lds);
+    float (*s_dw)[16 * ND] = reinterpret_cast<float (*)[16 * ND]>(dyn_lds + W * WREG);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -501,8 +512,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
     // wave-slice ws of the channel walks segments ws, ws + stride, ...: at any moment the chip reads
     // whole rows of a few batches, contiguous over the channels.  (b, seg) are wave-uniform and
     // advanced without divisions.
-    const int stride = (int)gridDim.y * kWavesPerBlock;
-    const int ws = (int)blockIdx.y * kWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    const int stride = (int)gridDim.y * W;
+    const int ws = (int)blockIdx.y * W + __builtin_amdgcn_readfirstlane(wave);
     const int step_b = stride / segs_per_row, step_seg = stride % segs_per_row;
     int b = ws / segs_per_row, seg = ws % segs_per_row;
     int b_n, seg_n;
@@ -589,15 +600,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock, kMfmaWavesPerSimd) void dw_par
         b = b_n; seg = seg_n;
     }
 
-    // ---- per-wave diagonal sums, then the four waves in wave order
+    // ---- per-wave diagonal sums, then the waves of the block in wave order
     static_assert(WREG >= ((16 * ND + 15) * 17 + 3) / 4 * 4, "diagonal image fits the wave's region");
     dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, K, pad, dmin);
     __syncthreads();
-    for (int j = tid; j < K; j += 64 * kWavesPerBlock) {
+    for (int j = tid; j < K; j += 64 * W) {
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWavesPerBlock; ++w) sum += s_dw[w][j];
-        part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
+        for (int w = 0; w < W; ++w) sum += s_dw[w][j];
+        if (dw_out) st_elem(dw_out + (size_t)c * (size_t)K + (size_t)j, sum);
+        else part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
     }
 }
 

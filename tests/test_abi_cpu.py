@@ -92,6 +92,19 @@ def test_workspace_query_rejects_bad_shapes(lib):
         assert S >= 1 and n >= S * C * K * 4 and n % 16 == 0
 
 
+def test_single_pass_query(lib):
+    # whole-channel workgroups: C a small multiple of the 256 compute units, enough segments per wave
+    f = lib.dwconv_bwd_weight_single_pass
+    assert f(32, 256, 4096, 64, 63, 0) == 1 and lib.dwconv_bwd_weight_slices(32, 256, 4096, 64, 63, 0) == 1
+    assert f(64, 512, 2048, 7, 3, 0) == 1
+    assert f(128, 768, 1024, 32, 31, 1) == 1
+    assert f(4, 64, 1024, 16, 15, 0) == 0            # channels do not fill the chip
+    assert f(8, 256, 8192, 8192, 8191, 0) == 0       # long filter: two zero-filled slices
+    assert f(1, 256, 1024, 16, 15, 0) == 0           # a single segment per channel
+    assert f(32, 256, 4098, 64, 63, 0) == 0          # row length not a multiple of 4
+    assert f(0, 256, 4096, 64, 63, 0) == 0           # bad shape
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     from paper_2604_25422_amd import binding

@@ -109,3 +109,30 @@ def test_runs_on_a_non_default_stream(oracle_mod):
     r, ra = oracle_mod.fwd(x.numpy(), w.numpy(), p)
     e, _ = normalised_error(y.cpu().numpy(), r, ra)
     assert e <= 1e-5
+
+
+# One workgroup per channel (C = 256, 512, 768 with enough segments per wave): the weight gradient is a single
+# kernel that writes dw itself.  Ragged last segments, rows of one segment, fp32 and bf16.
+SINGLE = [
+    (8, 256, 4096, 16, 15, "f32"), (9, 256, 3900, 64, 63, "f32"), (33, 256, 1000, 33, 16, "f32"),
+    (4, 512, 4096, 7, 3, "f32"), (17, 512, 1028, 48, 24, "f32"),
+    (10, 768, 1024, 32, 31, "bf16"), (11, 768, 1032, 20, 0, "f32"), (40, 256, 1024, 64, 63, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,C,L,K,p,dtype", SINGLE)
+def test_single_kernel_weight_gradient(oracle_mod, B, C, L, K, p, dtype):
+    from paper_2604_25422_amd import binding
+    print(f"case single {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    code = binding.F32 if dtype == "f32" else binding.BF16
+    assert binding.dwconv_bwd_weight_single_pass(B, C, L, K, p, code)
+    check_case(oracle_mod, B, C, L, K, p, dtype, seed=11)
+    # the two-stage entry points give the same bits (one slice, copied by stage 2)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = seeded((B, C, L), 1011, tdt).cuda(); dy = seeded((B, C, L), 3011, tdt).cuda()
+    one = binding.dwconv_bwd_weight(x, dy, K, p)
+    ws = binding.dwconv_bwd_weight_partial(x, dy, K, p)
+    two = binding.dwconv_bwd_weight_finalize(ws, B, C, L, K, p, tdt)
+    again = binding.dwconv_bwd_weight(x, dy, K, p)
+    torch.cuda.synchronize()
+    assert torch.equal(one, two) and torch.equal(one, again)
