@@ -532,7 +532,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_mfma_ker
 
     float4 pre_x[NLX], pre_g[NLG];
     auto prefetch = [&](int pb, int pseg) {
-        const size_t row = ((size_t)pb * (size_t)C + (size_t)c) * (size_t)L;
+        // batches are walked from the last to the first: the input-gradient call that usually runs just before
+        // this one walks them upwards, so its last rows of dY are still in the last-level cache
+        const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
         const int t0 = pseg * kSegLen;
         const int u0 = t0 + 16 * dmin;
 #pragma unroll
