@@ -115,6 +115,23 @@ int dwconv_bwd_weight_partial(const void *x, const void *dy,
 int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw,
                                int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
+/*
+ * Both gradients of the backward pass in one call: dx as dwconv_bwd_input, dw as dwconv_bwd_weight.
+ * The paper names kernel fusion as the remaining lever for the backward path (Sec. VI): for fp32 tensors
+ * and filters of the register-resident class (dwconv_bwd_is_fused(...) == 1, 16-byte aligned tensors) one
+ * kernel reads dy once and produces dx and the stage-1 sums of dw (5 tensor passes over memory per
+ * forward + backward step instead of 6); every other shape or type runs the two separate paths one after the
+ * other.  dy, x [B,C,L] in; w [C,K] in; dx [B,C,L] out; dw [C,K] out; workspace as for dwconv_bwd_weight.
+ * dx must not alias dy or x.  Results: dx equals dwconv_bwd_input's bit for bit; dw is a fixed-order sum like
+ * dwconv_bwd_weight's (same tolerance, run-to-run identical).
+ */
+int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw,
+               void *workspace, size_t workspace_bytes,
+               int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/* 1 when dwconv_bwd runs the fused kernel for this shape (given 16-byte aligned tensors); 0 otherwise. */
+int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype);
+
 /* Number S of partial slices per coefficient stage 1 writes for this shape; 0 on bad arguments. */
 int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype);
 

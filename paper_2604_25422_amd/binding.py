@@ -22,7 +22,7 @@ _lib = None
 SYMBOLS = (
     "dwconv_fwd", "dwconv_bwd_input", "dwconv_bwd_weight", "dwconv_bwd_weight_partial",
     "dwconv_bwd_weight_finalize", "dwconv_bwd_weight_slices", "dwconv_bwd_weight_single_pass",
-    "dwconv_bwd_weight_workspace_bytes",
+    "dwconv_bwd_weight_workspace_bytes", "dwconv_bwd", "dwconv_bwd_is_fused",
     "dwconv_status_string", "dwconv_version",
 )
 
@@ -54,6 +54,10 @@ def lib():
             getattr(l, n).restype = i
         l.dwconv_bwd_weight_slices.argtypes = shape
         l.dwconv_bwd_weight_slices.restype = i
+        l.dwconv_bwd.argtypes = [vp, vp, vp, vp, vp, vp, sz] + shape + [vp]
+        l.dwconv_bwd.restype = i
+        l.dwconv_bwd_is_fused.argtypes = shape
+        l.dwconv_bwd_is_fused.restype = i
         l.dwconv_bwd_weight_single_pass.argtypes = shape
         l.dwconv_bwd_weight_single_pass.restype = i
         l.dwconv_bwd_weight_workspace_bytes.argtypes = shape
@@ -170,6 +174,25 @@ def dwconv_bwd_weight(x, dy, K: int, pad_left: int, workspace=None, out=None) ->
     _check(lib().dwconv_bwd_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), workspace.data_ptr(), nbytes,
                                    B, C, L, int(K), int(pad_left), _dtype_code(x), _stream()))
     return dw
+
+
+def dwconv_bwd(dy, x, w, pad_left: int, workspace=None, out_dx=None, out_dw=None):
+    """Both gradients in one call (fused kernel where it applies): returns (dx, dw)."""
+    K = int(w.shape[1])
+    workspace, nbytes = _dw_args(x, dy, K, pad_left, workspace)
+    B, C, L = x.shape
+    wd = _dev2(w, "w", C)
+    dx = torch.empty_like(dy) if out_dx is None else out_dx
+    dw = torch.empty((C, K), dtype=x.dtype, device=x.device) if out_dw is None else _dev2(out_dw, "out_dw", C)
+    if dx.shape != dy.shape or dx.dtype != dy.dtype or not dx.is_cuda or not dx.is_contiguous():
+        raise ValueError("out_dx must be a contiguous device tensor shaped and typed like dy")
+    _check(lib().dwconv_bwd(dy.data_ptr(), x.data_ptr(), wd.data_ptr(), dx.data_ptr(), dw.data_ptr(),
+                            workspace.data_ptr(), nbytes, B, C, L, K, int(pad_left), _dtype_code(x), _stream()))
+    return dx, dw
+
+
+def dwconv_bwd_is_fused(B, C, L, K, pad_left, dtype_code) -> bool:
+    return bool(lib().dwconv_bwd_is_fused(B, C, L, K, pad_left, dtype_code))
 
 
 def dwconv_bwd_weight_partial(x, dy, K: int, pad_left: int, workspace=None) -> torch.Tensor:

@@ -10,6 +10,7 @@
 #include <mutex>
 #include <type_traits>
 
+#include "dwconv_bwd_fused.hip.h"
 #include "dwconv_common.hip.h"
 #include "dwconv_dw_direct.hip.h"
 #include "dwconv_longk.hip.h"
@@ -451,6 +452,57 @@ int launch_dw_partial(const void *x, const void *dy, float *part, void *dw_out, 
     return launch_status();
 }
 
+// Fused input + weight gradient (fp32, matrix-core shape class).  Returns -1 when it does not apply.
+template <int ND, int W>
+int launch_bwd_fused_ndw(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,
+                         const Shape &s, const DwPlan &p, int dmin, hipStream_t st)
+{
+    auto kernel = dwconv::bwd_fused_kernel<ND, W>;
+    constexpr size_t lds = dwconv::bwd_fused_lds_bytes(ND, W);
+    static_assert(lds <= kMaxLdsBytes, "LDS budget");
+    if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const float *>(dy),
+                       static_cast<const float *>(x), static_cast<const float *>(w), static_cast<float *>(dx), part,
+                       static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+    return launch_status();
+}
+
+template <int ND>
+int launch_bwd_fused_nd(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,
+                        const Shape &s, const DwPlan &p, int dmin, hipStream_t st)
+{
+    switch (p.wpb) {
+    case 4: return launch_bwd_fused_ndw<ND, 4>(dy, x, w, dx, part, dw_out, s, p, dmin, st);
+    case 5: return launch_bwd_fused_ndw<ND, 5>(dy, x, w, dx, part, dw_out, s, p, dmin, st);
+    case 8: return launch_bwd_fused_ndw<ND, 8>(dy, x, w, dx, part, dw_out, s, p, dmin, st);
+    case 16: return launch_bwd_fused_ndw<ND, 16>(dy, x, w, dx, part, dw_out, s, p, dmin, st);
+    default: return -1;
+    }
+}
+
+int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
+                     const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    *wrote_dw = false;
+    if (s.dtype != DWCONV_F32 || p.longk) return -1;
+    const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
+    const int nd = dmax - dmin + 1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
+    if (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)) return -1;
+    void *direct = (p.single && p.S == 1) ? dw_out : nullptr;
+    int rc = -1;
+    switch (nd) {
+    case 2: rc = launch_bwd_fused_nd<2>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
+    case 3: rc = launch_bwd_fused_nd<3>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
+    case 4: rc = launch_bwd_fused_nd<4>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
+    case 5: rc = launch_bwd_fused_nd<5>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
+    case 6: rc = launch_bwd_fused_nd<6>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
+    default: break;
+    }
+    if (rc == DWCONV_OK && direct) *wrote_dw = true;
+    return rc;
+}
+
 template <typename T>
 int launch_dw_finalize(const float *part, void *dw, const Shape &s, const DwPlan &p, hipStream_t st)
 {
@@ -538,6 +590,43 @@ int dwconv_bwd_weight(const void *x, const void *dy, void *dw, void *workspace, 
     if (rc != DWCONV_OK || wrote_dw) return rc;
     if (dtype == DWCONV_F32) return launch_dw_finalize<float>(part, dw, s, p, st);
     return launch_dw_finalize<bf16_t>(part, dw, s, p, st);
+}
+
+int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, void *workspace,
+               size_t workspace_bytes, int B, int C, int L, int K, int pad_left, int dtype, void *stream)
+{
+    if (!dy || !x || !w || !dx || !dw) return DWCONV_ERR_NULL;
+    int rc = check_dw_shape(B, C, L, K, pad_left, dtype);
+    if (rc != DWCONV_OK) return rc;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(dy, es) || !aligned_to(x, es) || !aligned_to(w, es) || !aligned_to(dx, es) || !aligned_to(dw, es))
+        return DWCONV_ERR_ALIGN;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    const DwPlan p = plan_dw(s);
+    rc = check_workspace(workspace, workspace_bytes, s, p);
+    if (rc != DWCONV_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *part = static_cast<float *>(workspace);
+    bool wrote_dw = false;
+    rc = launch_bwd_fused(dy, x, w, dx, part, dw, &wrote_dw, s, p, st);
+    if (rc >= 0) {
+        if (rc != DWCONV_OK || wrote_dw) return rc;
+        return launch_dw_finalize<float>(part, dw, s, p, st);
+    }
+    // shapes and types the fused kernel does not take: the two gradients one after the other
+    rc = dwconv_bwd_input(dy, w, dx, B, C, L, K, pad_left, dtype, stream);
+    if (rc != DWCONV_OK) return rc;
+    return dwconv_bwd_weight(x, dy, dw, workspace, workspace_bytes, B, C, L, K, pad_left, dtype, stream);
+}
+
+int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
+{
+    if (check_dw_shape(B, C, L, K, pad_left, dtype) != DWCONV_OK) return 0;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    const DwPlan p = plan_dw(s);
+    const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
+    return (dtype == DWCONV_F32 && !p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % 4) == 0 &&
+            L <= kMfmaMaxL) ? 1 : 0;
 }
 
 int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype)

@@ -136,3 +136,42 @@ def test_single_kernel_weight_gradient(oracle_mod, B, C, L, K, p, dtype):
     again = binding.dwconv_bwd_weight(x, dy, K, p)
     torch.cuda.synchronize()
     assert torch.equal(one, two) and torch.equal(one, again)
+
+
+# Fused backward call: dx and dw from one pass over dy (fp32, register-resident filters), the two separate paths
+# for everything else.  (B, C, L, K, pad_left, dtype, fused?)
+BWD = [
+    (2, 3, 600, 64, 63, "f32", True), (1, 2, 4100, 64, 32, "f32", True), (3, 7, 336, 31, 30, "f32", True),
+    (2, 3, 100, 5, 0, "f32", True), (2, 3, 100, 5, 4, "f32", True), (1, 4, 1024, 16, 15, "f32", True),
+    (2, 4, 1028, 16, 8, "f32", True), (2, 2, 48, 48, 24, "f32", True), (5, 3, 48, 48, 0, "f32", True),
+    (2, 2, 2060, 64, 63, "f32", True), (1, 5, 44, 7, 3, "f32", True), (4, 16, 4096, 64, 63, "f32", True),
+    (3, 2, 2048, 66, 65, "f32", True), (2, 2, 3072, 66, 0, "f32", True), (2, 3, 2052, 40, 20, "f32", True),
+    (9, 256, 3900, 64, 63, "f32", True), (4, 512, 4096, 7, 3, "f32", True), (11, 768, 1032, 20, 0, "f32", True),
+    (2, 5, 257, 7, 3, "f32", False), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", False),
+    (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", False),
+]
+
+
+@pytest.mark.parametrize("B,C,L,K,p,dtype,fused", BWD)
+def test_fused_backward(oracle_mod, B, C, L, K, p, dtype, fused):
+    from paper_2604_25422_amd import binding
+    from paper_2604_25422_amd.roofline import normalised_error
+    from paper_2604_25422_amd.workloads import as_f32_numpy
+    print(f"case bwd {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    code = binding.F32 if dtype == "f32" else binding.BF16
+    assert binding.dwconv_bwd_is_fused(B, C, L, K, p, code) == fused
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = seeded((B, C, L), 1021, tdt); w = seeded((C, K), 2021, tdt); dy = seeded((B, C, L), 3021, tdt)
+    xd, wd, dyd = x.cuda(), w.cuda(), dy.cuda()
+    dx, dw = binding.dwconv_bwd(dyd, xd, wd, p)
+    dx_sep = binding.dwconv_bwd_input(dyd, wd, p)
+    dx2, dw2 = binding.dwconv_bwd(dyd, xd, wd, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx_sep), "fused dx differs from the separate input-gradient path"
+    assert torch.equal(dx, dx2) and torch.equal(dw, dw2), "not run-to-run identical"
+    xn, wn, dyn = as_f32_numpy(x), as_f32_numpy(w), as_f32_numpy(dy)
+    for name, got, (ref, ra) in (("dx", dx, oracle_mod.bwd_input(dyn, wn, p)), ("dw", dw, oracle_mod.bwd_weight(xn, dyn, K, p))):
+        g = got.float().cpu().numpy().astype(np.float64)
+        e, i = normalised_error(g, ref, ra)
+        assert e <= TOL[(dtype, name)], f"{name}: err {e:.3e} at flat index {i}: gpu {g.ravel()[i]!r} oracle {ref.ravel()[i]!r}"
+        assert np.all(g[ra == 0] == 0)
