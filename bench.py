@@ -152,6 +152,34 @@ def main():
     if single:
         us["dw_finalize"] = 0.0          # no second stage: "dw_partial" is the whole weight-gradient kernel
 
+    # the same step with the fused backward call (reads dY once: 5 tensor passes instead of 6); reported beside
+    # the headline number against its own algorithmic bytes, never as `value`
+    fused = None
+    if binding.dwconv_bwd_is_fused(wl.B, wl.C, wl.L, K, p, code):
+        def step_fused(s, ev=None):
+            if ev: ev[0].record()
+            binding.dwconv_fwd(s["x"], s["w"], p, out=s["y"])
+            if ev: ev[1].record()
+            binding.dwconv_bwd(s["dy"], s["x"], s["w"], p, workspace=s["ws"], out_dx=s["dx"], out_dw=s["dw"])
+            if ev: ev[2].record()
+        for i in range(args.warmup):
+            step_fused(sets[i % args.sets])
+        torch.cuda.synchronize()
+        f0 = torch.cuda.Event(enable_timing=True); f1 = torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for i in range(args.steps):
+            step_fused(sets[i % args.sets])
+        f1.record()
+        torch.cuda.synchronize()
+        fused_ms = f0.elapsed_time(f1) / args.steps
+        fevs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            step_fused(sets[i % args.sets], fevs[i])
+        torch.cuda.synchronize()
+        fused = {"us_per_step": round(fused_ms * 1e3, 2),
+                 "fwd_us": round(1e3 * sum(e[0].elapsed_time(e[1]) for e in fevs) / args.steps, 2),
+                 "bwd_us": round(1e3 * sum(e[1].elapsed_time(e[2]) for e in fevs) / args.steps, 2)}
+
     es = wl.elem_size
     step_bytes = algorithmic_bytes(wl.B, wl.C, wl.L, K, es, "step")
     path_bytes = algorithmic_bytes(wl.B, wl.C, wl.L, K, es, "fwd")
@@ -193,6 +221,17 @@ def main():
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_F32_PEAK_TFLOPS,
                            "unit": "TFLOP/s", "frac": round(mfma_frac, 4), "traffic": traffic,
                            "kernel_us": round(us[dom], 2), "algorithmic_flops": flops}
+    if fused:
+        n_elems = wl.B * wl.C * wl.L
+        fused_step_bytes = (5 * n_elems + 3 * wl.C * K) * es        # fwd 2N + CK, fused backward 3N + 2CK
+        fused_bwd_bytes = (3 * n_elems + 2 * wl.C * K) * es
+        fused["step_algorithmic_bytes"] = fused_step_bytes
+        fused["step_gbps"] = round(fused_step_bytes / (fused["us_per_step"] * 1e-6) / 1e9, 1)
+        fused["bwd_gbps"] = round(fused_bwd_bytes / (fused["bwd_us"] * 1e-6) / 1e9, 1)
+        fused["bwd_frac_of_hbm_peak"] = round(fused["bwd_gbps"] / HBM_PEAK_GBPS, 4)
+        fused["speedup_vs_three_calls"] = round(ms_per_step * 1e3 / fused["us_per_step"], 3)
+        fused["bwd_traffic"] = measured_traffic(args.workload, "bwd_fused")
+        out["fused_backward"] = fused
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, inputs)
     print(json.dumps(out), flush=True)
