@@ -12,6 +12,7 @@
 
 #include "dwconv_bwd_fused.hip.h"
 #include "dwconv_common.hip.h"
+#include "dwconv_dw_bf16.hip.h"
 #include "dwconv_dw_direct.hip.h"
 #include "dwconv_longk.hip.h"
 #include "dwconv_mfma.hip.h"
@@ -336,6 +337,15 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                            static_cast<const float *>(x), static_cast<const float *>(dy), part,
                            static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+    } else if ((s.L % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
+        // bf16 rows of whole 16-byte granules: raw rows straight into LDS, bf16 matrix instruction
+        auto kernel = dwconv::dw_partial_bf16_kernel<ND, W>;
+        constexpr size_t lds = dwconv::dw_bf16_lds_bytes(ND, W);
+        static_assert(lds <= kMaxLdsBytes, "LDS budget");
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part,
+                           static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
     } else {
         auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W>;
         constexpr size_t lds = dwconv::dw_mfma_lds_bytes(ND, W);
