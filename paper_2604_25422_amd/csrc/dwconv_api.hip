@@ -60,6 +60,34 @@ constexpr int kMfmaMaxND = 6;
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
+// Short rows (see dwconv::RowsMap): whether the matrix-core kernels should walk the virtual row of a channel, and
+// its geometry.  Depends on the shape only; the gap is the same for the forward and the input-gradient pads.
+struct RowsPlan {
+    bool on;
+    int nvs;                // 1024-position segments of the virtual row
+    dwconv::RowsMap map;
+};
+RowsPlan plan_rows(const Shape &s)
+{
+    RowsPlan r;
+    r.on = false; r.nvs = 0;
+    r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
+    const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
+    if (s.dtype != DWCONV_F32 || s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return r;
+    const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
+    const long long P = s.L + (halo + 3) / 4 * 4;
+    const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
+    if (4 * padded <= 5 * P) return r;                       // ordinary segments waste less than a quarter
+    const long long elems = (long long)s.B * s.C * s.L;
+    if (elems * 4 > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) return r;
+    r.on = true;
+    r.nvs = (int)(((long long)s.B * P + dwconv::kSegLen - 1) / dwconv::kSegLen);
+    r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
+    r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
+    r.map.bytes = (unsigned)(elems * 4);
+    return r;
+}
+
 template <typename T>
 int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
@@ -239,9 +267,11 @@ struct DwPlan {
     bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
     int lk_wgs, lk_gd, lk_groups;   // its workgroups per channel, offsets per group, number of groups
     int S;                 // partial slices per coefficient
+    RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
     int wpb;               // waves per block of the matrix-core stage-1 kernels
     bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
-    int tiles_per_row;     // segments (tiles of kDwTT positions) along L
+    int tiles_per_row;     // segments the matrix-core kernels walk per row (per virtual row for short rows)
+    int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel (always real rows)
     int segs_per_wave;     // consecutive (b, segment) items a wave of the matrix-core kernel walks
     int items_per_slice;   // (b, segment) items each slice owns = 4 * segs_per_wave
 };
@@ -254,8 +284,9 @@ DwPlan plan_dw(const Shape &s)
 {
     DwPlan p;
     p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
-    const long long tiles = ((long long)s.L + kDwTT - 1) / kDwTT;
-    const long long items = (long long)s.B * tiles;                  // per channel
+    p.rows = plan_rows(s);
+    const long long tiles = p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
+    const long long items = p.rows.on ? tiles : (long long)s.B * tiles;                  // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
@@ -277,6 +308,12 @@ DwPlan plan_dw(const Shape &s)
     p.items_per_slice = (int)per;
     p.S = (int)((items + per - 1) / per);
     p.tiles_per_row = (int)tiles;
+    {
+        const long long real_tiles = ((long long)s.L + kDwTT - 1) / kDwTT;
+        const long long real_items = (long long)s.B * real_tiles;
+        p.valu_tiles_per_row = (int)real_tiles;
+        p.valu_items_per_slice = (int)((real_items + p.S - 1) / p.S);
+    }
     // long filters: offsets are split over waves instead, partials land in exactly two slices
     p.longk = false;
     p.lk_wgs = p.lk_gd = p.lk_groups = 0;
@@ -295,6 +332,7 @@ DwPlan plan_dw(const Shape &s)
         p.longk = true;
         p.S = 2;
         p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
+        p.valu_items_per_slice = p.items_per_slice;
     }
     return p;
 }
@@ -320,7 +358,7 @@ void launch_dw_partial_valu(const void *x, const void *dy, float *part, const Sh
 {
     hipLaunchKernelGGL((dwconv::dw_partial_valu_kernel<T, kDwThreads, kDwTT, KCH>), dim3((unsigned)s.C, (unsigned)p.S),
                        dim3(kDwThreads), 0, st, static_cast<const T *>(x), static_cast<const T *>(dy), part, s.B, s.C,
-                       s.L, s.K, s.pad, p.tiles_per_row, p.items_per_slice);
+                       s.L, s.K, s.pad, p.valu_tiles_per_row, p.valu_items_per_slice);
 }
 
 // One stage-1 launch on the matrix cores.  dw_out != nullptr only for single-slice plans.
@@ -330,13 +368,21 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
 {
     if constexpr (std::is_same<T, float>::value) {
         // fp32 rows go from memory straight into LDS
-        auto kernel = dwconv::dw_partial_direct_kernel<ND, W>;
         constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
-        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
-                           static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+        if (p.rows.on) {
+            auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
+            if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                               static_cast<const float *>(x), static_cast<const float *>(dy), part,
+                               static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
+        } else {
+            auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
+            if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                               static_cast<const float *>(x), static_cast<const float *>(dy), part,
+                               static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
+        }
     } else if ((s.L % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
         // bf16 rows of whole 16-byte granules: raw rows straight into LDS, bf16 matrix instruction
         auto kernel = dwconv::dw_partial_bf16_kernel<ND, W>;
@@ -467,13 +513,23 @@ template <int ND, int W>
 int launch_bwd_fused_ndw(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,
                          const Shape &s, const DwPlan &p, int dmin, hipStream_t st)
 {
-    auto kernel = dwconv::bwd_fused_kernel<ND, W>;
     constexpr size_t lds = dwconv::bwd_fused_lds_bytes(ND, W);
     static_assert(lds <= kMaxLdsBytes, "LDS budget");
-    if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const float *>(dy),
-                       static_cast<const float *>(x), static_cast<const float *>(w), static_cast<float *>(dx), part,
-                       static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+    if (p.rows.on) {
+        auto kernel = dwconv::bwd_fused_kernel<ND, W, true>;
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const float *>(dy), static_cast<const float *>(x), static_cast<const float *>(w),
+                           static_cast<float *>(dx), part, static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin,
+                           p.tiles_per_row, p.rows.map);
+    } else {
+        auto kernel = dwconv::bwd_fused_kernel<ND, W, false>;
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const float *>(dy), static_cast<const float *>(x), static_cast<const float *>(w),
+                           static_cast<float *>(dx), part, static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin,
+                           p.tiles_per_row, p.rows.map);
+    }
     return launch_status();
 }
 

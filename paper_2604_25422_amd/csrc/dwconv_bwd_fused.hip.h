@@ -49,11 +49,13 @@ __device__ __forceinline__ constexpr int swz_pos(int f)
     return 16 * nb + 4 * (g ^ ((nb >> 1) & 3)) + e;
 }
 
-template <int ND, int W>
+// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap); B is then 1 and segs_per_row the
+// number of segments of the virtual row.
+template <int ND, int W, bool ROWS>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
     const float *__restrict__ dy, const float *__restrict__ x, const float *__restrict__ f, float *__restrict__ dx,
     float *__restrict__ part, float *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin,
-    int segs_per_row)
+    int segs_per_row, const RowsMap rm)
 {
     static_assert(ND >= 2 && 16 * ND <= 128, "window tails are two 64-float loads");
     constexpr int XW = kSegLen + 16 * ND;          // floats of either window that are ever read
@@ -104,18 +106,17 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
 #pragma unroll
     for (int h = 0; h < 2; ++h) gw[h] = sg + swz_pos(64 * h + lane - 16 * dmin_x) - 64 * h;
     const float *xw = sx + lane;
-    // byte offsets of the loads inside the windows (memory side)
-    const int off_x = 16 * lane;                                                        // plain granule order
-    const int off_g = 16 * (4 * (lane >> 2) + ((lane & 3) ^ ((lane >> 3) & 3)));        // granule that belongs in slot `lane`
-    int off_xt[2], off_gt[2];
+    // offsets of the loads inside the windows (memory side), in floats
+    const int fo_x = 4 * lane;                                                          // plain granule order
+    const int fo_g = 4 * (4 * (lane >> 2) + ((lane & 3) ^ ((lane >> 3) & 3)));          // granule that belongs in slot `lane`
+    int fo_xt[2], fo_gt[2];     // tails: the logical float that belongs in LDS float slot 1024 + 64 h + lane (-1: none)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int fx = kSegLen + 64 * h + lane;                     // LDS float slot = logical float of the x window
-        off_xt[h] = fx < XW ? 4 * fx : kOutOfRow;
-        const int slot = kSegLen + 64 * h + lane;                   // LDS float slot of the dY window
+        const int slot = kSegLen + 64 * h + lane;
+        fo_xt[h] = slot < XW ? slot : -1;
         const int nb = slot >> 4, gp = (slot >> 2) & 3, e = slot & 3;
-        const int fg = 16 * nb + 4 * (gp ^ ((nb >> 1) & 3)) + e;    // the logical float that belongs there
-        off_gt[h] = fg < XW ? 4 * fg : kOutOfRow;
+        const int fg = 16 * nb + 4 * (gp ^ ((nb >> 1) & 3)) + e;
+        fo_gt[h] = fg < XW ? fg : -1;
     }
 
     floatx4 G[ND];
@@ -125,15 +126,27 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
     // resources of the segment the next loads belong to (wave-uniform); empty past the last segment
     uintx4 rx, rg;
     int x_shift, g_shift;       // negative when a window starts before the row: added to the lane offsets
+    int vx0 = 0, vg0 = 0;       // ROWS: virtual positions of the first floats of the two windows
     auto aim = [&](int pb, int pseg) {
         if (pb < B) {
-            const size_t row = ((size_t)pb * (size_t)C + (size_t)c) * (size_t)L;
             const int t0 = pseg * kSegLen;
-            const int u0 = 4 * (t0 + 16 * dmin), v0 = 4 * (t0 + 16 * dmin_x);
-            x_shift = u0 < 0 ? u0 : 0;
-            g_shift = v0 < 0 ? v0 : 0;
-            rx = row_tail_resource(x + row, L, u0 > 0 ? u0 : 0);
-            rg = row_tail_resource(dy + row, L, v0 > 0 ? v0 : 0);
+            if constexpr (ROWS) {
+                vx0 = t0 + 16 * dmin;
+                vg0 = t0 + 16 * dmin_x;
+                x_shift = g_shift = 0;
+                const unsigned nbytes = rm.bytes - (unsigned)(c * L) * 4u;
+                const unsigned long long ax = reinterpret_cast<unsigned long long>(x + (size_t)c * (size_t)L);
+                const unsigned long long ag = reinterpret_cast<unsigned long long>(dy + (size_t)c * (size_t)L);
+                rx = uintx4{(unsigned)ax, (unsigned)(ax >> 32) & 0xffffu, nbytes, kBufferFlags};
+                rg = uintx4{(unsigned)ag, (unsigned)(ag >> 32) & 0xffffu, nbytes, kBufferFlags};
+            } else {
+                const size_t row = ((size_t)pb * (size_t)C + (size_t)c) * (size_t)L;
+                const int u0 = 4 * (t0 + 16 * dmin), v0 = 4 * (t0 + 16 * dmin_x);
+                x_shift = u0 < 0 ? u0 : 0;
+                g_shift = v0 < 0 ? v0 : 0;
+                rx = row_tail_resource(x + row, L, u0 > 0 ? u0 : 0);
+                rg = row_tail_resource(dy + row, L, v0 > 0 ? v0 : 0);
+            }
         } else {
             x_shift = g_shift = 0;
             rx = uintx4{0u, 0u, 0u, kBufferFlags};
@@ -142,14 +155,23 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
     };
     auto load_region = [&](auto ic) {       // x_i then g_i, i = 0..3
         constexpr int i = decltype(ic)::value;
-        buffer_load_x4_to_lds(rx, off_x + (1024 * i + x_shift), lds_x + 1024u * (unsigned)i);
-        buffer_load_x4_to_lds(rg, off_g + (1024 * i + g_shift), lds_g + 1024u * (unsigned)i);
+        if constexpr (ROWS) {
+            buffer_load_x4_to_lds(rx, rows_byte_offset<4>(rm, vx0 + fo_x + 256 * i), lds_x + 1024u * (unsigned)i);
+            buffer_load_x4_to_lds(rg, rows_byte_offset<4>(rm, vg0 + fo_g + 256 * i), lds_g + 1024u * (unsigned)i);
+        } else {
+            buffer_load_x4_to_lds(rx, 4 * fo_x + (1024 * i + x_shift), lds_x + 1024u * (unsigned)i);
+            buffer_load_x4_to_lds(rg, 4 * fo_g + (1024 * i + g_shift), lds_g + 1024u * (unsigned)i);
+        }
+    };
+    auto tail_offset = [&](int fo, int v0, int shift) {
+        if constexpr (ROWS) return fo >= 0 ? rows_byte_offset<4>(rm, v0 + fo) : kOutOfRow;
+        else return fo >= 0 ? 4 * fo + shift : kOutOfRow;
     };
     auto load_tails = [&]() {               // xa xb ga gb
-        buffer_load_x1_to_lds(rx, off_xt[0] + x_shift, lds_x + 4096u);
-        buffer_load_x1_to_lds(rx, off_xt[1] + x_shift, lds_x + 4096u + 256u);
-        buffer_load_x1_to_lds(rg, off_gt[0] + g_shift, lds_g + 4096u);
-        buffer_load_x1_to_lds(rg, off_gt[1] + g_shift, lds_g + 4096u + 256u);
+        buffer_load_x1_to_lds(rx, tail_offset(fo_xt[0], vx0, x_shift), lds_x + 4096u);
+        buffer_load_x1_to_lds(rx, tail_offset(fo_xt[1], vx0, x_shift), lds_x + 4096u + 256u);
+        buffer_load_x1_to_lds(rg, tail_offset(fo_gt[0], vg0, g_shift), lds_g + 4096u);
+        buffer_load_x1_to_lds(rg, tail_offset(fo_gt[1], vg0, g_shift), lds_g + 4096u + 256u);
     };
 
     aim(b, seg);
@@ -162,8 +184,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
         seg_n -= carry ? segs_per_row : 0;
         const int b_n = b + step_b + carry;
         // where this segment's input gradient goes (wave-uniform)
-        float *out_seg = dx + ((size_t)b * (size_t)C + (size_t)c) * (size_t)L + (size_t)(seg * kSegLen);
-        const bool whole = (seg + 1) * kSegLen <= L;
+        float *out_seg = ROWS ? dx + (size_t)c * (size_t)L
+                              : dx + ((size_t)b * (size_t)C + (size_t)c) * (size_t)L + (size_t)(seg * kSegLen);
+        const bool whole = !ROWS && (seg + 1) * kSegLen <= L;
         const int t_seg = seg * kSegLen;
         aim(b_n, seg_n);
 
@@ -204,8 +227,13 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
             if constexpr (i == 3) load_tails();
             // ---- store tile i: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3
             const int lt = 256 * i + 16 * i16 + 4 * k4;
-            if (whole || t_seg + lt + 3 < L)
-                *reinterpret_cast<float4 *>(out_seg + lt) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            if constexpr (ROWS) {
+                const int e = rows_element(rm, t_seg + lt);         // the four outputs are in one row or in one gap
+                if (e >= 0) *reinterpret_cast<float4 *>(out_seg + e) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            } else {
+                if (whole || t_seg + lt + 3 < L)
+                    *reinterpret_cast<float4 *>(out_seg + lt) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            }
         });
         b = b_n; seg = seg_n;
     }

@@ -99,10 +99,12 @@ constexpr size_t dw_direct_lds_bytes(int ND, int W) { return (size_t)W * (size_t
 
 // W waves per block.  dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (one
 // block per channel, gridDim.y == 1) they are the weight gradient itself and go to dw_out.
-template <int ND, int W>
+// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap); B is then 1 and segs_per_row the
+// number of segments of the virtual row.
+template <int ND, int W, bool ROWS>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_kernel(
     const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int segs_per_row)
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, const RowsMap rm)
 {
     constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
     constexpr int NGX = XW / 4;                    // its 16-byte granules: 4 full loads and a tail
@@ -142,16 +144,32 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     // resources of the segment the next loads belong to (wave-uniform); empty past the last segment
     uintx4 rx, rg;
     int x_shift;        // negative when the x window starts before the row: added to the lane offsets
+    int vx0 = 0, vg0 = 0;   // ROWS: virtual positions of the first floats of the two windows
     auto aim = [&](int pb, int pseg) {
         if (pb < B) {
-            // batches are walked from the last to the first: the input-gradient call that usually runs just before
-            // this one walks them upwards, so its last rows of dY are still in the last-level cache
-            const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
-            const int t0 = pseg * kSegLen;
-            const int u0 = 4 * (t0 + 16 * dmin);
-            x_shift = u0 < 0 ? u0 : 0;
-            rx = row_tail_resource(x + row, L, u0 > 0 ? u0 : 0);
-            rg = row_tail_resource(dy + row, L, 4 * t0);
+            if constexpr (ROWS) {
+                // (virtual segments are walked downwards, like the batches below)
+                const int t0 = (segs_per_row - 1 - pseg) * kSegLen;
+                vx0 = t0 + 16 * dmin;
+                vg0 = t0;
+                x_shift = 0;
+                const unsigned nbytes = rm.bytes - (unsigned)(c * L) * 4u;
+                rx = uintx4{0u, 0u, nbytes, kBufferFlags};
+                rg = rx;
+                const unsigned long long ax = reinterpret_cast<unsigned long long>(x + (size_t)c * (size_t)L);
+                const unsigned long long ag = reinterpret_cast<unsigned long long>(dy + (size_t)c * (size_t)L);
+                rx[0] = (unsigned)ax; rx[1] = (unsigned)(ax >> 32) & 0xffffu;
+                rg[0] = (unsigned)ag; rg[1] = (unsigned)(ag >> 32) & 0xffffu;
+            } else {
+                // batches are walked from the last to the first: the input-gradient call that usually runs just
+                // before this one walks them upwards, so its last rows of dY are still in the last-level cache
+                const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
+                const int t0 = pseg * kSegLen;
+                const int u0 = 4 * (t0 + 16 * dmin);
+                x_shift = u0 < 0 ? u0 : 0;
+                rx = row_tail_resource(x + row, L, u0 > 0 ? u0 : 0);
+                rg = row_tail_resource(dy + row, L, 4 * t0);
+            }
         } else {
             x_shift = 0;
             rx = uintx4{0u, 0u, 0u, kBufferFlags};
@@ -162,12 +180,18 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     // and the chunk loop stays one straight-line block without a second code path)
     auto load_x = [&](auto ic) {        // ic = 0..4
         constexpr int i = decltype(ic)::value;
-        if constexpr (i < 4) buffer_load_x4_to_lds(rx, off_lane + (1024 * i + x_shift), lds_x + 1024u * (unsigned)i);
-        else buffer_load_x4_to_lds(rx, off_tail + x_shift, lds_x + 4096u);
+        if constexpr (ROWS) {
+            const int off = (i < 4 || lane + 256 < NGX) ? rows_byte_offset<4>(rm, vx0 + 4 * (lane + 64 * i)) : kOutOfRow;
+            buffer_load_x4_to_lds(rx, off, lds_x + 1024u * (unsigned)i);
+        } else {
+            if constexpr (i < 4) buffer_load_x4_to_lds(rx, off_lane + (1024 * i + x_shift), lds_x + 1024u * (unsigned)i);
+            else buffer_load_x4_to_lds(rx, off_tail + x_shift, lds_x + 4096u);
+        }
     };
     auto load_g = [&](auto ic) {        // ic = 0..3
         constexpr int i = decltype(ic)::value;
-        buffer_load_x4_to_lds_imm<1024 * i>(rg, off_lane, lds_g);
+        if constexpr (ROWS) buffer_load_x4_to_lds(rg, rows_byte_offset<4>(rm, vg0 + 4 * (lane + 64 * i)), lds_g + 1024u * (unsigned)i);
+        else buffer_load_x4_to_lds_imm<1024 * i>(rg, off_lane, lds_g);
     };
 
     // first segment: all nine loads, in the order every later segment uses
