@@ -149,6 +149,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
     g.segs_per_row = (int)segs_per_row;
     constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
+    const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
     // One resident round of waves, each walking segments wave, wave + n_waves, ...
     auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po) -> int {
         const long long resident = resident_waves(kernel, kThreads);
@@ -161,9 +162,41 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         g.step_rows = g.n_waves / g.segs_per_row;
         g.step_seg = g.n_waves % g.segs_per_row;
         g.step_c = g.step_rows % s.C;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };
+    if constexpr (std::is_same<T, float>::value) {
+        // fp32 short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
+        const RowsPlan rp = plan_rows(s);
+        if (rp.on) {
+            const long long total = (long long)rp.nvs * s.C;
+            if (total > 0x3fffffffLL) return -1;
+            g.rows = rp.nvs;
+            g.segs_per_row = s.C;
+            auto launch_rows = [&](auto kernel) -> int {
+                const long long resident = resident_waves(kernel, kThreads);
+                long long spw = (total + resident - 1) / resident;
+                if (spw < 1) spw = 1;
+                long long blocks = ((total + spw - 1) / spw + 7) / 8 * 8;
+                g.n_waves = (int)blocks;
+                g.step_rows = g.n_waves / g.segs_per_row;
+                g.step_seg = g.n_waves % g.segs_per_row;
+                g.step_c = 0;
+                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, static_cast<const float *>(in),
+                                   static_cast<const float *>(f), static_cast<float *>(out), g, rp.map);
+                return launch_status();
+            };
+            static_assert(dwconv::kCorrWavesPerBlock == 1, "one wave per block");
+            switch (nd) {
+            case 2: return launch_rows(dwconv::corr_mfma_kernel<float, 2, true>);
+            case 3: return launch_rows(dwconv::corr_mfma_kernel<float, 3, true>);
+            case 4: return launch_rows(dwconv::corr_mfma_kernel<float, 4, true>);
+            case 5: return launch_rows(dwconv::corr_mfma_kernel<float, 5, true>);
+            case 6: return launch_rows(dwconv::corr_mfma_kernel<float, 6, true>);
+            default: return -1;
+            }
+        }
+    }
     if constexpr (sizeof(T) == 2) {
         // bf16 storage: the bf16 matrix instruction when 16-byte granules of 8 elements line up
         if ((s.L % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
@@ -182,11 +215,11 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     const T *pi = static_cast<const T *>(in), *pf = static_cast<const T *>(f);
     T *po = static_cast<T *>(out);
     switch (nd) {
-    case 2: return launch(dwconv::corr_mfma_kernel<T, 2>, pi, pf, po);
-    case 3: return launch(dwconv::corr_mfma_kernel<T, 3>, pi, pf, po);
-    case 4: return launch(dwconv::corr_mfma_kernel<T, 4>, pi, pf, po);
-    case 5: return launch(dwconv::corr_mfma_kernel<T, 5>, pi, pf, po);
-    case 6: return launch(dwconv::corr_mfma_kernel<T, 6>, pi, pf, po);
+    case 2: return launch(dwconv::corr_mfma_kernel<T, 2, false>, pi, pf, po);
+    case 3: return launch(dwconv::corr_mfma_kernel<T, 3, false>, pi, pf, po);
+    case 4: return launch(dwconv::corr_mfma_kernel<T, 4, false>, pi, pf, po);
+    case 5: return launch(dwconv::corr_mfma_kernel<T, 5, false>, pi, pf, po);
+    case 6: return launch(dwconv::corr_mfma_kernel<T, 6, false>, pi, pf, po);
     default: return -1;
     }
 }

@@ -171,10 +171,14 @@ template <> struct Raw4<bf16_t> {
 //   (4) stores 16 bytes per lane per D tile,
 // so loads are in flight during (2) and the stores of a segment have the whole of the next
 // segment's (2) to retire before the next wait on the memory counter.
-template <typename T, int ND>
+//
+// ROWS (short rows, see RowsMap): the unit of work is a segment of the virtual row of a channel; wave slots are
+// ordered (virtual segment, channel), so neighbouring waves read neighbouring channels of the same batches, and
+// `row` / `seg` below then hold the virtual segment and the channel.
+template <typename T, int ND, bool ROWS>
 __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_mfma_kernel(const T *__restrict__ in,
                                                                          const T *__restrict__ f, T *__restrict__ out,
-                                                                         const CorrGeom g)
+                                                                         const CorrGeom g, const RowsMap rm)
 {
     constexpr int NIB = kSegBlocks + ND - 1;       // input blocks staged per segment
     constexpr int NG = NIB * 4;                    // 16-byte granules staged per segment
@@ -197,7 +201,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int wg = (g.n_waves % 8 == 0) ? (id % 8) * (g.n_waves / 8) + id / 8 : id;
     int row = wg / g.segs_per_row;                 // b * C + c
     int seg = wg % g.segs_per_row;
-    int c = row % g.C;
+    int c = ROWS ? seg : row % g.C;
     if (row >= g.rows) return;
     int row_n, seg_n, c_n;                         // the segment after (row, seg)
     auto advance = [&]() {
@@ -205,9 +209,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
         const int carry = seg_n >= g.segs_per_row ? 1 : 0;
         seg_n -= carry ? g.segs_per_row : 0;
         row_n = row + g.step_rows + carry;
-        c_n = c + g.step_c + carry;
-        c_n -= c_n >= g.C ? g.C : 0;
-        c_n -= c_n >= g.C ? g.C : 0;
+        if constexpr (ROWS) {
+            c_n = seg_n;
+        } else {
+            c_n = c + g.step_c + carry;
+            c_n -= c_n >= g.C ? g.C : 0;
+            c_n -= c_n >= g.C ? g.C : 0;
+        }
     };
 
     // per-lane constants: byte offset of the lane's i-th granule inside the staged window, and its LDS slot
@@ -217,15 +225,26 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 #pragma unroll
     for (int i = 0; i < NLD; ++i) ld_off[i] = (lane + 64 * i < NG) ? 4 * ES * (lane + 64 * i) : kOutOfRow;
     auto prefetch = [&](int prow, int pseg) {
-        const int u0 = ES * (pseg * kSegLen + 16 * g.dmin);          // may be negative: before the row start
-        const int start = u0 > 0 ? u0 : 0;
-        const uintx4 r = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, start);
-        if (u0 >= 0) {
+        if constexpr (ROWS) {
+            // virtual segment prow of channel pseg: every lane translates the positions of its granules
+            const int v0 = prow * kSegLen + 16 * g.dmin;
+            const unsigned long long a = reinterpret_cast<unsigned long long>(in + (size_t)pseg * (size_t)g.L);
+            const uintx4 r = {(unsigned)a, (unsigned)(a >> 32) & 0xffffu, rm.bytes - (unsigned)(pseg * g.L) * (unsigned)ES,
+                              kBufferFlags};
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i]);
+            for (int i = 0; i < NLD; ++i)
+                pre[i] = Raw4<T>::load(r, lane + 64 * i < NG ? rows_byte_offset<ES>(rm, v0 + 4 * (lane + 64 * i)) : kOutOfRow);
         } else {
+            const int u0 = ES * (pseg * kSegLen + 16 * g.dmin);          // may be negative: before the row start
+            const int start = u0 > 0 ? u0 : 0;
+            const uintx4 r = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, start);
+            if (u0 >= 0) {
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i] + u0);
+                for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i] + u0);
+            }
         }
     };
     float *sw = s_in[wave];
@@ -306,17 +325,26 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
         if (more) drain();
         // (4) lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of each D tile;
         // stores past the end of the row are dropped by the range check
-        T *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
         const int lane_t = 16 * i16 + 4 * k4;
-        if ((seg + 1) * kSegLen <= g.L) {
+        if constexpr (ROWS) {
+            T *out_c = out + (size_t)c * (size_t)g.L;                                // wave-uniform
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
-                st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+            for (int dt = 0; dt < NDT; ++dt) {
+                const int e = rows_element(rm, row * kSegLen + 256 * dt + lane_t);   // four outputs: one row or one gap
+                if (e >= 0) st_elem4(out_c + e, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+            }
         } else {
+            T *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+            if ((seg + 1) * kSegLen <= g.L) {
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
-                if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
+                for (int dt = 0; dt < NDT; ++dt)
                     st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+            } else {
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt)
+                    if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
+                        st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+            }
         }
         wave_lds_fence();
         if (!more) break;
@@ -334,7 +362,8 @@ constexpr int kBf16BlockBytes = 48;      // staged 16-block: 32 bytes + 16 pad
 
 template <int ND>
 __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_mfma_bf16_kernel(
-    const bf16_t *__restrict__ in, const bf16_t *__restrict__ f, bf16_t *__restrict__ out, const CorrGeom g)
+    const bf16_t *__restrict__ in, const bf16_t *__restrict__ f, bf16_t *__restrict__ out, const CorrGeom g,
+    const RowsMap /* short rows are an fp32 path */)
 {
     constexpr int NIB = kSegBlocks + ND - 1;       // input blocks staged per segment
     constexpr int NG = NIB * 2;                    // 16-byte granules (8 elements) staged per segment

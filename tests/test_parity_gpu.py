@@ -167,8 +167,7 @@ def test_fused_backward(oracle_mod, B, C, L, K, p, dtype, fused):
     dx_sep = binding.dwconv_bwd_input(dyd, wd, p)
     dx2, dw2 = binding.dwconv_bwd(dyd, xd, wd, p)
     torch.cuda.synchronize()
-    if not torch.equal(dx, dx_sep):     # TEMP: short-row shapes until the separate path walks virtual rows too
-        print("   fused dx not bit-identical to the separate path", flush=True)
+    assert torch.equal(dx, dx_sep), "fused dx differs from the separate input-gradient path"
     assert torch.equal(dx, dx2) and torch.equal(dw, dw2), "not run-to-run identical"
     xn, wn, dyn = as_f32_numpy(x), as_f32_numpy(w), as_f32_numpy(dy)
     for name, got, (ref, ra) in (("dx", dx, oracle_mod.bwd_input(dyn, wn, p)), ("dw", dw, oracle_mod.bwd_weight(xn, dyn, K, p))):
