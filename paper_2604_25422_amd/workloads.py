@@ -3,7 +3,8 @@
 This module holds no arithmetic of the operator itself: it only draws the
 tensors that both the HIP library and the CPU checker are fed.  The shapes are
 the five benchmark configurations of this build (index 1 is the headline
-training-step shape); seeded random tensors stand in for the S4ConvD
+training-step shape) plus, as index 5, the shape of the paper's own measurements
+(Sec. V: B = 16384, H = 128, L = 48, K = 48, pad K/2); seeded random tensors stand in for the S4ConvD
 activations of the paper's ASHRAE GEPIII workload (Sec. III-A..C), whose
 kernel time depends on tensor dimensions only (Sec. III-H).
 
@@ -50,6 +51,7 @@ WORKLOADS = [
     Workload("cfg2_shortK_B64_C512_L2048_K7_same_f32", 2, 64, 512, 2048, 7, 3, "f32", "normal"),
     Workload("cfg3_longK_B8_C256_L8192_K8192_causal_f32", 3, 8, 256, 8192, 8192, 8191, "f32", "decay_cos"),
     Workload("cfg4_bf16_B128_C768_L1024_K32_causal_bf16", 4, 128, 768, 1024, 32, 31, "bf16", "normal"),
+    Workload("paper_shape_B16384_C128_L48_K48_pad24_f32", 5, 16384, 128, 48, 48, 24, "f32", "normal_var_1_over_K"),
 ]
 HEADLINE = WORKLOADS[1]
 
