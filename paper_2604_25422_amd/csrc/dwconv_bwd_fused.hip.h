@@ -60,7 +60,6 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
     static_assert(ND >= 2 && 16 * ND <= 128, "window tails are two 64-float loads");
     constexpr int XW = kSegLen + 16 * ND;          // floats of either window that are ever read
     constexpr int WREG = bwd_fused_wave_floats(ND);
-    constexpr int NCH = kSegLen / 64;
     extern __shared__ __align__(16) float dyn_lds[];
     float (*s_mem)[WREG] = reinterpret_cast<float (*)[WREG]>(dyn_lds);
     float (*s_dw)[16 * ND] = reinterpret_cast<float (*)[16 * ND]>(dyn_lds + W * WREG);

@@ -111,7 +111,6 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     static_assert(NGX > 256 && NGX <= 320, "five loads per x window");
     constexpr int XREG = 5 * 256;                  // x window plus slack for the tail load
     static_assert(XREG - XW <= kDirectSlackFloats, "slack");
-    constexpr int NCH = kSegLen / 64;              // 64-position chunks per segment
     constexpr int GF = ND * 256;                   // floats of one wave's G
     constexpr int STAGE = XREG + kSegLen;
     constexpr int WREG = STAGE > GF ? STAGE : GF;  // per-wave LDS region
