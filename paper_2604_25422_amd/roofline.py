@@ -59,7 +59,8 @@ MEASURED_TRAFFIC_BYTES = {
     (1, "fwd"): 262616 * 1024, (1, "dx"): 262616 * 1024, (1, "dw_partial"): 263038 * 1024, (1, "bwd_fused"): 398094 * 1024,
     (2, "fwd"): 526398 * 1024, (2, "dx"): 526398 * 1024, (2, "dw_partial"): 526656 * 1024, (2, "bwd_fused"): 794173 * 1024,
     (3, "fwd"): 163881 * 1024, (3, "dx"): 163881 * 1024, (3, "dw_partial"): 271351 * 1024,
-    (4, "fwd"): 393986 * 1024, (4, "dx"): 393986 * 1024, (4, "dw_partial"): 393339 * 1024,
+    (4, "fwd"): 393986 * 1024, (4, "dx"): 393986 * 1024, (4, "dw_partial"): 393319 * 1024,
+    (5, "fwd"): 833328 * 1024, (5, "dx"): 833328 * 1024, (5, "dw_partial"): 1062859 * 1024, (5, "bwd_fused"): 1480983 * 1024,
 }
 
 
