@@ -81,12 +81,33 @@ def test_weight_gradient_argument_validation(lib):
     assert lib.dwconv_bwd_weight_finalize(P, need, None, 2, 3, 100, 5, 2, 0, None) == 1
 
 
+def test_fused_backward_argument_validation(lib):
+    need = lib.dwconv_bwd_weight_workspace_bytes(2, 3, 100, 5, 2, 0)
+    f = lib.dwconv_bwd          # (dy, x, w, dx, dw, workspace, bytes, B, C, L, K, pad, dtype, stream)
+    for missing in range(5):
+        args = [P] * 5
+        args[missing] = None
+        assert f(*args, P, need, 2, 3, 100, 5, 2, 0, None) == 1
+    assert f(P, P, P, P, P, P, need, 0, 3, 100, 5, 2, 0, None) == 2
+    assert f(P, P, P, P, P, P, need, 2, 3, 100, 5, 5, 0, None) == 3
+    assert f(P, P, P, P, P, P, need, 2, 3, 100, 5, 2, 9, None) == 4
+    assert f(P, P, P, P, P, None, need, 2, 3, 100, 5, 2, 0, None) == 5
+    assert f(P, P, P, P, P, P, need - 1, 2, 3, 100, 5, 2, 0, None) == 5
+    assert f(P, P, P, P + 2, P, P, need, 2, 3, 100, 5, 2, 0, None) == 6
+    # which shapes take the fused kernel: fp32, filters of the register-resident class, row length a multiple of 4
+    q = lib.dwconv_bwd_is_fused
+    assert q(32, 256, 4096, 64, 63, 0) == 1 and q(16384, 128, 48, 48, 24, 0) == 1 and q(2, 3, 100, 5, 2, 0) == 1
+    assert q(128, 768, 1024, 32, 31, 1) == 0 and q(8, 256, 8192, 8192, 8191, 0) == 0 and q(2, 3, 101, 5, 2, 0) == 0
+    assert q(2, 3, 100, 2, 1, 0) == 0 and q(0, 3, 100, 5, 2, 0) == 0
+
+
 def test_workspace_query_rejects_bad_shapes(lib):
     assert lib.dwconv_bwd_weight_workspace_bytes(0, 3, 100, 5, 2, 0) == 0
     assert lib.dwconv_bwd_weight_workspace_bytes(2, 3, 100, 5, 9, 0) == 0
     assert lib.dwconv_bwd_weight_slices(2, 3, 100, 5, 2, 3) == 0
     for (B, C, L, K, p, dt) in [(32, 256, 4096, 64, 63, 0), (64, 512, 2048, 7, 3, 0), (8, 256, 8192, 8192, 8191, 0),
-                                (128, 768, 1024, 32, 31, 1), (1, 1, 1, 1, 0, 0)]:
+                                (128, 768, 1024, 32, 31, 1), (1, 1, 1, 1, 0, 0), (16384, 128, 48, 48, 24, 0),
+                                (3, 5, 600, 64, 63, 0)]:
         S = lib.dwconv_bwd_weight_slices(B, C, L, K, p, dt)
         n = lib.dwconv_bwd_weight_workspace_bytes(B, C, L, K, p, dt)
         assert S >= 1 and n >= S * C * K * 4 and n % 16 == 0
