@@ -175,3 +175,44 @@ def test_fused_backward(oracle_mod, B, C, L, K, p, dtype, fused):
         e, i = normalised_error(g, ref, ra)
         assert e <= TOL[(dtype, name)], f"{name}: err {e:.3e} at flat index {i}: gpu {g.ravel()[i]!r} oracle {ref.ravel()[i]!r}"
         assert np.all(g[ra == 0] == 0)
+
+
+def _random_shapes(n, seed):
+    """Seeded shapes that mix every dispatch class: register-resident and long filters, short rows, rows that
+    are not a multiple of 4, channel counts that trigger whole-channel workgroups, every pad class."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([1, 2, 3, 5, 7, 16, 31, 32, 33, 48, 64, 66, 67, 90, 200]))
+        L = int(rng.choice([4, 12, 36, 48, 64, 100, 128, 257, 512, 1000, 1024, 1028, 2048, 3000]))
+        C = int(rng.choice([1, 2, 3, 5, 8, 16, 256, 512]))
+        B = int(rng.choice([1, 2, 3, 7, 16, 40]))
+        if C >= 256:
+            L = min(L, 128); B = int(rng.choice([8, 64, 300]))
+        if B * C * L * min(K, L) > 6e7 or B * C * L > 4e6:
+            continue
+        p = int(rng.choice([0, K // 2, K - 1, int(rng.integers(0, K))]))
+        dtype = "bf16" if rng.random() < 0.3 else "f32"
+        out.append((B, C, L, K, p, dtype))
+    return out
+
+
+@pytest.mark.parametrize("B,C,L,K,p,dtype", _random_shapes(140, 20260425))
+def test_random_shapes(oracle_mod, B, C, L, K, p, dtype):
+    from paper_2604_25422_amd import binding
+    print(f"case random {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    check_case(oracle_mod, B, C, L, K, p, dtype, seed=B + 3 * C + 5 * L + 7 * K + p)
+    # the fused backward call on the same inputs: same dx bits as the separate call, dw within tolerance
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    sd = B + 3 * C + 5 * L + 7 * K + p
+    x = seeded((B, C, L), 1000 + sd, tdt); w = seeded((C, K), 2000 + sd, tdt); dy = seeded((B, C, L), 3000 + sd, tdt)
+    xd, wd, dyd = x.cuda(), w.cuda(), dy.cuda()
+    dx, dw = binding.dwconv_bwd(dyd, xd, wd, p)
+    dx_sep = binding.dwconv_bwd_input(dyd, wd, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx_sep)
+    from paper_2604_25422_amd.roofline import normalised_error
+    from paper_2604_25422_amd.workloads import as_f32_numpy
+    ref, ra = oracle_mod.bwd_weight(as_f32_numpy(x), as_f32_numpy(dy), K, p)
+    e, i = normalised_error(dw.float().cpu().numpy().astype(np.float64), ref, ra)
+    assert e <= TOL[(dtype, "dw")], f"fused dw err {e:.3e} at {i}"
