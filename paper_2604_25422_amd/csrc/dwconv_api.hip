@@ -11,6 +11,7 @@
 #include <type_traits>
 
 #include "dwconv_bwd_fused.hip.h"
+#include "dwconv_bwd_fused_bf16.hip.h"
 #include "dwconv_common.hip.h"
 #include "dwconv_dw_bf16.hip.h"
 #include "dwconv_dw_direct.hip.h"
@@ -541,11 +542,22 @@ int launch_dw_partial(const void *x, const void *dy, float *part, void *dw_out, 
     return launch_status();
 }
 
-// Fused input + weight gradient (fp32, matrix-core shape class).  Returns -1 when it does not apply.
+// Fused input + weight gradient (matrix-core shape class).  Returns -1 when it does not apply.
 template <int ND, int W>
 int launch_bwd_fused_ndw(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,
                          const Shape &s, const DwPlan &p, int dmin, hipStream_t st)
 {
+    if (s.dtype == DWCONV_BF16) {
+        auto kernel = dwconv::bwd_fused_bf16_kernel<ND, W>;
+        constexpr size_t lds = dwconv::bwd_fused_bf16_lds_bytes(ND, W);
+        static_assert(lds <= kMaxLdsBytes, "LDS budget");
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(w),
+                           static_cast<bf16_t *>(dx), part, static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin,
+                           p.tiles_per_row);
+        return launch_status();
+    }
     constexpr size_t lds = dwconv::bwd_fused_lds_bytes(ND, W);
     static_assert(lds <= kMaxLdsBytes, "LDS budget");
     if (p.rows.on) {
@@ -583,7 +595,9 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
                      const Shape &s, const DwPlan &p, hipStream_t st)
 {
     *wrote_dw = false;
-    if (s.dtype != DWCONV_F32 || p.longk) return -1;
+    if (p.longk) return -1;
+    // bf16: whole 16-byte granules of 8 elements
+    if (s.dtype == DWCONV_BF16 && (s.L % 8) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
     if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
@@ -710,7 +724,8 @@ int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw,
     rc = launch_bwd_fused(dy, x, w, dx, part, dw, &wrote_dw, s, p, st);
     if (rc >= 0) {
         if (rc != DWCONV_OK || wrote_dw) return rc;
-        return launch_dw_finalize<float>(part, dw, s, p, st);
+        if (dtype == DWCONV_F32) return launch_dw_finalize<float>(part, dw, s, p, st);
+        return launch_dw_finalize<bf16_t>(part, dw, s, p, st);
     }
     // shapes and types the fused kernel does not take: the two gradients one after the other
     rc = dwconv_bwd_input(dy, w, dx, B, C, L, K, pad_left, dtype, stream);
@@ -724,7 +739,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const Shape s{B, C, L, K, pad_left, dtype};
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
-    return (dtype == DWCONV_F32 && !p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % 4) == 0 &&
+    return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
             L <= kMfmaMaxL) ? 1 : 0;
 }
 
