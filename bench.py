@@ -74,8 +74,8 @@ def cpu_baseline(wl, inputs):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists, "
-              "see DESIGN.md for how the operator would shard)", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists: channels shard "
+              "without communication, batches need one all-reduce of dW)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2604_25422_amd import binding, workloads
