@@ -228,10 +228,10 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
             const int lt = 256 * i + 16 * i16 + 4 * k4;
             if constexpr (ROWS) {
                 const int e = rows_element(rm, t_seg + lt);         // the four outputs are in one row or in one gap
-                if (e >= 0) *reinterpret_cast<float4 *>(out_seg + e) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                if (e >= 0) st_elem4_stream(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]));
             } else {
                 if (whole || t_seg + lt + 3 < L)
-                    *reinterpret_cast<float4 *>(out_seg + lt) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                    st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
             }
         });
         b = b_n; seg = seg_n;

@@ -34,12 +34,27 @@ __device__ __forceinline__ float4 ld_elem4(const bf16_t *p)
                        __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
 }
 __device__ __forceinline__ void st_elem4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+// Streaming variants: the line is not kept in the caches on its way to memory.
+typedef float nt_floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int nt_uintx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void st_elem4_stream(float *p, float4 v)
+{
+    nt_floatx4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<nt_floatx4 *>(p));
+}
 __device__ __forceinline__ void st_elem4(bf16_t *p, float4 v)
 {
     uint2 u;
     u.x = f32_to_bf16_bits(v.x) | (f32_to_bf16_bits(v.y) << 16);
     u.y = f32_to_bf16_bits(v.z) | (f32_to_bf16_bits(v.w) << 16);
     *reinterpret_cast<uint2 *>(p) = u;
+}
+__device__ __forceinline__ void st_elem4_stream(bf16_t *p, float4 v)
+{
+    nt_uintx2 u;
+    u[0] = f32_to_bf16_bits(v.x) | (f32_to_bf16_bits(v.y) << 16);
+    u[1] = f32_to_bf16_bits(v.z) | (f32_to_bf16_bits(v.w) << 16);
+    __builtin_nontemporal_store(u, reinterpret_cast<nt_uintx2 *>(p));
 }
 
 }  // namespace dwconv

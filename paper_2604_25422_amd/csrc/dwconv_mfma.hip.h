@@ -168,7 +168,8 @@ template <> struct Raw4<bf16_t> {
 //   (2) contracts the 4 D tiles (16 blocks = 256 outputs each) of the current segment out of its
 //       private LDS region (16-blocks padded to 20 floats, zeros outside the row),
 //   (3) drains the prefetch registers into the same LDS region, and
-//   (4) stores 16 bytes per lane per D tile,
+//   (4) stores 16 bytes per lane per D tile (streaming stores: the outputs are not read again by this
+//       operator, and keeping them out of the last-level cache leaves it to the inputs the backward calls re-read),
 // so loads are in flight during (2) and the stores of a segment have the whole of the next
 // segment's (2) to retire before the next wait on the memory counter.
 //
@@ -331,19 +332,19 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) {
                 const int e = rows_element(rm, row * kSegLen + 256 * dt + lane_t);   // four outputs: one row or one gap
-                if (e >= 0) st_elem4(out_c + e, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                if (e >= 0) st_elem4_stream(out_c + e, make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
             }
         } else {
             T *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
             if ((seg + 1) * kSegLen <= g.L) {
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt)
-                    st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                    st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
             } else {
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt)
                     if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
-                        st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                        st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
             }
         }
         wave_lds_fence();
@@ -467,12 +468,12 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
         if ((seg + 1) * kSegLen <= g.L) {
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
-                st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
         } else {
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
                 if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
-                    st_elem4(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                    st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
         }
         wave_lds_fence();
         if (!more) break;
