@@ -30,7 +30,7 @@ namespace dwconv {
 // One 4-byte-per-lane load into LDS: LDS[lds_base + 4 lane] <- resource[byte_off], zero outside the resource.
 __device__ __forceinline__ void buffer_load_x1_to_lds(uintx4 rsrc, int byte_off, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen nt lds"
                  :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
 }
 

@@ -26,17 +26,20 @@
 namespace dwconv {
 
 // One 16-byte-per-lane load into LDS:  LDS[lds_base + 16 lane ..] <- resource[byte_off ..], zeros when
-// byte_off is outside the resource.  M0 carries the LDS base of the instruction.
+// byte_off is outside the resource.  M0 carries the LDS base of the instruction.  The loads carry the
+// non-temporal hint: the kernels that use them are the last readers of x and dY in a training step, and lines
+// that are not kept do not push out the rows still waiting in the last-level cache (measured: -8 % on the
+// short-filter weight gradient, -11 % on its fused backward, neutral on the headline shape).
 __device__ __forceinline__ void buffer_load_x4_to_lds(uintx4 rsrc, int byte_off, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen nt lds"
                  :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
 }
 template <int OFF>
 __device__ __forceinline__ void buffer_load_x4_to_lds_imm(uintx4 rsrc, int byte_off, unsigned lds_base)
 {
     // the immediate offset advances the memory side and the LDS side alike
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 lds"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 nt lds"
                  :: "s"(lds_base), "v"(byte_off), "s"(rsrc), "n"(OFF) : "memory");
 }
 // s_waitcnt vmcnt(N)
