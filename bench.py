@@ -5,7 +5,10 @@ A step is one pass of the whole hot path over one batch of synthetic input: forw
 input gradient, and weight gradient (stage 1 + stage 2), through the C ABI, at the
 headline training-step shape (fp32 B32 C256 L4096 K64 causal) unless --workload says
 otherwise.  Inputs are resident in HBM before the timed region; buffers rotate over
-several sets so that no step finds its operands in the 256 MB Infinity Cache.
+several sets so that no step finds what an earlier step left in the 256 MB last-level
+cache.  Within a step the weight gradient re-reads x and dY after the forward and
+input-gradient launches have read them, as a training step does, and the library keeps
+its outputs out of that cache (streaming stores) so that part of them is still there.
 
 Prints ONE JSON line:  metric / value = effective HBM GB/s of the full step (algorithmic
 bytes: each path reads two [B,C,L] tensors' worth and one [C,K], i.e. reads two and
