@@ -218,3 +218,38 @@ def test_random_shapes(oracle_mod, B, C, L, K, p, dtype):
     ref, ra = oracle_mod.bwd_weight(as_f32_numpy(x), as_f32_numpy(dy), K, p)
     e, i = normalised_error(dw.float().cpu().numpy().astype(np.float64), ref, ra)
     assert e <= TOL[(dtype, "dw")], f"fused dw err {e:.3e} at {i}"
+
+
+@pytest.mark.parametrize("B,C,L,K,p,dtype", [(4, 64, 1024, 16, 15, "f32"), (3, 5, 96, 48, 24, "f32"),
+                                              (2, 3, 512, 300, 299, "f32"), (4, 6, 1024, 32, 31, "bf16")])
+def test_calls_can_be_captured_in_a_graph(B, C, L, K, p, dtype):
+    """Every entry point only enqueues kernels (no allocation, no synchronisation, no memset nodes), so a step can
+    be captured once and replayed; replays, with eager work in between, give the bits of the eager calls."""
+    from paper_2604_25422_amd import binding
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = seeded((B, C, L), 41, tdt).cuda(); w = seeded((C, K), 42, tdt).cuda(); dy = seeded((B, C, L), 43, tdt).cuda()
+    y = torch.empty_like(x); dx = torch.empty_like(x); dw = torch.empty_like(w)
+    dx2 = torch.empty_like(x); dw2 = torch.empty_like(w)
+    ws = binding.new_workspace(x, K, p)
+
+    def step():
+        binding.dwconv_fwd(x, w, p, out=y)
+        binding.dwconv_bwd_input(dy, w, p, out=dx)
+        binding.dwconv_bwd_weight(x, dy, K, p, workspace=ws, out=dw)
+        binding.dwconv_bwd(dy, x, w, p, workspace=ws, out_dx=dx2, out_dw=dw2)
+
+    step()                      # eager: also warms the per-kernel caches of the library
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (y, dx, dw, dx2, dw2)]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=side):
+        step()
+    for rep in range(3):
+        for t in (y, dx, dw, dx2, dw2):
+            t.fill_(float("nan"))           # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for name, t, r in zip(("y", "dx", "dw", "dx fused", "dw fused"), (y, dx, dw, dx2, dw2), ref):
+            assert torch.equal(t, r), f"replay {rep}: {name} differs from the eager call"
