@@ -81,3 +81,14 @@ def test_cfg4_bf16_full_size(oracle_mod):
 def test_paper_shape_full_size(oracle_mod):
     # the shape the paper measures (Sec. V): many short rows, walked as virtual rows
     run_full_size(oracle_mod, workloads.WORKLOADS[5], 8192, 16)
+
+
+@pytest.mark.parametrize("B,C,L,K,p,dtype", [
+    (50, 100, 5000, 40, 11, "f32"),        # channel count unrelated to the chip, ragged last segment, several slices
+    (7, 300, 12000, 64, 63, "f32"),        # long rows, odd batch
+    (33, 257, 2040, 20, 19, "bf16"),       # bf16, odd channel count, row length a multiple of 8 but not of 16
+    (600, 96, 200, 31, 15, "f32"),         # short rows: virtual rows with several slices
+])
+def test_mid_size_odd_shapes(oracle_mod, B, C, L, K, p, dtype):
+    wl = workloads.Workload(f"odd_B{B}_C{C}_L{L}_K{K}_p{p}_{dtype}", 9, B, C, L, K, p, dtype, "normal")
+    run_full_size(oracle_mod, wl, 512, 12)
