@@ -56,10 +56,10 @@ def normalised_error(got, ref, ref_abs, floor=2.0 ** -100):
 # scaled by 2.00 and WRITE_SIZE by 1.00: what the same counters read for a plain 128 MiB device copy).
 # Keyed by (workload index, kernel); the figures and the commands are in the text summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    (1, "fwd"): 262616 * 1024, (1, "dx"): 262616 * 1024, (1, "dw_partial"): 263038 * 1024, (1, "bwd_fused"): 398094 * 1024,
-    (2, "fwd"): 526398 * 1024, (2, "dx"): 526398 * 1024, (2, "dw_partial"): 526656 * 1024, (2, "bwd_fused"): 794173 * 1024,
+    (1, "fwd"): 262486 * 1024, (1, "dx"): 262486 * 1024, (1, "dw_partial"): 268469 * 1024, (1, "bwd_fused"): 407599 * 1024,
+    (2, "fwd"): 524861 * 1024, (2, "dx"): 524861 * 1024, (2, "dw_partial"): 539596 * 1024, (2, "bwd_fused"): 831223 * 1024,
     (3, "fwd"): 163881 * 1024, (3, "dx"): 163881 * 1024, (3, "dw_partial"): 271351 * 1024,
-    (4, "fwd"): 393986 * 1024, (4, "dx"): 393986 * 1024, (4, "dw_partial"): 393319 * 1024,
+    (4, "fwd"): 393693 * 1024, (4, "dx"): 393693 * 1024, (4, "dw_partial"): 396079 * 1024, (4, "bwd_fused"): 598797 * 1024,
     (5, "fwd"): 833328 * 1024, (5, "dx"): 833328 * 1024, (5, "dw_partial"): 1062859 * 1024, (5, "bwd_fused"): 1480983 * 1024,
 }
 
