@@ -306,8 +306,8 @@ struct DwPlan {
     bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
     int tiles_per_row;     // segments the matrix-core kernels walk per row (per virtual row for short rows)
     int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel (always real rows)
-    int segs_per_wave;     // consecutive (b, segment) items a wave of the matrix-core kernel walks
-    int items_per_slice;   // (b, segment) items each slice owns = 4 * segs_per_wave
+    int segs_per_wave;     // (b, segment) items a wave of the matrix-core kernels walks
+    int items_per_slice;   // (b, segment) items each slice owns = wpb * segs_per_wave
 };
 
 constexpr int kDwTT = dwconv::kSegLen;   // positions per staged tile (every stage-1 kernel)

@@ -166,7 +166,7 @@ template <> struct Raw4<bf16_t> {
 // Per segment it
 //   (1) issues the global loads of the NEXT segment plus halo into registers,
 //   (2) contracts the 4 D tiles (16 blocks = 256 outputs each) of the current segment out of its
-//       private LDS region (16-blocks padded to 20 floats, zeros outside the row),
+//       private LDS region (16-blocks padded to 24 floats, zeros outside the row),
 //   (3) drains the prefetch registers into the same LDS region, and
 //   (4) stores 16 bytes per lane per D tile (streaming stores: the outputs are not read again by this
 //       operator, and keeping them out of the last-level cache leaves it to the inputs the backward calls re-read),
