@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--workload", type=int, default=1, help="index into workloads.WORKLOADS (1 = headline)")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-roof", action="store_true",
+                    help="instead of the benchmark, time plain device copies of 128 MiB .. 1 GiB (what a streaming "
+                         "read + write reaches on this part, with and without help from the last-level cache)")
     return ap.parse_args()
 
 
@@ -74,8 +77,32 @@ def cpu_baseline(wl, inputs):
                       f"fp64 accumulate, OpenMP over rows/coefficients"}
 
 
+def copy_roof():
+    """Plain device-to-device copies, 20 back to back after 3 warm-ups: read + write GB/s per size."""
+    import torch
+    out = {}
+    for mib in (128, 256, 1024):
+        n = mib * (1 << 20) // 4
+        a = torch.ones(n, dtype=torch.float32, device="cuda"); b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(); e0.record()
+        for _ in range(20):
+            b.copy_(a)
+        e1.record(); torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        out[f"{mib}MiB"] = {"us": round(us, 1), "GBps": round(2 * n * 4 / (us * 1e-6) / 1e9, 1)}
+        del a, b
+    print(json.dumps({"copy_roof": out, "note": "same source and destination every repetition: up to 256 MiB the "
+                      "source stays in the 256 MB last-level cache, 1 GiB is served by HBM alone"}), flush=True)
+
+
 def main():
     args = parse_args()
+    if args.copy_roof:
+        copy_roof()
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists: channels shard "
               "without communication, batches need one all-reduce of dW)", file=sys.stderr)
