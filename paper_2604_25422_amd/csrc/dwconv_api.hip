@@ -6,8 +6,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <array>
 #include <map>
+#include <memory>
 #include <mutex>
+#include <vector>
 #include <type_traits>
 
 #include "dwconv_bwd_fused.hip.h"
@@ -299,7 +303,8 @@ enum DwKernel { DW_VALU_K8, DW_VALU_K32, DW_VALU_K64, DW_VALU_K256 };
 struct DwPlan {
     DwKernel kernel;
     bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
-    int lk_wgs, lk_gd, lk_groups;   // its workgroups per channel, offsets per group, number of groups
+    int lk_wgs, lk_gd;     // its workgroups per channel, largest group of offsets (accumulators per group)
+    std::shared_ptr<const dwconv::LongKDwTable> lk_table;   // which offsets every wave slot owns
     int S;                 // partial slices per coefficient
     RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
     int wpb;               // waves per block of the matrix-core stage-1 kernels
@@ -312,6 +317,90 @@ struct DwPlan {
 
 constexpr int kDwTT = dwconv::kSegLen;   // positions per staged tile (every stage-1 kernel)
 constexpr int kDwThreads = 256;
+
+// Long filters: the assignment of block offsets to wave slots (dwconv::LongKDwTable), balanced by work.
+// Work of an offset d = the 64-position chunks in which it reaches the row; a group of n offsets runs n matrix
+// instructions over the union of its offsets' chunks.  Groups are cut greedily under a cap on size (9) and on
+// work; the cap is searched so that at most two groups per slot suffice and the busiest slot is as light as
+// possible; groups go to slots heaviest first, each to the least loaded slot that still has room.  The result
+// depends on (L, K, pad, slots) only and is cached.
+std::shared_ptr<const dwconv::LongKDwTable> longk_dw_table(const Shape &s, int wgs, int *max_group)
+{
+    struct Entry { std::shared_ptr<const dwconv::LongKDwTable> table; int max_group; };
+    static std::mutex mu;
+    static std::map<std::array<int, 4>, Entry> cache;
+    const std::array<int, 4> key = {s.L, s.K, s.pad, wgs};
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) { *max_group = it->second.max_group; return it->second.table; }
+
+    const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
+    const int NCH = (s.L + 63) / 64;
+    const int nslots = wgs * dwconv::kLkWaves;
+    auto fdiv = [](int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); };
+    auto ch_lo = [&](int d) { const int v = -fdiv(63 + 16 * d, 64); return v > 0 ? v : 0; };      // ceil((-63 - 16 d) / 64)
+    auto ch_hi = [&](int d) { const int v = fdiv(s.L - 1 - 16 * d, 64); return v < NCH - 1 ? v : NCH - 1; };
+    auto group_work = [&](int a, int n) {           // n offsets a .. a + n - 1
+        const int c = ch_hi(a) - ch_lo(a + n - 1) + 1;
+        return (long long)n * (c > 0 ? c : 0);
+    };
+    long long exact = 0;
+    for (int d = dmin; d <= dmax; ++d) exact += group_work(d, 1);
+    struct Group { int a, n; long long w; };
+    std::vector<Group> best_groups;
+    std::vector<int> best_slot;
+    long long best_max = -1;
+    for (int pct = 40; pct <= 400; pct += 4) {
+        const long long cap = exact * pct / (100LL * nslots) + 1;
+        std::vector<Group> groups;
+        for (int d = dmin; d <= dmax;) {
+            int n = 1;
+            while (d + n <= dmax && n < dwconv::kLkDwMaxGD && group_work(d, n + 1) <= cap) ++n;
+            groups.push_back({d, n, group_work(d, n)});
+            d += n;
+        }
+        if ((int)groups.size() > 2 * nslots || (int)groups.size() > dwconv::kLkDwMaxGroups) continue;
+        std::vector<int> order(groups.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+        std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return groups[x].w > groups[y].w; });
+        std::vector<long long> load(nslots, 0);
+        std::vector<int> count(nslots, 0), slot_of(groups.size(), 0);
+        for (int gi : order) {
+            int pick = -1;
+            for (int j = 0; j < nslots; ++j)
+                if (count[j] < 2 && (pick < 0 || load[j] < load[pick])) pick = j;
+            load[pick] += groups[gi].w;
+            ++count[pick];
+            slot_of[gi] = pick;
+        }
+        const long long mx = *std::max_element(load.begin(), load.end());
+        if (best_max < 0 || mx < best_max) { best_max = mx; best_groups = groups; best_slot = slot_of; }
+    }
+    if (best_max < 0 || nslots > dwconv::kLkDwMaxSlots) {        // no assignment with two groups per slot
+        cache[key] = Entry{nullptr, 0};
+        *max_group = 0;
+        return nullptr;
+    }
+    auto table = std::make_shared<dwconv::LongKDwTable>();
+    for (int i = 0; i < dwconv::kLkDwMaxGroups; ++i) { table->da[i] = 0; table->n[i] = 0; }
+    for (int j = 0; j < dwconv::kLkDwMaxSlots; ++j) table->g0[j] = table->g1[j] = dwconv::kLkDwNoGroup;
+    int mg = 1;
+    for (size_t i = 0; i < best_groups.size(); ++i) {
+        table->da[i] = (short)best_groups[i].a;
+        table->n[i] = (unsigned char)best_groups[i].n;
+        if (best_groups[i].n > mg) mg = best_groups[i].n;
+        const int j = best_slot[i];
+        if (table->g0[j] == dwconv::kLkDwNoGroup) table->g0[j] = (unsigned char)i;
+        else table->g1[j] = (unsigned char)i;
+    }
+    static const int kGd[] = {1, 2, 3, 4, 6, 9};
+    int gd = 9;
+    for (int v : kGd)
+        if (v >= mg) { gd = v; break; }
+    cache[key] = Entry{table, gd};
+    *max_group = gd;
+    return table;
+}
 
 // Depends on the shape only, so stage 1, stage 2 and the workspace query always agree.
 DwPlan plan_dw(const Shape &s)
@@ -350,19 +439,15 @@ DwPlan plan_dw(const Shape &s)
     }
     // long filters: offsets are split over waves instead, partials land in exactly two slices
     p.longk = false;
-    p.lk_wgs = p.lk_gd = p.lk_groups = 0;
+    p.lk_wgs = p.lk_gd = 0;
     const int NCH = (s.L + 63) / 64;
     if (nd > kMfmaMaxND && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
         const int per_wg = 2 * dwconv::kLkWaves * dwconv::kLkDwMaxGD;
         p.lk_wgs = (nd + per_wg - 1) / per_wg;
-        const int slots2 = 2 * dwconv::kLkWaves * p.lk_wgs;
-        const int need = (nd + slots2 - 1) / slots2;
-        static const int kGd[] = {1, 2, 3, 4, 6, 9};
-        p.lk_gd = 9;
-        for (int gd : kGd)
-            if (gd >= need) { p.lk_gd = gd; break; }
-        p.lk_groups = (nd + p.lk_gd - 1) / p.lk_gd;
+        p.lk_table = longk_dw_table(s, p.lk_wgs, &p.lk_gd);
+    }
+    if (p.lk_table) {
         p.longk = true;
         p.S = 2;
         p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
@@ -476,7 +561,7 @@ void launch_dw_longk_gd(const void *x, const void *dy, float *part, const Shape 
 {
     hipLaunchKernelGGL((dwconv::dw_longk_kernel<T, GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
                        dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(x), static_cast<const T *>(dy),
-                       part, g);
+                       part, g, *p.lk_table);
 }
 
 // Returns -1 when the pointers do not fit the long-filter matrix-core kernel.
@@ -488,7 +573,6 @@ int launch_dw_partial_longk(const void *x, const void *dy, float *part, const Sh
     g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K; g.pad = s.pad;
     g.dmin = toeplitz_dmin(s.pad); g.dmax = toeplitz_dmax(s.K, s.pad);
     g.NCH = (s.L + 63) / 64;
-    g.groups = p.lk_groups;
     const size_t lds = dwconv::longk_dw_lds_bytes(s.L, g.NCH);
     bool ok = true;
     switch (p.lk_gd) {

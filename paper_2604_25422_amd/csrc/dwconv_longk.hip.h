@@ -143,9 +143,10 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_kernel(const T *__re
 // Stage 1 of the weight gradient for long filters (eq. (dk_def)):
 //     G_d[q'][q] = sum_b sum_n X[n + d][q'] dY[n][q],      dw[j] = sum over 16 d + q' - q + pad = j.
 // There are hundreds of offsets d, each with a 16x16 accumulator, so the offsets are what is split
-// over waves: with W = 16 * gridDim.y waves per channel the offsets are cut into 2 W groups of GD and
-// wave slot s owns groups s and 2 W - 1 - s (a causal filter makes the work of a group fall linearly
-// with |d|, the pairing evens it out).  A workgroup stages two rows of x (256 zero floats on both
+// over waves: they are cut into contiguous groups of at most GD offsets and every one of the
+// W = 16 * gridDim.y wave slots of a channel owns at most two groups.  An offset far from lag 0 reaches
+// the row in few chunks, one near lag 0 in all of them, so the host sizes the groups and pairs heavy with
+// light ones until the slots carry about equal work (LongKDwTable).  A workgroup stages two rows of x (256 zero floats on both
 // sides) and of dY at a time; a wave walks the 64-position chunks that its groups can touch: one LDS
 // dword of dY and, per offset, one of x feed one matrix instruction.  At the end each wave sums the
 // diagonals of its accumulators into the taps of its groups and stores them into slice (group & 1)
@@ -158,7 +159,19 @@ struct LongKDwGeom {
     int B, C, L, K, pad;
     int dmin, dmax;
     int NCH;        // 64-position chunks per row
-    int groups;     // number of offset groups, ceil((dmax - dmin + 1) / GD)
+};
+
+// Which offsets a wave slot owns.  The block offsets dmin..dmax are cut into contiguous groups of 1..9 offsets
+// (group i: offsets da[i] .. da[i] + n[i] - 1, in increasing order of i); every wave slot owns at most two groups.
+// The host balances the work (offsets near the edge of the filter reach the row in few chunks, offsets near lag 0
+// in all of them) and passes the table by value with the launch.
+constexpr int kLkDwMaxGroups = 128;
+constexpr int kLkDwMaxSlots = 64;
+constexpr unsigned char kLkDwNoGroup = 255;
+struct LongKDwTable {
+    short da[kLkDwMaxGroups];
+    unsigned char n[kLkDwMaxGroups];
+    unsigned char g0[kLkDwMaxSlots], g1[kLkDwMaxSlots];
 };
 
 inline size_t longk_dw_lds_bytes(int L, int NCH)
@@ -176,9 +189,32 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, s
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
 }
 
+// The chunks [ch_lo, ch_hi] of one staged row for a group of N offsets.
+template <int N, int GD>
+__device__ __forceinline__ void lk_dw_chunks(floatx4 (&G)[GD], const float *xp, const float *gp, int ch_lo, int ch_hi)
+{
+#pragma unroll 2
+    for (int ch = ch_lo; ch <= ch_hi; ++ch) {
+        const float gq = gp[64 * ch];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const float xa = xp[64 * ch + 16 * i];
+            G[i] = mfma16x16x4(xa, gq, G[i]);
+        }
+    }
+}
+// ... for a group size known at run time (wave-uniform)
+template <int GD, int N = GD>
+__device__ __forceinline__ void lk_dw_chunks_n(int n, floatx4 (&G)[GD], const float *xp, const float *gp, int ch_lo, int ch_hi)
+{
+    if (n == N) lk_dw_chunks<N, GD>(G, xp, gp, ch_lo, ch_hi);
+    else if constexpr (N > 1) lk_dw_chunks_n<GD, N - 1>(n, G, xp, gp, ch_lo, ch_hi);
+}
+
 template <typename T, int GD>
 __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__restrict__ x, const T *__restrict__ dy,
-                                                                     float *__restrict__ part, const LongKDwGeom g)
+                                                                     float *__restrict__ part, const LongKDwGeom g,
+                                                                     const LongKDwTable tb)
 {
     extern __shared__ __align__(16) float lk_smem[];
     const int XW = (g.L + 2 * kLkDwMargin + 3) & ~3;        // floats of one staged x row
@@ -190,18 +226,19 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = blockIdx.x;
-    const int W = (int)gridDim.y * kLkWaves;                // wave slots of this channel
     const int slot = (int)blockIdx.y * kLkWaves + wave;
 
-    // the two groups of this wave: [da, db] inclusive, empty if da > db
-    int grp[2], da[2], db[2], ch_lo[2], ch_hi[2];
-    grp[0] = slot;
-    grp[1] = 2 * W - 1 - slot;
+    // the two groups of this wave: offsets [da, db] inclusive, empty if da > db
+    int grp[2], da[2], db[2], nn[2], ch_lo[2], ch_hi[2];
+    grp[0] = tb.g0[slot];
+    grp[1] = tb.g1[slot];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-        const bool valid = grp[k] < g.groups;
-        da[k] = g.dmin + grp[k] * GD;
-        db[k] = valid ? min(g.dmax, da[k] + GD - 1) : da[k] - 1;
+        const bool valid = grp[k] != kLkDwNoGroup;
+        const int gi = valid ? grp[k] : 0;
+        nn[k] = valid ? min((int)tb.n[gi], GD) : 0;
+        da[k] = tb.da[gi];
+        db[k] = da[k] + nn[k] - 1;
         // chunks in which some offset of the group reaches the row
         ch_lo[k] = max(0, ceil_div(-63 - 16 * db[k], 64));
         ch_hi[k] = valid ? min(g.NCH - 1, floor_div(g.L - 1 - 16 * da[k], 64)) : -1;
@@ -241,16 +278,8 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
                 // A operand: X[n0 + kk + d][q'] = sx[64 ch + 16 d + lane];  B operand: dY[n0 + kk][q] = sg[64 ch + lane]
                 const float *xp = sx + rb * XW + kLkDwMargin + 16 * da[k] + lane;
                 const float *gp = sg + rb * GW + lane;
-#pragma unroll 2
-                for (int ch = ch_lo[k]; ch <= ch_hi[k]; ++ch) {
-                    const float gq = gp[64 * ch];
-#pragma unroll
-                    for (int i = 0; i < GD; ++i) {
-                        const float xa = xp[64 * ch + 16 * i];
-                        if (k == 0) G0[i] = mfma16x16x4(xa, gq, G0[i]);
-                        else G1[i] = mfma16x16x4(xa, gq, G1[i]);
-                    }
-                }
+                if (k == 0) lk_dw_chunks_n<GD>(nn[0], G0, xp, gp, ch_lo[0], ch_hi[0]);
+                else lk_dw_chunks_n<GD>(nn[1], G1, xp, gp, ch_lo[1], ch_hi[1]);
             }
         }
     }
