@@ -21,6 +21,7 @@
 #include "dwconv_dw_direct.hip.h"
 #include "dwconv_longk.hip.h"
 #include "dwconv_mfma.hip.h"
+#include "dwconv_rowbatch.hip.h"
 #include "dwconv_valu.hip.h"
 
 namespace {
@@ -69,13 +70,15 @@ constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below 
 // its geometry.  Depends on the shape only; the gap is the same for the forward and the input-gradient pads.
 struct RowsPlan {
     bool on;
+    bool batch;             // rows of at most 64 positions: sixteen rows of a channel per matrix tile instead
+    int units;              // batch: groups of sixteen rows per channel
     int nvs;                // 1024-position segments of the virtual row
     dwconv::RowsMap map;
 };
 RowsPlan plan_rows(const Shape &s)
 {
     RowsPlan r;
-    r.on = false; r.nvs = 0;
+    r.on = false; r.batch = false; r.units = 0; r.nvs = 0;
     r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     if (s.dtype != DWCONV_F32 || s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return r;
@@ -90,6 +93,11 @@ RowsPlan plan_rows(const Shape &s)
     r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
     r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
     r.map.bytes = (unsigned)(elems * 4);
+    // byte offsets inside a unit of sixteen rows stay below the out-of-row marker
+    if (s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * 4 < (1ll << 30)) {
+        r.batch = true;
+        r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
+    }
     return r;
 }
 
@@ -173,6 +181,38 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     if constexpr (std::is_same<T, float>::value) {
         // fp32 short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
         const RowsPlan rp = plan_rows(s);
+        if (rp.batch) {
+            dwconv::RowBatchGeom rg;
+            rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
+            rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
+            rg.m = (s.L + 15) / 16;
+            rg.n_units = rp.units;
+            auto launch_batch = [&](auto kernel) -> int {
+                // one resident round of waves: J per channel, each walking units j, j + J, ...
+                const long long resident = resident_waves(kernel, 64 * dwconv::kRbCorrWaves);
+                long long J = resident / s.C;
+                if (J < 1) J = 1;
+                if (J > rg.n_units) J = rg.n_units;
+                const long long upw = (rg.n_units + J - 1) / J;
+                J = (rg.n_units + upw - 1) / upw;
+                const long long blocks = ((long long)s.C * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
+                if (blocks > 0x1fffffffLL) return -1;
+                rg.J = (int)J;
+                const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L) * sizeof(float);
+                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
+                                   static_cast<const float *>(in), static_cast<const float *>(f),
+                                   static_cast<float *>(out), rg);
+                return launch_status();
+            };
+            switch (nd) {
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<2>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<3>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<4>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<5>);
+            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<6>);
+            default: return -1;
+            }
+        }
         if (rp.on) {
             const long long total = (long long)rp.nvs * s.C;
             if (total > 0x3fffffffLL) return -1;
@@ -408,7 +448,7 @@ DwPlan plan_dw(const Shape &s)
     DwPlan p;
     p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
     p.rows = plan_rows(s);
-    const long long tiles = p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
+    const long long tiles = p.rows.batch ? p.rows.units : p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
     const long long items = p.rows.on ? tiles : (long long)s.B * tiles;                  // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
@@ -418,7 +458,10 @@ DwPlan plan_dw(const Shape &s)
     p.single = false;
     if (mfma_shape && s.C % kComputeUnits == 0 && s.C / kComputeUnits <= 3) {
         const int wpb = 16 / (s.C / kComputeUnits);
-        if (items >= 2 * wpb) { p.wpb = wpb; p.single = true; }
+        // (sixteen-row units of rows longer than 48 positions need more LDS than sixteen waves have)
+        const bool fits = !p.rows.batch ||
+                          (size_t)wpb * (size_t)(dwconv::rb_dw_wave_floats(s.L, nd) + 16 * nd) * sizeof(float) <= kMaxLdsBytes;
+        if (items >= 2 * wpb && fits) { p.wpb = wpb; p.single = true; }
     }
     long long want = (kTargetWaves / p.wpb + s.C - 1) / s.C;   // blocks per channel
     if (p.single) want = 1;
@@ -489,7 +532,15 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         // fp32 rows go from memory straight into LDS
         constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
-        if (p.rows.on) {
+        if (p.rows.batch) {
+            auto kernel = dwconv::dw_rowbatch_kernel<ND, W>;
+            const size_t lds_rb = (size_t)W * (size_t)(dwconv::rb_dw_wave_floats(s.L, ND) + 16 * ND) * sizeof(float);
+            if (lds_rb > kMaxLdsBytes) return -1;
+            if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds_rb, st,
+                               static_cast<const float *>(x), static_cast<const float *>(dy), part,
+                               static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+        } else if (p.rows.on) {
             auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
             hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
@@ -680,6 +731,7 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
 {
     *wrote_dw = false;
     if (p.longk) return -1;
+    if (p.rows.batch) return -1;      // rows of at most 64 positions: the two separate kernels move less per output
     // bf16: whole 16-byte granules of 8 elements
     if (s.dtype == DWCONV_BF16 && (s.L % 8) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
@@ -823,7 +875,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const Shape s{B, C, L, K, pad_left, dtype};
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
-    return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
+    return (!p.longk && !p.rows.batch && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
             L <= kMfmaMaxL) ? 1 : 0;
 }
 
