@@ -187,29 +187,42 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
             rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
             rg.m = (s.L + 15) / 16;
             rg.n_units = rp.units;
+            // two channels per wave where that makes whole cache lines of rows that are not (L * 4 % 128 != 0);
+            // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
+            const int nc = (s.C % 2 == 0 && (s.L * 4) % 128 != 0 && s.L <= 48 && nd <= 5) ? 2 : 1;
             auto launch_batch = [&](auto kernel) -> int {
-                // one resident round of waves: J per channel, each walking units j, j + J, ...
+                // one resident round of waves: J per channel group, each walking units j, j + J, ...
+                const long long groups = s.C / nc;
                 const long long resident = resident_waves(kernel, 64 * dwconv::kRbCorrWaves);
-                long long J = resident / s.C;
+                long long J = resident / groups;
                 if (J < 1) J = 1;
                 if (J > rg.n_units) J = rg.n_units;
                 const long long upw = (rg.n_units + J - 1) / J;
                 J = (rg.n_units + upw - 1) / upw;
-                const long long blocks = ((long long)s.C * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
+                const long long blocks = (groups * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
                 if (blocks > 0x1fffffffLL) return -1;
                 rg.J = (int)J;
-                const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L) * sizeof(float);
+                const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L, nc) * sizeof(float);
                 hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
                                    static_cast<const float *>(in), static_cast<const float *>(f),
                                    static_cast<float *>(out), rg);
                 return launch_status();
             };
+            if (nc == 2) {
+                switch (nd) {
+                case 2: return launch_batch(dwconv::corr_rowbatch_kernel<2, 2>);
+                case 3: return launch_batch(dwconv::corr_rowbatch_kernel<3, 2>);
+                case 4: return launch_batch(dwconv::corr_rowbatch_kernel<4, 2>);
+                case 5: return launch_batch(dwconv::corr_rowbatch_kernel<5, 2>);
+                default: return -1;
+                }
+            }
             switch (nd) {
-            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<2>);
-            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<3>);
-            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<4>);
-            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<5>);
-            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<6>);
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<2, 1>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<3, 1>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<4, 1>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<5, 1>);
+            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<6, 1>);
             default: return -1;
             }
         }
@@ -348,6 +361,7 @@ struct DwPlan {
     int S;                 // partial slices per coefficient
     RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
     int wpb;               // waves per block of the matrix-core stage-1 kernels
+    int dw_nc;             // short rows, sixteen-row units: channels per block of the stage-1 kernel (1 or 2)
     bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
     int tiles_per_row;     // segments the matrix-core kernels walk per row (per virtual row for short rows)
     int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel (always real rows)
@@ -448,22 +462,31 @@ DwPlan plan_dw(const Shape &s)
     DwPlan p;
     p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
     p.rows = plan_rows(s);
-    const long long tiles = p.rows.batch ? p.rows.units : p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
-    const long long items = p.rows.on ? tiles : (long long)s.B * tiles;                  // per channel
+    long long tiles = p.rows.batch ? p.rows.units : p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
+    long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
     // waves takes a whole channel: no slices, no second stage.
     p.wpb = dwconv::kWavesPerBlock;
     p.single = false;
+    p.dw_nc = 1;
     if (mfma_shape && s.C % kComputeUnits == 0 && s.C / kComputeUnits <= 3) {
         const int wpb = 16 / (s.C / kComputeUnits);
         // (sixteen-row units of rows longer than 48 positions need more LDS than sixteen waves have)
-        const bool fits = !p.rows.batch ||
-                          (size_t)wpb * (size_t)(dwconv::rb_dw_wave_floats(s.L, nd) + 16 * nd) * sizeof(float) <= kMaxLdsBytes;
+        const bool fits = !p.rows.batch || dwconv::rb_dw_lds_bytes(s.L, nd, wpb, 1) <= kMaxLdsBytes;
         if (items >= 2 * wpb && fits) { p.wpb = wpb; p.single = true; }
     }
-    long long want = (kTargetWaves / p.wpb + s.C - 1) / s.C;   // blocks per channel
+    long long groups = s.C;                                      // blocks along the channel axis
+    if (p.rows.batch && !p.single && s.C % 2 == 0 && (s.L * 4) % 128 != 0 && s.L <= 48) {
+        // two neighbouring channels per block: rows that are not whole cache lines become pieces that are;
+        // a unit is then eight rows of both channels
+        p.dw_nc = 2;
+        groups = s.C / 2;
+        tiles = (s.B + dwconv::kRbRows / 2 - 1) / (dwconv::kRbRows / 2);
+        items = tiles;
+    }
+    long long want = (kTargetWaves / p.wpb + groups - 1) / groups;   // blocks per channel (group)
     if (p.single) want = 1;
     if (want < 1) want = 1;
     if (want > 65535) want = 65535;
@@ -533,13 +556,19 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
         if (p.rows.batch) {
-            auto kernel = dwconv::dw_rowbatch_kernel<ND, W>;
-            const size_t lds_rb = (size_t)W * (size_t)(dwconv::rb_dw_wave_floats(s.L, ND) + 16 * ND) * sizeof(float);
-            if (lds_rb > kMaxLdsBytes) return -1;
-            if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-            hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds_rb, st,
-                               static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                               static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+            auto launch_rb = [&](auto kernel, int nc) -> int {
+                const size_t lds_rb = dwconv::rb_dw_lds_bytes(s.L, ND, W, nc);
+                if (lds_rb > kMaxLdsBytes) return -1;
+                if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+                hipLaunchKernelGGL(kernel, dim3((unsigned)(s.C / nc), (unsigned)p.S), dim3(64 * W), lds_rb, st,
+                                   static_cast<const float *>(x), static_cast<const float *>(dy), part,
+                                   static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+                return launch_status();
+            };
+            if constexpr (W == dwconv::kWavesPerBlock) {
+                if (p.dw_nc == 2) return launch_rb(dwconv::dw_rowbatch_kernel<ND, W, 2>, 2);
+            }
+            return launch_rb(dwconv::dw_rowbatch_kernel<ND, W, 1>, 1);
         } else if (p.rows.on) {
             auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;

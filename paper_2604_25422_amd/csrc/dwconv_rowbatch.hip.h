@@ -20,21 +20,26 @@ constexpr int kRbMaxL = 64;       // longest row
 constexpr int kRbMaxBlocks = 4;   // 16-blocks per row
 constexpr int kRbMaxLoads = 4;    // 16 rows * (L / 4) granules over 64 lanes
 
-// Pitch (floats) of a row in the weight-gradient kernel's LDS image: at least the row rounded up to whole blocks,
-// and congruent to 16 or 48 modulo 64 so that the four rows one operand read touches (64 bytes each) fall into
-// four different quarters of the LDS banks.
-__host__ __device__ constexpr int rb_dw_pitch(int L)
+// Weight-gradient kernel: a wave owns NC neighbouring channels and works on units of 16 / NC rows (b), so a unit
+// is the same number of bytes either way.  Pitch (floats) of a row (b, c0 .. c0 + NC - 1) in the LDS image: every
+// channel rounded up to whole 16-blocks, the sum congruent to 16 or 48 modulo 64 so that the four rows one operand
+// read touches (64 bytes each) fall into four different quarters of the LDS banks.
+__host__ __device__ constexpr int rb_dw_pitch(int L, int NC)
 {
-    int p = (L + 15) / 16 * 16;
+    int p = NC * ((L + 15) / 16 * 16);
     while (p % 64 != 16 && p % 64 != 48) p += 16;
     return p;
 }
 // Floats of one wave's LDS region in the weight-gradient kernel: both operands, or the diagonal image of the epilogue.
-__host__ __device__ constexpr int rb_dw_wave_floats(int L, int ND)
+__host__ __device__ constexpr int rb_dw_wave_floats(int L, int ND, int NC)
 {
-    const int stage = 2 * kRbRows * rb_dw_pitch(L);
+    const int stage = 2 * (kRbRows / NC) * rb_dw_pitch(L, NC);
     const int diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
     return stage > diag ? stage : diag;
+}
+__host__ __device__ constexpr size_t rb_dw_lds_bytes(int L, int ND, int W, int NC)
+{
+    return (size_t)W * (size_t)(rb_dw_wave_floats(L, ND, NC) + NC * 16 * ND) * sizeof(float);
 }
 
 struct RowBatchGeom {
@@ -55,83 +60,87 @@ __device__ __forceinline__ uintx4 rb_unit_resource(const float *base, int nr, in
     return r;
 }
 
-// Floats of one wave's LDS region in the correlate kernel: the input image (16-block mi of row r at float
-// (mi * 16 + r) * kLdsBlockStride, the layout the strided 16-byte operand reads of the long-row kernel use), then
-// the output image (row r at r * rb_out_pitch(L); the pitch is 4 modulo 8 floats so that the 16-byte tile writes
-// of sixteen rows spread over the banks).
-__host__ __device__ constexpr int rb_out_pitch(int L) { return (L % 8) == 0 ? L + 4 : L; }
-__host__ __device__ constexpr int rb_corr_wave_floats(int L)
-{
-    return (L + 15) / 16 * 16 * kLdsBlockStride + kRbRows * rb_out_pitch(L);
-}
-constexpr int kRbCorrWaves = 4;   // waves per block: four neighbouring channels, whose rows share cache lines
+// LDS image of a unit in the correlate kernel, one per wave: row r of the unit at float r * pitch; inside it the
+// NC channels the wave owns, each rounded up to whole 16-blocks (the floats between the end of a row and the end
+// of its last block stay zero).  The pitch is 4 modulo 8 floats, so the 16-byte operand reads and tile writes of
+// sixteen rows spread over the banks.  The outputs of a unit replace its inputs in the same image.
+__host__ __device__ constexpr int rb_corr_pitch(int L, int NC) { return NC * ((L + 15) / 16 * 16) + 4; }
+__host__ __device__ constexpr int rb_corr_wave_floats(int L, int NC) { return kRbRows * rb_corr_pitch(L, NC); }
+constexpr int kRbCorrWaves = 4;   // waves per block: neighbouring channels, whose rows share cache lines
 
-// out[b, c, t] = sum_j in~[b, c, t + j - pad] * f_eff[c, j].   Grid = C * J waves, channel fastest, four to a
-// block.  Per unit: the loads of the next unit are issued into registers, the current one is contracted, the
-// D tiles go to the output image, the prefetch registers are drained into the input image, and the output image
-// is stored with the lane-to-granule map of the loads (whole rows per store instruction; streaming stores, as in
-// the long-row kernel).
-template <int ND>
+// out[b, c, t] = sum_j in~[b, c, t + j - pad] * f_eff[c, j].
+// A wave owns NC neighbouring channels (NC divides C): their rows (b, c0 .. c0 + NC - 1) are one contiguous piece
+// of NC * L elements, so with NC = 2 a wave touches whole cache lines where rows of 48 elements would share them
+// with the neighbouring channel's wave.  Grid = (C / NC) * J waves, channel group fastest, four waves to a block.
+// Per unit: the loads of the next unit are issued into registers; the current one is contracted out of the LDS
+// image, channel by channel, and the tiles of a channel replace its inputs; then every lane swaps its granules of
+// the image (the lane-to-granule map of the loads): the outputs go out as whole rows (streaming stores, as in the
+// long-row kernel), the prefetched inputs of the next unit come in.
+template <int ND, int NC>
 __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_rowbatch_kernel(
     const float *__restrict__ in, const float *__restrict__ f, float *__restrict__ out, const RowBatchGeom g)
 {
+    // two channels per wave: rows of at most 48 positions (register budget)
+    constexpr int NLD = NC == 2 ? 6 : kRbMaxLoads;
+    constexpr int MB = NC == 2 ? 3 : kRbMaxBlocks;
     extern __shared__ __align__(16) float dyn_lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int i16 = lane & 15;      // A: output position r;  B/D: row of the unit
     const int k4 = lane >> 4;       // contraction sub-index;  D: position group
-    float *sw = dyn_lds + wave * rb_corr_wave_floats(g.L);
-    float *so = sw + g.m * 16 * kLdsBlockStride;
-    const int Lo = rb_out_pitch(g.L);
+    const int Lc = 16 * g.m;
+    const int Lo = NC * Lc + 4;
+    float *sw = dyn_lds + wave * (kRbRows * Lo);
 
+    const int Cg = g.C / NC;                    // channel groups
     const int id = (int)blockIdx.x * kRbCorrWaves + wave;
-    const int c = id % g.C;
-    int unit = id / g.C;
+    const int c0 = NC * (id % Cg);
+    int unit = id / Cg;
     if (unit >= g.J) return;                    // (no workgroup barrier below)
 
     const int CL = g.C * g.L;
     const int Lg = g.L >> 2;                    // granules per row
-    const int NG = kRbRows * Lg;                // granules per unit
+    const int NG = kRbRows * NC * Lg;           // granules per unit
     const int nld = (NG + 63) >> 6;             // loads per lane (wave-uniform)
-    int gl_off[kRbMaxLoads], lds_idx[kRbMaxLoads], so_idx[kRbMaxLoads];
+    int gl_off[NLD], img[NLD];
 #pragma unroll
-    for (int i = 0; i < kRbMaxLoads; ++i) {
+    for (int i = 0; i < NLD; ++i) {
         const int gi = lane + 64 * i;
-        const int r = gi / Lg, cg = gi - r * Lg;
+        const int r = gi / (NC * Lg), cg = gi - r * (NC * Lg);
+        const int h = (NC > 1 && cg >= Lg) ? 1 : 0;
+        static_assert(NC <= 2, "one or two channels per wave");
         gl_off[i] = gi < NG ? 4 * (r * CL + 4 * cg) : kOutOfRow;
-        lds_idx[i] = gi < NG ? (((cg >> 2) * 16 + r) * kLdsBlockStride + 4 * (cg & 3)) : 0;
-        so_idx[i] = gi < NG ? r * Lo + 4 * cg : 0;
+        img[i] = gi < NG ? r * Lo + h * Lc + 4 * (cg - h * Lg) : 0;
     }
-    // zeros once: the part of the last block past the end of the row is never written again
-    for (int i = lane; i < g.m * 16 * kLdsBlockStride / 4; i += 64)
+    for (int i = lane; i < kRbRows * Lo / 4; i += 64)
         *reinterpret_cast<float4 *>(sw + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_fence();
 
-    uintx4 pre[kRbMaxLoads];
+    uintx4 pre[NLD];
     auto prefetch = [&](int u) {
         const int b0 = kRbRows * u;
         const int nr = g.B - b0 < kRbRows ? g.B - b0 : kRbRows;        // rows past the batch read as zeros
-        const uintx4 r = rb_unit_resource(in + ((size_t)b0 * (size_t)g.C + (size_t)c) * (size_t)g.L, nr, CL, g.L);
+        const uintx4 r = rb_unit_resource(in + ((size_t)b0 * (size_t)g.C + (size_t)c0) * (size_t)g.L, nr, CL, NC * g.L);
 #pragma unroll
-        for (int i = 0; i < kRbMaxLoads; ++i)
+        for (int i = 0; i < NLD; ++i)
             if (i < nld) pre[i] = buffer_load_x4_untracked(r, gl_off[i]);
     };
     auto drain = [&]() {
         wait_untracked_loads();
         release_after_wait(pre);
 #pragma unroll
-        for (int i = 0; i < kRbMaxLoads; ++i)
-            if (i < nld && lane + 64 * i < NG)
-                *reinterpret_cast<float4 *>(sw + lds_idx[i]) = Raw4<float>::widen(pre[i]);
+        for (int i = 0; i < NLD; ++i)
+            if (i < nld && lane + 64 * i < NG) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<float>::widen(pre[i]);
     };
     prefetch(unit);
     drain();
     wave_lds_fence();
 
-    // Toeplitz operands: A[d][v] (lane (r, k)) = f_eff[16 (dmin + d) + 4k + v - r + pad]
-    float A[ND][4];
-    {
-        const float *f_c = f + (size_t)c * (size_t)g.K;
+    // Toeplitz operands: A[h][d][v] (lane (r, k)) = f_eff[c0 + h][16 (dmin + d) + 4k + v - r + pad]
+    float A[NC][ND][4];
+#pragma unroll
+    for (int h = 0; h < NC; ++h) {
+        const float *f_c = f + (size_t)(c0 + h) * (size_t)g.K;
 #pragma unroll
         for (int d = 0; d < ND; ++d)
 #pragma unroll
@@ -140,47 +149,60 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
                 const bool ok = j >= 0 && j < g.K;
                 const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
                 const float a = f_c[jc];
-                A[d][v] = ok ? a : 0.f;
+                A[h][d][v] = ok ? a : 0.f;
             }
     }
-    const float *sp = sw + i16 * kLdsBlockStride + 4 * k4;
-    float *so_lane = so + i16 * Lo + 4 * k4;
+    float *sp = sw + i16 * Lo + 4 * k4;
 
     for (;;) {
         const int unit_n = unit + g.J;
         const bool more = unit_n < g.n_units;
         if (more) prefetch(unit_n);
-        // lane (row i16 of the unit, position group k4) owns outputs 16 mo + 4 k4 + 0..3 of block mo
+        // lane (row i16 of the unit, position group k4) owns outputs 16 mo + 4 k4 + 0..3 of block mo; one channel
+        // at a time: its tiles replace its own inputs once all of them are computed
 #pragma unroll
-        for (int mo = 0; mo < kRbMaxBlocks; ++mo) {
-            if (mo < g.m) {
+        for (int h = 0; h < NC; ++h) {
+            floatx4 acc[MB];
+#pragma unroll
+            for (int mo = 0; mo < MB; ++mo) {
                 floatx4 a4 = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (mo < g.m) {
 #pragma unroll
-                for (int d = 0; d < ND; ++d) {
-                    const int mi = mo + g.dmin + d;
-                    if (mi >= 0 && mi < g.m) {
-                        const float4 cur = *reinterpret_cast<const float4 *>(sp + mi * 16 * kLdsBlockStride);
-                        a4 = mfma16x16x4(A[d][0], cur.x, a4);
-                        a4 = mfma16x16x4(A[d][1], cur.y, a4);
-                        a4 = mfma16x16x4(A[d][2], cur.z, a4);
-                        a4 = mfma16x16x4(A[d][3], cur.w, a4);
+                    for (int d = 0; d < ND; ++d) {
+                        const int mi = mo + g.dmin + d;
+                        if (mi >= 0 && mi < g.m) {
+                            const float4 cur = *reinterpret_cast<const float4 *>(sp + h * Lc + 16 * mi);
+                            a4 = mfma16x16x4(A[h][d][0], cur.x, a4);
+                            a4 = mfma16x16x4(A[h][d][1], cur.y, a4);
+                            a4 = mfma16x16x4(A[h][d][2], cur.z, a4);
+                            a4 = mfma16x16x4(A[h][d][3], cur.w, a4);
+                        }
                     }
                 }
-                if (16 * mo + 4 * k4 < g.L)
-                    *reinterpret_cast<float4 *>(so_lane + 16 * mo) = make_float4(a4[0], a4[1], a4[2], a4[3]);
+                acc[mo] = a4;
             }
+            wave_lds_fence();
+#pragma unroll
+            for (int mo = 0; mo < MB; ++mo)
+                if (mo < g.m && 16 * mo + 4 * k4 < g.L)
+                    *reinterpret_cast<float4 *>(sp + h * Lc + 16 * mo) = make_float4(acc[mo][0], acc[mo][1], acc[mo][2], acc[mo][3]);
         }
         wave_lds_fence();
-        if (more) drain();
+        // every lane swaps its granules of the image: outputs out (stored as whole rows), inputs of the next unit in
+        wait_untracked_loads();
+        release_after_wait(pre);
         {
             const int b0 = kRbRows * unit;
             const int nr = g.B - b0 < kRbRows ? g.B - b0 : kRbRows;
             const int lim = 4 * nr * CL;                                                   // byte offsets of real rows
-            float *out_u = out + ((size_t)b0 * (size_t)g.C + (size_t)c) * (size_t)g.L;      // wave-uniform
+            float *out_u = out + ((size_t)b0 * (size_t)g.C + (size_t)c0) * (size_t)g.L;     // wave-uniform
 #pragma unroll
-            for (int i = 0; i < kRbMaxLoads; ++i)
-                if (i < nld && gl_off[i] < lim)
-                    st_elem4_stream(out_u + (gl_off[i] >> 2), *reinterpret_cast<const float4 *>(so + so_idx[i]));
+            for (int i = 0; i < NLD; ++i)
+                if (i < nld && lane + 64 * i < NG) {
+                    const float4 ov = *reinterpret_cast<const float4 *>(sw + img[i]);
+                    if (more) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<float>::widen(pre[i]);
+                    if (gl_off[i] < lim) st_elem4_stream(out_u + (gl_off[i] >> 2), ov);
+                }
         }
         wave_lds_fence();
         if (!more) break;
@@ -188,62 +210,71 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
     }
 }
 
-// Stage 1 of the weight gradient for short rows.  grid = (C, S), W waves per block; wave w of slice s takes the
-// units W s + w, W s + w + W S, ... of its channel (walked from the last batch to the first, see the long-row
-// kernel) and keeps ND 16x16 accumulators G_d for its whole life.  LDS image of a unit: rows of x, then rows
-// of dY, pitch rb_dw_pitch(L) floats, zeros between the end of a row and the end of its last block.  One matrix
-// instruction contracts four rows: A operand x[row 4 g + k][16 (mo + d) + q'], B operand dY[row 4 g + k][16 mo + q].
+// Stage 1 of the weight gradient for short rows.  grid = (C / NC, S), W waves per block; wave w of slice s takes
+// the units W s + w, W s + w + W S, ... of its channel group (walked from the last batch to the first, see the
+// long-row kernel) and keeps ND 16x16 accumulators G_d per channel for its whole life.  A unit is 16 / NC rows of
+// NC neighbouring channels (NC = 2 makes whole cache lines of rows of 48 elements, see corr_rowbatch_kernel).
+// LDS image of a unit: rows of x, then rows of dY, pitch rb_dw_pitch floats, zeros between the end of a row and
+// the end of its last block.  One matrix instruction contracts four rows:
+//     A operand x[row 4 g + k][c0 + h][16 (mo + d) + q'],  B operand dY[row 4 g + k][c0 + h][16 mo + q].
 // dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (gridDim.y == 1) they are the
 // weight gradient itself.
-template <int ND, int W>
+template <int ND, int W, int NC>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
     int B, int C, int L, int K, int pad, int dmin, int n_units)
 {
+    static_assert(NC == 1 || NC == 2, "one or two channels per wave");
+    constexpr int RU = kRbRows / NC;                          // rows per unit
+    constexpr int NLD = NC == 2 ? 3 : kRbMaxLoads;            // two channels: rows of at most 48 positions
     extern __shared__ __align__(16) float dyn_lds[];
-    const int wreg = rb_dw_wave_floats(L, ND);
+    const int wreg = rb_dw_wave_floats(L, ND, NC);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, k4 = lane >> 4;
-    const int c = blockIdx.x;
+    const int c0 = NC * (int)blockIdx.x;
     float *s_wave = dyn_lds + wave * wreg;
-    float *s_dw = dyn_lds + W * wreg + wave * (16 * ND);
-    const int Lp = rb_dw_pitch(L);
+    float *s_dw = dyn_lds + W * wreg;                         // [wave][h][16 ND]
+    const int Lp = rb_dw_pitch(L, NC);
     const int m = (L + 15) >> 4;
-    float *sx = s_wave, *sg = s_wave + kRbRows * Lp;
+    const int Lc = 16 * m;
+    float *sx = s_wave, *sg = s_wave + RU * Lp;
 
     const int CL = C * L;
     const int Lg = L >> 2;
-    const int NG = kRbRows * Lg;
+    const int NG = RU * NC * Lg;
     const int nld = (NG + 63) >> 6;
-    int gl_off[kRbMaxLoads], lds_idx[kRbMaxLoads];
+    int gl_off[NLD], lds_idx[NLD];
 #pragma unroll
-    for (int i = 0; i < kRbMaxLoads; ++i) {
+    for (int i = 0; i < NLD; ++i) {
         const int gi = lane + 64 * i;
-        const int r = gi / Lg, cg = gi - r * Lg;
+        const int r = gi / (NC * Lg), cg = gi - r * (NC * Lg);
+        const int h = (NC > 1 && cg >= Lg) ? 1 : 0;
         gl_off[i] = gi < NG ? 4 * (r * CL + 4 * cg) : kOutOfRow;
-        lds_idx[i] = gi < NG ? r * Lp + 4 * cg : 0;
+        lds_idx[i] = gi < NG ? r * Lp + h * Lc + 4 * (cg - h * Lg) : 0;
     }
-    for (int i = lane; i < 2 * kRbRows * Lp / 4; i += 64)
+    for (int i = lane; i < 2 * RU * Lp / 4; i += 64)
         *reinterpret_cast<float4 *>(s_wave + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_fence();
 
-    floatx4 G[ND];
+    floatx4 G[NC][ND];
 #pragma unroll
-    for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < NC; ++h)
+#pragma unroll
+        for (int d = 0; d < ND; ++d) G[h][d] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int stride = (int)gridDim.y * W;
     int unit = (int)blockIdx.y * W + wave;
-    uintx4 px[kRbMaxLoads], pg[kRbMaxLoads];
+    uintx4 px[NLD], pg[NLD];
     auto prefetch = [&](int u) {
-        const int b0 = kRbRows * (n_units - 1 - u);
-        const int nr = B - b0 < kRbRows ? B - b0 : kRbRows;
-        const size_t first = ((size_t)b0 * (size_t)C + (size_t)c) * (size_t)L;
-        const uintx4 rx = rb_unit_resource(x + first, nr, CL, L);
-        const uintx4 rg = rb_unit_resource(dy + first, nr, CL, L);
+        const int b0 = RU * (n_units - 1 - u);
+        const int nr = B - b0 < RU ? B - b0 : RU;
+        const size_t first = ((size_t)b0 * (size_t)C + (size_t)c0) * (size_t)L;
+        const uintx4 rx = rb_unit_resource(x + first, nr, CL, NC * L);
+        const uintx4 rg = rb_unit_resource(dy + first, nr, CL, NC * L);
 #pragma unroll
-        for (int i = 0; i < kRbMaxLoads; ++i)
+        for (int i = 0; i < NLD; ++i)
             if (i < nld) {
                 px[i] = buffer_load_x4_untracked(rx, gl_off[i]);
                 pg[i] = buffer_load_x4_untracked(rg, gl_off[i]);
@@ -254,7 +285,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
         release_after_wait(px);
         release_after_wait(pg);
 #pragma unroll
-        for (int i = 0; i < kRbMaxLoads; ++i)
+        for (int i = 0; i < NLD; ++i)
             if (i < nld && lane + 64 * i < NG) {
                 *reinterpret_cast<float4 *>(sx + lds_idx[i]) = Raw4<float>::widen(px[i]);
                 *reinterpret_cast<float4 *>(sg + lds_idx[i]) = Raw4<float>::widen(pg[i]);
@@ -270,18 +301,20 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
         const bool more = unit_n < n_units;
         if (more) prefetch(unit_n);
 #pragma unroll
-        for (int g4 = 0; g4 < kRbRows / 4; ++g4) {
-            const float *xrow = sx + (4 * g4 + k4) * Lp + i16;
-            const float *grow = sg + (4 * g4 + k4) * Lp + i16;
-            for (int mo = 0; mo < m; ++mo) {
-                const float bq = grow[16 * mo];
+        for (int g4 = 0; g4 < RU / 4; ++g4)
 #pragma unroll
-                for (int d = 0; d < ND; ++d) {
-                    const int mi = mo + dmin + d;
-                    if (mi >= 0 && mi < m) G[d] = mfma16x16x4(xrow[16 * mi], bq, G[d]);
+            for (int h = 0; h < NC; ++h) {
+                const float *xrow = sx + (4 * g4 + k4) * Lp + h * Lc + i16;
+                const float *grow = sg + (4 * g4 + k4) * Lp + h * Lc + i16;
+                for (int mo = 0; mo < m; ++mo) {
+                    const float bq = grow[16 * mo];
+#pragma unroll
+                    for (int d = 0; d < ND; ++d) {
+                        const int mi = mo + dmin + d;
+                        if (mi >= 0 && mi < m) G[h][d] = mfma16x16x4(xrow[16 * mi], bq, G[h][d]);
+                    }
                 }
             }
-        }
         wave_lds_fence();
         if (more) {
             drain();
@@ -291,14 +324,20 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     }
 
     // ---- per-wave diagonal sums, then the waves of the block in wave order
-    dw_wave_diagonal_sums<ND>(G, s_wave, s_dw, lane, K, pad, dmin);
+#pragma unroll
+    for (int h = 0; h < NC; ++h) {
+        dw_wave_diagonal_sums<ND>(G[h], s_wave, s_dw + (wave * NC + h) * (16 * ND), lane, K, pad, dmin);
+        wave_lds_fence();
+    }
     __syncthreads();
-    for (int j = tid; j < K; j += 64 * W) {
+    for (int e = tid; e < NC * K; e += 64 * W) {
+        const int h = e / K, j = e - h * K;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < W; ++w) sum += dyn_lds[W * wreg + w * (16 * ND) + j];
-        if (dw_out) dw_out[(size_t)c * (size_t)K + (size_t)j] = sum;
-        else part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
+        for (int w = 0; w < W; ++w) sum += s_dw[(w * NC + h) * (16 * ND) + j];
+        const size_t o = (size_t)(c0 + h) * (size_t)K + (size_t)j;
+        if (dw_out) dw_out[o] = sum;
+        else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = sum;
     }
 }
 
