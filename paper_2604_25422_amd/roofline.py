@@ -60,7 +60,7 @@ MEASURED_TRAFFIC_BYTES = {
     (2, "fwd"): 524861 * 1024, (2, "dx"): 524861 * 1024, (2, "dw_partial"): 539596 * 1024, (2, "bwd_fused"): 831223 * 1024,
     (3, "fwd"): 163881 * 1024, (3, "dx"): 163881 * 1024, (3, "dw_partial"): 271351 * 1024,
     (4, "fwd"): 393693 * 1024, (4, "dx"): 393693 * 1024, (4, "dw_partial"): 396079 * 1024, (4, "bwd_fused"): 598797 * 1024,
-    (5, "fwd"): 833328 * 1024, (5, "dx"): 833328 * 1024, (5, "dw_partial"): 1062859 * 1024, (5, "bwd_fused"): 1480983 * 1024,
+    (5, "fwd"): 786611 * 1024, (5, "dx"): 786611 * 1024, (5, "dw_partial"): 787015 * 1024,
 }
 
 
