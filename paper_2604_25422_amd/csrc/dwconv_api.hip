@@ -170,7 +170,6 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         if (spw < 1) spw = 1;
         const long long waves = (total_segs + spw - 1) / spw;
         long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
-        blocks = (blocks + 7) / 8 * 8;                               // whole rounds of the 8 XCDs
         g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
         g.step_rows = g.n_waves / g.segs_per_row;
         g.step_seg = g.n_waves % g.segs_per_row;
@@ -235,8 +234,9 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                 const long long resident = resident_waves(kernel, kThreads);
                 long long spw = (total + resident - 1) / resident;
                 if (spw < 1) spw = 1;
-                long long blocks = ((total + spw - 1) / spw + 7) / 8 * 8;
-                g.n_waves = (int)blocks;
+                const long long waves = (total + spw - 1) / spw;
+                long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+                g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
                 g.step_rows = g.n_waves / g.segs_per_row;
                 g.step_seg = g.n_waves % g.segs_per_row;
                 g.step_c = 0;
@@ -244,7 +244,6 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                                    static_cast<const float *>(f), static_cast<float *>(out), g, rp.map);
                 return launch_status();
             };
-            static_assert(dwconv::kCorrWavesPerBlock == 1, "one wave per block");
             switch (nd) {
             case 2: return launch_rows(dwconv::corr_mfma_kernel<float, 2, true>);
             case 3: return launch_rows(dwconv::corr_mfma_kernel<float, 3, true>);

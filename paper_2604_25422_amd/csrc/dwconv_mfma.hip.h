@@ -35,7 +35,7 @@ constexpr int kSegBlocks = 64;        // 16-blocks per segment: one segment = 10
 constexpr int kSegLen = kSegBlocks * 16;
 constexpr int kWavesPerBlock = 4;        // weight-gradient kernel (block-level final reduction)
 constexpr int kMfmaWavesPerSimd = 4;      // register budget both kernels are compiled for (512 / 4 = 128 per lane)
-constexpr int kCorrWavesPerBlock = 1;    // correlate kernel: waves are independent
+constexpr int kCorrWavesPerBlock = 4;    // correlate kernel: waves are independent; neighbours share halos
 
 // Orders LDS traffic of one wave: everything before is visible to every lane after.
 // The LDS regions below are private to a wave, so no workgroup barrier is needed.
@@ -195,11 +195,9 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     // Wave w walks segments w, w + n_waves, ...: at any moment the waves of the chip read one
     // contiguous stretch of memory, which spreads the traffic evenly over the HBM channels.
     // (row, seg, c) are wave-uniform and advanced without divisions.
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): wave index
-    // (id % 8) * (n_waves / 8) + id / 8 gives every XCD a contiguous run of segments, so the halo a
-    // segment shares with its neighbour is found in that XCD's L2.
-    const int id = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    const int wg = (g.n_waves % 8 == 0) ? (id % 8) * (g.n_waves / 8) + id / 8 : id;
+    // The four waves of a block take four consecutive segments, so three of the four halos a block
+    // needs are the tails of segments the same compute unit has just read.
+    const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
     int row = wg / g.segs_per_row;                 // b * C + c
     int seg = wg % g.segs_per_row;
     int c = ROWS ? seg : row % g.C;
@@ -377,8 +375,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int i16 = lane & 15;      // A: output position r;  B/D: block j
     const int k4 = lane >> 4;       // contraction group (k = 4 k4 + e);  D: row group
 
-    const int id = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    const int wg = (g.n_waves % 8 == 0) ? (id % 8) * (g.n_waves / 8) + id / 8 : id;
+    const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
     int row = wg / g.segs_per_row;                 // b * C + c
     int seg = wg % g.segs_per_row;
     int c = row % g.C;
