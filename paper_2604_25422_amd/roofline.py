@@ -56,10 +56,10 @@ def normalised_error(got, ref, ref_abs, floor=2.0 ** -100):
 # scaled by 2.00 and WRITE_SIZE by 1.00: what the same counters read for a plain 128 MiB device copy).
 # Keyed by (workload index, kernel); the figures and the commands are in the text summaries under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    (1, "fwd"): 262486 * 1024, (1, "dx"): 262486 * 1024, (1, "dw_partial"): 268469 * 1024, (1, "bwd_fused"): 407599 * 1024,
-    (2, "fwd"): 524861 * 1024, (2, "dx"): 524861 * 1024, (2, "dw_partial"): 539596 * 1024, (2, "bwd_fused"): 831223 * 1024,
+    (1, "fwd"): 262325 * 1024, (1, "dx"): 262325 * 1024, (1, "dw_partial"): 268418 * 1024, (1, "bwd_fused"): 407515 * 1024,
+    (2, "fwd"): 525294 * 1024, (2, "dx"): 525294 * 1024, (2, "dw_partial"): 539684 * 1024, (2, "bwd_fused"): 831299 * 1024,
     (3, "fwd"): 163881 * 1024, (3, "dx"): 163881 * 1024, (3, "dw_partial"): 271351 * 1024,
-    (4, "fwd"): 393693 * 1024, (4, "dx"): 393693 * 1024, (4, "dw_partial"): 396079 * 1024, (4, "bwd_fused"): 598797 * 1024,
+    (4, "fwd"): 393355 * 1024, (4, "dx"): 393355 * 1024, (4, "dw_partial"): 396139 * 1024, (4, "bwd_fused"): 598836 * 1024,
     (5, "fwd"): 786611 * 1024, (5, "dx"): 786611 * 1024, (5, "dw_partial"): 787015 * 1024,
 }
 
