@@ -361,6 +361,7 @@ struct DwPlan {
     RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
     int wpb;               // waves per block of the matrix-core stage-1 kernels
     int dw_nc;             // short rows, sixteen-row units: channels per block of the stage-1 kernel (1 or 2)
+    int S_fused;           // slices the fused backward call writes (differs from S for rows of at most 48 positions)
     bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
     int tiles_per_row;     // segments the matrix-core kernels walk per row (per virtual row for short rows)
     int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel (always real rows)
@@ -495,6 +496,17 @@ DwPlan plan_dw(const Shape &s)
     p.segs_per_wave = (int)spw;
     p.items_per_slice = (int)per;
     p.S = (int)((items + per - 1) / per);
+    // the fused backward kernel of these shapes works on one channel per block: its own slice count
+    p.S_fused = p.S;
+    if (p.rows.batch && s.L <= dwconv::kRbBwdMaxL) {
+        // one wave per (channel, slice), sixteen-row units: about kTargetWaves waves
+        long long wantf = kTargetWaves / s.C;
+        if (wantf < 1) wantf = 1;
+        if (wantf > p.rows.units) wantf = p.rows.units;
+        if (wantf > 65535) wantf = 65535;
+        const long long upw = (p.rows.units + wantf - 1) / wantf;
+        p.S_fused = (int)((p.rows.units + upw - 1) / upw);
+    }
     p.tiles_per_row = (int)tiles;
     {
         const long long real_tiles = ((long long)s.L + kDwTT - 1) / kDwTT;
@@ -523,7 +535,7 @@ DwPlan plan_dw(const Shape &s)
 
 size_t dw_workspace_bytes(const Shape &s, const DwPlan &p)
 {
-    const size_t bytes = (size_t)p.S * (size_t)s.C * (size_t)s.K * sizeof(float);
+    const size_t bytes = (size_t)(p.S > p.S_fused ? p.S : p.S_fused) * (size_t)s.C * (size_t)s.K * sizeof(float);
     return (bytes + 255) & ~(size_t)255;
 }
 
@@ -759,7 +771,6 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
 {
     *wrote_dw = false;
     if (p.longk) return -1;
-    if (p.rows.batch) return -1;      // rows of at most 64 positions: the two separate kernels move less per output
     // bf16: whole 16-byte granules of 8 elements
     if (s.dtype == DWCONV_BF16 && (s.L % 8) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
@@ -768,6 +779,30 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     if (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)) return -1;
     void *direct = (p.single && p.S == 1) ? dw_out : nullptr;
     int rc = -1;
+    if (p.rows.batch) {
+        // rows of at most 48 positions: sixteen rows per tile, one wave per (channel, slice)
+        if (s.L > dwconv::kRbBwdMaxL) return -1;
+        void *direct_rb = p.S_fused == 1 ? dw_out : nullptr;
+        auto launch_rb = [&](auto kernel, size_t lds_rb) -> int {
+            if (lds_rb > kMaxLdsBytes) return -1;
+            if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)((s.C + dwconv::kRbBwdWaves - 1) / dwconv::kRbBwdWaves), (unsigned)p.S_fused),
+                               dim3(64 * dwconv::kRbBwdWaves), lds_rb, st, static_cast<const float *>(dy),
+                               static_cast<const float *>(x), static_cast<const float *>(w), static_cast<float *>(dx), part,
+                               static_cast<float *>(direct_rb), s.B, s.C, s.L, s.K, s.pad, dmin, p.rows.units);
+            return launch_status();
+        };
+        switch (nd) {
+        case 2: rc = launch_rb(dwconv::bwd_rowbatch_kernel<2>, dwconv::rb_bwd_lds_bytes(s.L, 2)); break;
+        case 3: rc = launch_rb(dwconv::bwd_rowbatch_kernel<3>, dwconv::rb_bwd_lds_bytes(s.L, 3)); break;
+        case 4: rc = launch_rb(dwconv::bwd_rowbatch_kernel<4>, dwconv::rb_bwd_lds_bytes(s.L, 4)); break;
+        case 5: rc = launch_rb(dwconv::bwd_rowbatch_kernel<5>, dwconv::rb_bwd_lds_bytes(s.L, 5)); break;
+        case 6: rc = launch_rb(dwconv::bwd_rowbatch_kernel<6>, dwconv::rb_bwd_lds_bytes(s.L, 6)); break;
+        default: break;
+        }
+        if (rc == DWCONV_OK && direct_rb) *wrote_dw = true;
+        return rc;
+    }
     switch (nd) {
     case 2: rc = launch_bwd_fused_nd<2>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
     case 3: rc = launch_bwd_fused_nd<3>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
@@ -885,11 +920,13 @@ int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw,
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(workspace);
     bool wrote_dw = false;
+    DwPlan pf = p;
+    pf.S = p.S_fused;                                             // slices the fused kernel wrote
     rc = launch_bwd_fused(dy, x, w, dx, part, dw, &wrote_dw, s, p, st);
     if (rc >= 0) {
         if (rc != DWCONV_OK || wrote_dw) return rc;
-        if (dtype == DWCONV_F32) return launch_dw_finalize<float>(part, dw, s, p, st);
-        return launch_dw_finalize<bf16_t>(part, dw, s, p, st);
+        if (dtype == DWCONV_F32) return launch_dw_finalize<float>(part, dw, s, pf, st);
+        return launch_dw_finalize<bf16_t>(part, dw, s, pf, st);
     }
     // shapes and types the fused kernel does not take: the two gradients one after the other
     rc = dwconv_bwd_input(dy, w, dx, B, C, L, K, pad_left, dtype, stream);
@@ -903,7 +940,8 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const Shape s{B, C, L, K, pad_left, dtype};
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
-    return (!p.longk && !p.rows.batch && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
+    if (p.rows.batch && L > dwconv::kRbBwdMaxL) return 0;
+    return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
             L <= kMfmaMaxL) ? 1 : 0;
 }
 

@@ -341,4 +341,196 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     }
 }
 
+// Fused backward for short rows: dx = correlate(dY, reversed w, pad' = K - 1 - pad) and stage 1 of the weight
+// gradient from ONE pass over dY (units of sixteen rows of one channel).  grid = (ceil(C / 4), S): the four waves
+// of a block own four neighbouring channels (their rows share cache lines) and slice blockIdx.y of the units,
+// walked from the last batch to the first; every wave writes its own slice of part (or dw itself when S == 1), so
+// there is no workgroup barrier.  Per unit a wave holds two LDS images: dY (row pitch
+// 16 m + 4 floats, the layout of corr_rowbatch_kernel: 16-byte operand reads for dx, the tiles of dx replace dY in
+// place) and x (pitch rb_dw_pitch).  Order per unit: prefetch of the next unit's dY and x rows into registers;
+// G_d += x * dY; D tiles of dx from the dY image with the arithmetic of corr_rowbatch_kernel (same instruction
+// order per output, so dx is bit-identical to the separate call); the tiles replace dY; every lane swaps its
+// granules (dx out as whole rows, next dY in) and drains the next x rows.
+constexpr int kRbBwdMaxL = 48;
+__host__ __device__ constexpr int rb_bwd_dy_pitch(int L) { return (L + 15) / 16 * 16 + 4; }
+__host__ __device__ constexpr int rb_bwd_wave_floats(int L, int ND)
+{
+    const int stage = kRbRows * (rb_bwd_dy_pitch(L) + rb_dw_pitch(L, 1));
+    const int diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
+    return stage > diag ? stage : diag;
+}
+constexpr int kRbBwdWaves = 4;
+__host__ __device__ constexpr size_t rb_bwd_lds_bytes(int L, int ND)
+{
+    return (size_t)kRbBwdWaves * (size_t)(rb_bwd_wave_floats(L, ND) + 16 * ND) * sizeof(float);
+}
+
+template <int ND>
+__global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowbatch_kernel(
+    const float *__restrict__ dy, const float *__restrict__ x, const float *__restrict__ w, float *__restrict__ dx,
+    float *__restrict__ part, float *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin, int n_units)
+{
+    // rows of at most kRbBwdMaxL positions (register budget: two prefetched tensors, Toeplitz operands, accumulators)
+    constexpr int NLD = kRbRows * (kRbBwdMaxL / 4) / 64;
+    constexpr int MB = kRbBwdMaxL / 16;
+    extern __shared__ __align__(16) float dyn_lds[];
+    const int wreg = rb_bwd_wave_floats(L, ND);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i16 = lane & 15, k4 = lane >> 4;
+    const int c = kRbBwdWaves * (int)blockIdx.x + wave;
+    if (c >= C) return;                                       // (no workgroup barrier below)
+    float *s_wave = dyn_lds + wave * wreg;
+    float *s_dw = dyn_lds + kRbBwdWaves * wreg + wave * (16 * ND);
+    const int m = (L + 15) >> 4;
+    const int Ld = 16 * m + 4;                                // pitch of the dY image
+    const int Lp = rb_dw_pitch(L, 1);                         // pitch of the x image
+    float *sd = s_wave, *sx = s_wave + kRbRows * Ld;
+    // input-gradient geometry: pad' = K - 1 - pad, offsets -(dmin + ND - 1) .. -dmin
+    const int padx = K - 1 - pad;
+    const int dminx = -(dmin + ND - 1);
+
+    const int CL = C * L;
+    const int Lg = L >> 2;
+    const int NG = kRbRows * Lg;
+    const int nld = (NG + 63) >> 6;
+    int gl_off[NLD], img_d[NLD], img_x[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int gi = lane + 64 * i;
+        const int r = gi / Lg, cg = gi - r * Lg;
+        gl_off[i] = gi < NG ? 4 * (r * CL + 4 * cg) : kOutOfRow;
+        img_d[i] = gi < NG ? r * Ld + 4 * cg : 0;
+        img_x[i] = gi < NG ? r * Lp + 4 * cg : 0;
+    }
+    for (int i = lane; i < kRbRows * (Ld + Lp) / 4; i += 64)
+        *reinterpret_cast<float4 *>(s_wave + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    wave_lds_fence();
+
+    floatx4 G[ND];
+#pragma unroll
+    for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // Toeplitz operands of the input gradient: A[d][v] (lane (r, k)) = w[K - 1 - (16 (dminx + d) + 4k + v - r + padx)]
+    float A[ND][4];
+    {
+        const float *f_c = w + (size_t)c * (size_t)K;
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int j = 16 * (dminx + d) + 4 * k4 + v - i16 + padx;
+                const bool ok = j >= 0 && j < K;
+                const float a = f_c[ok ? K - 1 - j : 0];
+                A[d][v] = ok ? a : 0.f;
+            }
+    }
+
+    const int stride = (int)gridDim.y;
+    int unit = (int)blockIdx.y;
+    uintx4 pd[NLD], px[NLD];
+    auto prefetch = [&](int u) {
+        const int b0 = kRbRows * (n_units - 1 - u);
+        const int nr = B - b0 < kRbRows ? B - b0 : kRbRows;
+        const size_t first = ((size_t)b0 * (size_t)C + (size_t)c) * (size_t)L;
+        const uintx4 rd = rb_unit_resource(dy + first, nr, CL, L);
+        const uintx4 rx = rb_unit_resource(x + first, nr, CL, L);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            if (i < nld) {
+                pd[i] = buffer_load_x4_untracked(rd, gl_off[i]);
+                px[i] = buffer_load_x4_untracked(rx, gl_off[i]);
+            }
+    };
+    if (unit < n_units) {
+        prefetch(unit);
+        wait_untracked_loads();
+        release_after_wait(pd);
+        release_after_wait(px);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            if (i < nld && lane + 64 * i < NG) {
+                *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<float>::widen(pd[i]);
+                *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<float>::widen(px[i]);
+            }
+        wave_lds_fence();
+    }
+    float *sp = sd + i16 * Ld + 4 * k4;
+    while (unit < n_units) {
+        const int unit_n = unit + stride;
+        const bool more = unit_n < n_units;
+        if (more) prefetch(unit_n);
+        // weight gradient: four rows per instruction
+#pragma unroll
+        for (int g4 = 0; g4 < kRbRows / 4; ++g4) {
+            const float *xrow = sx + (4 * g4 + k4) * Lp + i16;
+            const float *grow = sd + (4 * g4 + k4) * Ld + i16;
+            for (int mo = 0; mo < m; ++mo) {
+                const float bq = grow[16 * mo];
+#pragma unroll
+                for (int d = 0; d < ND; ++d) {
+                    const int mi = mo + dmin + d;
+                    if (mi >= 0 && mi < m) G[d] = mfma16x16x4(xrow[16 * mi], bq, G[d]);
+                }
+            }
+        }
+        // input gradient: lane (row i16, position group k4) owns outputs 16 mo + 4 k4 + 0..3 of block mo
+        floatx4 acc[MB];
+#pragma unroll
+        for (int mo = 0; mo < MB; ++mo) {
+            floatx4 a4 = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (mo < m) {
+#pragma unroll
+                for (int d = 0; d < ND; ++d) {
+                    const int mi = mo + dminx + d;
+                    if (mi >= 0 && mi < m) {
+                        const float4 cur = *reinterpret_cast<const float4 *>(sp + 16 * mi);
+                        a4 = mfma16x16x4(A[d][0], cur.x, a4);
+                        a4 = mfma16x16x4(A[d][1], cur.y, a4);
+                        a4 = mfma16x16x4(A[d][2], cur.z, a4);
+                        a4 = mfma16x16x4(A[d][3], cur.w, a4);
+                    }
+                }
+            }
+            acc[mo] = a4;
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int mo = 0; mo < MB; ++mo)
+            if (mo < m && 16 * mo + 4 * k4 < L)
+                *reinterpret_cast<float4 *>(sp + 16 * mo) = make_float4(acc[mo][0], acc[mo][1], acc[mo][2], acc[mo][3]);
+        wave_lds_fence();
+        wait_untracked_loads();
+        release_after_wait(pd);
+        release_after_wait(px);
+        {
+            const int b0 = kRbRows * (n_units - 1 - unit);
+            const int nr = B - b0 < kRbRows ? B - b0 : kRbRows;
+            const int lim = 4 * nr * CL;
+            float *dx_u = dx + ((size_t)b0 * (size_t)C + (size_t)c) * (size_t)L;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i)
+                if (i < nld && lane + 64 * i < NG) {
+                    const float4 ov = *reinterpret_cast<const float4 *>(sd + img_d[i]);
+                    if (more) {
+                        *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<float>::widen(pd[i]);
+                        *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<float>::widen(px[i]);
+                    }
+                    if (gl_off[i] < lim) st_elem4_stream(dx_u + (gl_off[i] >> 2), ov);
+                }
+        }
+        wave_lds_fence();
+        unit = unit_n;
+    }
+
+    // ---- diagonal sums of this wave's accumulators: its slice of the partial sums
+    dw_wave_diagonal_sums<ND>(G, s_wave, s_dw, lane, K, pad, dmin);
+    wave_lds_fence();
+    for (int j = lane; j < K; j += 64) {
+        const size_t o = (size_t)c * (size_t)K + (size_t)j;
+        if (dw_out) dw_out[o] = s_dw[j];
+        else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = s_dw[j];
+    }
+}
+
 }  // namespace dwconv

@@ -162,8 +162,9 @@ def test_single_kernel_weight_gradient(oracle_mod, B, C, L, K, p, dtype):
 BWD = [
     (2, 3, 600, 64, 63, "f32", True), (1, 2, 4100, 64, 32, "f32", True), (3, 7, 336, 31, 30, "f32", True),
     (2, 3, 100, 5, 0, "f32", True), (2, 3, 100, 5, 4, "f32", True), (1, 4, 1024, 16, 15, "f32", True),
-    (2, 4, 1028, 16, 8, "f32", True), (2, 2, 48, 48, 24, "f32", False), (5, 3, 48, 48, 0, "f32", False),
-    (2, 2, 2060, 64, 63, "f32", True), (1, 5, 44, 7, 3, "f32", False), (20, 5, 68, 7, 3, "f32", True), (4, 16, 4096, 64, 63, "f32", True),
+    (2, 4, 1028, 16, 8, "f32", True), (2, 2, 48, 48, 24, "f32", True), (5, 3, 48, 48, 0, "f32", True),
+    (2, 2, 2060, 64, 63, "f32", True), (1, 5, 44, 7, 3, "f32", True), (20, 5, 68, 7, 3, "f32", True), (100, 6, 48, 48, 24, "f32", True), (37, 3, 64, 66, 33, "f32", False),
+    (70, 256, 48, 48, 24, "f32", True), (300, 4, 20, 9, 8, "f32", True), (4, 16, 4096, 64, 63, "f32", True),
     (3, 2, 2048, 66, 65, "f32", True), (2, 2, 3072, 66, 0, "f32", True), (2, 3, 2052, 40, 20, "f32", True),
     (9, 256, 3900, 64, 63, "f32", True), (4, 512, 4096, 7, 3, "f32", True), (11, 768, 1032, 20, 0, "f32", True),
     (2, 5, 257, 7, 3, "f32", False), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", True), (3, 5, 1004, 32, 16, "bf16", False),
