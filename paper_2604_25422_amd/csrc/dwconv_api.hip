@@ -145,6 +145,16 @@ long long resident_waves(Kernel kernel, int block_threads)
     return waves;
 }
 
+// Wave slots of a correlate launch: one resident round, but no more than 16 waves per compute unit.  Kernels
+// light enough for five or six waves per SIMD measured slower with the larger round (short filter, K = 7:
+// 105 us with 5120 slots, 97.6 us with 4096).
+template <typename Kernel>
+long long corr_wave_slots(Kernel kernel, int block_threads)
+{
+    const long long r = resident_waves(kernel, block_threads);
+    return r < kTargetWaves ? r : kTargetWaves;
+}
+
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
 template <typename T>
 int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
@@ -165,7 +175,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
     // One resident round of waves, each walking segments wave, wave + n_waves, ...
     auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po) -> int {
-        const long long resident = resident_waves(kernel, kThreads);
+        const long long resident = corr_wave_slots(kernel, kThreads);
         long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
         if (spw < 1) spw = 1;
         const long long waves = (total_segs + spw - 1) / spw;
@@ -192,7 +202,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
             auto launch_batch = [&](auto kernel) -> int {
                 // one resident round of waves: J per channel group, each walking units j, j + J, ...
                 const long long groups = s.C / nc;
-                const long long resident = resident_waves(kernel, 64 * dwconv::kRbCorrWaves);
+                const long long resident = corr_wave_slots(kernel, 64 * dwconv::kRbCorrWaves);
                 long long J = resident / groups;
                 if (J < 1) J = 1;
                 if (J > rg.n_units) J = rg.n_units;
@@ -231,7 +241,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
             g.rows = rp.nvs;
             g.segs_per_row = s.C;
             auto launch_rows = [&](auto kernel) -> int {
-                const long long resident = resident_waves(kernel, kThreads);
+                const long long resident = corr_wave_slots(kernel, kThreads);
                 long long spw = (total + resident - 1) / resident;
                 if (spw < 1) spw = 1;
                 const long long waves = (total + spw - 1) / spw;
