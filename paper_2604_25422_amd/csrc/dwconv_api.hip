@@ -62,7 +62,9 @@ int toeplitz_dmin(int pad) { return -((pad + 15) / 16); }
 int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
 
 constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
-constexpr int kMfmaMaxND = 6;
+constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
+constexpr int kMfmaMaxNDWide = 10;     // fp32 forward / input gradient / weight gradient on long rows (K up to 130)
+int mfma_max_nd(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND; }
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
@@ -161,7 +163,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
 {
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
     const long long rows = (long long)s.B * s.C;
     const long long segs_per_row = (s.L + dwconv::kSegLen - 1) / dwconv::kSegLen;
@@ -178,9 +180,19 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         const long long resident = corr_wave_slots(kernel, kThreads);
         long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
         if (spw < 1) spw = 1;
-        const long long waves = (total_segs + spw - 1) / spw;
-        long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
-        g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
+        long long waves = (total_segs + spw - 1) / spw;
+        // A whole number of batch entries per round where one fits: the stride of the walk is then a multiple of
+        // C rows, a wave stays on one channel and loads its Toeplitz operands once.
+        const long long per_b = (long long)s.C * segs_per_row;
+        if (per_b <= resident) {
+            long long J = resident / per_b;
+            if (J > s.B) J = s.B;
+            const long long rounds = (s.B + J - 1) / J;
+            J = (s.B + rounds - 1) / rounds;                           // same number of rounds, evened out
+            waves = J * per_b;
+        }
+        const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+        g.n_waves = (int)waves;
         g.step_rows = g.n_waves / g.segs_per_row;
         g.step_seg = g.n_waves % g.segs_per_row;
         g.step_c = g.step_rows % s.C;
@@ -244,9 +256,16 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                 const long long resident = corr_wave_slots(kernel, kThreads);
                 long long spw = (total + resident - 1) / resident;
                 if (spw < 1) spw = 1;
-                const long long waves = (total + spw - 1) / spw;
-                long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
-                g.n_waves = (int)(blocks * dwconv::kCorrWavesPerBlock);
+                long long waves = (total + spw - 1) / spw;
+                if (s.C <= resident) {                                // whole virtual segments per round: channel fixed
+                    long long J = resident / s.C;
+                    if (J > rp.nvs) J = rp.nvs;
+                    const long long rounds = (rp.nvs + J - 1) / J;
+                    J = (rp.nvs + rounds - 1) / rounds;
+                    waves = J * s.C;
+                }
+                const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+                g.n_waves = (int)waves;
                 g.step_rows = g.n_waves / g.segs_per_row;
                 g.step_seg = g.n_waves % g.segs_per_row;
                 g.step_c = 0;
@@ -287,8 +306,18 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     case 4: return launch(dwconv::corr_mfma_kernel<T, 4, false>, pi, pf, po);
     case 5: return launch(dwconv::corr_mfma_kernel<T, 5, false>, pi, pf, po);
     case 6: return launch(dwconv::corr_mfma_kernel<T, 6, false>, pi, pf, po);
-    default: return -1;
+    default: break;
     }
+    if constexpr (std::is_same<T, float>::value) {
+        switch (nd) {
+        case 7: return launch(dwconv::corr_mfma_kernel<float, 7, false>, pi, pf, po);
+        case 8: return launch(dwconv::corr_mfma_kernel<float, 8, false>, pi, pf, po);
+        case 9: return launch(dwconv::corr_mfma_kernel<float, 9, false>, pi, pf, po);
+        case 10: return launch(dwconv::corr_mfma_kernel<float, 10, false>, pi, pf, po);
+        default: break;
+        }
+    }
+    return -1;
 }
 
 constexpr size_t kMaxLdsBytes = 160 * 1024;
@@ -315,7 +344,7 @@ template <typename T>
 int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
-    if (dmax - dmin + 1 <= kMfmaMaxND || s.K > dwconv::kLkMaxK || (s.L % 4) != 0) return -1;
+    if (dmax - dmin + 1 <= mfma_max_nd(s.dtype) || s.K > dwconv::kLkMaxK || (s.L % 4) != 0) return -1;
     const int NB = (s.L + 15) / 16;
     if (NB > dwconv::kLkMaxBlocks) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
@@ -475,7 +504,7 @@ DwPlan plan_dw(const Shape &s)
     long long tiles = p.rows.batch ? p.rows.units : p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
     long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
+    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd(s.dtype) && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
     // waves takes a whole channel: no slices, no second stage.
     p.wpb = dwconv::kWavesPerBlock;
@@ -484,7 +513,8 @@ DwPlan plan_dw(const Shape &s)
     if (mfma_shape && s.C % kComputeUnits == 0 && s.C / kComputeUnits <= 3) {
         const int wpb = 16 / (s.C / kComputeUnits);
         // (sixteen-row units of rows longer than 48 positions need more LDS than sixteen waves have)
-        const bool fits = !p.rows.batch || dwconv::rb_dw_lds_bytes(s.L, nd, wpb, 1) <= kMaxLdsBytes;
+        const bool fits = (!p.rows.batch || dwconv::rb_dw_lds_bytes(s.L, nd, wpb, 1) <= kMaxLdsBytes) &&
+                          (nd <= kMfmaMaxND || dwconv::dw_direct_lds_bytes(nd, wpb) <= kMaxLdsBytes);
         if (items >= 2 * wpb && fits) { p.wpb = wpb; p.single = true; }
     }
     long long groups = s.C;                                      // blocks along the channel axis
@@ -528,7 +558,7 @@ DwPlan plan_dw(const Shape &s)
     p.longk = false;
     p.lk_wgs = p.lk_gd = 0;
     const int NCH = (s.L + 63) / 64;
-    if (nd > kMfmaMaxND && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
+    if (nd > mfma_max_nd(s.dtype) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
         const int per_wg = 2 * dwconv::kLkWaves * dwconv::kLkDwMaxGD;
         p.lk_wgs = (nd + per_wg - 1) / per_wg;
@@ -637,6 +667,37 @@ int launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, void *
     }
 }
 
+// fp32, seven to ten block offsets (K up to 130): the LDS-direct kernel on ordinary rows.
+template <int ND, int W>
+int launch_dw_partial_wide_ndw(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                               int dmin, hipStream_t st)
+{
+    constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
+    if constexpr (lds > kMaxLdsBytes) {
+        return -1;
+    } else {
+        auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const float *>(x), static_cast<const float *>(dy), part,
+                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
+        return launch_status();
+    }
+}
+template <int ND>
+int launch_dw_partial_wide_nd(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                              int dmin, hipStream_t st)
+{
+    if (p.rows.on) return -1;
+    switch (p.wpb) {
+    case 4: return launch_dw_partial_wide_ndw<ND, 4>(x, dy, part, dw_out, s, p, dmin, st);
+    case 5: return launch_dw_partial_wide_ndw<ND, 5>(x, dy, part, dw_out, s, p, dmin, st);
+    case 8: return launch_dw_partial_wide_ndw<ND, 8>(x, dy, part, dw_out, s, p, dmin, st);
+    case 16: return launch_dw_partial_wide_ndw<ND, 16>(x, dy, part, dw_out, s, p, dmin, st);
+    default: return -1;
+    }
+}
+
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
 template <typename T>
 int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
@@ -644,8 +705,17 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
+    if constexpr (std::is_same<T, float>::value) {
+        switch (nd) {
+        case 7: return launch_dw_partial_wide_nd<7>(x, dy, part, dw_out, s, p, dmin, st);
+        case 8: return launch_dw_partial_wide_nd<8>(x, dy, part, dw_out, s, p, dmin, st);
+        case 9: return launch_dw_partial_wide_nd<9>(x, dy, part, dw_out, s, p, dmin, st);
+        case 10: return launch_dw_partial_wide_nd<10>(x, dy, part, dw_out, s, p, dmin, st);
+        default: break;
+        }
+    }
     switch (nd) {
     case 2: return launch_dw_partial_mfma_nd<T, 2>(x, dy, part, dw_out, s, p, dmin, st);
     case 3: return launch_dw_partial_mfma_nd<T, 3>(x, dy, part, dw_out, s, p, dmin, st);

@@ -95,8 +95,8 @@ constexpr int kDirectSlackFloats = 256;   // x4 writes a full 1 KiB: the tail of
 // Per-wave LDS region (floats) and dynamic LDS bytes of a block of W waves.
 constexpr int dw_direct_wave_floats(int ND)
 {
-    const int stage = 5 * 256 + kSegLen, gf = ND * 256;
-    return stage > gf ? stage : gf;
+    const int stage = 5 * 256 + kSegLen, gf = ND * 256, diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
+    return stage > gf ? (stage > diag ? stage : diag) : (gf > diag ? gf : diag);
 }
 constexpr size_t dw_direct_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_direct_wave_floats(ND) + 16 * ND) * sizeof(float); }
 
@@ -116,8 +116,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     static_assert(XREG - XW <= kDirectSlackFloats, "slack");
     constexpr int GF = ND * 256;                   // floats of one wave's G
     constexpr int STAGE = XREG + kSegLen;
-    constexpr int WREG = STAGE > GF ? STAGE : GF;  // per-wave LDS region
-    static_assert(WREG == dw_direct_wave_floats(ND), "host and kernel agree on the LDS layout");
+    constexpr int WREG = dw_direct_wave_floats(ND);   // per-wave LDS region: the staged windows, or the epilogue's images
+    static_assert(WREG >= STAGE && WREG >= GF, "the staged windows fit the wave's region");
     extern __shared__ __align__(16) float dyn_lds[];
     float (*s_mem)[WREG] = reinterpret_cast<float (*)[WREG]>(dyn_lds);
     float (*s_dw)[16 * ND] = reinterpret_cast<float (*)[16 * ND]>(dyn_lds + W * WREG);

@@ -177,7 +177,7 @@ template <> struct Raw4<bf16_t> {
 // ordered (virtual segment, channel), so neighbouring waves read neighbouring channels of the same batches, and
 // `row` / `seg` below then hold the virtual segment and the channel.
 template <typename T, int ND, bool ROWS>
-__global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_mfma_kernel(const T *__restrict__ in,
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
                                                                          const T *__restrict__ f, T *__restrict__ out,
                                                                          const CorrGeom g, const RowsMap rm)
 {
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     int row = wg / g.segs_per_row;                 // b * C + c
     int seg = wg % g.segs_per_row;
     int c = ROWS ? seg : row % g.C;
-    if (row >= g.rows) return;
+    if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
     int row_n, seg_n, c_n;                         // the segment after (row, seg)
     auto advance = [&]() {
         seg_n = seg + g.step_seg;
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     int row = wg / g.segs_per_row;                 // b * C + c
     int seg = wg % g.segs_per_row;
     int c = row % g.C;
-    if (row >= g.rows) return;
+    if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
     int row_n, seg_n, c_n;                         // the segment after (row, seg)
     auto advance = [&]() {
         seg_n = seg + g.step_seg;

@@ -32,6 +32,8 @@ SMALL = [
     (3, 2, 256, 200, 100), (2, 3, 512, 512, 511), (1, 2, 2048, 1500, 700), (2, 2, 1024, 130, 129),
     (1, 1, 1024, 90, 0), (3, 1, 640, 640, 320), (1, 2, 4096, 4096, 4095), (2, 1, 1000, 2500, 1200),
     (1, 1, 8192, 300, 299), (1, 2, 72, 67, 66),
+    # seven to ten block offsets (fp32 register-resident class up to K = 130): every count, ragged rows, several rows per wave
+    (3, 5, 2060, 100, 99), (2, 3, 1028, 112, 50), (5, 2, 3072, 128, 127), (2, 2, 1100, 130, 0), (9, 4, 1024, 97, 96),
     # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
     (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
@@ -134,7 +136,7 @@ def test_runs_on_a_non_default_stream(oracle_mod):
 # kernel that writes dw itself.  Ragged last segments, rows of one segment, fp32 and bf16.
 SINGLE = [
     (8, 256, 4096, 16, 15, "f32"), (9, 256, 3900, 64, 63, "f32"), (33, 256, 1000, 33, 16, "f32"),
-    (4, 512, 4096, 7, 3, "f32"), (17, 512, 1028, 48, 24, "f32"),
+    (4, 512, 4096, 7, 3, "f32"), (17, 512, 1028, 48, 24, "f32"), (9, 512, 2048, 100, 99, "f32"), (20, 512, 1024, 128, 127, "f32"),
     (10, 768, 1024, 32, 31, "bf16"), (11, 768, 1032, 20, 0, "f32"), (40, 256, 1024, 64, 63, "bf16"),
 ]
 
