@@ -56,6 +56,16 @@ def test_short_rows_f32(oracle_mod, B, C, L, K, p):
     check_case(oracle_mod, B, C, L, K, p, "f32", seed=B + C + L + K)
 
 
+# Rows of a million positions and more: byte offsets inside a row beyond 2^22, thousands of segments per row.
+@pytest.mark.parametrize("B,C,L,K,p,dtype", [
+    (1, 2, (1 << 20) + 4, 64, 63, "f32"), (1, 1, 3000004, 7, 3, "f32"), (1, 2, (1 << 20) + 8, 32, 31, "bf16"),
+    (1, 1, (1 << 21) + 12, 100, 50, "f32"),
+])
+def test_long_rows(oracle_mod, B, C, L, K, p, dtype):
+    print(f"case long rows {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    check_case(oracle_mod, B, C, L, K, p, dtype, seed=5)
+
+
 @pytest.mark.parametrize("B,C,L,K,p", SMALL)
 def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
     print(f"case f32 B{B} C{C} L{L} K{K} p{p}", flush=True)
