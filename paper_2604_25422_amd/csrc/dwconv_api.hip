@@ -613,13 +613,28 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                 if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
                 hipLaunchKernelGGL(kernel, dim3((unsigned)(s.C / nc), (unsigned)p.S), dim3(64 * W), lds_rb, st,
                                    static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                                   static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
+                                   static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, ND, p.tiles_per_row);
                 return launch_status();
             };
+            // (the kernel is compiled per number of 16-blocks of a row, not per number of block offsets)
+            const int m = (s.L + 15) / 16;
             if constexpr (W == dwconv::kWavesPerBlock) {
-                if (p.dw_nc == 2) return launch_rb(dwconv::dw_rowbatch_kernel<ND, W, 2>, 2);
+                if (p.dw_nc == 2) {
+                    switch (m) {
+                    case 1: return launch_rb(dwconv::dw_rowbatch_kernel<1, W, 2>, 2);
+                    case 2: return launch_rb(dwconv::dw_rowbatch_kernel<2, W, 2>, 2);
+                    case 3: return launch_rb(dwconv::dw_rowbatch_kernel<3, W, 2>, 2);
+                    default: return -1;
+                    }
+                }
             }
-            return launch_rb(dwconv::dw_rowbatch_kernel<ND, W, 1>, 1);
+            switch (m) {
+            case 1: return launch_rb(dwconv::dw_rowbatch_kernel<1, W, 1>, 1);
+            case 2: return launch_rb(dwconv::dw_rowbatch_kernel<2, W, 1>, 1);
+            case 3: return launch_rb(dwconv::dw_rowbatch_kernel<3, W, 1>, 1);
+            case 4: return launch_rb(dwconv::dw_rowbatch_kernel<4, W, 1>, 1);
+            default: return -1;
+            }
         } else if (p.rows.on) {
             auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;

@@ -19,6 +19,8 @@
 //   A (16x4):  lane holds A[i][k]          B (4x16): lane holds B[k][i]
 //   D (16x16): lane holds D[4*k + v][i] in vector element v = 0..3
 #pragma once
+#include <type_traits>
+
 #include "dwconv_common.hip.h"
 
 namespace dwconv {
@@ -92,6 +94,15 @@ __device__ __forceinline__ uintx4 buffer_load_x4_untracked(uintx4 rsrc, int byte
 {
     uintx4 v;
     asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(v) : "v"(byte_off), "s"(rsrc) : "memory");
+    return v;
+}
+// ... with a compile-time byte offset (0 .. 4095) added by the instruction: one offset register serves several loads
+template <int IMM>
+__device__ __forceinline__ uintx4 buffer_load_x4_untracked_imm(uintx4 rsrc, int byte_off)
+{
+    static_assert(IMM >= 0 && IMM < 4096, "12-bit immediate offset");
+    uintx4 v;
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3" : "=v"(v) : "v"(byte_off), "s"(rsrc), "n"(IMM) : "memory");
     return v;
 }
 __device__ __forceinline__ uintx2 buffer_load_x2_untracked(uintx4 rsrc, int byte_off)
@@ -220,9 +231,15 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPe
     // per-lane constants: byte offset of the lane's i-th granule inside the staged window, and its LDS slot
     constexpr int ES = (int)sizeof(T);
     typename Raw4<T>::type pre[NLD];
-    int ld_off[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) ld_off[i] = (lane + 64 * i < NG) ? 4 * ES * (lane + 64 * i) : kOutOfRow;
+    // every round of loads but the last is full: one lane offset plus the instruction's immediate offset (fp32)
+    const int off_lane = 4 * ES * lane;
+    const int off_tail = (lane + 64 * (NLD - 1) < NG) ? 4 * ES * (lane + 64 * (NLD - 1)) : kOutOfRow;
+    auto load_round = [&](uintx4 r, int base, auto ic) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i == NLD - 1) pre[i] = Raw4<T>::load(r, off_tail + base);
+        else if constexpr (ES == 4 && 1024 * i < 4096) pre[i] = buffer_load_x4_untracked_imm<(ES == 4 ? 1024 * i : 0)>(r, off_lane + base);
+        else pre[i] = Raw4<T>::load(r, off_lane + 4 * ES * 64 * i + base);
+    };
     auto prefetch = [&](int prow, int pseg) {
         if constexpr (ROWS) {
             // virtual segment prow of channel pseg: every lane translates the positions of its granules
@@ -237,13 +254,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPe
             const int u0 = ES * (pseg * kSegLen + 16 * g.dmin);          // may be negative: before the row start
             const int start = u0 > 0 ? u0 : 0;
             const uintx4 r = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, start);
-            if (u0 >= 0) {
-#pragma unroll
-                for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < NLD; ++i) pre[i] = Raw4<T>::load(r, ld_off[i] + u0);
-            }
+            const int base = u0 < 0 ? u0 : 0;          // a window that starts before the row: negative offsets
+            load_round(r, base, std::integral_constant<int, 0>{});
+            if constexpr (NLD > 1) load_round(r, base, std::integral_constant<int, 1>{});
+            if constexpr (NLD > 2) load_round(r, base, std::integral_constant<int, 2>{});
+            if constexpr (NLD > 3) load_round(r, base, std::integral_constant<int, 3>{});
+            if constexpr (NLD > 4) load_round(r, base, std::integral_constant<int, 4>{});
+            static_assert(NLD <= 5, "at most five rounds of loads per segment");
         }
     };
     float *sw = s_in[wave];
@@ -290,7 +307,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPe
         floatx4 acc[NDT];
         {
             constexpr int NGRP = NDT * ND;
-            constexpr int PF = 4;
+            constexpr int PF = (ND == 6 || ND == 10) ? 2 : 4;     // shorter read-ahead where registers run out
             float4 bv[PF];
 #pragma unroll
             for (int q = 0; q < PF; ++q)

@@ -11,6 +11,7 @@
 // of m blocks costs (pairs inside the row) * 4 matrix instructions per unit and no position of a padded segment
 // is computed: for L = 48, K = 48, pad = 24 that is 36 instructions per 768 outputs.
 #pragma once
+#include "dwconv_dw_direct.hip.h"   // static_for
 #include "dwconv_mfma.hip.h"
 
 namespace dwconv {
@@ -210,36 +211,77 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
     }
 }
 
-// Stage 1 of the weight gradient for short rows.  grid = (C / NC, S), W waves per block; wave w of slice s takes
-// the units W s + w, W s + w + W S, ... of its channel group (walked from the last batch to the first, see the
-// long-row kernel) and keeps ND 16x16 accumulators G_d per channel for its whole life.  A unit is 16 / NC rows of
-// NC neighbouring channels (NC = 2 makes whole cache lines of rows of 48 elements, see corr_rowbatch_kernel).
-// LDS image of a unit: rows of x, then rows of dY, pitch rb_dw_pitch floats, zeros between the end of a row and
-// the end of its last block.  One matrix instruction contracts four rows:
-//     A operand x[row 4 g + k][c0 + h][16 (mo + d) + q'],  B operand dY[row 4 g + k][c0 + h][16 mo + q].
+// Diagonal sums of accumulators that are indexed by the RELATIVE block offset rel = mi - mo = e - (M - 1)
+// (the run-time counterpart of dw_wave_diagonal_sums: which offsets exist, dmin .. dmax, is known at run time only).
+// sw: the wave's LDS region, at least ((16 nd + 15) * 17 + 3) / 4 * 4 floats; dw_wave[j], j < K, receives the sums.
+template <int NR>
+__device__ __forceinline__ void rb_diagonal_sums(const floatx4 (&G)[NR], int M, float *sw, float *dw_wave, int lane, int K,
+                                                 int pad, int dmin, int nd)
+{
+    constexpr int RS = 17;
+    const int rows = 16 * nd + 15;
+    const int n4 = (rows * RS + 3) / 4;
+    for (int i = lane; i < n4; i += 64) *reinterpret_cast<float4 *>(sw + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    wave_lds_fence();
+    const int q = lane & 15, k4 = lane >> 4;
+#pragma unroll
+    for (int e = 0; e < NR; ++e) {
+        const int d = e - (M - 1) - dmin;            // slot of this relative offset among dmin .. dmax
+        if (d >= 0 && d < nd) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sw[(16 * d + 4 * k4 + v - q + 15) * RS + q] = G[e][v];
+        }
+    }
+    wave_lds_fence();
+    for (int j = lane; j < K; j += 64) {
+        const int jl = j - pad - 16 * dmin + 15;
+        float sum = 0.f;
+        if (jl >= 0 && jl < rows) {
+            float t[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[i] = sw[jl * RS + i];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += t[i];
+        }
+        dw_wave[j] = sum;
+    }
+}
+
+// Stage 1 of the weight gradient for short rows of M 16-blocks.  grid = (C / NC, S), W waves per block; wave w of
+// slice s takes the units W s + w, W s + w + W S, ... of its channel group (walked from the last batch to the
+// first, see the long-row kernel).  A unit is 16 / NC rows of NC neighbouring channels (NC = 2 makes whole cache
+// lines of rows of 48 elements, see corr_rowbatch_kernel).  LDS image of a unit: rows of x, then rows of dY, pitch
+// rb_dw_pitch floats, zeros between the end of a row and the end of its last block.  One matrix instruction
+// contracts four rows:  A operand x[row 4 g + k][c0 + h][16 mi + q'],  B operand dY[row 4 g + k][c0 + h][16 mo + q],
+// for every block pair (mo, mi) of the row whose offset mi - mo is one of the nd offsets dmin .. dmin + nd - 1 of
+// the filter.  The accumulators are indexed by that relative offset (2 M - 1 per channel, compile-time indices;
+// which of them exist is a wave-uniform run-time test), so the 2 M operand reads of a row group are issued
+// together, ahead of its matrix instructions.
 // dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (gridDim.y == 1) they are the
 // weight gradient itself.
-template <int ND, int W, int NC>
+template <int M, int W, int NC>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int n_units)
+    int B, int C, int L, int K, int pad, int dmin, int nd, int n_units)
 {
     static_assert(NC == 1 || NC == 2, "one or two channels per wave");
+    static_assert(M >= 1 && M <= kRbMaxBlocks && (NC == 1 || M <= 3), "rows of at most 64 (two channels: 48) positions");
     constexpr int RU = kRbRows / NC;                          // rows per unit
-    constexpr int NLD = NC == 2 ? 3 : kRbMaxLoads;            // two channels: rows of at most 48 positions
+    constexpr int NLD = (RU * NC * 4 * M + 63) / 64;          // 16-byte granules of a unit over 64 lanes
+    constexpr int NR = 2 * M - 1;                             // relative block offsets -(M-1) .. M-1
     extern __shared__ __align__(16) float dyn_lds[];
-    const int wreg = rb_dw_wave_floats(L, ND, NC);
+    const int wreg = rb_dw_wave_floats(L, nd, NC);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, k4 = lane >> 4;
     const int c0 = NC * (int)blockIdx.x;
     float *s_wave = dyn_lds + wave * wreg;
-    float *s_dw = dyn_lds + W * wreg;                         // [wave][h][16 ND]
+    float *s_dw = dyn_lds + W * wreg;                         // [wave][h][16 nd]
     const int Lp = rb_dw_pitch(L, NC);
-    const int m = (L + 15) >> 4;
-    const int Lc = 16 * m;
+    constexpr int Lc = 16 * M;
     float *sx = s_wave, *sg = s_wave + RU * Lp;
+    const int dmax = dmin + nd - 1;
 
     const int CL = C * L;
     const int Lg = L >> 2;
@@ -258,11 +300,11 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
         *reinterpret_cast<float4 *>(s_wave + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_fence();
 
-    floatx4 G[NC][ND];
+    floatx4 G[NC][NR];
 #pragma unroll
     for (int h = 0; h < NC; ++h)
 #pragma unroll
-        for (int d = 0; d < ND; ++d) G[h][d] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int e = 0; e < NR; ++e) G[h][e] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int stride = (int)gridDim.y * W;
     int unit = (int)blockIdx.y * W + wave;
@@ -300,21 +342,23 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
         const int unit_n = unit + stride;
         const bool more = unit_n < n_units;
         if (more) prefetch(unit_n);
-#pragma unroll
-        for (int g4 = 0; g4 < RU / 4; ++g4)
-#pragma unroll
-            for (int h = 0; h < NC; ++h) {
-                const float *xrow = sx + (4 * g4 + k4) * Lp + h * Lc + i16;
-                const float *grow = sg + (4 * g4 + k4) * Lp + h * Lc + i16;
-                for (int mo = 0; mo < m; ++mo) {
-                    const float bq = grow[16 * mo];
-#pragma unroll
-                    for (int d = 0; d < ND; ++d) {
-                        const int mi = mo + dmin + d;
-                        if (mi >= 0 && mi < m) G[h][d] = mfma16x16x4(xrow[16 * mi], bq, G[h][d]);
-                    }
-                }
-            }
+        // (template recursion instead of unroll pragmas: every accumulator index has to be a constant)
+        static_for<0, (RU / 4) * NC>([&](auto gc) {
+            constexpr int g4 = decltype(gc)::value / NC, h = decltype(gc)::value % NC;
+            const float *xrow = sx + (4 * g4 + k4) * Lp + h * Lc + i16;
+            const float *grow = sg + (4 * g4 + k4) * Lp + h * Lc + i16;
+            float xa[M], gb[M];
+            static_for<0, M>([&](auto bc) {
+                constexpr int b = decltype(bc)::value;
+                xa[b] = xrow[16 * b];
+                gb[b] = grow[16 * b];
+            });
+            static_for<0, M * M>([&](auto pc) {
+                constexpr int mo = decltype(pc)::value / M, mi = decltype(pc)::value % M;
+                constexpr int rel = mi - mo;
+                if (rel >= dmin && rel <= dmax) G[h][rel + M - 1] = mfma16x16x4(xa[mi], gb[mo], G[h][rel + M - 1]);
+            });
+        });
         wave_lds_fence();
         if (more) {
             drain();
@@ -326,7 +370,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     // ---- per-wave diagonal sums, then the waves of the block in wave order
 #pragma unroll
     for (int h = 0; h < NC; ++h) {
-        dw_wave_diagonal_sums<ND>(G[h], s_wave, s_dw + (wave * NC + h) * (16 * ND), lane, K, pad, dmin);
+        rb_diagonal_sums<NR>(G[h], M, s_wave, s_dw + (wave * NC + h) * (16 * nd), lane, K, pad, dmin, nd);
         wave_lds_fence();
     }
     __syncthreads();
@@ -334,7 +378,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
         const int h = e / K, j = e - h * K;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < W; ++w) sum += s_dw[(w * NC + h) * (16 * ND) + j];
+        for (int w = 0; w < W; ++w) sum += s_dw[(w * NC + h) * (16 * nd) + j];
         const size_t o = (size_t)(c0 + h) * (size_t)K + (size_t)j;
         if (dw_out) dw_out[o] = sum;
         else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = sum;
