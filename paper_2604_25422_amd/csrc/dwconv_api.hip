@@ -887,12 +887,17 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
                                static_cast<float *>(direct_rb), s.B, s.C, s.L, s.K, s.pad, dmin, p.rows.units);
             return launch_status();
         };
+        const int m = (s.L + 15) / 16;              // the kernel is compiled per (block offsets, 16-blocks of a row)
+        auto launch_m = [&](auto k1, auto k2, auto k3, int ndv) -> int {
+            const size_t lds_rb = dwconv::rb_bwd_lds_bytes(s.L, ndv);
+            return m == 1 ? launch_rb(k1, lds_rb) : m == 2 ? launch_rb(k2, lds_rb) : launch_rb(k3, lds_rb);
+        };
         switch (nd) {
-        case 2: rc = launch_rb(dwconv::bwd_rowbatch_kernel<2>, dwconv::rb_bwd_lds_bytes(s.L, 2)); break;
-        case 3: rc = launch_rb(dwconv::bwd_rowbatch_kernel<3>, dwconv::rb_bwd_lds_bytes(s.L, 3)); break;
-        case 4: rc = launch_rb(dwconv::bwd_rowbatch_kernel<4>, dwconv::rb_bwd_lds_bytes(s.L, 4)); break;
-        case 5: rc = launch_rb(dwconv::bwd_rowbatch_kernel<5>, dwconv::rb_bwd_lds_bytes(s.L, 5)); break;
-        case 6: rc = launch_rb(dwconv::bwd_rowbatch_kernel<6>, dwconv::rb_bwd_lds_bytes(s.L, 6)); break;
+        case 2: rc = launch_m(dwconv::bwd_rowbatch_kernel<2, 1>, dwconv::bwd_rowbatch_kernel<2, 2>, dwconv::bwd_rowbatch_kernel<2, 3>, 2); break;
+        case 3: rc = launch_m(dwconv::bwd_rowbatch_kernel<3, 1>, dwconv::bwd_rowbatch_kernel<3, 2>, dwconv::bwd_rowbatch_kernel<3, 3>, 3); break;
+        case 4: rc = launch_m(dwconv::bwd_rowbatch_kernel<4, 1>, dwconv::bwd_rowbatch_kernel<4, 2>, dwconv::bwd_rowbatch_kernel<4, 3>, 4); break;
+        case 5: rc = launch_m(dwconv::bwd_rowbatch_kernel<5, 1>, dwconv::bwd_rowbatch_kernel<5, 2>, dwconv::bwd_rowbatch_kernel<5, 3>, 5); break;
+        case 6: rc = launch_m(dwconv::bwd_rowbatch_kernel<6, 1>, dwconv::bwd_rowbatch_kernel<6, 2>, dwconv::bwd_rowbatch_kernel<6, 3>, 6); break;
         default: break;
         }
         if (rc == DWCONV_OK && direct_rb) *wrote_dw = true;

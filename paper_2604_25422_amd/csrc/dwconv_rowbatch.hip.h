@@ -409,14 +409,16 @@ __host__ __device__ constexpr size_t rb_bwd_lds_bytes(int L, int ND)
     return (size_t)kRbBwdWaves * (size_t)(rb_bwd_wave_floats(L, ND) + 16 * ND) * sizeof(float);
 }
 
-template <int ND>
+template <int ND, int M>
 __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowbatch_kernel(
     const float *__restrict__ dy, const float *__restrict__ x, const float *__restrict__ w, float *__restrict__ dx,
     float *__restrict__ part, float *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin, int n_units)
 {
     // rows of at most kRbBwdMaxL positions (register budget: two prefetched tensors, Toeplitz operands, accumulators)
-    constexpr int NLD = kRbRows * (kRbBwdMaxL / 4) / 64;
-    constexpr int MB = kRbBwdMaxL / 16;
+    static_assert(M >= 1 && 16 * M <= kRbBwdMaxL, "rows of M 16-blocks");
+    constexpr int NLD = (kRbRows * 4 * M + 63) / 64;
+    constexpr int MB = M;
+    constexpr int NR = 2 * M - 1;                             // relative block offsets of the weight gradient
     extern __shared__ __align__(16) float dyn_lds[];
     const int wreg = rb_bwd_wave_floats(L, ND);
     const int tid = threadIdx.x;
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
     if (c >= C) return;                                       // (no workgroup barrier below)
     float *s_wave = dyn_lds + wave * wreg;
     float *s_dw = dyn_lds + kRbBwdWaves * wreg + wave * (16 * ND);
-    const int m = (L + 15) >> 4;
+    constexpr int m = M;
     const int Ld = 16 * m + 4;                                // pitch of the dY image
     const int Lp = rb_dw_pitch(L, 1);                         // pitch of the x image
     float *sd = s_wave, *sx = s_wave + kRbRows * Ld;
@@ -452,9 +454,10 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
         *reinterpret_cast<float4 *>(s_wave + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_fence();
 
-    floatx4 G[ND];
+    floatx4 G[NR];
 #pragma unroll
-    for (int d = 0; d < ND; ++d) G[d] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < NR; ++e) G[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int dmax = dmin + ND - 1;
     // Toeplitz operands of the input gradient: A[d][v] (lane (r, k)) = w[K - 1 - (16 (dminx + d) + 4k + v - r + padx)]
     float A[ND][4];
     {
@@ -504,20 +507,23 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
         const int unit_n = unit + stride;
         const bool more = unit_n < n_units;
         if (more) prefetch(unit_n);
-        // weight gradient: four rows per instruction
-#pragma unroll
-        for (int g4 = 0; g4 < kRbRows / 4; ++g4) {
+        // weight gradient: four rows per instruction, accumulators by relative block offset (see dw_rowbatch_kernel)
+        static_for<0, kRbRows / 4>([&](auto gc) {
+            constexpr int g4 = decltype(gc)::value;
             const float *xrow = sx + (4 * g4 + k4) * Lp + i16;
             const float *grow = sd + (4 * g4 + k4) * Ld + i16;
-            for (int mo = 0; mo < m; ++mo) {
-                const float bq = grow[16 * mo];
-#pragma unroll
-                for (int d = 0; d < ND; ++d) {
-                    const int mi = mo + dmin + d;
-                    if (mi >= 0 && mi < m) G[d] = mfma16x16x4(xrow[16 * mi], bq, G[d]);
-                }
-            }
-        }
+            float xa[M], gb[M];
+            static_for<0, M>([&](auto bc) {
+                constexpr int b = decltype(bc)::value;
+                xa[b] = xrow[16 * b];
+                gb[b] = grow[16 * b];
+            });
+            static_for<0, M * M>([&](auto pc) {
+                constexpr int mo = decltype(pc)::value / M, mi = decltype(pc)::value % M;
+                constexpr int rel = mi - mo;
+                if (rel >= dmin && rel <= dmax) G[rel + M - 1] = mfma16x16x4(xa[mi], gb[mo], G[rel + M - 1]);
+            });
+        });
         // input gradient: lane (row i16, position group k4) owns outputs 16 mo + 4 k4 + 0..3 of block mo
         floatx4 acc[MB];
 #pragma unroll
@@ -568,7 +574,7 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
     }
 
     // ---- diagonal sums of this wave's accumulators: its slice of the partial sums
-    dw_wave_diagonal_sums<ND>(G, s_wave, s_dw, lane, K, pad, dmin);
+    rb_diagonal_sums<NR>(G, M, s_wave, s_dw, lane, K, pad, dmin, ND);
     wave_lds_fence();
     for (int j = lane; j < K; j += 64) {
         const size_t o = (size_t)c * (size_t)K + (size_t)j;
