@@ -118,7 +118,8 @@ int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, vo
 /*
  * Both gradients of the backward pass in one call: dx as dwconv_bwd_input, dw as dwconv_bwd_weight.
  * The paper names kernel fusion as the remaining lever for the backward path (Sec. VI): for filters of the
- * register-resident class (dwconv_bwd_is_fused(...) == 1: fp32 with L % 4 == 0 or bf16 with L % 8 == 0, 16-byte aligned tensors) one
+ * register-resident class (dwconv_bwd_is_fused(...) == 1: K up to about 66, fp32 with L % 4 == 0 or bf16 with L % 8 == 0,
+ * 16-byte aligned tensors; not fp32 rows of 52 to 64 positions) one
  * kernel reads dy once and produces dx and the stage-1 sums of dw (5 tensor passes over memory per
  * forward + backward step instead of 6); every other shape or type runs the two separate paths one after the
  * other.  dy, x [B,C,L] in; w [C,K] in; dx [B,C,L] out; dw [C,K] out; workspace as for dwconv_bwd_weight.
@@ -141,7 +142,10 @@ int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype
  */
 int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype);
 
-/* Bytes of workspace dwconv_bwd_weight needs for this shape (S*C*K*4 rounded up); 0 on bad arguments. */
+/*
+ * Bytes of workspace dwconv_bwd_weight and dwconv_bwd need for this shape (fp32 [S', C, K] rounded up, S' the larger
+ * of S and the slice count of the fused kernel, which differs for rows of at most 48 positions); 0 on bad arguments.
+ */
 size_t dwconv_bwd_weight_workspace_bytes(int B, int C, int L, int K, int pad_left, int dtype);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
