@@ -83,20 +83,36 @@ RowsPlan plan_rows(const Shape &s)
     r.on = false; r.batch = false; r.units = 0; r.nvs = 0;
     r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    if (s.dtype != DWCONV_F32 || s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return r;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return r;
+    const long long es = (long long)elem_size(s.dtype);
     const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
     const long long P = s.L + (halo + 3) / 4 * 4;
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
     if (4 * padded <= 5 * P) return r;                       // ordinary segments waste less than a quarter
+    // sixteen rows per tile (either storage type): byte offsets inside a unit stay below the out-of-row marker
+    const bool batch = s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30);
+    if (s.dtype != DWCONV_F32) {                             // bf16: no virtual rows, the sixteen-row kernels or nothing
+        if (batch) {
+            r.on = true; r.batch = true;
+            r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
+        }
+        return r;
+    }
     const long long elems = (long long)s.B * s.C * s.L;
-    if (elems * 4 > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) return r;
+    if (elems * 4 > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) {
+        // too large for virtual rows (32-bit positions); the sixteen-row kernels have no such limit
+        if (batch) {
+            r.on = true; r.batch = true;
+            r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
+        }
+        return r;
+    }
     r.on = true;
     r.nvs = (int)(((long long)s.B * P + dwconv::kSegLen - 1) / dwconv::kSegLen);
     r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
     r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
     r.map.bytes = (unsigned)(elems * 4);
-    // byte offsets inside a unit of sixteen rows stay below the out-of-row marker
-    if (s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * 4 < (1ll << 30)) {
+    if (batch) {
         r.batch = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
     }
@@ -199,54 +215,54 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };
-    if constexpr (std::is_same<T, float>::value) {
-        // fp32 short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
-        const RowsPlan rp = plan_rows(s);
-        if (rp.batch) {
-            dwconv::RowBatchGeom rg;
-            rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
-            rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
-            rg.m = (s.L + 15) / 16;
-            rg.n_units = rp.units;
-            // two channels per wave where that makes whole cache lines of rows that are not (L * 4 % 128 != 0);
-            // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
-            const int nc = (s.C % 2 == 0 && (s.L * 4) % 128 != 0 && s.L <= 48 && nd <= 5) ? 2 : 1;
-            auto launch_batch = [&](auto kernel) -> int {
-                // one resident round of waves: J per channel group, each walking units j, j + J, ...
-                const long long groups = s.C / nc;
-                const long long resident = corr_wave_slots(kernel, 64 * dwconv::kRbCorrWaves);
-                long long J = resident / groups;
-                if (J < 1) J = 1;
-                if (J > rg.n_units) J = rg.n_units;
-                const long long upw = (rg.n_units + J - 1) / J;
-                J = (rg.n_units + upw - 1) / upw;
-                const long long blocks = (groups * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
-                if (blocks > 0x1fffffffLL) return -1;
-                rg.J = (int)J;
-                const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L, nc) * sizeof(float);
-                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
-                                   static_cast<const float *>(in), static_cast<const float *>(f),
-                                   static_cast<float *>(out), rg);
-                return launch_status();
-            };
-            if (nc == 2) {
-                switch (nd) {
-                case 2: return launch_batch(dwconv::corr_rowbatch_kernel<2, 2>);
-                case 3: return launch_batch(dwconv::corr_rowbatch_kernel<3, 2>);
-                case 4: return launch_batch(dwconv::corr_rowbatch_kernel<4, 2>);
-                case 5: return launch_batch(dwconv::corr_rowbatch_kernel<5, 2>);
-                default: return -1;
-                }
-            }
+    const RowsPlan rp = plan_rows(s);
+    if (rp.batch) {
+        // rows of at most 64 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
+        dwconv::RowBatchGeom rg;
+        rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
+        rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
+        rg.m = (s.L + 15) / 16;
+        rg.n_units = rp.units;
+        // two channels per wave where that makes whole cache lines of rows that are not, or at least longer pieces;
+        // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
+        const int nc = (s.C % 2 == 0 && (s.L * (int)sizeof(T)) % 128 != 0 && s.L <= 48 && nd <= 5) ? 2 : 1;
+        auto launch_batch = [&](auto kernel) -> int {
+            // one resident round of waves: J per channel group, each walking units j, j + J, ...
+            const long long groups = s.C / nc;
+            const long long resident = corr_wave_slots(kernel, 64 * dwconv::kRbCorrWaves);
+            long long J = resident / groups;
+            if (J < 1) J = 1;
+            if (J > rg.n_units) J = rg.n_units;
+            const long long upw = (rg.n_units + J - 1) / J;
+            J = (rg.n_units + upw - 1) / upw;
+            const long long blocks = (groups * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
+            if (blocks > 0x1fffffffLL) return -1;
+            rg.J = (int)J;
+            const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L, nc) * sizeof(float);
+            hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
+                               static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), rg);
+            return launch_status();
+        };
+        if (nc == 2) {
             switch (nd) {
-            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<2, 1>);
-            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<3, 1>);
-            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<4, 1>);
-            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<5, 1>);
-            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<6, 1>);
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2>);
             default: return -1;
             }
         }
+        switch (nd) {
+        case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1>);
+        case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1>);
+        case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1>);
+        case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1>);
+        case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1>);
+        default: return -1;
+        }
+    }
+    if constexpr (std::is_same<T, float>::value) {
+        // fp32 short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
         if (rp.on) {
             const long long total = (long long)rp.nvs * s.C;
             if (total > 0x3fffffffLL) return -1;
@@ -518,7 +534,7 @@ DwPlan plan_dw(const Shape &s)
         if (items >= 2 * wpb && fits) { p.wpb = wpb; p.single = true; }
     }
     long long groups = s.C;                                      // blocks along the channel axis
-    if (p.rows.batch && !p.single && s.C % 2 == 0 && (s.L * 4) % 128 != 0 && s.L <= 48) {
+    if (p.rows.batch && !p.single && s.C % 2 == 0 && (s.L * (int)elem_size(s.dtype)) % 128 != 0 && s.L <= 48) {
         // two neighbouring channels per block: rows that are not whole cache lines become pieces that are;
         // a unit is then eight rows of both channels
         p.dw_nc = 2;
@@ -602,40 +618,42 @@ template <typename T, int ND, int W>
 int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
                                int dmin, hipStream_t st)
 {
+    if (p.rows.batch) {
+        // rows of at most 64 positions, either storage type: sixteen rows per matrix tile
+        auto launch_rb = [&](auto kernel, int nc) -> int {
+            const size_t lds_rb = dwconv::rb_dw_lds_bytes(s.L, ND, W, nc);
+            if (lds_rb > kMaxLdsBytes) return -1;
+            if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)(s.C / nc), (unsigned)p.S), dim3(64 * W), lds_rb, st,
+                               static_cast<const T *>(x), static_cast<const T *>(dy), part, static_cast<T *>(dw_out), s.B,
+                               s.C, s.L, s.K, s.pad, dmin, ND, p.tiles_per_row);
+            return launch_status();
+        };
+        // (the kernel is compiled per number of 16-blocks of a row, not per number of block offsets)
+        const int m = (s.L + 15) / 16;
+        if constexpr (W == dwconv::kWavesPerBlock) {
+            if (p.dw_nc == 2) {
+                switch (m) {
+                case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 2>, 2);
+                case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 2>, 2);
+                case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 2>, 2);
+                default: return -1;
+                }
+            }
+        }
+        switch (m) {
+        case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 1>, 1);
+        case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 1>, 1);
+        case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 1>, 1);
+        case 4: return launch_rb(dwconv::dw_rowbatch_kernel<T, 4, W, 1>, 1);
+        default: return -1;
+        }
+    }
     if constexpr (std::is_same<T, float>::value) {
         // fp32 rows go from memory straight into LDS
         constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
-        if (p.rows.batch) {
-            auto launch_rb = [&](auto kernel, int nc) -> int {
-                const size_t lds_rb = dwconv::rb_dw_lds_bytes(s.L, ND, W, nc);
-                if (lds_rb > kMaxLdsBytes) return -1;
-                if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-                hipLaunchKernelGGL(kernel, dim3((unsigned)(s.C / nc), (unsigned)p.S), dim3(64 * W), lds_rb, st,
-                                   static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                                   static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, ND, p.tiles_per_row);
-                return launch_status();
-            };
-            // (the kernel is compiled per number of 16-blocks of a row, not per number of block offsets)
-            const int m = (s.L + 15) / 16;
-            if constexpr (W == dwconv::kWavesPerBlock) {
-                if (p.dw_nc == 2) {
-                    switch (m) {
-                    case 1: return launch_rb(dwconv::dw_rowbatch_kernel<1, W, 2>, 2);
-                    case 2: return launch_rb(dwconv::dw_rowbatch_kernel<2, W, 2>, 2);
-                    case 3: return launch_rb(dwconv::dw_rowbatch_kernel<3, W, 2>, 2);
-                    default: return -1;
-                    }
-                }
-            }
-            switch (m) {
-            case 1: return launch_rb(dwconv::dw_rowbatch_kernel<1, W, 1>, 1);
-            case 2: return launch_rb(dwconv::dw_rowbatch_kernel<2, W, 1>, 1);
-            case 3: return launch_rb(dwconv::dw_rowbatch_kernel<3, W, 1>, 1);
-            case 4: return launch_rb(dwconv::dw_rowbatch_kernel<4, W, 1>, 1);
-            default: return -1;
-            }
-        } else if (p.rows.on) {
+        if (p.rows.on) {
             auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
             hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
@@ -861,11 +879,52 @@ int launch_bwd_fused_nd(const void *dy, const void *x, const void *w, void *dx, 
     }
 }
 
+// Rows of at most 48 positions: sixteen rows per tile, one wave per (channel, slice).  Returns -1 when it does not apply.
+template <typename T>
+int launch_bwd_rowbatch(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
+                        const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
+    const int nd = dmax - dmin + 1;
+    if (s.L > dwconv::kRbBwdMaxL || nd < 2 || nd > kMfmaMaxND) return -1;
+    if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T)) || !aligned_to(dx, 4 * sizeof(T))) return -1;
+    void *direct_rb = p.S_fused == 1 ? dw_out : nullptr;
+    auto launch_rb = [&](auto kernel, size_t lds_rb) -> int {
+        if (lds_rb > kMaxLdsBytes) return -1;
+        if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)((s.C + dwconv::kRbBwdWaves - 1) / dwconv::kRbBwdWaves), (unsigned)p.S_fused),
+                           dim3(64 * dwconv::kRbBwdWaves), lds_rb, st, static_cast<const T *>(dy), static_cast<const T *>(x),
+                           static_cast<const T *>(w), static_cast<T *>(dx), part, static_cast<T *>(direct_rb), s.B, s.C, s.L,
+                           s.K, s.pad, dmin, p.rows.units);
+        return launch_status();
+    };
+    const int m = (s.L + 15) / 16;              // the kernel is compiled per (block offsets, 16-blocks of a row)
+    auto launch_m = [&](auto k1, auto k2, auto k3, int ndv) -> int {
+        const size_t lds_rb = dwconv::rb_bwd_lds_bytes(s.L, ndv);
+        return m == 1 ? launch_rb(k1, lds_rb) : m == 2 ? launch_rb(k2, lds_rb) : launch_rb(k3, lds_rb);
+    };
+    int rc = -1;
+    switch (nd) {
+    case 2: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 2, 1>, dwconv::bwd_rowbatch_kernel<T, 2, 2>, dwconv::bwd_rowbatch_kernel<T, 2, 3>, 2); break;
+    case 3: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 3, 1>, dwconv::bwd_rowbatch_kernel<T, 3, 2>, dwconv::bwd_rowbatch_kernel<T, 3, 3>, 3); break;
+    case 4: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 4, 1>, dwconv::bwd_rowbatch_kernel<T, 4, 2>, dwconv::bwd_rowbatch_kernel<T, 4, 3>, 4); break;
+    case 5: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 5, 1>, dwconv::bwd_rowbatch_kernel<T, 5, 2>, dwconv::bwd_rowbatch_kernel<T, 5, 3>, 5); break;
+    case 6: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 6, 1>, dwconv::bwd_rowbatch_kernel<T, 6, 2>, dwconv::bwd_rowbatch_kernel<T, 6, 3>, 6); break;
+    default: break;
+    }
+    if (rc == DWCONV_OK && direct_rb) *wrote_dw = true;
+    return rc;
+}
+
 int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
                      const Shape &s, const DwPlan &p, hipStream_t st)
 {
     *wrote_dw = false;
     if (p.longk) return -1;
+    if (p.rows.batch) {
+        if (s.dtype == DWCONV_F32) return launch_bwd_rowbatch<float>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
+        return launch_bwd_rowbatch<bf16_t>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
+    }
     // bf16: whole 16-byte granules of 8 elements
     if (s.dtype == DWCONV_BF16 && (s.L % 8) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
@@ -874,35 +933,6 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     if (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)) return -1;
     void *direct = (p.single && p.S == 1) ? dw_out : nullptr;
     int rc = -1;
-    if (p.rows.batch) {
-        // rows of at most 48 positions: sixteen rows per tile, one wave per (channel, slice)
-        if (s.L > dwconv::kRbBwdMaxL) return -1;
-        void *direct_rb = p.S_fused == 1 ? dw_out : nullptr;
-        auto launch_rb = [&](auto kernel, size_t lds_rb) -> int {
-            if (lds_rb > kMaxLdsBytes) return -1;
-            if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-            hipLaunchKernelGGL(kernel, dim3((unsigned)((s.C + dwconv::kRbBwdWaves - 1) / dwconv::kRbBwdWaves), (unsigned)p.S_fused),
-                               dim3(64 * dwconv::kRbBwdWaves), lds_rb, st, static_cast<const float *>(dy),
-                               static_cast<const float *>(x), static_cast<const float *>(w), static_cast<float *>(dx), part,
-                               static_cast<float *>(direct_rb), s.B, s.C, s.L, s.K, s.pad, dmin, p.rows.units);
-            return launch_status();
-        };
-        const int m = (s.L + 15) / 16;              // the kernel is compiled per (block offsets, 16-blocks of a row)
-        auto launch_m = [&](auto k1, auto k2, auto k3, int ndv) -> int {
-            const size_t lds_rb = dwconv::rb_bwd_lds_bytes(s.L, ndv);
-            return m == 1 ? launch_rb(k1, lds_rb) : m == 2 ? launch_rb(k2, lds_rb) : launch_rb(k3, lds_rb);
-        };
-        switch (nd) {
-        case 2: rc = launch_m(dwconv::bwd_rowbatch_kernel<2, 1>, dwconv::bwd_rowbatch_kernel<2, 2>, dwconv::bwd_rowbatch_kernel<2, 3>, 2); break;
-        case 3: rc = launch_m(dwconv::bwd_rowbatch_kernel<3, 1>, dwconv::bwd_rowbatch_kernel<3, 2>, dwconv::bwd_rowbatch_kernel<3, 3>, 3); break;
-        case 4: rc = launch_m(dwconv::bwd_rowbatch_kernel<4, 1>, dwconv::bwd_rowbatch_kernel<4, 2>, dwconv::bwd_rowbatch_kernel<4, 3>, 4); break;
-        case 5: rc = launch_m(dwconv::bwd_rowbatch_kernel<5, 1>, dwconv::bwd_rowbatch_kernel<5, 2>, dwconv::bwd_rowbatch_kernel<5, 3>, 5); break;
-        case 6: rc = launch_m(dwconv::bwd_rowbatch_kernel<6, 1>, dwconv::bwd_rowbatch_kernel<6, 2>, dwconv::bwd_rowbatch_kernel<6, 3>, 6); break;
-        default: break;
-        }
-        if (rc == DWCONV_OK && direct_rb) *wrote_dw = true;
-        return rc;
-    }
     switch (nd) {
     case 2: rc = launch_bwd_fused_nd<2>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
     case 3: rc = launch_bwd_fused_nd<3>(dy, x, w, dx, part, direct, s, p, dmin, st); break;
@@ -1040,7 +1070,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const Shape s{B, C, L, K, pad_left, dtype};
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
-    if (p.rows.batch && L > dwconv::kRbBwdMaxL) return 0;
+    if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type, L % 4 == 0
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
             L <= kMfmaMaxL) ? 1 : 0;
 }

@@ -1,4 +1,5 @@
-// Short rows on the matrix cores, sixteen rows at a time (fp32, L <= 64, L % 4 == 0).
+// Short rows on the matrix cores, sixteen rows at a time (L <= 64, L % 4 == 0; fp32, or bf16 storage widened to
+// fp32 on the way into LDS: fp32 matrix instructions and sums either way, one rounding at the store).
 //
 // The operator of Sec. IV-A eq. (dwconv) treats every row (b, c) on its own, and the paper's own workload
 // (Sec. V: windows of 48 steps) has rows of three 16-blocks.  The blocked-Toeplitz contraction of
@@ -54,10 +55,12 @@ struct RowBatchGeom {
 };
 
 // Resource over rows b0 .. b0 + nr - 1 of channel c (row r of the unit starts r * C * L elements after the first).
-__device__ __forceinline__ uintx4 rb_unit_resource(const float *base, int nr, int CL, int L)
+template <typename T>
+__device__ __forceinline__ uintx4 rb_unit_resource(const T *base, int nr, int CL, int L)
 {
     const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-    const uintx4 r = {(unsigned)a, (unsigned)(a >> 32) & 0xffffu, (unsigned)(((nr - 1) * CL + L) * 4), kBufferFlags};
+    const uintx4 r = {(unsigned)a, (unsigned)(a >> 32) & 0xffffu, (unsigned)(((nr - 1) * CL + L) * (int)sizeof(T)),
+                      kBufferFlags};
     return r;
 }
 
@@ -77,10 +80,11 @@ constexpr int kRbCorrWaves = 4;   // waves per block: neighbouring channels, who
 // image, channel by channel, and the tiles of a channel replace its inputs; then every lane swaps its granules of
 // the image (the lane-to-granule map of the loads): the outputs go out as whole rows (streaming stores, as in the
 // long-row kernel), the prefetched inputs of the next unit come in.
-template <int ND, int NC>
+template <typename T, int ND, int NC>
 __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_rowbatch_kernel(
-    const float *__restrict__ in, const float *__restrict__ f, float *__restrict__ out, const RowBatchGeom g)
+    const T *__restrict__ in, const T *__restrict__ f, T *__restrict__ out, const RowBatchGeom g)
 {
+    constexpr int ES = (int)sizeof(T);          // bf16 storage is widened on the way into LDS; fp32 arithmetic
     // two channels per wave: rows of at most 48 positions (register budget)
     constexpr int NLD = NC == 2 ? 6 : kRbMaxLoads;
     constexpr int MB = NC == 2 ? 3 : kRbMaxBlocks;
@@ -110,28 +114,28 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
         const int r = gi / (NC * Lg), cg = gi - r * (NC * Lg);
         const int h = (NC > 1 && cg >= Lg) ? 1 : 0;
         static_assert(NC <= 2, "one or two channels per wave");
-        gl_off[i] = gi < NG ? 4 * (r * CL + 4 * cg) : kOutOfRow;
+        gl_off[i] = gi < NG ? ES * (r * CL + 4 * cg) : kOutOfRow;
         img[i] = gi < NG ? r * Lo + h * Lc + 4 * (cg - h * Lg) : 0;
     }
     for (int i = lane; i < kRbRows * Lo / 4; i += 64)
         *reinterpret_cast<float4 *>(sw + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_fence();
 
-    uintx4 pre[NLD];
+    typename Raw4<T>::type pre[NLD];
     auto prefetch = [&](int u) {
         const int b0 = kRbRows * u;
         const int nr = g.B - b0 < kRbRows ? g.B - b0 : kRbRows;        // rows past the batch read as zeros
         const uintx4 r = rb_unit_resource(in + ((size_t)b0 * (size_t)g.C + (size_t)c0) * (size_t)g.L, nr, CL, NC * g.L);
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
-            if (i < nld) pre[i] = buffer_load_x4_untracked(r, gl_off[i]);
+            if (i < nld) pre[i] = Raw4<T>::load(r, gl_off[i]);
     };
     auto drain = [&]() {
         wait_untracked_loads();
         release_after_wait(pre);
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
-            if (i < nld && lane + 64 * i < NG) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<float>::widen(pre[i]);
+            if (i < nld && lane + 64 * i < NG) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<T>::widen(pre[i]);
     };
     prefetch(unit);
     drain();
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
     float A[NC][ND][4];
 #pragma unroll
     for (int h = 0; h < NC; ++h) {
-        const float *f_c = f + (size_t)(c0 + h) * (size_t)g.K;
+        const T *f_c = f + (size_t)(c0 + h) * (size_t)g.K;
 #pragma unroll
         for (int d = 0; d < ND; ++d)
 #pragma unroll
@@ -149,7 +153,7 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
                 const int j = 16 * (g.dmin + d) + 4 * k4 + v - i16 + g.pad;
                 const bool ok = j >= 0 && j < g.K;
                 const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
-                const float a = f_c[jc];
+                const float a = ld_elem(f_c + jc);
                 A[h][d][v] = ok ? a : 0.f;
             }
     }
@@ -195,14 +199,14 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_row
         {
             const int b0 = kRbRows * unit;
             const int nr = g.B - b0 < kRbRows ? g.B - b0 : kRbRows;
-            const int lim = 4 * nr * CL;                                                   // byte offsets of real rows
-            float *out_u = out + ((size_t)b0 * (size_t)g.C + (size_t)c0) * (size_t)g.L;     // wave-uniform
+            const int lim = ES * nr * CL;                                                  // byte offsets of real rows
+            T *out_u = out + ((size_t)b0 * (size_t)g.C + (size_t)c0) * (size_t)g.L;     // wave-uniform
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
                 if (i < nld && lane + 64 * i < NG) {
                     const float4 ov = *reinterpret_cast<const float4 *>(sw + img[i]);
-                    if (more) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<float>::widen(pre[i]);
-                    if (gl_off[i] < lim) st_elem4_stream(out_u + (gl_off[i] >> 2), ov);
+                    if (more) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<T>::widen(pre[i]);
+                    if (gl_off[i] < lim) st_elem4_stream(out_u + gl_off[i] / ES, ov);
                 }
         }
         wave_lds_fence();
@@ -259,11 +263,12 @@ __device__ __forceinline__ void rb_diagonal_sums(const floatx4 (&G)[NR], int M, 
 // together, ahead of its matrix instructions.
 // dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (gridDim.y == 1) they are the
 // weight gradient itself.
-template <int M, int W, int NC>
+template <typename T, int M, int W, int NC>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
-    const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
+    const T *__restrict__ x, const T *__restrict__ dy, float *__restrict__ part, T *__restrict__ dw_out,
     int B, int C, int L, int K, int pad, int dmin, int nd, int n_units)
 {
+    constexpr int ES = (int)sizeof(T);
     static_assert(NC == 1 || NC == 2, "one or two channels per wave");
     static_assert(M >= 1 && M <= kRbMaxBlocks && (NC == 1 || M <= 3), "rows of at most 64 (two channels: 48) positions");
     constexpr int RU = kRbRows / NC;                          // rows per unit
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
         const int gi = lane + 64 * i;
         const int r = gi / (NC * Lg), cg = gi - r * (NC * Lg);
         const int h = (NC > 1 && cg >= Lg) ? 1 : 0;
-        gl_off[i] = gi < NG ? 4 * (r * CL + 4 * cg) : kOutOfRow;
+        gl_off[i] = gi < NG ? ES * (r * CL + 4 * cg) : kOutOfRow;
         lds_idx[i] = gi < NG ? r * Lp + h * Lc + 4 * (cg - h * Lg) : 0;
     }
     for (int i = lane; i < 2 * RU * Lp / 4; i += 64)
@@ -308,7 +313,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
 
     const int stride = (int)gridDim.y * W;
     int unit = (int)blockIdx.y * W + wave;
-    uintx4 px[NLD], pg[NLD];
+    typename Raw4<T>::type px[NLD], pg[NLD];
     auto prefetch = [&](int u) {
         const int b0 = RU * (n_units - 1 - u);
         const int nr = B - b0 < RU ? B - b0 : RU;
@@ -318,8 +323,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld) {
-                px[i] = buffer_load_x4_untracked(rx, gl_off[i]);
-                pg[i] = buffer_load_x4_untracked(rg, gl_off[i]);
+                px[i] = Raw4<T>::load(rx, gl_off[i]);
+                pg[i] = Raw4<T>::load(rg, gl_off[i]);
             }
     };
     auto drain = [&]() {
@@ -329,8 +334,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld && lane + 64 * i < NG) {
-                *reinterpret_cast<float4 *>(sx + lds_idx[i]) = Raw4<float>::widen(px[i]);
-                *reinterpret_cast<float4 *>(sg + lds_idx[i]) = Raw4<float>::widen(pg[i]);
+                *reinterpret_cast<float4 *>(sx + lds_idx[i]) = Raw4<T>::widen(px[i]);
+                *reinterpret_cast<float4 *>(sg + lds_idx[i]) = Raw4<T>::widen(pg[i]);
             }
     };
     if (unit < n_units) {
@@ -380,7 +385,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
 #pragma unroll
         for (int w = 0; w < W; ++w) sum += s_dw[(w * NC + h) * (16 * nd) + j];
         const size_t o = (size_t)(c0 + h) * (size_t)K + (size_t)j;
-        if (dw_out) dw_out[o] = sum;
+        if (dw_out) st_elem(dw_out + o, sum);
         else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = sum;
     }
 }
@@ -409,11 +414,12 @@ __host__ __device__ constexpr size_t rb_bwd_lds_bytes(int L, int ND)
     return (size_t)kRbBwdWaves * (size_t)(rb_bwd_wave_floats(L, ND) + 16 * ND) * sizeof(float);
 }
 
-template <int ND, int M>
+template <typename T, int ND, int M>
 __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowbatch_kernel(
-    const float *__restrict__ dy, const float *__restrict__ x, const float *__restrict__ w, float *__restrict__ dx,
-    float *__restrict__ part, float *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin, int n_units)
+    const T *__restrict__ dy, const T *__restrict__ x, const T *__restrict__ w, T *__restrict__ dx,
+    float *__restrict__ part, T *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin, int n_units)
 {
+    constexpr int ES = (int)sizeof(T);
     // rows of at most kRbBwdMaxL positions (register budget: two prefetched tensors, Toeplitz operands, accumulators)
     static_assert(M >= 1 && 16 * M <= kRbBwdMaxL, "rows of M 16-blocks");
     constexpr int NLD = (kRbRows * 4 * M + 63) / 64;
@@ -446,7 +452,7 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
     for (int i = 0; i < NLD; ++i) {
         const int gi = lane + 64 * i;
         const int r = gi / Lg, cg = gi - r * Lg;
-        gl_off[i] = gi < NG ? 4 * (r * CL + 4 * cg) : kOutOfRow;
+        gl_off[i] = gi < NG ? ES * (r * CL + 4 * cg) : kOutOfRow;
         img_d[i] = gi < NG ? r * Ld + 4 * cg : 0;
         img_x[i] = gi < NG ? r * Lp + 4 * cg : 0;
     }
@@ -461,21 +467,21 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
     // Toeplitz operands of the input gradient: A[d][v] (lane (r, k)) = w[K - 1 - (16 (dminx + d) + 4k + v - r + padx)]
     float A[ND][4];
     {
-        const float *f_c = w + (size_t)c * (size_t)K;
+        const T *f_c = w + (size_t)c * (size_t)K;
 #pragma unroll
         for (int d = 0; d < ND; ++d)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int j = 16 * (dminx + d) + 4 * k4 + v - i16 + padx;
                 const bool ok = j >= 0 && j < K;
-                const float a = f_c[ok ? K - 1 - j : 0];
+                const float a = ld_elem(f_c + (ok ? K - 1 - j : 0));
                 A[d][v] = ok ? a : 0.f;
             }
     }
 
     const int stride = (int)gridDim.y;
     int unit = (int)blockIdx.y;
-    uintx4 pd[NLD], px[NLD];
+    typename Raw4<T>::type pd[NLD], px[NLD];
     auto prefetch = [&](int u) {
         const int b0 = kRbRows * (n_units - 1 - u);
         const int nr = B - b0 < kRbRows ? B - b0 : kRbRows;
@@ -485,8 +491,8 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld) {
-                pd[i] = buffer_load_x4_untracked(rd, gl_off[i]);
-                px[i] = buffer_load_x4_untracked(rx, gl_off[i]);
+                pd[i] = Raw4<T>::load(rd, gl_off[i]);
+                px[i] = Raw4<T>::load(rx, gl_off[i]);
             }
     };
     if (unit < n_units) {
@@ -497,8 +503,8 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld && lane + 64 * i < NG) {
-                *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<float>::widen(pd[i]);
-                *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<float>::widen(px[i]);
+                *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<T>::widen(pd[i]);
+                *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<T>::widen(px[i]);
             }
         wave_lds_fence();
     }
@@ -556,17 +562,17 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
         {
             const int b0 = kRbRows * (n_units - 1 - unit);
             const int nr = B - b0 < kRbRows ? B - b0 : kRbRows;
-            const int lim = 4 * nr * CL;
-            float *dx_u = dx + ((size_t)b0 * (size_t)C + (size_t)c) * (size_t)L;
+            const int lim = ES * nr * CL;
+            T *dx_u = dx + ((size_t)b0 * (size_t)C + (size_t)c) * (size_t)L;
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
                 if (i < nld && lane + 64 * i < NG) {
                     const float4 ov = *reinterpret_cast<const float4 *>(sd + img_d[i]);
                     if (more) {
-                        *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<float>::widen(pd[i]);
-                        *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<float>::widen(px[i]);
+                        *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<T>::widen(pd[i]);
+                        *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<T>::widen(px[i]);
                     }
-                    if (gl_off[i] < lim) st_elem4_stream(dx_u + (gl_off[i] >> 2), ov);
+                    if (gl_off[i] < lim) st_elem4_stream(dx_u + gl_off[i] / ES, ov);
                 }
         }
         wave_lds_fence();
@@ -578,7 +584,7 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
     wave_lds_fence();
     for (int j = lane; j < K; j += 64) {
         const size_t o = (size_t)c * (size_t)K + (size_t)j;
-        if (dw_out) dw_out[o] = s_dw[j];
+        if (dw_out) st_elem(dw_out + o, s_dw[j]);
         else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = s_dw[j];
     }
 }

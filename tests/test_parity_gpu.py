@@ -56,6 +56,13 @@ def test_short_rows_f32(oracle_mod, B, C, L, K, p):
     check_case(oracle_mod, B, C, L, K, p, "f32", seed=B + C + L + K)
 
 
+# the same kernels on bf16 storage (rows widened to fp32 on the way into LDS, one rounding at the store)
+@pytest.mark.parametrize("B,C,L,K,p", SHORT_ROWS)
+def test_short_rows_bf16(oracle_mod, B, C, L, K, p):
+    print(f"case short rows bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
+    check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K + 1)
+
+
 # Rows of a million positions and more: byte offsets inside a row beyond 2^22, thousands of segments per row.
 @pytest.mark.parametrize("B,C,L,K,p,dtype", [
     (1, 2, (1 << 20) + 4, 64, 63, "f32"), (1, 1, 3000004, 7, 3, "f32"), (1, 2, (1 << 20) + 8, 32, 31, "bf16"),
@@ -182,6 +189,7 @@ BWD = [
     (2, 5, 257, 7, 3, "f32", False), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", True), (3, 5, 1004, 32, 16, "bf16", False),
     (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", True), (10, 768, 1024, 32, 31, "bf16", True),
     (2, 2, 48, 48, 24, "bf16", True), (3, 2, 4096, 66, 65, "bf16", True), (40, 256, 1024, 64, 63, "bf16", True),
+    (100, 6, 44, 31, 15, "bf16", True), (37, 3, 60, 20, 10, "bf16", False), (70, 256, 48, 48, 24, "bf16", True),
     (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", False),
 ]
 
