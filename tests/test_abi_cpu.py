@@ -113,6 +113,11 @@ def test_workspace_query_rejects_bad_shapes(lib):
         S = lib.dwconv_bwd_weight_slices(B, C, L, K, p, dt)
         n = lib.dwconv_bwd_weight_workspace_bytes(B, C, L, K, p, dt)
         assert S >= 1 and n >= S * C * K * 4 and n % 16 == 0
+    # rows of at most 48 positions: the fused backward call writes one slice per wave (about 4096 / C per channel),
+    # more than the separate weight-gradient call; the query covers both
+    assert lib.dwconv_bwd_weight_workspace_bytes(16384, 128, 48, 48, 24, 0) >= 32 * 128 * 48 * 4
+    assert lib.dwconv_bwd_weight_workspace_bytes(16384, 128, 48, 48, 24, 1) >= 32 * 128 * 48 * 4
+    assert lib.dwconv_bwd_is_fused(16384, 128, 48, 48, 24, 1) == 1 and lib.dwconv_bwd_is_fused(4096, 8, 60, 16, 8, 1) == 0
 
 
 def test_single_pass_query(lib):
