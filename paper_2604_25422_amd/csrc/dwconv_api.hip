@@ -91,15 +91,8 @@ RowsPlan plan_rows(const Shape &s)
     if (4 * padded <= 5 * P) return r;                       // ordinary segments waste less than a quarter
     // sixteen rows per tile (either storage type): byte offsets inside a unit stay below the out-of-row marker
     const bool batch = s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30);
-    if (s.dtype != DWCONV_F32) {                             // bf16: no virtual rows, the sixteen-row kernels or nothing
-        if (batch) {
-            r.on = true; r.batch = true;
-            r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
-        }
-        return r;
-    }
     const long long elems = (long long)s.B * s.C * s.L;
-    if (elems * 4 > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) {
+    if (elems * es > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) {
         // too large for virtual rows (32-bit positions); the sixteen-row kernels have no such limit
         if (batch) {
             r.on = true; r.batch = true;
@@ -111,7 +104,7 @@ RowsPlan plan_rows(const Shape &s)
     r.nvs = (int)(((long long)s.B * P + dwconv::kSegLen - 1) / dwconv::kSegLen);
     r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
     r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
-    r.map.bytes = (unsigned)(elems * 4);
+    r.map.bytes = (unsigned)(elems * es);
     if (batch) {
         r.batch = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
@@ -261,8 +254,8 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         default: return -1;
         }
     }
-    if constexpr (std::is_same<T, float>::value) {
-        // fp32 short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
+    {
+        // longer short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
         if (rp.on) {
             const long long total = (long long)rp.nvs * s.C;
             if (total > 0x3fffffffLL) return -1;
@@ -285,16 +278,16 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                 g.step_rows = g.n_waves / g.segs_per_row;
                 g.step_seg = g.n_waves % g.segs_per_row;
                 g.step_c = 0;
-                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, static_cast<const float *>(in),
-                                   static_cast<const float *>(f), static_cast<float *>(out), g, rp.map);
+                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, static_cast<const T *>(in),
+                                   static_cast<const T *>(f), static_cast<T *>(out), g, rp.map);
                 return launch_status();
             };
             switch (nd) {
-            case 2: return launch_rows(dwconv::corr_mfma_kernel<float, 2, true>);
-            case 3: return launch_rows(dwconv::corr_mfma_kernel<float, 3, true>);
-            case 4: return launch_rows(dwconv::corr_mfma_kernel<float, 4, true>);
-            case 5: return launch_rows(dwconv::corr_mfma_kernel<float, 5, true>);
-            case 6: return launch_rows(dwconv::corr_mfma_kernel<float, 6, true>);
+            case 2: return launch_rows(dwconv::corr_mfma_kernel<T, 2, true>);
+            case 3: return launch_rows(dwconv::corr_mfma_kernel<T, 3, true>);
+            case 4: return launch_rows(dwconv::corr_mfma_kernel<T, 4, true>);
+            case 5: return launch_rows(dwconv::corr_mfma_kernel<T, 5, true>);
+            case 6: return launch_rows(dwconv::corr_mfma_kernel<T, 6, true>);
             default: return -1;
             }
         }
@@ -666,6 +659,15 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                                static_cast<const float *>(x), static_cast<const float *>(dy), part,
                                static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
         }
+    } else if (p.rows.on) {
+        // bf16 short rows (longer than 64 positions): the virtual row of a channel, widened to fp32 through registers
+        auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W, true>;
+        constexpr size_t lds = dwconv::dw_mfma_lds_bytes(ND, W);
+        static_assert(lds <= kMaxLdsBytes, "LDS budget");
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const T *>(x),
+                           static_cast<const T *>(dy), part, static_cast<T *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin,
+                           p.tiles_per_row, p.rows.map);
     } else if ((s.L % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
         // bf16 rows of whole 16-byte granules: raw rows straight into LDS, bf16 matrix instruction
         auto kernel = dwconv::dw_partial_bf16_kernel<ND, W>;
@@ -676,13 +678,13 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                            static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part,
                            static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row);
     } else {
-        auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W>;
+        auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W, false>;
         constexpr size_t lds = dwconv::dw_mfma_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
         if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
         hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const T *>(x),
                            static_cast<const T *>(dy), part, static_cast<T *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin,
-                           p.tiles_per_row);
+                           p.tiles_per_row, p.rows.map);
     }
     return launch_status();
 }
@@ -925,6 +927,7 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
         if (s.dtype == DWCONV_F32) return launch_bwd_rowbatch<float>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
         return launch_bwd_rowbatch<bf16_t>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
     }
+    if (s.dtype == DWCONV_BF16 && p.rows.on) return -1;      // bf16 virtual rows: the two separate kernels
     // bf16: whole 16-byte granules of 8 elements
     if (s.dtype == DWCONV_BF16 && (s.L % 8) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
@@ -1071,6 +1074,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
     if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type, L % 4 == 0
+    if (dtype == DWCONV_BF16 && p.rows.on) return 0;
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
             L <= kMfmaMaxL) ? 1 : 0;
 }

@@ -560,10 +560,12 @@ constexpr size_t dw_mfma_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(
 
 // W waves per block.  dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (one
 // block per channel, gridDim.y == 1) they are the weight gradient itself and go to dw_out.
-template <typename T, int ND, int W>
+// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap); B is then 1 and segs_per_row the
+// number of segments of the virtual row.
+template <typename T, int ND, int W, bool ROWS>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_mfma_kernel(
     const T *__restrict__ x, const T *__restrict__ dy, float *__restrict__ part, T *__restrict__ dw_out, int B, int C,
-    int L, int K, int pad, int dmin, int segs_per_row)
+    int L, int K, int pad, int dmin, int segs_per_row, const RowsMap rm)
 {
     constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
     constexpr int NGX = XW / 4;
@@ -605,15 +607,33 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_mfma_ker
 
     float4 pre_x[NLX], pre_g[NLG];
     auto prefetch = [&](int pb, int pseg) {
-        // batches are walked from the last to the first: the input-gradient call that usually runs just before
-        // this one walks them upwards, so its last rows of dY are still in the last-level cache
-        const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
-        const int t0 = pseg * kSegLen;
-        const int u0 = t0 + 16 * dmin;
+        if constexpr (ROWS) {
+            // virtual segments are walked downwards, like the batches below; every lane translates its positions
+            const int t0 = (segs_per_row - 1 - pseg) * kSegLen;
+            const int u0 = t0 + 16 * dmin;
+            const T *xc = x + (size_t)c * (size_t)L, *gc = dy + (size_t)c * (size_t)L;
+            const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int i = 0; i < NLX; ++i) pre_x[i] = ld4_clamped(x + row, u0 + 4 * (lane + 64 * i), L);
+            for (int i = 0; i < NLX; ++i) {
+                const int e = rows_element(rm, u0 + 4 * (lane + 64 * i));
+                pre_x[i] = e >= 0 ? ld_elem4(xc + e) : zero;
+            }
 #pragma unroll
-        for (int i = 0; i < NLG; ++i) pre_g[i] = ld4_clamped(dy + row, t0 + 4 * (lane + 64 * i), L);
+            for (int i = 0; i < NLG; ++i) {
+                const int e = rows_element(rm, t0 + 4 * (lane + 64 * i));
+                pre_g[i] = e >= 0 ? ld_elem4(gc + e) : zero;
+            }
+        } else {
+            // batches are walked from the last to the first: the input-gradient call that usually runs just before
+            // this one walks them upwards, so its last rows of dY are still in the last-level cache
+            const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
+            const int t0 = pseg * kSegLen;
+            const int u0 = t0 + 16 * dmin;
+#pragma unroll
+            for (int i = 0; i < NLX; ++i) pre_x[i] = ld4_clamped(x + row, u0 + 4 * (lane + 64 * i), L);
+#pragma unroll
+            for (int i = 0; i < NLG; ++i) pre_g[i] = ld4_clamped(dy + row, t0 + 4 * (lane + 64 * i), L);
+        }
     };
     auto drain = [&](int pseg) {
         const int t0 = pseg * kSegLen;
@@ -621,12 +641,12 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_mfma_ker
 #pragma unroll
         for (int i = 0; i < NLX; ++i) {
             const int gi = lane + 64 * i;
-            if (gi < NGX) *reinterpret_cast<float4 *>(sx + 4 * gi) = mask4(pre_x[i], u0 + 4 * gi, L);
+            if (gi < NGX) *reinterpret_cast<float4 *>(sx + 4 * gi) = ROWS ? pre_x[i] : mask4(pre_x[i], u0 + 4 * gi, L);
         }
 #pragma unroll
         for (int i = 0; i < NLG; ++i) {
             const int gi = lane + 64 * i;
-            *reinterpret_cast<float4 *>(sg + 4 * gi) = mask4(pre_g[i], t0 + 4 * gi, L);
+            *reinterpret_cast<float4 *>(sg + 4 * gi) = ROWS ? pre_g[i] : mask4(pre_g[i], t0 + 4 * gi, L);
         }
     };
     if (b < B) {

@@ -80,7 +80,10 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
 
 
 @pytest.mark.parametrize("B,C,L,K,p", SMALL[::2] + [(4, 6, 1024, 32, 31), (3, 5, 1000, 32, 16), (2, 3, 1004, 32, 31),
-                                                   (3, 2, 256, 200, 100), (1, 2, 2048, 1500, 700), (2, 2, 2056, 64, 0)])
+                                                   (3, 2, 256, 200, 100), (1, 2, 2048, 1500, 700), (2, 2, 2056, 64, 0),
+                                                   # bf16 short rows longer than 64 positions: virtual rows
+                                                   (40, 6, 128, 16, 15), (33, 3, 100, 31, 30), (9, 256, 256, 33, 16),
+                                                   (64, 2, 512, 64, 63), (7, 5, 68, 7, 3), (300, 2, 72, 48, 24)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
@@ -187,9 +190,10 @@ BWD = [
     (3, 2, 2048, 66, 65, "f32", True), (2, 2, 3072, 66, 0, "f32", True), (2, 3, 2052, 40, 20, "f32", True),
     (9, 256, 3900, 64, 63, "f32", True), (4, 512, 4096, 7, 3, "f32", True), (11, 768, 1032, 20, 0, "f32", True),
     (2, 5, 257, 7, 3, "f32", False), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", True), (3, 5, 1004, 32, 16, "bf16", False),
-    (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", True), (10, 768, 1024, 32, 31, "bf16", True),
+    (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", False), (10, 768, 1024, 32, 31, "bf16", True),
     (2, 2, 48, 48, 24, "bf16", True), (3, 2, 4096, 66, 65, "bf16", True), (40, 256, 1024, 64, 63, "bf16", True),
     (100, 6, 44, 31, 15, "bf16", True), (37, 3, 60, 20, 10, "bf16", False), (70, 256, 48, 48, 24, "bf16", True),
+    (20, 4, 128, 16, 15, "bf16", False), (20, 4, 128, 16, 15, "f32", True),
     (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", False),
 ]
 
