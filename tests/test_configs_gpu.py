@@ -79,7 +79,7 @@ def test_cfg4_bf16_full_size(oracle_mod):
 
 
 def test_paper_shape_full_size(oracle_mod):
-    # the shape the paper measures (Sec. V): many short rows, walked as virtual rows
+    # the shape the paper measures (Sec. V): many short rows, sixteen rows to a matrix tile
     run_full_size(oracle_mod, workloads.WORKLOADS[5], 8192, 16)
 
 
@@ -88,6 +88,10 @@ def test_paper_shape_full_size(oracle_mod):
     (7, 300, 12000, 64, 63, "f32"),        # long rows, odd batch
     (33, 257, 2040, 20, 19, "bf16"),       # bf16, odd channel count, row length a multiple of 8 but not of 16
     (600, 96, 200, 31, 15, "f32"),         # short rows: virtual rows with several slices
+    (600, 96, 200, 31, 15, "bf16"),        # the same on bf16 storage (widening kernels)
+    (8192, 128, 48, 48, 24, "bf16"),       # half the paper's batch on bf16 storage: sixteen rows per tile, channel pairs
+    (5000, 130, 64, 64, 63, "f32"),        # rows of four blocks, six block offsets, batch not a multiple of sixteen
+    (24, 256, 4096, 128, 127, "f32"),      # nine block offsets (fp32 filters up to 130 taps)
 ])
 def test_mid_size_odd_shapes(oracle_mod, B, C, L, K, p, dtype):
     wl = workloads.Workload(f"odd_B{B}_C{C}_L{L}_K{K}_p{p}_{dtype}", 9, B, C, L, K, p, dtype, "normal")
