@@ -209,9 +209,10 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPe
     // The four waves of a block take four consecutive segments, so three of the four halos a block
     // needs are the tails of segments the same compute unit has just read.
     const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    int row = wg / g.segs_per_row;                 // b * C + c
-    int seg = wg % g.segs_per_row;
-    int c = ROWS ? seg : row % g.C;
+    // (the divisions run on the vector ALU; the results are wave-uniform and are needed in scalar registers)
+    int row = __builtin_amdgcn_readfirstlane(wg / g.segs_per_row);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(wg % g.segs_per_row);
+    int c = ROWS ? seg : __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
     int row_n, seg_n, c_n;                         // the segment after (row, seg)
     auto advance = [&]() {
@@ -274,12 +275,29 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPe
             if (64 * (i + 1) <= NG || lane + 64 * i < NG)       // only the last round is partial
                 *reinterpret_cast<float4 *>(sw_lane + 16 * i * kLdsBlockStride) = Raw4<T>::widen(pre[i]);
     };
+    // Toeplitz operands: A[d][v] (lane (r, k)) = f_eff[16 (dmin + d) + 4k + v - r + pad]
+    float A[ND][4];
+    auto load_filter = [&](int ch) {
+        const T *f_c = f + (size_t)ch * (size_t)g.K;
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int j = 16 * (g.dmin + d) + 4 * k4 + v - i16 + g.pad;
+                const bool ok = j >= 0 && j < g.K;
+                const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
+                const float a = ld_elem(f_c + jc);
+                A[d][v] = ok ? a : 0.f;
+            }
+    };
+    // the filter loads of the first channel go out ahead of the first segment's loads: one memory round trip
+    // at the start of a wave instead of two
+    load_filter(c);
+    int cur_c = c;
     prefetch(row, seg);
     drain();
     wave_lds_fence();
 
-    float A[ND][4];
-    int cur_c = -1;
     const float *sp = sw + i16 * kLdsBlockStride + 4 * k4;
 
     for (;;) {
@@ -288,18 +306,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 6 ? 3 : kMfmaWavesPe
         // (1)
         if (more) prefetch(row_n, seg_n);
         if (c != cur_c) {
-            // Toeplitz operands: A[d][v] (lane (r, k)) = f_eff[16 (dmin + d) + 4k + v - r + pad]
-            const T *f_c = f + (size_t)c * (size_t)g.K;
-#pragma unroll
-            for (int d = 0; d < ND; ++d)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int j = 16 * (g.dmin + d) + 4 * k4 + v - i16 + g.pad;
-                    const bool ok = j >= 0 && j < g.K;
-                    const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
-                    const float a = ld_elem(f_c + jc);
-                    A[d][v] = ok ? a : 0.f;
-                }
+            load_filter(c);
             cur_c = c;
         }
         // (2) one dependent chain of 4*ND matrix instructions per D tile.  Group g = (dt, d) is one
