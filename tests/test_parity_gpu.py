@@ -229,10 +229,10 @@ def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []
     while len(out) < n:
-        K = int(rng.choice([1, 2, 3, 5, 7, 16, 31, 32, 33, 48, 64, 66, 67, 90, 200]))
-        L = int(rng.choice([4, 12, 36, 48, 64, 100, 128, 257, 512, 1000, 1024, 1028, 2048, 3000]))
+        K = int(rng.choice([1, 2, 3, 5, 7, 16, 31, 32, 33, 48, 64, 66, 67, 90, 100, 128, 130, 200]))
+        L = int(rng.choice([4, 12, 20, 36, 48, 52, 64, 68, 100, 128, 257, 512, 1000, 1024, 1028, 2048, 3000]))
         C = int(rng.choice([1, 2, 3, 5, 8, 16, 256, 512]))
-        B = int(rng.choice([1, 2, 3, 7, 16, 40]))
+        B = int(rng.choice([1, 2, 3, 7, 16, 17, 40, 130]))
         if C >= 256:
             L = min(L, 128); B = int(rng.choice([8, 64, 300]))
         if B * C * L * min(K, L) > 6e7 or B * C * L > 4e6:
@@ -244,7 +244,7 @@ def _random_shapes(n, seed):
 
 
 # DWCONV_SWEEP_N / DWCONV_SWEEP_SEED widen or move the sweep for a one-off soak; the defaults are what the suite runs.
-@pytest.mark.parametrize("B,C,L,K,p,dtype", _random_shapes(int(os.environ.get("DWCONV_SWEEP_N", "140")),
+@pytest.mark.parametrize("B,C,L,K,p,dtype", _random_shapes(int(os.environ.get("DWCONV_SWEEP_N", "180")),
                                                            int(os.environ.get("DWCONV_SWEEP_SEED", "20260425"))))
 def test_random_shapes(oracle_mod, B, C, L, K, p, dtype):
     from paper_2604_25422_amd import binding
