@@ -119,7 +119,7 @@ int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, vo
  * Both gradients of the backward pass in one call: dx as dwconv_bwd_input, dw as dwconv_bwd_weight.
  * The paper names kernel fusion as the remaining lever for the backward path (Sec. VI): for filters of the
  * register-resident class (dwconv_bwd_is_fused(...) == 1: K up to about 66, fp32 with L % 4 == 0 or bf16 with L % 8 == 0,
- * 16-byte aligned tensors; not fp32 rows of 52 to 64 positions) one
+ * 16-byte aligned tensors; not rows of 52 to 128 positions, not bf16 short rows above that) one
  * kernel reads dy once and produces dx and the stage-1 sums of dw (5 tensor passes over memory per
  * forward + backward step instead of 6); every other shape or type runs the two separate paths one after the
  * other.  dy, x [B,C,L] in; w [C,K] in; dx [B,C,L] out; dw [C,K] out; workspace as for dwconv_bwd_weight.

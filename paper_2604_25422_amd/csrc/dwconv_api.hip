@@ -72,7 +72,7 @@ constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below 
 // its geometry.  Depends on the shape only; the gap is the same for the forward and the input-gradient pads.
 struct RowsPlan {
     bool on;
-    bool batch;             // rows of at most 64 positions: sixteen rows of a channel per matrix tile instead
+    bool batch;             // rows of at most 128 positions: sixteen rows of a channel per matrix tile instead
     int units;              // batch: groups of sixteen rows per channel
     int nvs;                // 1024-position segments of the virtual row
     dwconv::RowsMap map;
@@ -210,7 +210,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     };
     const RowsPlan rp = plan_rows(s);
     if (rp.batch) {
-        // rows of at most 64 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
+        // rows of at most 128 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
         dwconv::RowBatchGeom rg;
         rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
         rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
@@ -238,19 +238,29 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         };
         if (nc == 2) {
             switch (nd) {
-            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2>);
-            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2>);
-            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2>);
-            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2>);
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2, 3>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2, 3>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2, 3>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2, 3>);
             default: return -1;
             }
         }
-        switch (nd) {
-        case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1>);
-        case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1>);
-        case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1>);
-        case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1>);
-        case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1>);
+        if (rg.m <= 4) {
+            switch (nd) {
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4>);
+            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4>);
+            default: return -1;
+            }
+        }
+        switch (nd) {                              // rows of five to eight blocks
+        case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8>);
+        case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8>);
+        case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8>);
+        case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8>);
+        case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8>);
         default: return -1;
         }
     }
@@ -510,7 +520,11 @@ DwPlan plan_dw(const Shape &s)
     DwPlan p;
     p.kernel = s.K <= 8 ? DW_VALU_K8 : s.K <= 32 ? DW_VALU_K32 : s.K <= 64 ? DW_VALU_K64 : DW_VALU_K256;
     p.rows = plan_rows(s);
-    long long tiles = p.rows.batch ? p.rows.units : p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
+    long long tiles = p.rows.on ? p.rows.nvs : ((long long)s.L + kDwTT - 1) / kDwTT;
+    if (p.rows.batch) {                                          // units of the weight-gradient kernel, one channel per block
+        const int ru = dwconv::rb_dw_unit_rows(s.L, 1);
+        tiles = (s.B + ru - 1) / ru;
+    }
     long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd(s.dtype) && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
@@ -612,7 +626,7 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                                int dmin, hipStream_t st)
 {
     if (p.rows.batch) {
-        // rows of at most 64 positions, either storage type: sixteen rows per matrix tile
+        // rows of at most 128 positions, either storage type: sixteen rows per matrix tile
         auto launch_rb = [&](auto kernel, int nc) -> int {
             const size_t lds_rb = dwconv::rb_dw_lds_bytes(s.L, ND, W, nc);
             if (lds_rb > kMaxLdsBytes) return -1;
@@ -639,6 +653,10 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 1>, 1);
         case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 1>, 1);
         case 4: return launch_rb(dwconv::dw_rowbatch_kernel<T, 4, W, 1>, 1);
+        case 5: return launch_rb(dwconv::dw_rowbatch_kernel<T, 5, W, 1>, 1);
+        case 6: return launch_rb(dwconv::dw_rowbatch_kernel<T, 6, W, 1>, 1);
+        case 7: return launch_rb(dwconv::dw_rowbatch_kernel<T, 7, W, 1>, 1);
+        case 8: return launch_rb(dwconv::dw_rowbatch_kernel<T, 8, W, 1>, 1);
         default: return -1;
         }
     }

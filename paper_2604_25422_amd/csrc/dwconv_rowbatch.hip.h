@@ -1,4 +1,4 @@
-// Short rows on the matrix cores, sixteen rows at a time (L <= 64, L % 4 == 0; fp32, or bf16 storage widened to
+// Short rows on the matrix cores, sixteen rows at a time (L <= 128, L % 4 == 0; fp32, or bf16 storage widened to
 // fp32 on the way into LDS: fp32 matrix instructions and sums either way, one rounding at the store).
 //
 // The operator of Sec. IV-A eq. (dwconv) treats every row (b, c) on its own, and the paper's own workload
@@ -18,9 +18,8 @@
 namespace dwconv {
 
 constexpr int kRbRows = 16;       // rows of one channel per unit
-constexpr int kRbMaxL = 64;       // longest row
-constexpr int kRbMaxBlocks = 4;   // 16-blocks per row
-constexpr int kRbMaxLoads = 4;    // 16 rows * (L / 4) granules over 64 lanes
+constexpr int kRbMaxL = 128;      // longest row
+constexpr int kRbMaxBlocks = 8;   // 16-blocks per row
 
 // Weight-gradient kernel: a wave owns NC neighbouring channels and works on units of 16 / NC rows (b), so a unit
 // is the same number of bytes either way.  Pitch (floats) of a row (b, c0 .. c0 + NC - 1) in the LDS image: every
@@ -33,9 +32,12 @@ __host__ __device__ constexpr int rb_dw_pitch(int L, int NC)
     return p;
 }
 // Floats of one wave's LDS region in the weight-gradient kernel: both operands, or the diagonal image of the epilogue.
+// Rows (b) of a weight-gradient unit: 16 / NC, or 4 for rows of more than four blocks (one row group; the
+// accumulators, one per relative block offset, leave fewer registers for staging).
+__host__ __device__ constexpr int rb_dw_unit_rows(int L, int NC) { return (L + 15) / 16 > 4 ? 4 : kRbRows / NC; }
 __host__ __device__ constexpr int rb_dw_wave_floats(int L, int ND, int NC)
 {
-    const int stage = 2 * (kRbRows / NC) * rb_dw_pitch(L, NC);
+    const int stage = 2 * rb_dw_unit_rows(L, NC) * rb_dw_pitch(L, NC);
     const int diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
     return stage > diag ? stage : diag;
 }
@@ -80,14 +82,14 @@ constexpr int kRbCorrWaves = 4;   // waves per block: neighbouring channels, who
 // image, channel by channel, and the tiles of a channel replace its inputs; then every lane swaps its granules of
 // the image (the lane-to-granule map of the loads): the outputs go out as whole rows (streaming stores, as in the
 // long-row kernel), the prefetched inputs of the next unit come in.
-template <typename T, int ND, int NC>
-__global__ __launch_bounds__(64 * kRbCorrWaves, kMfmaWavesPerSimd) void corr_rowbatch_kernel(
+template <typename T, int ND, int NC, int MB>
+__global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 ? 3 : kMfmaWavesPerSimd)) void corr_rowbatch_kernel(
     const T *__restrict__ in, const T *__restrict__ f, T *__restrict__ out, const RowBatchGeom g)
 {
     constexpr int ES = (int)sizeof(T);          // bf16 storage is widened on the way into LDS; fp32 arithmetic
-    // two channels per wave: rows of at most 48 positions (register budget)
-    constexpr int NLD = NC == 2 ? 6 : kRbMaxLoads;
-    constexpr int MB = NC == 2 ? 3 : kRbMaxBlocks;
+    // MB: 16-blocks per row the kernel is compiled for (two channels per wave: 3, the register budget)
+    static_assert(MB >= 1 && MB <= kRbMaxBlocks && (NC == 1 || MB <= 3), "row blocks");
+    constexpr int NLD = NC * MB;                 // 16 rows * NC * 4 MB granules over 64 lanes
     extern __shared__ __align__(16) float dyn_lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -270,8 +272,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
 {
     constexpr int ES = (int)sizeof(T);
     static_assert(NC == 1 || NC == 2, "one or two channels per wave");
-    static_assert(M >= 1 && M <= kRbMaxBlocks && (NC == 1 || M <= 3), "rows of at most 64 (two channels: 48) positions");
-    constexpr int RU = kRbRows / NC;                          // rows per unit
+    static_assert(M >= 1 && M <= kRbMaxBlocks && (NC == 1 || M <= 3), "rows of at most 128 (two channels: 48) positions");
+    constexpr int RU = M > 4 ? 4 : kRbRows / NC;              // rows per unit (rb_dw_unit_rows)
     constexpr int NLD = (RU * NC * 4 * M + 63) / 64;          // 16-byte granules of a unit over 64 lanes
     constexpr int NR = 2 * M - 1;                             // relative block offsets -(M-1) .. M-1
     extern __shared__ __align__(16) float dyn_lds[];

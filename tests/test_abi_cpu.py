@@ -96,7 +96,7 @@ def test_fused_backward_argument_validation(lib):
     assert f(P, P, P, P + 2, P, P, need, 2, 3, 100, 5, 2, 0, None) == 6
     # which shapes take the fused kernel: filters of the register-resident class, row length a multiple of 4 (fp32)
     q = lib.dwconv_bwd_is_fused
-    assert q(32, 256, 4096, 64, 63, 0) == 1 and q(4096, 128, 96, 48, 24, 0) == 1 and q(2, 3, 100, 5, 2, 0) == 1
+    assert q(32, 256, 4096, 64, 63, 0) == 1 and q(4096, 128, 196, 48, 24, 0) == 1 and q(2, 3, 200, 5, 2, 0) == 1
     assert q(128, 768, 1024, 32, 31, 1) == 1 and q(2, 3, 100, 5, 2, 1) == 0     # bf16: rows of whole 16-byte granules
     assert q(8, 256, 8192, 8192, 8191, 0) == 0 and q(2, 3, 101, 5, 2, 0) == 0
     assert q(2, 3, 100, 2, 1, 0) == 0 and q(0, 3, 100, 5, 2, 0) == 0

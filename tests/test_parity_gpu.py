@@ -47,6 +47,9 @@ SHORT_ROWS = [
     (31, 2, 36, 31, 30), (40, 5, 48, 48, 24), (64, 2, 48, 48, 47), (100, 3, 48, 48, 0), (7, 4, 52, 20, 10),
     (50, 2, 64, 64, 63), (48, 3, 64, 66, 33), (129, 2, 60, 40, 0), (300, 9, 48, 48, 24), (1000, 2, 12, 7, 3),
     (2100, 1, 48, 33, 16), (70, 256, 48, 48, 24), (36, 512, 24, 9, 4), (20, 2, 8, 50, 25),
+    # rows of five to eight blocks (weight-gradient units of four rows)
+    (40, 3, 68, 7, 3), (33, 2, 80, 48, 24), (17, 5, 96, 64, 63), (9, 4, 100, 66, 0), (130, 2, 128, 31, 15),
+    (50, 256, 128, 16, 15), (21, 3, 124, 33, 32), (6, 2, 112, 5, 2),
 ]
 
 
@@ -183,9 +186,9 @@ def test_single_kernel_weight_gradient(oracle_mod, B, C, L, K, p, dtype):
 # for everything else.  (B, C, L, K, pad_left, dtype, fused?)
 BWD = [
     (2, 3, 600, 64, 63, "f32", True), (1, 2, 4100, 64, 32, "f32", True), (3, 7, 336, 31, 30, "f32", True),
-    (2, 3, 100, 5, 0, "f32", True), (2, 3, 100, 5, 4, "f32", True), (1, 4, 1024, 16, 15, "f32", True),
+    (2, 3, 100, 5, 0, "f32", False), (2, 3, 100, 5, 4, "f32", False), (1, 4, 1024, 16, 15, "f32", True),
     (2, 4, 1028, 16, 8, "f32", True), (2, 2, 48, 48, 24, "f32", True), (5, 3, 48, 48, 0, "f32", True),
-    (2, 2, 2060, 64, 63, "f32", True), (1, 5, 44, 7, 3, "f32", True), (20, 5, 68, 7, 3, "f32", True), (100, 6, 48, 48, 24, "f32", True), (37, 3, 64, 66, 33, "f32", False),
+    (2, 2, 2060, 64, 63, "f32", True), (1, 5, 44, 7, 3, "f32", True), (20, 5, 68, 7, 3, "f32", False), (100, 6, 48, 48, 24, "f32", True), (37, 3, 64, 66, 33, "f32", False),
     (70, 256, 48, 48, 24, "f32", True), (300, 4, 20, 9, 8, "f32", True), (4, 16, 4096, 64, 63, "f32", True),
     (3, 2, 2048, 66, 65, "f32", True), (2, 2, 3072, 66, 0, "f32", True), (2, 3, 2052, 40, 20, "f32", True),
     (9, 256, 3900, 64, 63, "f32", True), (4, 512, 4096, 7, 3, "f32", True), (11, 768, 1032, 20, 0, "f32", True),
@@ -193,7 +196,7 @@ BWD = [
     (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", False), (10, 768, 1024, 32, 31, "bf16", True),
     (2, 2, 48, 48, 24, "bf16", True), (3, 2, 4096, 66, 65, "bf16", True), (40, 256, 1024, 64, 63, "bf16", True),
     (100, 6, 44, 31, 15, "bf16", True), (37, 3, 60, 20, 10, "bf16", False), (70, 256, 48, 48, 24, "bf16", True),
-    (20, 4, 128, 16, 15, "bf16", False), (20, 4, 128, 16, 15, "f32", True),
+    (20, 4, 128, 16, 15, "bf16", False), (20, 4, 128, 16, 15, "f32", False), (20, 4, 132, 16, 15, "f32", True),
     (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", False),
 ]
 
