@@ -10,12 +10,13 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libdwconv_gfx950.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # plain v_fma_f32 only
     "-ffp-contract=off",
     "-Wall", "-Wno-unused-command-line-argument",
     "-Wno-pass-failed",      # "#pragma unroll" on loops with run-time trip counts (long-filter kernels) is a hint only
 ]
+OBJ_DIR = os.path.join(HERE, "_build")     # object files of the translation units (not tracked)
 
 
 def sources():
@@ -26,13 +27,31 @@ def dependencies():
     return sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + [os.path.join(HERE, "..", "include", "dwconv.h")]
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Always recompiles; returns the path of the shared library."""
+def build(verbose: bool = False, extra_flags=(), jobs: int | None = None) -> str:
+    """Always recompiles: every translation unit to an object file (side by side), then one link.
+    Returns the path of the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-o", LIB_PATH] + sources()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sources()
+    objs = [os.path.join(OBJ_DIR, os.path.basename(p)[:-4] + ".o") for p in srcs]
+
+    def compile_one(pair):
+        src, obj = pair
+        cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+
+    if jobs is None:
+        jobs = max(1, min(len(srcs), os.cpu_count() or 1, 8))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(compile_one, zip(srcs, objs)))
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB_PATH
 
 

@@ -1,0 +1,156 @@
+// Host side shared by the translation units of the library: shapes, limits, the plans that pick kernels, and the
+// launch entry points every unit provides.  The kernels are instantiated in the dwconv_launch_*.hip units (one per
+// path and storage type, so that they compile side by side); dwconv_api.hip holds validation, the plans and the C ABI.
+#pragma once
+#include "../../include/dwconv.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <algorithm>
+#include <array>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <vector>
+#include <type_traits>
+
+#include "dwconv_common.hip.h"
+#include "dwconv_dw_direct.hip.h"
+#include "dwconv_longk.hip.h"
+#include "dwconv_mfma.hip.h"
+#include "dwconv_rowbatch.hip.h"
+
+namespace dwhost {
+
+using dwconv::bf16_t;
+
+struct Shape {
+    int B, C, L, K, pad, dtype;
+};
+
+inline bool aligned_to(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t elem_size(int dtype) { return dtype == DWCONV_F32 ? 4 : 2; }
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
+}
+
+// Block offsets d of the 16-blocked Toeplitz form that can hold a tap: d in [dmin, dmax].
+inline int toeplitz_dmin(int pad) { return -((pad + 15) / 16); }
+inline int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
+
+constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
+constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
+constexpr int kMfmaMaxNDWide = 10;     // fp32 forward / input gradient / weight gradient on long rows (K up to 130)
+inline int mfma_max_nd(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND; }
+constexpr int kComputeUnits = 256;     // MI355X
+constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
+
+// Short rows (see dwconv::RowsMap): whether the matrix-core kernels should walk the virtual row of a channel, and
+// its geometry.  Depends on the shape only; the gap is the same for the forward and the input-gradient pads.
+struct RowsPlan {
+    bool on;
+    bool batch;             // rows of at most 128 positions: sixteen rows of a channel per matrix tile instead
+    int units;              // batch: groups of sixteen rows per channel
+    int nvs;                // 1024-position segments of the virtual row
+    dwconv::RowsMap map;
+};
+RowsPlan plan_rows(const Shape &s);
+
+constexpr long long kTargetWaves = 4096;   // 256 CUs x 16 resident waves (weight-gradient plan; shape-only)
+
+// Waves of `kernel` that are resident on the current device at once (one full round), from the
+// occupancy the runtime reports; falls back to kTargetWaves if the query fails.
+template <typename Kernel>
+long long resident_waves(Kernel kernel, int block_threads)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, long long> cache;      // (device, kernel) -> waves
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return kTargetWaves;
+    }
+    const std::pair<int, const void *> key(dev, reinterpret_cast<const void *>(kernel));
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int cus = 0, blocks_per_cu = 0;
+    long long waves = kTargetWaves;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, kernel, block_threads, 0) == hipSuccess &&
+        cus >= 1 && blocks_per_cu >= 1)
+        waves = (long long)cus * blocks_per_cu * (block_threads / 64);
+    else
+        (void)hipGetLastError();
+    cache[key] = waves;
+    return waves;
+}
+
+// Wave slots of a correlate launch: one resident round, but no more than 16 waves per compute unit.  Kernels
+// light enough for five or six waves per SIMD measured slower with the larger round (short filter, K = 7:
+// 105 us with 5120 slots, 97.6 us with 4096).
+template <typename Kernel>
+long long corr_wave_slots(Kernel kernel, int block_threads)
+{
+    const long long r = resident_waves(kernel, block_threads);
+    return r < kTargetWaves ? r : kTargetWaves;
+}
+
+constexpr size_t kMaxLdsBytes = 160 * 1024;
+
+// Lets `kernel` use more than the default 64 KiB of dynamic LDS (once per kernel and process).
+template <typename Kernel>
+bool allow_large_lds(Kernel kernel)
+{
+    static std::mutex mu;
+    static std::map<const void *, bool> done;
+    std::lock_guard<std::mutex> lock(mu);
+    const void *key = reinterpret_cast<const void *>(kernel);
+    auto it = done.find(key);
+    if (it != done.end()) return it->second;
+    const bool ok = hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLdsBytes) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    done[key] = ok;
+    return ok;
+}
+
+enum DwKernel { DW_VALU_K8, DW_VALU_K32, DW_VALU_K64, DW_VALU_K256 };
+
+struct DwPlan {
+    DwKernel kernel;
+    bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
+    int lk_wgs, lk_gd;     // its workgroups per channel, largest group of offsets (accumulators per group)
+    std::shared_ptr<const dwconv::LongKDwTable> lk_table;   // which offsets every wave slot owns
+    int S;                 // partial slices per coefficient
+    RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
+    int wpb;               // waves per block of the matrix-core stage-1 kernels
+    int dw_nc;             // short rows, sixteen-row units: channels per block of the stage-1 kernel (1 or 2)
+    int S_fused;           // slices the fused backward call writes (differs from S for rows of at most 48 positions)
+    bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
+    int tiles_per_row;     // segments the matrix-core kernels walk per row (per virtual row for short rows)
+    int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel (always real rows)
+    int segs_per_wave;     // (b, segment) items a wave of the matrix-core kernels walks
+    int items_per_slice;   // (b, segment) items each slice owns = wpb * segs_per_wave
+};
+
+constexpr int kDwTT = dwconv::kSegLen;   // positions per staged tile (every stage-1 kernel)
+constexpr int kDwThreads = 256;
+
+DwPlan plan_dw(const Shape &s);
+
+// Launch entry points of the per-path units.  A return value of -1 (fused backward only) means "does not apply".
+int launch_corr_f32(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st);
+int launch_corr_bf16(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st);
+int launch_dw_partial_f32(const void *x, const void *dy, float *part, void *dw_out, bool *wrote_dw, const Shape &s,
+                          const DwPlan &p, hipStream_t st);
+int launch_dw_partial_bf16(const void *x, const void *dy, float *part, void *dw_out, bool *wrote_dw, const Shape &s,
+                           const DwPlan &p, hipStream_t st);
+int launch_bwd_fused_f32(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
+                         const Shape &s, const DwPlan &p, hipStream_t st);
+int launch_bwd_fused_bf16(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,
+                          bool *wrote_dw, const Shape &s, const DwPlan &p, hipStream_t st);
+
+}  // namespace dwhost

@@ -1,0 +1,12 @@
+// Fused backward kernels, bf16 storage.
+#include "dwconv_launch_bwd.hip.h"
+
+namespace dwhost {
+
+int launch_bwd_fused_bf16(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
+                          const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    return launch_bwd_fused<bf16_t>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
+}
+
+}  // namespace dwhost

@@ -1,0 +1,231 @@
+// Launchers of the forward / input-gradient kernels (templates on the storage type; instantiated by
+// dwconv_launch_corr_f32.hip and dwconv_launch_corr_bf16.hip).
+//   out = correlate(in, f_eff, pad_eff): the forward is (x, w, pad); the input gradient is (dy, reversed w, K-1-pad).
+#pragma once
+#include "dwconv_host.hip.h"
+#include "dwconv_valu.hip.h"
+
+namespace dwhost {
+
+template <typename T>
+int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    constexpr int R = 4, THREADS = 256, KCH = 512;
+    constexpr int TILE = R * THREADS;
+    const long long tiles_per_row = ((long long)s.L + TILE - 1) / TILE;
+    const long long blocks = (long long)s.B * s.C * tiles_per_row;
+    if (blocks > 0x7fffffffLL) return DWCONV_ERR_SHAPE;
+    hipLaunchKernelGGL((dwconv::corr_valu_kernel<T, R, THREADS, KCH>), dim3((unsigned)blocks), dim3(THREADS), 0, st,
+                       static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), s.C, s.L, s.K,
+                       pad_eff, reverse, (int)tiles_per_row);
+    return launch_status();
+}
+
+// Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
+template <typename T>
+int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
+    const int nd = dmax - dmin + 1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
+    if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    const long long rows = (long long)s.B * s.C;
+    const long long segs_per_row = (s.L + dwconv::kSegLen - 1) / dwconv::kSegLen;
+    const long long total_segs = rows * segs_per_row;
+    if (total_segs > 0x3fffffffLL) return -1;           // the kernel's segment walk is 32-bit
+    dwconv::CorrGeom g;
+    g.C = s.C; g.L = s.L; g.K = s.K; g.rows = (int)rows;
+    g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
+    g.segs_per_row = (int)segs_per_row;
+    constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
+    const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
+    // One resident round of waves, each walking segments wave, wave + n_waves, ...
+    auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po) -> int {
+        const long long resident = corr_wave_slots(kernel, kThreads);
+        long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
+        if (spw < 1) spw = 1;
+        long long waves = (total_segs + spw - 1) / spw;
+        // A whole number of batch entries per round where one fits: the stride of the walk is then a multiple of
+        // C rows, a wave stays on one channel and loads its Toeplitz operands once.
+        const long long per_b = (long long)s.C * segs_per_row;
+        if (per_b <= resident) {
+            long long J = resident / per_b;
+            if (J > s.B) J = s.B;
+            const long long rounds = (s.B + J - 1) / J;
+            J = (s.B + rounds - 1) / rounds;                           // same number of rounds, evened out
+            waves = J * per_b;
+        }
+        const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+        g.n_waves = (int)waves;
+        g.step_rows = g.n_waves / g.segs_per_row;
+        g.step_seg = g.n_waves % g.segs_per_row;
+        g.step_c = g.step_rows % s.C;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
+        return launch_status();
+    };
+    const RowsPlan rp = plan_rows(s);
+    if (rp.batch) {
+        // rows of at most 128 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
+        dwconv::RowBatchGeom rg;
+        rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
+        rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
+        rg.m = (s.L + 15) / 16;
+        rg.n_units = rp.units;
+        // two channels per wave where that makes whole cache lines of rows that are not, or at least longer pieces;
+        // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
+        const int nc = (s.C % 2 == 0 && (s.L * (int)sizeof(T)) % 128 != 0 && s.L <= 48 && nd <= 5) ? 2 : 1;
+        auto launch_batch = [&](auto kernel) -> int {
+            // one resident round of waves: J per channel group, each walking units j, j + J, ...
+            const long long groups = s.C / nc;
+            const long long resident = corr_wave_slots(kernel, 64 * dwconv::kRbCorrWaves);
+            long long J = resident / groups;
+            if (J < 1) J = 1;
+            if (J > rg.n_units) J = rg.n_units;
+            const long long upw = (rg.n_units + J - 1) / J;
+            J = (rg.n_units + upw - 1) / upw;
+            const long long blocks = (groups * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
+            if (blocks > 0x1fffffffLL) return -1;
+            rg.J = (int)J;
+            const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L, nc) * sizeof(float);
+            hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
+                               static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), rg);
+            return launch_status();
+        };
+        if (nc == 2) {
+            switch (nd) {
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2, 3>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2, 3>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2, 3>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2, 3>);
+            default: return -1;
+            }
+        }
+        if (rg.m <= 4) {
+            switch (nd) {
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4>);
+            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4>);
+            default: return -1;
+            }
+        }
+        switch (nd) {                              // rows of five to eight blocks
+        case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8>);
+        case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8>);
+        case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8>);
+        case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8>);
+        case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8>);
+        default: return -1;
+        }
+    }
+    {
+        // longer short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
+        if (rp.on) {
+            const long long total = (long long)rp.nvs * s.C;
+            if (total > 0x3fffffffLL) return -1;
+            g.rows = rp.nvs;
+            g.segs_per_row = s.C;
+            auto launch_rows = [&](auto kernel) -> int {
+                const long long resident = corr_wave_slots(kernel, kThreads);
+                long long spw = (total + resident - 1) / resident;
+                if (spw < 1) spw = 1;
+                long long waves = (total + spw - 1) / spw;
+                if (s.C <= resident) {                                // whole virtual segments per round: channel fixed
+                    long long J = resident / s.C;
+                    if (J > rp.nvs) J = rp.nvs;
+                    const long long rounds = (rp.nvs + J - 1) / J;
+                    J = (rp.nvs + rounds - 1) / rounds;
+                    waves = J * s.C;
+                }
+                const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+                g.n_waves = (int)waves;
+                g.step_rows = g.n_waves / g.segs_per_row;
+                g.step_seg = g.n_waves % g.segs_per_row;
+                g.step_c = 0;
+                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, static_cast<const T *>(in),
+                                   static_cast<const T *>(f), static_cast<T *>(out), g, rp.map);
+                return launch_status();
+            };
+            switch (nd) {
+            case 2: return launch_rows(dwconv::corr_mfma_kernel<T, 2, true>);
+            case 3: return launch_rows(dwconv::corr_mfma_kernel<T, 3, true>);
+            case 4: return launch_rows(dwconv::corr_mfma_kernel<T, 4, true>);
+            case 5: return launch_rows(dwconv::corr_mfma_kernel<T, 5, true>);
+            case 6: return launch_rows(dwconv::corr_mfma_kernel<T, 6, true>);
+            default: return -1;
+            }
+        }
+    }
+    if constexpr (sizeof(T) == 2) {
+        // bf16 storage: the bf16 matrix instruction when 16-byte granules of 8 elements line up
+        if ((s.L % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
+            const bf16_t *pi = static_cast<const bf16_t *>(in), *pf = static_cast<const bf16_t *>(f);
+            bf16_t *po = static_cast<bf16_t *>(out);
+            switch (nd) {
+            case 2: return launch(dwconv::corr_mfma_bf16_kernel<2>, pi, pf, po);
+            case 3: return launch(dwconv::corr_mfma_bf16_kernel<3>, pi, pf, po);
+            case 4: return launch(dwconv::corr_mfma_bf16_kernel<4>, pi, pf, po);
+            case 5: return launch(dwconv::corr_mfma_bf16_kernel<5>, pi, pf, po);
+            case 6: return launch(dwconv::corr_mfma_bf16_kernel<6>, pi, pf, po);
+            default: return -1;
+            }
+        }
+    }
+    const T *pi = static_cast<const T *>(in), *pf = static_cast<const T *>(f);
+    T *po = static_cast<T *>(out);
+    switch (nd) {
+    case 2: return launch(dwconv::corr_mfma_kernel<T, 2, false>, pi, pf, po);
+    case 3: return launch(dwconv::corr_mfma_kernel<T, 3, false>, pi, pf, po);
+    case 4: return launch(dwconv::corr_mfma_kernel<T, 4, false>, pi, pf, po);
+    case 5: return launch(dwconv::corr_mfma_kernel<T, 5, false>, pi, pf, po);
+    case 6: return launch(dwconv::corr_mfma_kernel<T, 6, false>, pi, pf, po);
+    default: break;
+    }
+    if constexpr (std::is_same<T, float>::value) {
+        switch (nd) {
+        case 7: return launch(dwconv::corr_mfma_kernel<float, 7, false>, pi, pf, po);
+        case 8: return launch(dwconv::corr_mfma_kernel<float, 8, false>, pi, pf, po);
+        case 9: return launch(dwconv::corr_mfma_kernel<float, 9, false>, pi, pf, po);
+        case 10: return launch(dwconv::corr_mfma_kernel<float, 10, false>, pi, pf, po);
+        default: break;
+        }
+    }
+    return -1;
+}
+
+// Filters too long for the register-resident Toeplitz form: whole rows and the whole filter in LDS.
+// Returns -1 when the shape or the pointers do not fit.
+template <typename T>
+int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
+    if (dmax - dmin + 1 <= mfma_max_nd(s.dtype) || s.K > dwconv::kLkMaxK || (s.L % 4) != 0) return -1;
+    const int NB = (s.L + 15) / 16;
+    if (NB > dwconv::kLkMaxBlocks) return -1;
+    if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    const size_t lds = dwconv::longk_corr_lds_bytes(s.K, NB);
+    const long long row_groups = ((long long)s.B + dwconv::kLkRows - 1) / dwconv::kLkRows;
+    if (lds > kMaxLdsBytes || row_groups > 65535) return -1;
+    if (!allow_large_lds(dwconv::corr_longk_kernel<T>)) return -1;
+    dwconv::LongKGeom g;
+    g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K;
+    g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin; g.dmax = dmax;
+    g.NB = NB; g.NT = (NB + 15) / 16;
+    hipLaunchKernelGGL((dwconv::corr_longk_kernel<T>), dim3((unsigned)s.C, (unsigned)row_groups),
+                       dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(in), static_cast<const T *>(f),
+                       static_cast<T *>(out), g);
+    return launch_status();
+}
+
+template <typename T>
+int launch_corr(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
+{
+    int rc = launch_corr_mfma<T>(in, f, out, s, pad_eff, reverse, st);
+    if (rc >= 0) return rc;
+    rc = launch_corr_longk<T>(in, f, out, s, pad_eff, reverse, st);
+    if (rc >= 0) return rc;
+    return launch_corr_valu<T>(in, f, out, s, pad_eff, reverse, st);
+}
+
+}  // namespace dwhost

@@ -184,6 +184,7 @@ inline size_t longk_dw_lds_bytes(int L, int NCH)
 __device__ __forceinline__ int floor_div(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
 __device__ __forceinline__ int ceil_div(int a, int b) { return -floor_div(-a, b); }
 
+template <int UNUSED = 0>   // (a template only so that the header can be included by several translation units)
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
