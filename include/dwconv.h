@@ -40,6 +40,9 @@
 
 #include <stddef.h>
 
+/* The entry points are the only symbols the shared library exports. */
+#define DWCONV_API __attribute__((visibility("default")))
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -66,7 +69,7 @@ enum dwconv_status {
  * (cross-correlation, the filter is not flipped).
  * x [B,C,L] in, w [C,K] in, y [B,C,L] out; all device, all of `dtype`.
  */
-int dwconv_fwd(const void *x, const void *w, void *y,
+DWCONV_API int dwconv_fwd(const void *x, const void *w, void *y,
                int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
 /*
@@ -76,7 +79,7 @@ int dwconv_fwd(const void *x, const void *w, void *y,
  * (equal to the printed eq. (dx_def) whenever K = 2*pad_left + 1).
  * dy [B,C,L] in, w [C,K] in, dx [B,C,L] out.
  */
-int dwconv_bwd_input(const void *dy, const void *w, void *dx,
+DWCONV_API int dwconv_bwd_input(const void *dy, const void *w, void *dx,
                      int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
 /*
@@ -90,7 +93,7 @@ int dwconv_bwd_input(const void *dy, const void *w, void *dx,
  * dwconv_bwd_weight_workspace_bytes(...) bytes, 16-byte aligned; its contents
  * on entry are ignored and it may be reused once the call's work has finished.
  */
-int dwconv_bwd_weight(const void *x, const void *dy, void *dw,
+DWCONV_API int dwconv_bwd_weight(const void *x, const void *dy, void *dw,
                       void *workspace, size_t workspace_bytes,
                       int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
@@ -102,7 +105,7 @@ int dwconv_bwd_weight(const void *x, const void *dy, void *dw,
  * Within a block the sum runs over wave-level and then LDS-level reductions in
  * a fixed order.
  */
-int dwconv_bwd_weight_partial(const void *x, const void *dy,
+DWCONV_API int dwconv_bwd_weight_partial(const void *x, const void *dy,
                               void *workspace, size_t workspace_bytes,
                               int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
@@ -112,7 +115,7 @@ int dwconv_bwd_weight_partial(const void *x, const void *dy,
  * Reads the fp32 partials stage 1 left in `workspace`, writes dw [C,K] in
  * `dtype`.  Shape arguments must equal those given to stage 1.
  */
-int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw,
+DWCONV_API int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw,
                                int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
 /*
@@ -126,33 +129,33 @@ int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, vo
  * dx must not alias dy or x.  Results: dx equals dwconv_bwd_input's bit for bit; dw is a fixed-order sum like
  * dwconv_bwd_weight's (same tolerance, run-to-run identical).
  */
-int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw,
+DWCONV_API int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw,
                void *workspace, size_t workspace_bytes,
                int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
 /* 1 when dwconv_bwd runs the fused kernel for this shape (given 16-byte aligned tensors); 0 otherwise. */
-int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype);
+DWCONV_API int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype);
 
 /* Number S of partial slices per coefficient stage 1 writes for this shape; 0 on bad arguments. */
-int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype);
+DWCONV_API int dwconv_bwd_weight_slices(int B, int C, int L, int K, int pad_left, int dtype);
 
 /*
  * 1 when, for this shape and 16-byte aligned tensors, dwconv_bwd_weight runs as a single kernel
  * (one workgroup per channel, S = 1, no second stage); 0 otherwise or on bad arguments.
  */
-int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype);
+DWCONV_API int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype);
 
 /*
  * Bytes of workspace dwconv_bwd_weight and dwconv_bwd need for this shape (fp32 [S', C, K] rounded up, S' the larger
  * of S and the slice count of the fused kernel, which differs for rows of at most 48 positions); 0 on bad arguments.
  */
-size_t dwconv_bwd_weight_workspace_bytes(int B, int C, int L, int K, int pad_left, int dtype);
+DWCONV_API size_t dwconv_bwd_weight_workspace_bytes(int B, int C, int L, int K, int pad_left, int dtype);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
-const char *dwconv_status_string(int status);
+DWCONV_API const char *dwconv_status_string(int status);
 
 /* Library version, major*10000 + minor*100 + patch. */
-int dwconv_version(void);
+DWCONV_API int dwconv_version(void);
 
 #ifdef __cplusplus
 }

@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(HERE, "libdwconv_gfx950.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    "-fvisibility=hidden",   # only the C ABI (DWCONV_API in include/dwconv.h) is exported
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # plain v_fma_f32 only
     "-ffp-contract=off",
     "-Wall", "-Wno-unused-command-line-argument",

@@ -101,17 +101,23 @@ long long corr_wave_slots(Kernel kernel, int block_threads)
 
 constexpr size_t kMaxLdsBytes = 160 * 1024;
 
-// Lets `kernel` use more than the default 64 KiB of dynamic LDS (once per kernel and process).
+// Lets `kernel` use more than the default 64 KiB of dynamic LDS (once per kernel, device and process).
 template <typename Kernel>
 bool allow_large_lds(Kernel kernel)
 {
     static std::mutex mu;
-    static std::map<const void *, bool> done;
+    static std::map<std::pair<int, const void *>, bool> done;        // (device, kernel)
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    const void *fn = reinterpret_cast<const void *>(kernel);
+    const std::pair<int, const void *> key(dev, fn);
     std::lock_guard<std::mutex> lock(mu);
-    const void *key = reinterpret_cast<const void *>(kernel);
     auto it = done.find(key);
     if (it != done.end()) return it->second;
-    const bool ok = hipFuncSetAttribute(key, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLdsBytes) == hipSuccess;
+    const bool ok = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLdsBytes) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     done[key] = ok;
     return ok;
