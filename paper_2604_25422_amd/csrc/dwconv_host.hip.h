@@ -44,7 +44,9 @@ inline int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
 constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
 constexpr int kMfmaMaxNDWide = 10;     // fp32 forward / input gradient / weight gradient on long rows (K up to 130)
-inline int mfma_max_nd(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND; }
+constexpr int kMfmaMaxNDDw = 16;       // fp32 weight gradient alone (K up to 226): sixteen accumulators per wave
+inline int mfma_max_nd(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND; }      // fwd, dX
+inline int mfma_max_nd_dw(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND; }      // dW stage 1
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
@@ -154,6 +156,9 @@ int launch_dw_partial_f32(const void *x, const void *dy, float *part, void *dw_o
                           const DwPlan &p, hipStream_t st);
 int launch_dw_partial_bf16(const void *x, const void *dy, float *part, void *dw_out, bool *wrote_dw, const Shape &s,
                            const DwPlan &p, hipStream_t st);
+// (fp32, seven to sixteen block offsets; returns -1 when it does not apply)
+int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                               int dmin, int nd, hipStream_t st);
 int launch_bwd_fused_f32(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
                          const Shape &s, const DwPlan &p, hipStream_t st);
 int launch_bwd_fused_bf16(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,

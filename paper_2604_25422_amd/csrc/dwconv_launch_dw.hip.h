@@ -115,37 +115,6 @@ int launch_dw_partial_mfma_nd(const void *x, const void *dy, float *part, void *
     }
 }
 
-// fp32, seven to ten block offsets (K up to 130): the LDS-direct kernel on ordinary rows.
-template <int ND, int W>
-int launch_dw_partial_wide_ndw(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
-                               int dmin, hipStream_t st)
-{
-    constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
-    if constexpr (lds > kMaxLdsBytes) {
-        return -1;
-    } else {
-        auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
-        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
-                           static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
-        return launch_status();
-    }
-}
-template <int ND>
-int launch_dw_partial_wide_nd(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
-                              int dmin, hipStream_t st)
-{
-    if (p.rows.on) return -1;
-    switch (p.wpb) {
-    case 4: return launch_dw_partial_wide_ndw<ND, 4>(x, dy, part, dw_out, s, p, dmin, st);
-    case 5: return launch_dw_partial_wide_ndw<ND, 5>(x, dy, part, dw_out, s, p, dmin, st);
-    case 8: return launch_dw_partial_wide_ndw<ND, 8>(x, dy, part, dw_out, s, p, dmin, st);
-    case 16: return launch_dw_partial_wide_ndw<ND, 16>(x, dy, part, dw_out, s, p, dmin, st);
-    default: return -1;
-    }
-}
-
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
 template <typename T>
 int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
@@ -153,16 +122,10 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
     if constexpr (std::is_same<T, float>::value) {
-        switch (nd) {
-        case 7: return launch_dw_partial_wide_nd<7>(x, dy, part, dw_out, s, p, dmin, st);
-        case 8: return launch_dw_partial_wide_nd<8>(x, dy, part, dw_out, s, p, dmin, st);
-        case 9: return launch_dw_partial_wide_nd<9>(x, dy, part, dw_out, s, p, dmin, st);
-        case 10: return launch_dw_partial_wide_nd<10>(x, dy, part, dw_out, s, p, dmin, st);
-        default: break;
-        }
+        if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
     }
     switch (nd) {
     case 2: return launch_dw_partial_mfma_nd<T, 2>(x, dy, part, dw_out, s, p, dmin, st);
