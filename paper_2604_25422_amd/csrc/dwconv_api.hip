@@ -181,6 +181,9 @@ DwPlan plan_dw(const Shape &s)
                           (nd <= kMfmaMaxND || dwconv::dw_direct_lds_bytes(nd, wpb) <= kMaxLdsBytes);
         if (items >= 2 * wpb && fits) { p.wpb = wpb; p.single = true; }
     }
+    // Small problems (at most four segments or units per wave of one four-wave workgroup per channel) are bound by
+    // launch latency: one workgroup per channel and no second launch there too.
+    if (mfma_shape && !p.single && items <= 4 * dwconv::kWavesPerBlock) p.single = true;
     long long groups = s.C;                                      // blocks along the channel axis
     if (p.rows.batch && !p.single && s.C % 2 == 0 && (s.L * (int)elem_size(s.dtype)) % 128 != 0 && s.L <= 48) {
         // two neighbouring channels per block: rows that are not whole cache lines become pieces that are;

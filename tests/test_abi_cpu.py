@@ -126,9 +126,10 @@ def test_single_pass_query(lib):
     assert f(32, 256, 4096, 64, 63, 0) == 1 and lib.dwconv_bwd_weight_slices(32, 256, 4096, 64, 63, 0) == 1
     assert f(64, 512, 2048, 7, 3, 0) == 1
     assert f(128, 768, 1024, 32, 31, 1) == 1
-    assert f(4, 64, 1024, 16, 15, 0) == 0            # channels do not fill the chip
+    assert f(40, 64, 1024, 16, 15, 0) == 0           # channels do not fill the chip
+    assert f(4, 64, 1024, 16, 15, 0) == 1            # ... but at most four segments per wave: launch-bound, one kernel
     assert f(8, 256, 8192, 8192, 8191, 0) == 0       # long filter: two zero-filled slices
-    assert f(1, 256, 1024, 16, 15, 0) == 0           # a single segment per channel
+    assert f(1, 256, 1024, 16, 15, 0) == 1           # a single segment per channel: one kernel as well
     assert f(32, 256, 4098, 64, 63, 0) == 0          # row length not a multiple of 4
     assert f(0, 256, 4096, 64, 63, 0) == 0           # bad shape
 
