@@ -83,6 +83,11 @@ def test_paper_shape_full_size(oracle_mod):
     run_full_size(oracle_mod, workloads.WORKLOADS[5], 8192, 16)
 
 
+def test_mid_filter_full_size(oracle_mod):
+    # a filter of 128 taps at the headline geometry: nine block offsets on the register-resident kernels
+    run_full_size(oracle_mod, workloads.WORKLOADS[6], 512, 16)
+
+
 @pytest.mark.parametrize("B,C,L,K,p,dtype", [
     (50, 100, 5000, 40, 11, "f32"),        # channel count unrelated to the chip, ragged last segment, several slices
     (7, 300, 12000, 64, 63, "f32"),        # long rows, odd batch
