@@ -29,6 +29,11 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     const int nd = dmax - dmin + 1;
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    // eleven to sixteen block offsets: only where rows fill their 1024-position segments to three quarters
+    // (shorter rows do less work on the long-filter kernel, which contracts in-row block pairs only)
+    if (nd > kMfmaMaxNDWide &&
+        4ll * s.L < 3ll * (((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen))
+        return -1;
     const long long rows = (long long)s.B * s.C;
     const long long segs_per_row = (s.L + dwconv::kSegLen - 1) / dwconv::kSegLen;
     const long long total_segs = rows * segs_per_row;
@@ -188,6 +193,12 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         case 8: return launch(dwconv::corr_mfma_kernel<float, 8, false>, pi, pf, po);
         case 9: return launch(dwconv::corr_mfma_kernel<float, 9, false>, pi, pf, po);
         case 10: return launch(dwconv::corr_mfma_kernel<float, 10, false>, pi, pf, po);
+        case 11: return launch(dwconv::corr_mfma_kernel<float, 11, false>, pi, pf, po);
+        case 12: return launch(dwconv::corr_mfma_kernel<float, 12, false>, pi, pf, po);
+        case 13: return launch(dwconv::corr_mfma_kernel<float, 13, false>, pi, pf, po);
+        case 14: return launch(dwconv::corr_mfma_kernel<float, 14, false>, pi, pf, po);
+        case 15: return launch(dwconv::corr_mfma_kernel<float, 15, false>, pi, pf, po);
+        case 16: return launch(dwconv::corr_mfma_kernel<float, 16, false>, pi, pf, po);
         default: break;
         }
     }
@@ -200,7 +211,7 @@ template <typename T>
 int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
-    if (dmax - dmin + 1 <= mfma_max_nd(s.dtype) || s.K > dwconv::kLkMaxK || (s.L % 4) != 0) return -1;
+    if (dmax - dmin + 1 <= longk_corr_min_nd(s.dtype) - 1 || s.K > dwconv::kLkMaxK || (s.L % 4) != 0) return -1;
     const int NB = (s.L + 15) / 16;
     if (NB > dwconv::kLkMaxBlocks) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;

@@ -34,8 +34,11 @@ SMALL = [
     (1, 1, 8192, 300, 299), (1, 2, 72, 67, 66),
     # seven to ten block offsets (fp32 register-resident class up to K = 130): every count, ragged rows, several rows per wave
     (3, 5, 2060, 100, 99), (2, 3, 1028, 112, 50), (5, 2, 3072, 128, 127), (2, 2, 1100, 130, 0), (9, 4, 1024, 97, 96),
-    # eleven to sixteen block offsets: the weight gradient stays on the register-resident kernel (fwd/dX: long-filter kernels)
+    # eleven to sixteen block offsets: register-resident kernels (fwd/dX: rows that fill three quarters of their
+    # 1024-position segments, the long-filter kernel otherwise); every count, ragged rows, several segments per wave
     (3, 4, 2060, 160, 159), (2, 3, 1028, 226, 100), (5, 2, 3072, 200, 0), (2, 2, 1100, 180, 90),
+    (7, 2, 1024, 161, 80), (3, 3, 1024, 176, 175), (2, 5, 800, 190, 95), (4, 2, 3000, 215, 214), (2, 3, 2048, 226, 225),
+    (2, 2, 4092, 226, 0), (70, 32, 1024, 170, 169),
     # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
     (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
