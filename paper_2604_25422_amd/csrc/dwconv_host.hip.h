@@ -45,9 +45,9 @@ constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
 constexpr int kMfmaMaxNDWide = 10;     // fp32 on long rows, K up to 130: whole-channel workgroups for dW still possible
 constexpr int kMfmaMaxNDDw = 16;       // fp32 on long rows, K up to 226: four-wave dW workgroups, two correlate waves per SIMD
-inline int mfma_max_nd(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND; }         // fwd, dX
-// fewest block offsets the long-filter forward / input-gradient kernel takes (fp32: eleven to sixteen go to
-// whichever of the two kernels wastes less on the row length)
+inline int mfma_max_nd(int /* either storage type */) { return kMfmaMaxNDDw; }                      // fwd, dX
+// fewest block offsets the long-filter forward / input-gradient kernel takes (from there to sixteen: whichever of
+// the two kernels wastes less on the row length)
 inline int longk_corr_min_nd(int dtype) { return (dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) + 1; }
 inline int mfma_max_nd_dw(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND; }      // dW stage 1
 constexpr int kComputeUnits = 256;     // MI355X

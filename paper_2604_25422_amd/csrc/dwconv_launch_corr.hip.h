@@ -29,9 +29,10 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     const int nd = dmax - dmin + 1;
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
-    // eleven to sixteen block offsets: only where rows fill their 1024-position segments to three quarters
-    // (shorter rows do less work on the long-filter kernel, which contracts in-row block pairs only)
-    if (nd > kMfmaMaxNDWide &&
+    // block offsets the long-filter kernel takes too (fp32 eleven to sixteen, bf16 seven to sixteen): only where rows
+    // fill their 1024-position segments to three quarters (shorter rows do less work on the long-filter kernel,
+    // which contracts in-row block pairs only)
+    if (nd >= longk_corr_min_nd(s.dtype) &&
         4ll * s.L < 3ll * (((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen))
         return -1;
     const long long rows = (long long)s.B * s.C;
@@ -173,6 +174,16 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
             case 4: return launch(dwconv::corr_mfma_bf16_kernel<4>, pi, pf, po);
             case 5: return launch(dwconv::corr_mfma_bf16_kernel<5>, pi, pf, po);
             case 6: return launch(dwconv::corr_mfma_bf16_kernel<6>, pi, pf, po);
+            case 7: return launch(dwconv::corr_mfma_bf16_kernel<7>, pi, pf, po);
+            case 8: return launch(dwconv::corr_mfma_bf16_kernel<8>, pi, pf, po);
+            case 9: return launch(dwconv::corr_mfma_bf16_kernel<9>, pi, pf, po);
+            case 10: return launch(dwconv::corr_mfma_bf16_kernel<10>, pi, pf, po);
+            case 11: return launch(dwconv::corr_mfma_bf16_kernel<11>, pi, pf, po);
+            case 12: return launch(dwconv::corr_mfma_bf16_kernel<12>, pi, pf, po);
+            case 13: return launch(dwconv::corr_mfma_bf16_kernel<13>, pi, pf, po);
+            case 14: return launch(dwconv::corr_mfma_bf16_kernel<14>, pi, pf, po);
+            case 15: return launch(dwconv::corr_mfma_bf16_kernel<15>, pi, pf, po);
+            case 16: return launch(dwconv::corr_mfma_bf16_kernel<16>, pi, pf, po);
             default: return -1;
             }
         }

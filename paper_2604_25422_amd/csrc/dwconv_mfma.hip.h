@@ -384,7 +384,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 constexpr int kBf16BlockBytes = 48;      // staged 16-block: 32 bytes + 16 pad
 
 template <int ND>
-__global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_mfma_bf16_kernel(
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 9 ? 2 : ND > 8 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_bf16_kernel(
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ f, bf16_t *__restrict__ out, const CorrGeom g,
     const RowsMap /* short rows are an fp32 path */)
 {
@@ -400,9 +400,10 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int k4 = lane >> 4;       // contraction group (k = 4 k4 + e);  D: row group
 
     const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    int row = wg / g.segs_per_row;                 // b * C + c
-    int seg = wg % g.segs_per_row;
-    int c = row % g.C;
+    // (wave-uniform, needed in scalar registers: the divisions run on the vector ALU)
+    int row = __builtin_amdgcn_readfirstlane(wg / g.segs_per_row);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(wg % g.segs_per_row);
+    int c = __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
     int row_n, seg_n, c_n;                         // the segment after (row, seg)
     auto advance = [&]() {

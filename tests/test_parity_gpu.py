@@ -91,7 +91,12 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
                                                    (3, 2, 256, 200, 100), (1, 2, 2048, 1500, 700), (2, 2, 2056, 64, 0),
                                                    # bf16 short rows longer than 64 positions: virtual rows
                                                    (40, 6, 128, 16, 15), (33, 3, 100, 31, 30), (9, 256, 256, 33, 16),
-                                                   (64, 2, 512, 64, 63), (7, 5, 68, 7, 3), (300, 2, 72, 48, 24)])
+                                                   (64, 2, 512, 64, 63), (7, 5, 68, 7, 3), (300, 2, 72, 48, 24),
+                                                   # bf16 forward / dX with seven to sixteen block offsets: every count
+                                                   (3, 5, 2048, 100, 99), (2, 3, 1024, 112, 50), (5, 2, 3072, 128, 127),
+                                                   (9, 4, 1024, 130, 0), (7, 2, 1024, 161, 80), (3, 3, 1024, 176, 175),
+                                                   (2, 5, 800, 190, 95), (4, 2, 3000, 215, 214), (2, 3, 2048, 226, 225),
+                                                   (2, 2, 4088, 200, 0), (70, 32, 1024, 170, 169), (2, 3, 1028, 150, 149)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
