@@ -168,13 +168,14 @@ DwPlan plan_dw(const Shape &s)
     }
     long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s.dtype) && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
+    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
     // waves takes a whole channel: no slices, no second stage.
     p.wpb = dwconv::kWavesPerBlock;
     p.single = false;
     p.dw_nc = 1;
-    if (mfma_shape && nd <= kMfmaMaxNDWide && s.C % kComputeUnits == 0 && s.C / kComputeUnits <= 3) {
+    if (mfma_shape && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) && s.C % kComputeUnits == 0 &&
+        s.C / kComputeUnits <= 3) {
         const int wpb = 16 / (s.C / kComputeUnits);
         // (sixteen-row units of rows longer than 48 positions need more LDS than sixteen waves have)
         const bool fits = (!p.rows.batch || dwconv::rb_dw_lds_bytes(s.L, nd, wpb, 1) <= kMaxLdsBytes) &&
@@ -225,7 +226,7 @@ DwPlan plan_dw(const Shape &s)
     p.longk = false;
     p.lk_wgs = p.lk_gd = 0;
     const int NCH = (s.L + 63) / 64;
-    if (nd > mfma_max_nd_dw(s.dtype) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
+    if (nd > mfma_max_nd_dw(s) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
         const int per_wg = 2 * dwconv::kLkWaves * dwconv::kLkDwMaxGD;
         p.lk_wgs = (nd + per_wg - 1) / per_wg;

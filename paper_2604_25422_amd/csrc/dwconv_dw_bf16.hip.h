@@ -13,16 +13,19 @@
 // (block nb at nb ^ ((nb >> 2) & 3) within its group): the four lane groups of a read touch blocks 4 apart, which
 // would otherwise fall on the same LDS banks.  The permutation is applied on the memory side of the loads.
 // Loads of a segment in issue order: x0 g0 x1 g1 xt (x_h, g_h: elements [512 h, 512 h + 512) of the x window and
-// of the dY tile; xt: 128 elements of x tail, two per lane).  Needs L % 8 == 0 and 16-byte aligned tensors.
+// of the dY tile; xt: 128 elements of x tail, two per lane; a second such load above eight block offsets).
+// Needs L % 8 == 0 and 16-byte aligned tensors.  Up to sixteen block offsets fit 128 registers; above six the
+// diagonal image of the accumulators (18 KB of LDS per wave at sixteen) is what limits the waves per compute unit.
 #pragma once
 #include "dwconv_bwd_fused.hip.h"
 
 namespace dwconv {
 
-constexpr int kBf16DwWinX = kSegLen + 128;      // elements of the staged x window (1024 + one tail load)
+constexpr int dw_bf16_tail_loads(int ND) { return (16 * ND + 127) / 128; }      // 128-element loads of x tail
+constexpr int dw_bf16_win_x(int ND) { return kSegLen + 128 * dw_bf16_tail_loads(ND); }   // elements of the staged x window
 constexpr int dw_bf16_wave_floats(int ND)
 {
-    const int stage = (kBf16DwWinX + kSegLen) / 2, diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
+    const int stage = (dw_bf16_win_x(ND) + kSegLen) / 2, diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
     return stage > diag ? stage : diag;
 }
 constexpr size_t dw_bf16_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_bf16_wave_floats(ND) + 16 * ND) * sizeof(float); }
@@ -35,7 +38,10 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ part, bf16_t *__restrict__ dw_out,
     int B, int C, int L, int K, int pad, int dmin, int segs_per_row)
 {
-    static_assert(ND >= 2 && 16 * ND <= 128, "the x tail is one 128-element load");
+    static_assert(ND >= 2 && 16 * ND <= 256, "the x tail is one or two 128-element loads");
+    constexpr int NT = dw_bf16_tail_loads(ND);     // tail loads per segment
+    constexpr int NLOADS = 4 + NT;                 // loads per segment
+    constexpr int WINX = dw_bf16_win_x(ND);
     constexpr int XWE = kSegLen + 16 * ND;         // elements of the x window that are ever read
     constexpr int WREG = dw_bf16_wave_floats(ND);
     extern __shared__ __align__(16) float dyn_lds[];
@@ -53,9 +59,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     int b = ws / segs_per_row, seg = ws % segs_per_row;
 
     const short *sx = reinterpret_cast<const short *>(s_mem[wave]);     // x window, element e of block nb at 16 pos(nb) + e
-    const short *sg = sx + kBf16DwWinX;                                 // dY tile, same block order
+    const short *sg = sx + WINX;                                        // dY tile, same block order
     const unsigned lds_x = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const void *)sx);
-    const unsigned lds_g = lds_x + 2u * kBf16DwWinX;
+    const unsigned lds_g = lds_x + 2u * WINX;
 
     // ---- loop constants
     // LDS read addresses (elements).  x: block 16 c4 + 4 kg + m, m = v + d = 4 mh + ml, sits at
@@ -72,9 +78,13 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     // memory-side byte offsets of the loads: LDS granule slot `lane` of a 512-element load holds half (lane & 1)
     // of the block whose position is lane >> 1
     const int off_main = 32 * bf16_block_pos(lane >> 1) + 16 * (lane & 1);
-    // tail: LDS elements 1024 + 2 lane, + 1: block position 64 + (lane >> 3), elements 2 (lane & 7), + 1
-    const int tail_elem = 16 * (64 + bf16_block_pos(lane >> 3)) + 2 * (lane & 7);
-    const int off_tail = tail_elem < XWE ? 2 * tail_elem : kOutOfRow;
+    // tail load t: LDS elements 1024 + 128 t + 2 lane, + 1: block position 64 + 8 t + (lane >> 3), elements 2 (lane & 7), + 1
+    int off_tail[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int tail_elem = 16 * (64 + bf16_block_pos(8 * t + (lane >> 3))) + 2 * (lane & 7);
+        off_tail[t] = tail_elem < XWE ? 2 * tail_elem : kOutOfRow;
+    }
 
     floatx4 G[ND];
 #pragma unroll
@@ -103,7 +113,10 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
         buffer_load_x4_to_lds(rx, off_main + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
         buffer_load_x4_to_lds(rg, off_main + 1024 * h, lds_g + 1024u * (unsigned)h);
     };
-    auto load_tail = [&]() { buffer_load_x1_to_lds(rx, off_tail + x_shift, lds_x + 2048u); };
+    auto load_tail = [&]() {
+        buffer_load_x1_to_lds(rx, off_tail[0] + x_shift, lds_x + 2048u);
+        if constexpr (NT > 1) buffer_load_x1_to_lds(rx, off_tail[NT - 1] + x_shift, lds_x + 2048u + 256u);
+    };
 
     aim(b, seg);
     load_half(std::integral_constant<int, 0>{});
@@ -116,12 +129,13 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
         seg_n -= carry ? segs_per_row : 0;
         const int b_n = b + step_b + carry;
         aim(b_n, seg_n);
-        // 256-position chunk c4: before it, load number need(c4) of this segment has landed
-        //   c4 = 0: g0 (1)   c4 = 1: x1 (2)   c4 = 2: g1 (3)   c4 = 3: xt (4);   two next-segment loads are out after chunk 1
+        // 256-position chunk c4 (x blocks 16 c4 .. 16 c4 + 15 + ND + 2): before it, load number need(c4) of this
+        // segment has landed
+        //   c4 = 0: g0 (1)   c4 = 1: x1 (2)   c4 = 2: g1 (3)   c4 = 3: the last tail;   two next-segment loads are out after chunk 1
         static_for<0, 4>([&](auto cc) {
             constexpr int c4 = decltype(cc)::value;
-            constexpr int need = c4 + 1, issued = c4 >= 2 ? 2 : 0;
-            wait_vmcnt_at_most<(4 - need) + issued>();
+            constexpr int need = c4 == 3 ? NLOADS - 1 : c4 + 1, issued = c4 >= 2 ? 2 : 0;
+            wait_vmcnt_at_most<(NLOADS - 1 - need) + issued>();
             shortx4 bq;
 #pragma unroll
             for (int v = 0; v < 4; ++v) bq[v] = ag[v][256 * c4];

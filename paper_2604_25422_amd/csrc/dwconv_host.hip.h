@@ -49,7 +49,8 @@ inline int mfma_max_nd(int /* either storage type */) { return kMfmaMaxNDDw; }  
 // fewest block offsets the long-filter forward / input-gradient kernel takes (from there to sixteen: whichever of
 // the two kernels wastes less on the row length)
 inline int longk_corr_min_nd(int dtype) { return (dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) + 1; }
-inline int mfma_max_nd_dw(int dtype) { return dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND; }      // dW stage 1
+// dW stage 1 (bf16 above six offsets: rows of whole 16-byte granules only)
+inline int mfma_max_nd_dw(const Shape &s) { return (s.dtype == DWCONV_F32 || (s.L % 8) == 0) ? kMfmaMaxNDDw : kMfmaMaxND; }
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
@@ -162,6 +163,9 @@ int launch_dw_partial_bf16(const void *x, const void *dy, float *part, void *dw_
 // (fp32, seven to sixteen block offsets; returns -1 when it does not apply)
 int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
                                int dmin, int nd, hipStream_t st);
+// (bf16, seven to sixteen block offsets, rows of whole 16-byte granules; returns -1 when it does not apply)
+int launch_dw_partial_wide_bf16(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                                int dmin, int nd, hipStream_t st);
 int launch_bwd_fused_f32(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
                          const Shape &s, const DwPlan &p, hipStream_t st);
 int launch_bwd_fused_bf16(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out,

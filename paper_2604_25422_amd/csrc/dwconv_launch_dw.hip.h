@@ -122,10 +122,12 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
     if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
     if constexpr (std::is_same<T, float>::value) {
         if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
+    } else {
+        if (nd > kMfmaMaxND) return launch_dw_partial_wide_bf16(x, dy, part, dw_out, s, p, dmin, nd, st);
     }
     switch (nd) {
     case 2: return launch_dw_partial_mfma_nd<T, 2>(x, dy, part, dw_out, s, p, dmin, st);
