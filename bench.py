@@ -114,7 +114,7 @@ def main():
         sys.exit(2)
     import torch
     from paper_2604_25422_amd import binding, workloads
-    from paper_2604_25422_amd.roofline import (HBM_PEAK_GBPS, MFMA_F32_PEAK_TFLOPS, algorithmic_bytes, dense_flops,
+    from paper_2604_25422_amd.roofline import (HBM_PEAK_GBPS, MFMA_BF16_PEAK_TFLOPS, MFMA_F32_PEAK_TFLOPS, algorithmic_bytes, dense_flops,
                                                in_range_flops, measured_traffic)
 
     if not torch.cuda.is_available():
@@ -243,17 +243,18 @@ def main():
         "roofline": None,
     }
     # The roof that binds the dominant kernel is the one it sits closest to: HBM (algorithmic bytes) or,
-    # for filters as long as the sequence, the fp32 matrix peak (in-range flops).
+    # for filters as long as the sequence, the matrix peak of the storage type (in-range flops).
     hbm_frac = achieved / HBM_PEAK_GBPS
     tflops = flops / us[dom] / 1e6
-    mfma_frac = tflops / MFMA_F32_PEAK_TFLOPS
+    mfma_peak = MFMA_F32_PEAK_TFLOPS if wl.dtype == "f32" else MFMA_BF16_PEAK_TFLOPS
+    mfma_frac = tflops / mfma_peak
     traffic = measured_traffic(args.workload, dom)
     if hbm_frac >= mfma_frac:
         out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                            "unit": "GB/s", "frac": round(hbm_frac, 4), "traffic": traffic,
                            "kernel_us": round(us[dom], 2), "algorithmic_bytes": path_bytes}
     else:
-        out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_F32_PEAK_TFLOPS,
+        out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": round(tflops, 2), "peak": mfma_peak,
                            "unit": "TFLOP/s", "frac": round(mfma_frac, 4), "traffic": traffic,
                            "kernel_us": round(us[dom], 2), "algorithmic_flops": flops}
     if fused:

@@ -54,6 +54,8 @@ WORKLOADS = [
     Workload("paper_shape_B16384_C128_L48_K48_pad24_f32", 5, 16384, 128, 48, 48, 24, "f32", "normal_var_1_over_K"),
     # not a configuration of the baseline file: a filter between the two classes it names (nine block offsets)
     Workload("midK_B32_C256_L4096_K128_causal_f32", 6, 32, 256, 4096, 128, 127, "f32", "normal_var_1_over_K"),
+    # ... and the same filter length on bf16 storage at the bf16 geometry
+    Workload("midK_B128_C768_L1024_K128_causal_bf16", 7, 128, 768, 1024, 128, 127, "bf16", "normal_var_1_over_K"),
 ]
 HEADLINE = WORKLOADS[1]
 

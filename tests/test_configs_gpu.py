@@ -88,6 +88,11 @@ def test_mid_filter_full_size(oracle_mod):
     run_full_size(oracle_mod, workloads.WORKLOADS[6], 512, 16)
 
 
+def test_mid_filter_bf16_full_size(oracle_mod):
+    # the same 128 taps on bf16 storage: nine block offsets on the bf16 matrix-instruction kernels
+    run_full_size(oracle_mod, workloads.WORKLOADS[7], 512, 16)
+
+
 @pytest.mark.parametrize("B,C,L,K,p,dtype", [
     (50, 100, 5000, 40, 11, "f32"),        # channel count unrelated to the chip, ragged last segment, several slices
     (7, 300, 12000, 64, 63, "f32"),        # long rows, odd batch
