@@ -226,17 +226,28 @@ int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, 
     const int NB = (s.L + 15) / 16;
     if (NB > dwconv::kLkMaxBlocks) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
-    const size_t lds = dwconv::longk_corr_lds_bytes(s.K, NB);
     const long long row_groups = ((long long)s.B + dwconv::kLkRows - 1) / dwconv::kLkRows;
-    if (lds > kMaxLdsBytes || row_groups > 65535) return -1;
-    if (!allow_large_lds(dwconv::corr_longk_kernel<T>)) return -1;
+    if (row_groups > 65535) return -1;
     dwconv::LongKGeom g;
     g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K;
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin; g.dmax = dmax;
     g.NB = NB; g.NT = (NB + 15) / 16;
-    hipLaunchKernelGGL((dwconv::corr_longk_kernel<T>), dim3((unsigned)s.C, (unsigned)row_groups),
-                       dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(in), static_cast<const T *>(f),
-                       static_cast<T *>(out), g);
+    if constexpr (sizeof(T) == 2) {
+        // bf16 storage: raw rows and four shifted copies of the filter in LDS, bf16 matrix instruction
+        const size_t lds = dwconv::longk_corr_bf16_lds_bytes(s.K, NB);
+        if (lds > kMaxLdsBytes) return -1;
+        if (!allow_large_lds(dwconv::corr_longk_bf16_kernel<>)) return -1;
+        hipLaunchKernelGGL(dwconv::corr_longk_bf16_kernel<>, dim3((unsigned)s.C, (unsigned)row_groups),
+                           dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const bf16_t *>(in),
+                           static_cast<const bf16_t *>(f), static_cast<bf16_t *>(out), g);
+    } else {
+        const size_t lds = dwconv::longk_corr_lds_bytes(s.K, NB);
+        if (lds > kMaxLdsBytes) return -1;
+        if (!allow_large_lds(dwconv::corr_longk_kernel<T>)) return -1;
+        hipLaunchKernelGGL((dwconv::corr_longk_kernel<T>), dim3((unsigned)s.C, (unsigned)row_groups),
+                           dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(in), static_cast<const T *>(f),
+                           static_cast<T *>(out), g);
+    }
     return launch_status();
 }
 

@@ -140,6 +140,125 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_kernel(const T *__re
 }
 
 // ------------------------------------------------------------------------------------------------
+// The same correlation for bf16 storage on the bf16 matrix instruction (v_mfma_f32_16x16x16_bf16): one
+// instruction covers a whole block offset of one row (products of two bf16 are exact in fp32, sums fp32, one
+// rounding at the store), so per offset a wave issues kLkRows instructions instead of 4 kLkRows.
+// LDS holds raw bf16:
+//   rows: 16-blocks of 32 bytes padded to 48 (as in corr_mfma_bf16_kernel), 15 zero blocks on both sides;
+//   filter: FOUR copies, copy s shifted by s taps (copy_s[i] = fw[i + s]), because lane (r, kg) needs the four
+//       consecutive taps fw[a .. a + 3], a = 16 d + 4 kg - r + pad (+ margin), as one aligned 8-byte read and
+//       a mod 4 depends on the lane only: it reads copy (a mod 4) at a - (a mod 4), and a grows by 16 per offset.
+//       The copies start 64 bytes apart modulo 256, which puts the sixteen r of a read on different banks.
+constexpr int kLkBf16CopyPad = 32;         // bf16 elements: makes the stride of the copies 64 bytes modulo 256
+__host__ __device__ inline int longk_bf16_copy_elems(int K)
+{
+    const int n = (K + 2 * kLkWMargin + 3) & ~3;                  // taps with margins, whole 8-byte granules
+    return (n + 127) / 128 * 128 + kLkBf16CopyPad;                // stride = 64 bytes mod 256
+}
+__host__ __device__ inline int longk_bf16_row_bytes(int NB) { return (NB + 2 * kLkMargin) * kBf16BlockBytes; }
+inline size_t longk_corr_bf16_lds_bytes(int K, int NB)
+{
+    return (size_t)4 * longk_bf16_copy_elems(K) * 2 + (size_t)kLkRows * longk_bf16_row_bytes(NB);
+}
+
+template <int UNUSED = 0>   // (a template only so that the header can be included by several translation units)
+__global__ __launch_bounds__(64 * kLkWaves) void corr_longk_bf16_kernel(const bf16_t *__restrict__ in,
+                                                                         const bf16_t *__restrict__ f,
+                                                                         bf16_t *__restrict__ out, const LongKGeom g)
+{
+    extern __shared__ __align__(16) unsigned char lkb_smem[];
+    const int CE = longk_bf16_copy_elems(g.K);
+    uint16_t *fwc = reinterpret_cast<uint16_t *>(lkb_smem);      // copy s at fwc + s * CE
+    unsigned char *xr = lkb_smem + (size_t)4 * CE * 2;
+    const int XR = longk_bf16_row_bytes(g.NB);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i16 = lane & 15;
+    const int kg = lane >> 4;
+    const int c = blockIdx.x;
+    const int b0 = blockIdx.y * kLkRows;
+
+    // ---- stage the filter copies and the rows
+    {
+        const bf16_t *f_c = f + (size_t)c * (size_t)g.K;
+        const int FW = (g.K + 2 * kLkWMargin + 3) & ~3;
+        for (int i = tid; i < 4 * FW; i += 64 * kLkWaves) {
+            const int s = i / FW, e = i - s * FW;
+            const int j = e + s - kLkWMargin;
+            uint16_t v = 0;
+            if (j >= 0 && j < g.K) v = f_c[g.reverse ? (g.K - 1 - j) : j].bits;
+            fwc[s * CE + e] = v;
+        }
+        for (int rb = 0; rb < kLkRows; ++rb) {
+            unsigned char *xrow = xr + rb * XR;
+            const int b = b0 + rb;
+            // zero margins (the 32 useful bytes of each of the 15 + 15 blocks, 8 bytes at a time)
+            for (int i = tid; i < 2 * kLkMargin * 4; i += 64 * kLkWaves) {
+                const int blk = i >> 2, q = i & 3;
+                const int lb = blk < kLkMargin ? blk : g.NB + blk;
+                *reinterpret_cast<uint2 *>(xrow + lb * kBf16BlockBytes + 8 * q) = make_uint2(0u, 0u);
+            }
+            const bf16_t *in_row = in + ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            for (int gi = tid; gi < g.NB * 4; gi += 64 * kLkWaves) {
+                const int u = 4 * gi;
+                uint2 v = make_uint2(0u, 0u);
+                if (b < g.B && u + 3 < g.L) v = *reinterpret_cast<const uint2 *>(in_row + u);
+                *reinterpret_cast<uint2 *>(xrow + (kLkMargin + (gi >> 2)) * kBf16BlockBytes + (gi & 3) * 8) = v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // this lane's filter copy: a = kLkWMargin + 16 d + 4 kg - i16 + pad, copy a & 3 read at a - (a & 3)
+    const int a0 = kLkWMargin + 4 * kg - i16 + g.pad;             // at d = 0; 16 d keeps a & 3
+    const int sh = a0 & 3;
+    const uint16_t *acopy = fwc + sh * CE + (a0 - sh);
+
+    // ---- D tiles of this wave: w, 2*16-1-w, 2*16+w, ...
+    for (int base = 0; base < g.NT; base += 2 * kLkWaves) {
+        for (int half = 0; half < 2; ++half) {
+            const int t = half == 0 ? base + wave : base + 2 * kLkWaves - 1 - wave;
+            if (t >= g.NT) continue;
+            // offsets d for which some block 16 t + j + d of the tile lies inside the row
+            const int dlo = max(g.dmin, -(16 * t + 15));
+            const int dhi = min(g.dmax, g.NB - 1 - 16 * t);
+            floatx4 tot0 = floatx4{0.f, 0.f, 0.f, 0.f}, tot1 = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (dlo <= dhi) {
+                // A: lane (r = i16, kg) reads taps 16 d + 4 kg + e - r + pad;  B: lane (j = i16, kg) reads X[16 t + j + d][4 kg ..]
+                const uint16_t *ap = acopy + 16 * dlo;
+                const unsigned char *bp = xr + (kLkMargin + 16 * t + i16 + dlo) * kBf16BlockBytes + 8 * kg;
+                for (int d0 = dlo; d0 <= dhi; d0 += kLkFold) {
+                    const int n = min(kLkFold, dhi - d0 + 1);
+                    floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                    for (int i = 0; i < n; ++i) {
+                        const shortx4 a = *reinterpret_cast<const shortx4 *>(ap);
+                        const shortx4 x0 = *reinterpret_cast<const shortx4 *>(bp);
+                        const shortx4 x1 = *reinterpret_cast<const shortx4 *>(bp + XR);
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, x0, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, x1, acc1, 0, 0, 0);
+                        ap += 16;
+                        bp += kBf16BlockBytes;
+                    }
+                    tot0 += acc0;
+                    tot1 += acc1;
+                }
+            }
+            // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the tile
+            const int to = 256 * t + 16 * i16 + 4 * kg;
+            if (to + 3 < g.L) {
+                bf16_t *o0 = out + ((size_t)b0 * (size_t)g.C + (size_t)c) * (size_t)g.L + to;
+                st_elem4(o0, make_float4(tot0[0], tot0[1], tot0[2], tot0[3]));
+                if (b0 + 1 < g.B)
+                    st_elem4(o0 + (size_t)g.C * (size_t)g.L, make_float4(tot1[0], tot1[1], tot1[2], tot1[3]));
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Stage 1 of the weight gradient for long filters (eq. (dk_def)):
 //     G_d[q'][q] = sum_b sum_n X[n + d][q'] dY[n][q],      dw[j] = sum over 16 d + q' - q + pad = j.
 // There are hundreds of offsets d, each with a 16x16 accumulator, so the offsets are what is split

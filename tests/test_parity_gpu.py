@@ -96,7 +96,12 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
                                                    (3, 5, 2048, 100, 99), (2, 3, 1024, 112, 50), (5, 2, 3072, 128, 127),
                                                    (9, 4, 1024, 130, 0), (7, 2, 1024, 161, 80), (3, 3, 1024, 176, 175),
                                                    (2, 5, 800, 190, 95), (4, 2, 3000, 215, 214), (2, 3, 2048, 226, 225),
-                                                   (2, 2, 4088, 200, 0), (70, 32, 1024, 170, 169), (2, 3, 1028, 150, 149)])
+                                                   (2, 2, 4088, 200, 0), (70, 32, 1024, 170, 169), (2, 3, 1028, 150, 149),
+                                                   # bf16 long filters (forward / dX on the bf16 matrix instruction): odd
+                                                   # batches, every pad class, filters longer than the row, ragged rows
+                                                   (2, 3, 512, 512, 511), (3, 1, 640, 640, 320), (1, 2, 4096, 4096, 4095),
+                                                   (2, 1, 1000, 2500, 1200), (1, 1, 8192, 300, 299), (3, 2, 1024, 1024, 0),
+                                                   (5, 2, 4100, 700, 350), (3, 3, 260, 513, 17), (1, 1, 8192, 8192, 8191)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
