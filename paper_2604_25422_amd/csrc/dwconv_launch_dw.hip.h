@@ -140,12 +140,33 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 }
 
 template <typename T, int GD>
-void launch_dw_longk_gd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p,
-                        const dwconv::LongKDwGeom &g, size_t lds, hipStream_t st)
+int launch_dw_longk_gd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p,
+                       const dwconv::LongKDwGeom &g, hipStream_t st)
 {
-    hipLaunchKernelGGL((dwconv::dw_longk_kernel<T, GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
-                       dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(x), static_cast<const T *>(dy),
-                       part, g, *p.lk_table);
+    // both slices start at zero: a group stores only the taps it owns
+    auto fill = [&]() {
+        const size_t n = (size_t)2 * (size_t)s.C * (size_t)s.K;
+        size_t fill_blocks = (n + 256 * 8 - 1) / (256 * 8);
+        if (fill_blocks > 65536) fill_blocks = 65536;
+        hipLaunchKernelGGL(dwconv::fill_zero_kernel<>, dim3((unsigned)fill_blocks), dim3(256), 0, st, part, n);
+    };
+    if constexpr (sizeof(T) == 2) {
+        // bf16 storage: raw rows in LDS, bf16 matrix instruction
+        const size_t lds = dwconv::longk_dw_bf16_lds_bytes(s.L);
+        if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::dw_longk_bf16_kernel<GD>)) return -1;
+        fill();
+        hipLaunchKernelGGL((dwconv::dw_longk_bf16_kernel<GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
+                           dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const bf16_t *>(x),
+                           static_cast<const bf16_t *>(dy), part, g, *p.lk_table);
+    } else {
+        const size_t lds = dwconv::longk_dw_lds_bytes(s.L, g.NCH);
+        if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::dw_longk_kernel<T, GD>)) return -1;
+        fill();
+        hipLaunchKernelGGL((dwconv::dw_longk_kernel<T, GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
+                           dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(x), static_cast<const T *>(dy),
+                           part, g, *p.lk_table);
+    }
+    return launch_status();
 }
 
 // Returns -1 when the pointers do not fit the long-filter matrix-core kernel.
@@ -157,31 +178,14 @@ int launch_dw_partial_longk(const void *x, const void *dy, float *part, const Sh
     g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K; g.pad = s.pad;
     g.dmin = toeplitz_dmin(s.pad); g.dmax = toeplitz_dmax(s.K, s.pad);
     g.NCH = (s.L + 63) / 64;
-    const size_t lds = dwconv::longk_dw_lds_bytes(s.L, g.NCH);
-    bool ok = true;
     switch (p.lk_gd) {
-    case 1: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 1>); break;
-    case 2: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 2>); break;
-    case 3: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 3>); break;
-    case 4: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 4>); break;
-    case 6: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 6>); break;
-    default: ok = allow_large_lds(dwconv::dw_longk_kernel<T, 9>); break;
+    case 1: return launch_dw_longk_gd<T, 1>(x, dy, part, s, p, g, st);
+    case 2: return launch_dw_longk_gd<T, 2>(x, dy, part, s, p, g, st);
+    case 3: return launch_dw_longk_gd<T, 3>(x, dy, part, s, p, g, st);
+    case 4: return launch_dw_longk_gd<T, 4>(x, dy, part, s, p, g, st);
+    case 6: return launch_dw_longk_gd<T, 6>(x, dy, part, s, p, g, st);
+    default: return launch_dw_longk_gd<T, 9>(x, dy, part, s, p, g, st);
     }
-    if (!ok) return -1;
-    // both slices start at zero: a group stores only the taps it owns
-    const size_t n = (size_t)2 * (size_t)s.C * (size_t)s.K;
-    size_t fill_blocks = (n + 256 * 8 - 1) / (256 * 8);
-    if (fill_blocks > 65536) fill_blocks = 65536;
-    hipLaunchKernelGGL(dwconv::fill_zero_kernel<>, dim3((unsigned)fill_blocks), dim3(256), 0, st, part, n);
-    switch (p.lk_gd) {
-    case 1: launch_dw_longk_gd<T, 1>(x, dy, part, s, p, g, lds, st); break;
-    case 2: launch_dw_longk_gd<T, 2>(x, dy, part, s, p, g, lds, st); break;
-    case 3: launch_dw_longk_gd<T, 3>(x, dy, part, s, p, g, lds, st); break;
-    case 4: launch_dw_longk_gd<T, 4>(x, dy, part, s, p, g, lds, st); break;
-    case 6: launch_dw_longk_gd<T, 6>(x, dy, part, s, p, g, lds, st); break;
-    default: launch_dw_longk_gd<T, 9>(x, dy, part, s, p, g, lds, st); break;
-    }
-    return launch_status();
 }
 
 template <typename T>

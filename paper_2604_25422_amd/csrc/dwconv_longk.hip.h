@@ -440,4 +440,185 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same stage 1 for bf16 storage on the bf16 matrix instruction (v_mfma_f32_16x16x16_bf16): the contraction of
+// one instruction runs over 16 consecutive blocks n, so a chunk is 256 positions and a wave issues a quarter of the
+// instructions.  Same groups, same table, same epilogue as dw_longk_kernel (the accumulators have the same lane
+// layout).  Lane (i = lane % 16, kg = lane / 16) holds the contraction entries k = 4 kg + v: element i of blocks
+// n0 + 4 kg + v (+ d), v = 0..3.  So that these four values are ONE LDS read, the rows are staged transposed:
+//     xt[i][m] = x[16 (m - 32) + i]   (16 lines of bf16, one entry per block, 32 zero blocks on both sides),
+//     gt[i][n] = dy[16 n + i],
+// and the operand of offset d is xt[i][32 + n0 + 4 kg + d .. + 3].  Its alignment is that of d: x is kept twice, the
+// second copy shifted by one entry, which makes every operand two aligned dwords (ds_read2_b32); dY needs one copy
+// (8-byte aligned).  Lines are 16 bytes modulo 256 apart: the 32 lanes of a half wave then read 64 different banks.
+constexpr int kLkDwBf16MarginBlocks = 32;
+__host__ __device__ inline int lk_bf16_line_bytes(int entries) { return (2 * entries + 255 - 16) / 256 * 256 + 16; }
+inline size_t longk_dw_bf16_lds_bytes(int L)
+{
+    const int nb = (L + 255) / 256 * 16;                            // blocks per row, whole chunks
+    const size_t xcopy = (size_t)16 * lk_bf16_line_bytes(nb + 2 * kLkDwBf16MarginBlocks);
+    const size_t stage = (size_t)kLkRows * (2 * xcopy + (size_t)16 * lk_bf16_line_bytes(nb));
+    const size_t reduce = sizeof(float) * (size_t)kLkWaves * (256 + 16 * kLkDwMaxGD + 32);
+    return stage > reduce ? stage : reduce;
+}
+
+typedef __attribute__((address_space(3))) const uint32_t *lds_u32_ptr;
+typedef unsigned int lk_uintx2 __attribute__((ext_vector_type(2)));
+
+// The 256-position chunks [ch_lo, ch_hi] of one staged row for a group of N offsets.  xa[i]: this lane's LDS address
+// of the operand of offset da + i in chunk 0; ga: of the dY operand.  A chunk further is 16 entries = 32 bytes.
+template <int N, int GD>
+__device__ __forceinline__ void lk_dw_chunks_bf16(floatx4 (&G)[GD], const lds_u32_ptr (&xa)[GD], lds_u32_ptr ga,
+                                                  int ch_lo, int ch_hi)
+{
+#pragma unroll 2
+    for (int ch = ch_lo; ch <= ch_hi; ++ch) {
+        const lk_uintx2 bw = {ga[8 * ch], ga[8 * ch + 1]};
+        const shortx4 bq = __builtin_bit_cast(shortx4, bw);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const lk_uintx2 aw = {xa[i][8 * ch], xa[i][8 * ch + 1]};
+            G[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, aw), bq, G[i], 0, 0, 0);
+        }
+    }
+}
+template <int GD, int N = GD>
+__device__ __forceinline__ void lk_dw_chunks_bf16_n(int n, floatx4 (&G)[GD], const lds_u32_ptr (&xa)[GD], lds_u32_ptr ga,
+                                                    int ch_lo, int ch_hi)
+{
+    if (n == N) lk_dw_chunks_bf16<N, GD>(G, xa, ga, ch_lo, ch_hi);
+    else if constexpr (N > 1) lk_dw_chunks_bf16_n<GD, N - 1>(n, G, xa, ga, ch_lo, ch_hi);
+}
+
+template <int GD>
+__global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const bf16_t *__restrict__ x,
+                                                                          const bf16_t *__restrict__ dy,
+                                                                          float *__restrict__ part, const LongKDwGeom g,
+                                                                          const LongKDwTable tb)
+{
+    extern __shared__ __align__(16) unsigned char lkb_dw_smem[];
+    constexpr int MB = kLkDwBf16MarginBlocks;
+    const int NB = (g.L + 255) / 256 * 16;                  // blocks per row, whole chunks
+    const int NC256 = NB / 16;
+    const int XL = lk_bf16_line_bytes(NB + 2 * MB);         // bytes of one line of a transposed x copy
+    const int GL = lk_bf16_line_bytes(NB);                  // ... of transposed dY
+    const int XC = 16 * XL;                                 // bytes of one x copy
+    const int ROWB = 2 * XC + 16 * GL;                      // bytes of one staged row: x copy 0, x copy 1, dY
+    // row rb: x copy s at rb * ROWB + s * XC, entry (i, m) at + i * XL + 2 (m - s);  dY at rb * ROWB + 2 XC + i * GL + 2 n
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i16 = lane & 15, kg = lane >> 4;
+    const int c = blockIdx.x;
+    const int slot = (int)blockIdx.y * kLkWaves + wave;
+
+    // the two groups of this wave: offsets [da, db] inclusive, empty if da > db
+    int grp[2], da[2], db[2], nn[2], ch_lo[2], ch_hi[2];
+    grp[0] = tb.g0[slot];
+    grp[1] = tb.g1[slot];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const bool valid = grp[k] != kLkDwNoGroup;
+        const int gi = valid ? grp[k] : 0;
+        nn[k] = valid ? min((int)tb.n[gi], GD) : 0;
+        da[k] = tb.da[gi];
+        db[k] = da[k] + nn[k] - 1;
+        // chunks in which some offset of the group reaches the row: x positions 256 ch + 16 da .. 256 ch + 255 + 16 db
+        ch_lo[k] = max(0, ceil_div(-255 - 16 * db[k], 256));
+        ch_hi[k] = valid ? min(NC256 - 1, floor_div(g.L - 1 - 16 * da[k], 256)) : -1;
+    }
+
+    floatx4 G0[GD], G1[GD];
+#pragma unroll
+    for (int i = 0; i < GD; ++i) {
+        G0[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        G1[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // the margins of the x copies stay zero for the whole kernel: clear the staging region once
+    for (int i = tid; i < kLkRows * ROWB / 16; i += 64 * kLkWaves)
+        *reinterpret_cast<uint4 *>(lkb_dw_smem + 16 * i) = make_uint4(0u, 0u, 0u, 0u);
+
+    for (int b0 = 0; b0 < g.B; b0 += kLkRows) {
+        __syncthreads();
+        for (int rb = 0; rb < kLkRows; ++rb) {
+            const int b = b0 + rb;
+            unsigned char *x0 = lkb_dw_smem + rb * ROWB, *x1 = x0 + XC, *gt = x0 + 2 * XC;
+            const size_t row = ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            for (int gi = tid; gi < NB * 4; gi += 64 * kLkWaves) {
+                const int u = 4 * gi;
+                uint2 vx = make_uint2(0u, 0u), vg = vx;
+                if (b < g.B && u + 3 < g.L) {
+                    vx = *reinterpret_cast<const uint2 *>(x + row + u);
+                    vg = *reinterpret_cast<const uint2 *>(dy + row + u);
+                }
+                const int blk = u >> 4, i0 = u & 15;
+                const uint16_t ex[4] = {(uint16_t)vx.x, (uint16_t)(vx.x >> 16), (uint16_t)vx.y, (uint16_t)(vx.y >> 16)};
+                const uint16_t eg[4] = {(uint16_t)vg.x, (uint16_t)(vg.x >> 16), (uint16_t)vg.y, (uint16_t)(vg.y >> 16)};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    *reinterpret_cast<uint16_t *>(x0 + (i0 + e) * XL + 2 * (MB + blk)) = ex[e];
+                    *reinterpret_cast<uint16_t *>(x1 + (i0 + e) * XL + 2 * (MB + blk - 1)) = ex[e];
+                    *reinterpret_cast<uint16_t *>(gt + (i0 + e) * GL + 2 * blk) = eg[e];
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (nn[k] == 0) continue;
+            for (int rb = 0; rb < kLkRows; ++rb) {
+                const unsigned char *x0 = lkb_dw_smem + rb * ROWB;
+                // operand of offset da + i: entries m0 .. m0 + 3, m0 = MB + 4 kg + da + i, from the copy of m0's parity
+                lds_u32_ptr xa[GD];
+#pragma unroll
+                for (int i = 0; i < GD; ++i) {
+                    const int m0 = MB + 4 * kg + da[k] + i;
+                    const int sh = m0 & 1;
+                    xa[i] = (lds_u32_ptr)(x0 + sh * XC + i16 * XL + 2 * (m0 - sh));
+                }
+                const lds_u32_ptr ga = (lds_u32_ptr)(x0 + 2 * XC + i16 * GL + 8 * kg);
+                if (k == 0) lk_dw_chunks_bf16_n<GD>(nn[0], G0, xa, ga, ch_lo[0], ch_hi[0]);
+                else lk_dw_chunks_bf16_n<GD>(nn[1], G1, xa, ga, ch_lo[1], ch_hi[1]);
+            }
+        }
+    }
+
+    // ---- diagonal sums.  Wave-private scratch in the (now free) staging region: 256 floats of one
+    // accumulator plus the taps of one group, tap T = 16 i + e + 15 for offset da + i, e = q' - q.
+    __syncthreads();
+    constexpr int NTAP = 16 * GD + 32;
+    float *scr = reinterpret_cast<float *>(lkb_dw_smem) + wave * (256 + NTAP);
+    float *tap = scr + 256;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        if (da[k] > db[k]) continue;
+        for (int i = lane; i < NTAP; i += 64) tap[i] = 0.f;
+        wave_lds_fence();
+#pragma unroll
+        for (int i = 0; i < GD; ++i) {
+            const floatx4 Gi = (k == 0) ? G0[i] : G1[i];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) scr[(4 * (lane >> 4) + v) * 16 + (lane & 15)] = Gi[v];
+            wave_lds_fence();
+            if (lane < 31) {
+                const int e = lane - 15;
+                const int q_lo = e > 0 ? e : 0, q_hi = e > 0 ? 15 : 15 + e;
+                float sum = 0.f;
+                for (int qp = q_lo; qp <= q_hi; ++qp) sum += scr[qp * 16 + (qp - e)];
+                if (da[k] + i <= db[k]) tap[16 * i + lane] += sum;     // a short last group owns fewer offsets
+            }
+            wave_lds_fence();
+        }
+        const int ntap = 16 * (db[k] - da[k]) + 31;
+        float *dst = part + ((size_t)(grp[k] & 1) * (size_t)g.C + (size_t)c) * (size_t)g.K;
+        for (int i = lane; i < ntap; i += 64) {
+            const int j = 16 * da[k] + (i - 15) + g.pad;
+            if (j >= 0 && j < g.K) dst[j] = tap[i];
+        }
+        wave_lds_fence();
+    }
+}
+
 }  // namespace dwconv
