@@ -232,7 +232,9 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_bf16_kernel(const bf
                 for (int d0 = dlo; d0 <= dhi; d0 += kLkFold) {
                     const int n = min(kLkFold, dhi - d0 + 1);
                     floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
+                    // (one offset per trip: four offsets per trip with all twelve reads issued first measured
+                    // 429 us instead of 224 us on B8 C256 L8192 K8192)
+#pragma unroll 1
                     for (int i = 0; i < n; ++i) {
                         const shortx4 a = *reinterpret_cast<const shortx4 *>(ap);
                         const shortx4 x0 = *reinterpret_cast<const shortx4 *>(bp);
@@ -465,29 +467,38 @@ inline size_t longk_dw_bf16_lds_bytes(int L)
 typedef __attribute__((address_space(3))) const uint32_t *lds_u32_ptr;
 typedef unsigned int lk_uintx2 __attribute__((ext_vector_type(2)));
 
-// The 256-position chunks [ch_lo, ch_hi] of one staged row for a group of N offsets.  xa[i]: this lane's LDS address
-// of the operand of offset da + i in chunk 0; ga: of the dY operand.  A chunk further is 16 entries = 32 bytes.
+// The 256-position chunks [ch_lo, ch_hi] of one staged row for a group of N offsets.  The operand of offset da + i is
+// the four entries m0 + i .. m0 + i + 3 of this lane's line.  Even i read them from the copy in which m0 is
+// dword-aligned (xe: address of entry m0 there), odd i from the other copy (xo: entry m0 + 1): the windows of a copy
+// overlap, so a chunk needs (N + 1) / 2 + 1 dwords of one copy and N / 2 + 1 of the other instead of two per
+// offset.  ga: the dY operand.  A chunk further is 16 entries = 32 bytes.
 template <int N, int GD>
-__device__ __forceinline__ void lk_dw_chunks_bf16(floatx4 (&G)[GD], const lds_u32_ptr (&xa)[GD], lds_u32_ptr ga,
+__device__ __forceinline__ void lk_dw_chunks_bf16(floatx4 (&G)[GD], lds_u32_ptr xe, lds_u32_ptr xo, lds_u32_ptr ga,
                                                   int ch_lo, int ch_hi)
 {
+    constexpr int NE = (N + 1) / 2, NO = N / 2;
 #pragma unroll 2
     for (int ch = ch_lo; ch <= ch_hi; ++ch) {
         const lk_uintx2 bw = {ga[8 * ch], ga[8 * ch + 1]};
         const shortx4 bq = __builtin_bit_cast(shortx4, bw);
+        unsigned e[NE + 1], o[NO + 1];
+#pragma unroll
+        for (int t = 0; t <= NE; ++t) e[t] = xe[8 * ch + t];
+#pragma unroll
+        for (int t = 0; t <= NO; ++t) o[t] = NO > 0 ? xo[8 * ch + t] : 0u;
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const lk_uintx2 aw = {xa[i][8 * ch], xa[i][8 * ch + 1]};
+            const lk_uintx2 aw = (i & 1) ? lk_uintx2{o[i / 2], o[i / 2 + 1]} : lk_uintx2{e[i / 2], e[i / 2 + 1]};
             G[i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, aw), bq, G[i], 0, 0, 0);
         }
     }
 }
 template <int GD, int N = GD>
-__device__ __forceinline__ void lk_dw_chunks_bf16_n(int n, floatx4 (&G)[GD], const lds_u32_ptr (&xa)[GD], lds_u32_ptr ga,
+__device__ __forceinline__ void lk_dw_chunks_bf16_n(int n, floatx4 (&G)[GD], lds_u32_ptr xe, lds_u32_ptr xo, lds_u32_ptr ga,
                                                     int ch_lo, int ch_hi)
 {
-    if (n == N) lk_dw_chunks_bf16<N, GD>(G, xa, ga, ch_lo, ch_hi);
-    else if constexpr (N > 1) lk_dw_chunks_bf16_n<GD, N - 1>(n, G, xa, ga, ch_lo, ch_hi);
+    if (n == N) lk_dw_chunks_bf16<N, GD>(G, xe, xo, ga, ch_lo, ch_hi);
+    else if constexpr (N > 1) lk_dw_chunks_bf16_n<GD, N - 1>(n, G, xe, xo, ga, ch_lo, ch_hi);
 }
 
 template <int GD>
@@ -544,9 +555,14 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const b
         __syncthreads();
         for (int rb = 0; rb < kLkRows; ++rb) {
             const int b = b0 + rb;
-            unsigned char *x0 = lkb_dw_smem + rb * ROWB, *x1 = x0 + XC, *gt = x0 + 2 * XC;
+            unsigned char *x0 = lkb_dw_smem + rb * ROWB, *gt = x0 + 2 * XC;
             const size_t row = ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
-            for (int gi = tid; gi < NB * 4; gi += 64 * kLkWaves) {
+#pragma unroll 1
+            for (int gi0 = tid; gi0 < NB * 4; gi0 += 64 * kLkWaves) {
+                // (the addresses below are recomputed from gi every time: kept as induction variables they would
+                // occupy two dozen registers for the whole kernel, next to the accumulators)
+                int gi = gi0;
+                asm volatile("" : "+v"(gi));
                 const int u = 4 * gi;
                 uint2 vx = make_uint2(0u, 0u), vg = vx;
                 if (b < g.B && u + 3 < g.L) {
@@ -556,11 +572,14 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const b
                 const int blk = u >> 4, i0 = u & 15;
                 const uint16_t ex[4] = {(uint16_t)vx.x, (uint16_t)(vx.x >> 16), (uint16_t)vx.y, (uint16_t)(vx.y >> 16)};
                 const uint16_t eg[4] = {(uint16_t)vg.x, (uint16_t)(vg.x >> 16), (uint16_t)vg.y, (uint16_t)(vg.y >> 16)};
+                unsigned char *px = x0 + i0 * XL + 2 * (MB + blk), *pg = gt + i0 * GL + 2 * blk;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    *reinterpret_cast<uint16_t *>(x0 + (i0 + e) * XL + 2 * (MB + blk)) = ex[e];
-                    *reinterpret_cast<uint16_t *>(x1 + (i0 + e) * XL + 2 * (MB + blk - 1)) = ex[e];
-                    *reinterpret_cast<uint16_t *>(gt + (i0 + e) * GL + 2 * blk) = eg[e];
+                    *reinterpret_cast<uint16_t *>(px) = ex[e];
+                    *reinterpret_cast<uint16_t *>(px + XC - 2) = ex[e];          // the copy shifted by one entry
+                    *reinterpret_cast<uint16_t *>(pg) = eg[e];
+                    px += XL;
+                    pg += GL;
                 }
             }
         }
@@ -570,17 +589,14 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const b
             if (nn[k] == 0) continue;
             for (int rb = 0; rb < kLkRows; ++rb) {
                 const unsigned char *x0 = lkb_dw_smem + rb * ROWB;
-                // operand of offset da + i: entries m0 .. m0 + 3, m0 = MB + 4 kg + da + i, from the copy of m0's parity
-                lds_u32_ptr xa[GD];
-#pragma unroll
-                for (int i = 0; i < GD; ++i) {
-                    const int m0 = MB + 4 * kg + da[k] + i;
-                    const int sh = m0 & 1;
-                    xa[i] = (lds_u32_ptr)(x0 + sh * XC + i16 * XL + 2 * (m0 - sh));
-                }
+                // operand of offset da + i: entries m0 + i .. m0 + i + 3, m0 = MB + 4 kg + da; copy s holds entry m at m - s
+                const int m0 = MB + 4 * kg + da[k];
+                const int sh = m0 & 1;                                   // (wave-uniform: the parity of da)
+                const lds_u32_ptr xe = (lds_u32_ptr)(x0 + sh * XC + i16 * XL + 2 * (m0 - sh));
+                const lds_u32_ptr xo = (lds_u32_ptr)(x0 + (1 - sh) * XC + i16 * XL + 2 * (m0 + sh));
                 const lds_u32_ptr ga = (lds_u32_ptr)(x0 + 2 * XC + i16 * GL + 8 * kg);
-                if (k == 0) lk_dw_chunks_bf16_n<GD>(nn[0], G0, xa, ga, ch_lo[0], ch_hi[0]);
-                else lk_dw_chunks_bf16_n<GD>(nn[1], G1, xa, ga, ch_lo[1], ch_hi[1]);
+                if (k == 0) lk_dw_chunks_bf16_n<GD>(nn[0], G0, xe, xo, ga, ch_lo[0], ch_hi[0]);
+                else lk_dw_chunks_bf16_n<GD>(nn[1], G1, xe, xo, ga, ch_lo[1], ch_hi[1]);
             }
         }
     }
