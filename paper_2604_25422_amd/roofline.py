@@ -61,6 +61,7 @@ MEASURED_TRAFFIC_BYTES = {
     (2, "fwd"): 525294 * 1024, (2, "dx"): 525294 * 1024, (2, "dw_partial"): 539684 * 1024, (2, "bwd_fused"): 831299 * 1024,
     (3, "fwd"): 163881 * 1024, (3, "dx"): 163881 * 1024, (3, "dw_partial"): 271351 * 1024,
     (4, "fwd"): 393355 * 1024, (4, "dx"): 393355 * 1024, (4, "dw_partial"): 396139 * 1024, (4, "bwd_fused"): 598836 * 1024,
+    (8, "fwd"): 69698 * 1024, (8, "dx"): 69698 * 1024, (8, "dw_partial"): 188048 * 1024,
     (7, "fwd"): 393537 * 1024, (7, "dx"): 393537 * 1024, (7, "dw_partial"): 394072 * 1024,
     (6, "fwd"): 262396 * 1024, (6, "dx"): 262396 * 1024, (6, "dw_partial"): 273273 * 1024,
     (5, "fwd"): 786611 * 1024, (5, "dx"): 786611 * 1024, (5, "dw_partial"): 786934 * 1024, (5, "bwd_fused"): 1234118 * 1024,

@@ -56,6 +56,8 @@ WORKLOADS = [
     Workload("midK_B32_C256_L4096_K128_causal_f32", 6, 32, 256, 4096, 128, 127, "f32", "normal_var_1_over_K"),
     # ... and the same filter length on bf16 storage at the bf16 geometry
     Workload("midK_B128_C768_L1024_K128_causal_bf16", 7, 128, 768, 1024, 128, 127, "bf16", "normal_var_1_over_K"),
+    # ... and the long-filter configuration on bf16 storage
+    Workload("longK_B8_C256_L8192_K8192_causal_bf16", 8, 8, 256, 8192, 8192, 8191, "bf16", "decay_cos"),
 ]
 HEADLINE = WORKLOADS[1]
 

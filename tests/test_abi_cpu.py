@@ -149,7 +149,7 @@ def test_binding_refuses_cpu_tensors():
 def test_workloads_are_seeded_and_shaped():
     import torch
     from paper_2604_25422_amd import workloads
-    assert len(workloads.WORKLOADS) == 8 and workloads.HEADLINE.K == 64
+    assert len(workloads.WORKLOADS) == 9 and workloads.HEADLINE.K == 64
     wl = workloads.WORKLOADS[0]
     a = workloads.make_inputs(wl); b = workloads.make_inputs(wl)
     for k in ("x", "w", "dy"):

@@ -88,6 +88,11 @@ def test_mid_filter_full_size(oracle_mod):
     run_full_size(oracle_mod, workloads.WORKLOADS[6], 512, 16)
 
 
+def test_long_filter_bf16_full_size(oracle_mod):
+    # the long-filter configuration on bf16 storage: the bf16 matrix-instruction long-filter kernels
+    run_full_size(oracle_mod, workloads.WORKLOADS[8], 48, 6)
+
+
 def test_mid_filter_bf16_full_size(oracle_mod):
     # the same 128 taps on bf16 storage: nine block offsets on the bf16 matrix-instruction kernels
     run_full_size(oracle_mod, workloads.WORKLOADS[7], 512, 16)
