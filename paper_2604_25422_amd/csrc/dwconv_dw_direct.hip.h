@@ -98,16 +98,21 @@ constexpr int dw_direct_wave_floats(int ND)
     const int stage = 5 * 256 + kSegLen, gf = ND * 256, diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
     return stage > gf ? (stage > diag ? stage : diag) : (gf > diag ? gf : diag);
 }
-constexpr size_t dw_direct_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_direct_wave_floats(ND) + 16 * ND) * sizeof(float); }
+// Taps a wave hands to the block-level sum: all of them fit 16 ND when the offsets cover the whole filter; a launch over
+// part of the offsets (nine and more, see the j0 / j1 arguments of the kernel) owns up to 16 ND + 15 taps.
+constexpr int dw_direct_row_floats(int ND) { return 16 * ND + (ND >= 9 ? 16 : 0); }
+constexpr size_t dw_direct_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_direct_wave_floats(ND) + dw_direct_row_floats(ND)) * sizeof(float); }
 
 // W waves per block.  dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (one
 // block per channel, gridDim.y == 1) they are the weight gradient itself and go to dw_out.
 // ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap); B is then 1 and segs_per_row the
 // number of segments of the virtual row.
+// [j0, j1): the taps this launch owns, at most dw_direct_row_floats(ND) of them (0, K unless the block offsets of the
+// filter are split over two launches); the other taps of its slices are written as zeros.
 template <int ND, int W, bool ROWS>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_kernel(
     const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, const RowsMap rm)
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, const RowsMap rm, int j0, int j1)
 {
     constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
     constexpr int NGX = XW / 4;                    // its 16-byte granules: 4 full loads and a tail
@@ -120,7 +125,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     static_assert(WREG >= STAGE && WREG >= GF, "the staged windows fit the wave's region");
     extern __shared__ __align__(16) float dyn_lds[];
     float (*s_mem)[WREG] = reinterpret_cast<float (*)[WREG]>(dyn_lds);
-    float (*s_dw)[16 * ND] = reinterpret_cast<float (*)[16 * ND]>(dyn_lds + W * WREG);
+    constexpr int ROWF = dw_direct_row_floats(ND);
+    float (*s_dw)[ROWF] = reinterpret_cast<float (*)[ROWF]>(dyn_lds + W * WREG);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -169,7 +175,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
                 const int t0 = pseg * kSegLen;
                 const int u0 = 4 * (t0 + 16 * dmin);
                 x_shift = u0 < 0 ? u0 : 0;
-                rx = row_tail_resource(x + row, L, u0 > 0 ? u0 : 0);
+                // (a window that starts past the end of the row - possible when dmin > 0, the second of two passes
+                // over the block offsets - gets an empty resource: every load returns zero)
+                rx = row_tail_resource(x + row, L, u0 > 0 ? min(u0, 4 * L) : 0);
                 rg = row_tail_resource(dy + row, L, 4 * t0);
             }
         } else {
@@ -261,12 +269,14 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
 
     // ---- per-wave diagonal sums, then the waves of the block in wave order
     static_assert(WREG >= ((16 * ND + 15) * 17 + 3) / 4 * 4, "diagonal image fits the wave's region");
-    dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, K, pad, dmin);
+    dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, j0, j1, pad, dmin);
     __syncthreads();
     for (int j = tid; j < K; j += 64 * W) {
         float sum = 0.f;
+        if (j >= j0 && j < j1) {
 #pragma unroll
-        for (int w = 0; w < W; ++w) sum += s_dw[w][j];
+            for (int w = 0; w < W; ++w) sum += s_dw[w][j - j0];
+        }
         if (dw_out) dw_out[(size_t)c * (size_t)K + (size_t)j] = sum;
         else part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
     }

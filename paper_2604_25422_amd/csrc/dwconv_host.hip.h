@@ -45,12 +45,21 @@ constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
 constexpr int kMfmaMaxNDWide = 10;     // fp32 on long rows, K up to 130: whole-channel workgroups for dW still possible
 constexpr int kMfmaMaxNDDw = 16;       // fp32 on long rows, K up to 226: four-wave dW workgroups, two correlate waves per SIMD
+constexpr int kMfmaMaxNDDw2 = 32;      // fp32 dW in two passes over the block offsets (K up to 482), each into its own slices
 inline int mfma_max_nd(int /* either storage type */) { return kMfmaMaxNDDw; }                      // fwd, dX
 // fewest block offsets the long-filter forward / input-gradient kernel takes (from there to sixteen: whichever of
 // the two kernels wastes less on the row length)
 inline int longk_corr_min_nd(int dtype) { return (dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) + 1; }
 // dW stage 1 (bf16 above six offsets: rows of whole 16-byte granules only)
-inline int mfma_max_nd_dw(const Shape &s) { return (s.dtype == DWCONV_F32 || (s.L % 8) == 0) ? kMfmaMaxNDDw : kMfmaMaxND; }
+inline int mfma_max_nd_dw(const Shape &s)
+{
+    if (s.dtype == DWCONV_F32) {
+        // two passes only where rows fill their 1024-position segments to three quarters (else the long-filter kernel)
+        const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
+        return 4ll * s.L >= 3 * padded ? kMfmaMaxNDDw2 : kMfmaMaxNDDw;
+    }
+    return (s.L % 8) == 0 ? kMfmaMaxNDDw : kMfmaMaxND;
+}
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 
@@ -136,7 +145,8 @@ struct DwPlan {
     bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
     int lk_wgs, lk_gd;     // its workgroups per channel, largest group of offsets (accumulators per group)
     std::shared_ptr<const dwconv::LongKDwTable> lk_table;   // which offsets every wave slot owns
-    int S;                 // partial slices per coefficient
+    int S;                 // partial slices per coefficient (all passes together)
+    int passes;            // launches of the stage-1 kernel, each over part of the block offsets into S / passes slices
     RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
     int wpb;               // waves per block of the matrix-core stage-1 kernels
     int dw_nc;             // short rows, sixteen-row units: channels per block of the stage-1 kernel (1 or 2)

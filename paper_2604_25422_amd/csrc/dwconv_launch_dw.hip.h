@@ -64,13 +64,15 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
             hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                                static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                               static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
+                               static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map, 0,
+                               s.K);
         } else {
             auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
             hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                                static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                               static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
+                               static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map,
+                               0, s.K);
         }
     } else if (p.rows.on) {
         // bf16 short rows (longer than 64 positions): the virtual row of a channel, widened to fp32 through registers

@@ -15,9 +15,15 @@ int launch_dw_partial_wide_ndw(const void *x, const void *dy, float *part, void 
     } else {
         auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
         if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+        // the taps this launch owns: those its ND offsets can reach (all K of them when they cover the filter)
+        int j0 = 16 * dmin + s.pad - 15, j1 = 16 * (dmin + ND - 1) + s.pad + 16;
+        j0 = j0 < 0 ? 0 : (j0 > s.K ? s.K : j0);
+        j1 = j1 < j0 ? j0 : (j1 > s.K ? s.K : j1);
+        if (j1 - j0 > dwconv::dw_direct_row_floats(ND)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)(p.S / p.passes)), dim3(64 * W), lds, st,
                            static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map);
+                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map, j0,
+                           j1);
         return launch_status();
     }
 }
@@ -43,6 +49,18 @@ int launch_dw_partial_wide_nd(const void *x, const void *dy, float *part, void *
 int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
                                int dmin, int nd, hipStream_t st)
 {
+    if (nd > kMfmaMaxNDDw) {
+        // two passes: offsets dmin .. dmin + na - 1 into the first half of the slices, the rest into the second half
+        if (p.passes != 2 || nd > kMfmaMaxNDDw2 || dw_out) return -1;
+        // (nine offsets at least per launch: from there the kernel's tap buffer holds the 16 ND + 15 taps a part of
+        // the offsets owns; offsets past the last one of the filter reach no tap below K)
+        const int na = (nd + 1) / 2;
+        const int nb = nd - na < 9 ? 9 : nd - na;
+        const int rc = launch_dw_partial_wide_f32(x, dy, part, nullptr, s, p, dmin, na, st);
+        if (rc != DWCONV_OK) return rc;
+        float *part_b = part + (size_t)(p.S / 2) * (size_t)s.C * (size_t)s.K;
+        return launch_dw_partial_wide_f32(x, dy, part_b, nullptr, s, p, dmin + na, nb, st);
+    }
     switch (nd) {
     case 7: return launch_dw_partial_wide_nd<7>(x, dy, part, dw_out, s, p, dmin, st);
     case 8: return launch_dw_partial_wide_nd<8>(x, dy, part, dw_out, s, p, dmin, st);

@@ -523,9 +523,10 @@ __device__ __forceinline__ float4 mask4(float4 v, int u, int L)
 // row: cell (jl, q) is written by at most one (d, q'), the cells nothing maps to stay zero, and lane j adds the
 // 16 cells of its row in q order (independent reads, conflict-free at stride 17).  sw: the wave's private LDS
 // region, at least (16 ND + 15) * 17 floats, 16-byte aligned.
+// The taps [j0, j1) only, tap j into dw_wave[j - j0] (a launch over part of the block offsets owns part of the taps).
 template <int ND>
-__device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], float *sw, float *dw_wave, int lane, int K,
-                                                      int pad, int dmin)
+__device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], float *sw, float *dw_wave, int lane, int j0,
+                                                      int j1, int pad, int dmin)
 {
     constexpr int ROWS = 16 * ND + 15, RS = 17;
     constexpr int N4 = (ROWS * RS + 3) / 4;
@@ -537,7 +538,7 @@ __device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], fl
 #pragma unroll
         for (int v = 0; v < 4; ++v) sw[(16 * d + 4 * k4 + v - q + 15) * RS + q] = G[d][v];
     wave_lds_fence();
-    for (int j = lane; j < K; j += 64) {
+    for (int j = j0 + lane; j < j1; j += 64) {
         const int jl = j - pad - 16 * dmin + 15;
         float sum = 0.f;
         if (jl >= 0 && jl < ROWS) {
@@ -547,8 +548,15 @@ __device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], fl
 #pragma unroll
             for (int i = 0; i < 16; ++i) sum += t[i];
         }
-        dw_wave[j] = sum;
+        dw_wave[j - j0] = sum;
     }
+}
+// ... all K taps
+template <int ND>
+__device__ __forceinline__ void dw_wave_diagonal_sums(const floatx4 (&G)[ND], float *sw, float *dw_wave, int lane, int K,
+                                                      int pad, int dmin)
+{
+    dw_wave_diagonal_sums<ND>(G, sw, dw_wave, lane, 0, K, pad, dmin);
 }
 
 // Stage 1 of the weight gradient on the matrix cores.

@@ -39,6 +39,10 @@ SMALL = [
     (3, 4, 2060, 160, 159), (2, 3, 1028, 226, 100), (5, 2, 3072, 200, 0), (2, 2, 1100, 180, 90),
     (7, 2, 1024, 161, 80), (3, 3, 1024, 176, 175), (2, 5, 800, 190, 95), (4, 2, 3000, 215, 214), (2, 3, 2048, 226, 225),
     (2, 2, 4092, 226, 0), (70, 32, 1024, 170, 169),
+    # seventeen to thirty-two block offsets: the weight gradient in two passes over the offsets (second pass with
+    # windows that start past the end of the row when pad is small), fwd/dX on the long-filter kernel
+    (3, 4, 1024, 256, 255), (2, 3, 2048, 300, 150), (2, 2, 3000, 482, 481), (5, 2, 1024, 400, 0), (4, 2, 4092, 350, 100),
+    (70, 32, 1024, 260, 259), (1, 1, 800, 480, 0),
     # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
     (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
