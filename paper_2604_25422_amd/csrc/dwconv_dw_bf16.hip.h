@@ -28,7 +28,9 @@ constexpr int dw_bf16_wave_floats(int ND)
     const int stage = (dw_bf16_win_x(ND) + kSegLen) / 2, diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
     return stage > diag ? stage : diag;
 }
-constexpr size_t dw_bf16_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_bf16_wave_floats(ND) + 16 * ND) * sizeof(float); }
+// taps a wave hands to the block-level sum (see dw_direct_row_floats: a launch over part of the offsets owns up to 16 ND + 15)
+constexpr int dw_bf16_row_floats(int ND) { return 16 * ND + (ND >= 9 ? 16 : 0); }
+constexpr size_t dw_bf16_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(dw_bf16_wave_floats(ND) + dw_bf16_row_floats(ND)) * sizeof(float); }
 
 // position of logical 16-block nb inside the staged windows
 __host__ __device__ constexpr int bf16_block_pos(int nb) { return (nb & ~3) | ((nb & 3) ^ ((nb >> 2) & 3)); }
@@ -36,8 +38,10 @@ __host__ __device__ constexpr int bf16_block_pos(int nb) { return (nb & ~3) | ((
 template <int ND, int W>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ part, bf16_t *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int segs_per_row)
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, int j0, int j1)
 {
+    // [j0, j1): the taps this launch owns (0, K unless the block offsets of the filter are split over two launches);
+    // the other taps of its slices are written as zeros
     static_assert(ND >= 2 && 16 * ND <= 256, "the x tail is one or two 128-element loads");
     constexpr int NT = dw_bf16_tail_loads(ND);     // tail loads per segment
     constexpr int NLOADS = 4 + NT;                 // loads per segment
@@ -46,7 +50,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     constexpr int WREG = dw_bf16_wave_floats(ND);
     extern __shared__ __align__(16) float dyn_lds[];
     float (*s_mem)[WREG] = reinterpret_cast<float (*)[WREG]>(dyn_lds);
-    float (*s_dw)[16 * ND] = reinterpret_cast<float (*)[16 * ND]>(dyn_lds + W * WREG);
+    constexpr int ROWF = dw_bf16_row_floats(ND);
+    float (*s_dw)[ROWF] = reinterpret_cast<float (*)[ROWF]>(dyn_lds + W * WREG);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -100,7 +105,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
             const int t0 = pseg * kSegLen;
             const int u0 = 2 * (t0 + 16 * dmin);
             x_shift = u0 < 0 ? u0 : 0;
-            rx = row_tail_resource(x + row, L, u0 > 0 ? u0 : 0);
+            // (a window that starts past the end of the row - the second of two launches - gets an empty resource)
+            rx = row_tail_resource(x + row, L, u0 > 0 ? min(u0, 2 * L) : 0);
             rg = row_tail_resource(dy + row, L, 2 * t0);
         } else {
             x_shift = 0;
@@ -161,12 +167,14 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     wave_lds_fence();
 
     // ---- per-wave diagonal sums, then the waves of the block in wave order
-    dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, K, pad, dmin);
+    dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, j0, j1, pad, dmin);
     __syncthreads();
     for (int j = tid; j < K; j += 64 * W) {
         float sum = 0.f;
+        if (j >= j0 && j < j1) {
 #pragma unroll
-        for (int w = 0; w < W; ++w) sum += s_dw[w][j];
+            for (int w = 0; w < W; ++w) sum += s_dw[w][j - j0];
+        }
         if (dw_out) st_elem(dw_out + (size_t)c * (size_t)K + (size_t)j, sum);
         else part[((size_t)blockIdx.y * (size_t)C + (size_t)c) * (size_t)K + (size_t)j] = sum;
     }

@@ -45,7 +45,7 @@ constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
 constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
 constexpr int kMfmaMaxNDWide = 10;     // fp32 on long rows, K up to 130: whole-channel workgroups for dW still possible
 constexpr int kMfmaMaxNDDw = 16;       // fp32 on long rows, K up to 226: four-wave dW workgroups, two correlate waves per SIMD
-constexpr int kMfmaMaxNDDw2 = 32;      // fp32 dW in two passes over the block offsets (K up to 482), each into its own slices
+constexpr int kMfmaMaxNDDw2 = 32;      // dW in two passes over the block offsets (K up to 482), each into its own slices
 inline int mfma_max_nd(int /* either storage type */) { return kMfmaMaxNDDw; }                      // fwd, dX
 // fewest block offsets the long-filter forward / input-gradient kernel takes (from there to sixteen: whichever of
 // the two kernels wastes less on the row length)
@@ -53,12 +53,12 @@ inline int longk_corr_min_nd(int dtype) { return (dtype == DWCONV_F32 ? kMfmaMax
 // dW stage 1 (bf16 above six offsets: rows of whole 16-byte granules only)
 inline int mfma_max_nd_dw(const Shape &s)
 {
-    if (s.dtype == DWCONV_F32) {
+    if (s.dtype == DWCONV_F32 || (s.L % 8) == 0) {
         // two passes only where rows fill their 1024-position segments to three quarters (else the long-filter kernel)
         const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
         return 4ll * s.L >= 3 * padded ? kMfmaMaxNDDw2 : kMfmaMaxNDDw;
     }
-    return (s.L % 8) == 0 ? kMfmaMaxNDDw : kMfmaMaxND;
+    return kMfmaMaxND;
 }
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads

@@ -15,9 +15,14 @@ int launch_dw_partial_wide_bf16_nd(const void *x, const void *dy, float *part, v
     if (p.rows.on || p.wpb != W) return -1;
     auto kernel = dwconv::dw_partial_bf16_kernel<ND, W>;
     if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const bf16_t *>(x),
-                       static_cast<const bf16_t *>(dy), part, static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad,
-                       dmin, p.tiles_per_row);
+    // the taps this launch owns: those its ND offsets can reach (all K of them when they cover the filter)
+    int j0 = 16 * dmin + s.pad - 15, j1 = 16 * (dmin + ND - 1) + s.pad + 16;
+    j0 = j0 < 0 ? 0 : (j0 > s.K ? s.K : j0);
+    j1 = j1 < j0 ? j0 : (j1 > s.K ? s.K : j1);
+    if (j1 - j0 > dwconv::dw_bf16_row_floats(ND)) return -1;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)(p.S / p.passes)), dim3(64 * W), lds, st,
+                       static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part, static_cast<bf16_t *>(dw_out),
+                       s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, j0, j1);
     return launch_status();
 }
 
@@ -25,6 +30,17 @@ int launch_dw_partial_wide_bf16(const void *x, const void *dy, float *part, void
                                 int dmin, int nd, hipStream_t st)
 {
     if ((s.L % 8) != 0 || !aligned_to(x, 16) || !aligned_to(dy, 16)) return -1;
+    if (nd > kMfmaMaxNDDw) {
+        // two launches over halves of the offsets, each into its own half of the slices (nine offsets at least per
+        // launch: from there the kernel's tap buffer holds the 16 ND + 15 taps a part of the offsets owns)
+        if (p.passes != 2 || nd > kMfmaMaxNDDw2 || dw_out) return -1;
+        const int na = (nd + 1) / 2;
+        const int nb = nd - na < 9 ? 9 : nd - na;
+        const int rc = launch_dw_partial_wide_bf16(x, dy, part, nullptr, s, p, dmin, na, st);
+        if (rc != DWCONV_OK) return rc;
+        float *part_b = part + (size_t)(p.S / 2) * (size_t)s.C * (size_t)s.K;
+        return launch_dw_partial_wide_bf16(x, dy, part_b, nullptr, s, p, dmin + na, nb, st);
+    }
     switch (nd) {
     case 7: return launch_dw_partial_wide_bf16_nd<7>(x, dy, part, dw_out, s, p, dmin, st);
     case 8: return launch_dw_partial_wide_bf16_nd<8>(x, dy, part, dw_out, s, p, dmin, st);

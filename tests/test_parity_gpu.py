@@ -105,7 +105,10 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
                                                    # batches, every pad class, filters longer than the row, ragged rows
                                                    (2, 3, 512, 512, 511), (3, 1, 640, 640, 320), (1, 2, 4096, 4096, 4095),
                                                    (2, 1, 1000, 2500, 1200), (1, 1, 8192, 300, 299), (3, 2, 1024, 1024, 0),
-                                                   (5, 2, 4100, 700, 350), (3, 3, 260, 513, 17), (1, 1, 8192, 8192, 8191)])
+                                                   (5, 2, 4100, 700, 350), (3, 3, 260, 513, 17), (1, 1, 8192, 8192, 8191),
+                                                   # bf16 weight gradient in two passes over seventeen to thirty-two offsets
+                                                   (3, 4, 1024, 256, 255), (2, 3, 2048, 300, 150), (2, 2, 3000, 482, 481),
+                                                   (5, 2, 1024, 400, 0), (70, 32, 1024, 260, 259), (1, 1, 8192, 300, 299)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
