@@ -226,22 +226,32 @@ int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, 
     const int NB = (s.L + 15) / 16;
     if (NB > dwconv::kLkMaxBlocks) return -1;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
-    const long long row_groups = ((long long)s.B + dwconv::kLkRows - 1) / dwconv::kLkRows;
-    if (row_groups > 65535) return -1;
     dwconv::LongKGeom g;
     g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K;
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin; g.dmax = dmax;
     g.NB = NB; g.NT = (NB + 15) / 16;
+    // rows per workgroup: about 32 (row pair, tile) items for its 16 waves, no more than the batch, and within half of
+    // the LDS of a compute unit, so that two workgroups share it and one stages its rows while the other computes
+    // (sixteen rows of 1024 positions in one resident workgroup measured slower than two rows in each of two)
+    auto lds_for = [&](int R) -> size_t {
+        return sizeof(T) == 2 ? dwconv::longk_corr_bf16_lds_bytes(s.K, NB, R) : dwconv::longk_corr_lds_bytes(s.K, NB, R);
+    };
+    int R = 2 * ((2 * dwconv::kLkWaves + g.NT - 1) / g.NT);
+    if (R > 2 * ((s.B + 1) / 2)) R = 2 * ((s.B + 1) / 2);
+    while (R > 2 && lds_for(R) > kMaxLdsBytes / 2) R -= 2;
+    g.R = R;
+    const long long row_groups = ((long long)s.B + R - 1) / R;
+    if (row_groups > 65535) return -1;
     if constexpr (sizeof(T) == 2) {
         // bf16 storage: raw rows and four shifted copies of the filter in LDS, bf16 matrix instruction
-        const size_t lds = dwconv::longk_corr_bf16_lds_bytes(s.K, NB);
+        const size_t lds = lds_for(R);
         if (lds > kMaxLdsBytes) return -1;
         if (!allow_large_lds(dwconv::corr_longk_bf16_kernel<>)) return -1;
         hipLaunchKernelGGL(dwconv::corr_longk_bf16_kernel<>, dim3((unsigned)s.C, (unsigned)row_groups),
                            dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const bf16_t *>(in),
                            static_cast<const bf16_t *>(f), static_cast<bf16_t *>(out), g);
     } else {
-        const size_t lds = dwconv::longk_corr_lds_bytes(s.K, NB);
+        const size_t lds = lds_for(R);
         if (lds > kMaxLdsBytes) return -1;
         if (!allow_large_lds(dwconv::corr_longk_kernel<T>)) return -1;
         hipLaunchKernelGGL((dwconv::corr_longk_kernel<T>), dim3((unsigned)s.C, (unsigned)row_groups),
