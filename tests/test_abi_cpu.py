@@ -131,6 +131,14 @@ def test_single_pass_query(lib):
     assert f(8, 256, 8192, 8192, 8191, 0) == 0       # long filter: two zero-filled slices
     assert f(1, 256, 1024, 16, 15, 0) == 1           # a single segment per channel: one kernel as well
     assert f(32, 256, 4098, 64, 63, 0) == 0          # row length not a multiple of 4
+    # seventeen to thirty-two block offsets: two launches over halves of the offsets, each into its own slices,
+    # so an even number of slices and never one kernel - also for small problems, in either storage type
+    S226, S256 = lib.dwconv_bwd_weight_slices(32, 256, 4096, 226, 225, 0), lib.dwconv_bwd_weight_slices(32, 256, 4096, 256, 255, 0)
+    assert S256 == 2 * S226 and f(32, 256, 4096, 256, 255, 0) == 0
+    assert f(2, 4, 1024, 300, 150, 0) == 0 and lib.dwconv_bwd_weight_slices(2, 4, 1024, 300, 150, 0) == 2
+    assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 256, 255, 1) == S256
+    # ... but not for rows that fill less than three quarters of their segments (long-filter kernel: two slices)
+    assert lib.dwconv_bwd_weight_slices(64, 256, 512, 300, 150, 0) == 2 and f(64, 256, 512, 300, 150, 0) == 0
     assert f(0, 256, 4096, 64, 63, 0) == 0           # bad shape
 
 
