@@ -409,7 +409,11 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
             const size_t row = ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
             for (int i = tid; i < 2 * kLkDwMargin; i += 64 * kLkWaves)
                 xrow[i < kLkDwMargin ? i : g.L + i] = 0.f;
-            for (int gi = tid; gi < g.NCH * 16; gi += 64 * kLkWaves) {
+            for (int gi0 = tid; gi0 < g.NCH * 16; gi0 += 64 * kLkWaves) {
+                // (addresses recomputed from gi every trip rather than kept as induction variables across the whole
+                // kernel, next to the accumulators)
+                int gi = gi0;
+                asm volatile("" : "+v"(gi));
                 const int u = 4 * gi;
                 float4 vx = make_float4(0.f, 0.f, 0.f, 0.f), vg = vx;
                 if (b < g.B && u + 3 < g.L) {
