@@ -43,6 +43,8 @@ SMALL = [
     # windows that start past the end of the row when pad is small), fwd/dX on the long-filter kernel
     (3, 4, 1024, 256, 255), (2, 3, 2048, 300, 150), (2, 2, 3000, 482, 481), (5, 2, 1024, 400, 0), (4, 2, 4092, 350, 100),
     (70, 32, 1024, 260, 259), (1, 1, 800, 480, 0),
+    # long filters on short rows: many rows per workgroup, batches that are not whole groups of them
+    (21, 2, 1024, 600, 599), (11, 2, 2048, 900, 450), (37, 1, 512, 700, 0),
     # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
     (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
@@ -108,7 +110,10 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
                                                    (5, 2, 4100, 700, 350), (3, 3, 260, 513, 17), (1, 1, 8192, 8192, 8191),
                                                    # bf16 weight gradient in two passes over seventeen to thirty-two offsets
                                                    (3, 4, 1024, 256, 255), (2, 3, 2048, 300, 150), (2, 2, 3000, 482, 481),
-                                                   (5, 2, 1024, 400, 0), (70, 32, 1024, 260, 259), (1, 1, 8192, 300, 299)])
+                                                   (5, 2, 1024, 400, 0), (70, 32, 1024, 260, 259), (1, 1, 8192, 300, 299),
+                                                   # long filters on short rows: many rows per workgroup, batches that
+                                                   # are not whole groups of them
+                                                   (21, 2, 1024, 600, 599), (11, 2, 2048, 900, 450), (37, 1, 512, 700, 0)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
