@@ -204,12 +204,13 @@ DwPlan plan_dw(const Shape &s)
     p.segs_per_wave = (int)spw;
     p.items_per_slice = (int)per;
     p.S = (int)((items + per - 1) / per);
-    // fp32, seventeen to thirty-two block offsets: two launches of the register-resident kernel, each over half of
+    // seventeen to thirty-two block offsets: two launches of the register-resident kernel, each over half of
     // the offsets and into its own slices (a launch writes zeros to the taps of the other half); stage 2 adds them
-    p.passes = (mfma_shape && nd > kMfmaMaxNDDw) ? 2 : 1;
-    if (p.passes == 2) {
+    // (bf16: up to four launches over quarters of up to sixty-four offsets)
+    p.passes = (mfma_shape && nd > kMfmaMaxNDDw) ? (nd + kMfmaMaxNDDw - 1) / kMfmaMaxNDDw : 1;
+    if (p.passes > 1) {
         p.single = false;
-        p.S *= 2;
+        p.S *= p.passes;
     }
     // the fused backward kernel of these shapes works on one channel per block: its own slice count
     p.S_fused = p.S;

@@ -113,7 +113,10 @@ def test_small_shapes_f32(oracle_mod, B, C, L, K, p):
                                                    (5, 2, 1024, 400, 0), (70, 32, 1024, 260, 259), (1, 1, 8192, 300, 299),
                                                    # long filters on short rows: many rows per workgroup, batches that
                                                    # are not whole groups of them
-                                                   (21, 2, 1024, 600, 599), (11, 2, 2048, 900, 450), (37, 1, 512, 700, 0)])
+                                                   (21, 2, 1024, 600, 599), (11, 2, 2048, 900, 450), (37, 1, 512, 700, 0),
+                                                   # bf16 weight gradient in three and four passes (33 to 64 offsets)
+                                                   (2, 3, 2048, 700, 350), (3, 2, 1024, 994, 993), (2, 2, 3000, 513, 0),
+                                                   (40, 8, 1024, 530, 529)])
 def test_small_shapes_bf16(oracle_mod, B, C, L, K, p):
     print(f"case bf16 B{B} C{C} L{L} K{K} p{p}", flush=True)
     check_case(oracle_mod, B, C, L, K, p, "bf16", seed=B + C + L + K)
