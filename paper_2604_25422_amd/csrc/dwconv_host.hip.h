@@ -46,6 +46,7 @@ constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
 constexpr int kMfmaMaxNDWide = 10;     // fp32 on long rows, K up to 130: whole-channel workgroups for dW still possible
 constexpr int kMfmaMaxNDDw = 16;       // fp32 on long rows, K up to 226: four-wave dW workgroups, two correlate waves per SIMD
 constexpr int kMfmaMaxNDDw2 = 32;      // dW in two passes over the block offsets (K up to 482), each into its own slices
+constexpr int kMfmaMaxNDDw3 = 48;      // fp32 dW in up to three passes (K up to 738)
 constexpr int kMfmaMaxNDDw4 = 64;      // bf16 dW in up to four passes (K up to 994): a pass is bound by memory there
 inline int mfma_max_nd(int /* either storage type */) { return kMfmaMaxNDDw; }                      // fwd, dX
 // fewest block offsets the long-filter forward / input-gradient kernel takes (from there to sixteen: whichever of
@@ -57,7 +58,7 @@ inline int mfma_max_nd_dw(const Shape &s)
     if (s.dtype == DWCONV_F32 || (s.L % 8) == 0) {
         // two passes only where rows fill their 1024-position segments to three quarters (else the long-filter kernel)
         const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
-        return 4ll * s.L >= 3 * padded ? (s.dtype == DWCONV_F32 ? kMfmaMaxNDDw2 : kMfmaMaxNDDw4) : kMfmaMaxNDDw;
+        return 4ll * s.L >= 3 * padded ? (s.dtype == DWCONV_F32 ? kMfmaMaxNDDw3 : kMfmaMaxNDDw4) : kMfmaMaxNDDw;
     }
     return kMfmaMaxND;
 }

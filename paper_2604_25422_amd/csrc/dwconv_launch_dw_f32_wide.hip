@@ -50,16 +50,19 @@ int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void 
                                int dmin, int nd, hipStream_t st)
 {
     if (nd > kMfmaMaxNDDw) {
-        // two passes: offsets dmin .. dmin + na - 1 into the first half of the slices, the rest into the second half
-        if (p.passes != 2 || nd > kMfmaMaxNDDw2 || dw_out) return -1;
-        // (nine offsets at least per launch: from there the kernel's tap buffer holds the 16 ND + 15 taps a part of
-        // the offsets owns; offsets past the last one of the filter reach no tap below K)
-        const int na = (nd + 1) / 2;
-        const int nb = nd - na < 9 ? 9 : nd - na;
-        const int rc = launch_dw_partial_wide_f32(x, dy, part, nullptr, s, p, dmin, na, st);
-        if (rc != DWCONV_OK) return rc;
-        float *part_b = part + (size_t)(p.S / 2) * (size_t)s.C * (size_t)s.K;
-        return launch_dw_partial_wide_f32(x, dy, part_b, nullptr, s, p, dmin + na, nb, st);
+        // p.passes launches over equal parts of the offsets, each into its own share of the slices (nine offsets at
+        // least per launch: from there the kernel's tap buffer holds the 16 ND + 15 taps a part of the offsets owns;
+        // offsets past the last one of the filter reach no tap below K)
+        if (p.passes < 2 || p.passes != (nd + kMfmaMaxNDDw - 1) / kMfmaMaxNDDw || nd > kMfmaMaxNDDw3 || dw_out) return -1;
+        const int per = (nd + p.passes - 1) / p.passes;
+        const size_t pass_floats = (size_t)(p.S / p.passes) * (size_t)s.C * (size_t)s.K;
+        for (int i = 0; i < p.passes; ++i) {
+            int n = nd - i * per < per ? nd - i * per : per;
+            if (n < 9) n = 9;
+            const int rc = launch_dw_partial_wide_f32(x, dy, part + (size_t)i * pass_floats, nullptr, s, p, dmin + i * per, n, st);
+            if (rc != DWCONV_OK) return rc;
+        }
+        return DWCONV_OK;
     }
     switch (nd) {
     case 7: return launch_dw_partial_wide_nd<7>(x, dy, part, dw_out, s, p, dmin, st);

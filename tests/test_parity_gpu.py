@@ -45,6 +45,8 @@ SMALL = [
     (70, 32, 1024, 260, 259), (1, 1, 800, 480, 0),
     # long filters on short rows: many rows per workgroup, batches that are not whole groups of them
     (21, 2, 1024, 600, 599), (11, 2, 2048, 900, 450), (37, 1, 512, 700, 0),
+    # thirty-three to forty-eight block offsets: the weight gradient in three passes
+    (2, 3, 2048, 700, 350), (2, 2, 3000, 513, 0), (40, 8, 1024, 530, 529), (3, 2, 1024, 738, 737),
     # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
     (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
