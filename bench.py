@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=1, help="index into workloads.WORKLOADS (1 = headline)")
+    ap.add_argument("--shape", nargs=6, metavar=("B", "C", "L", "K", "PAD", "DTYPE"), default=None,
+                    help="instead of a listed workload: any shape, e.g. --shape 32 256 4096 256 255 f32 "
+                         "(filters N(0, 1/K); no stored traffic figure; combine with --no-cpu-baseline for large K)")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-roof", action="store_true",
@@ -122,6 +125,14 @@ def main():
         sys.exit(1)
     binding.lib()   # fail loudly if the HIP library is missing
     wl = workloads.WORKLOADS[args.workload]
+    if args.shape is not None:
+        B_, C_, L_, K_, P_ = (int(v) for v in args.shape[:5])
+        dt_ = args.shape[5]
+        if dt_ not in ("f32", "bf16") or min(B_, C_, L_, K_) < 1 or not 0 <= P_ < K_:
+            print("bench.py: --shape B C L K PAD DTYPE with 0 <= PAD < K and DTYPE f32 or bf16", file=sys.stderr)
+            sys.exit(2)
+        wl = workloads.Workload(f"shape_B{B_}_C{C_}_L{L_}_K{K_}_pad{P_}_{dt_}", 99, B_, C_, L_, K_, P_, dt_, "normal_var_1_over_K")
+        args.workload = -1
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     inputs = workloads.make_inputs(wl)
