@@ -109,7 +109,9 @@ def test_workspace_query_rejects_bad_shapes(lib):
     assert lib.dwconv_bwd_weight_slices(2, 3, 100, 5, 2, 3) == 0
     for (B, C, L, K, p, dt) in [(32, 256, 4096, 64, 63, 0), (64, 512, 2048, 7, 3, 0), (8, 256, 8192, 8192, 8191, 0),
                                 (128, 768, 1024, 32, 31, 1), (1, 1, 1, 1, 0, 0), (16384, 128, 48, 48, 24, 0),
-                                (3, 5, 600, 64, 63, 0)]:
+                                (3, 5, 600, 64, 63, 0), (32, 256, 4096, 256, 255, 0), (32, 256, 4096, 600, 0, 0),
+                                (32, 256, 4096, 994, 993, 1), (128, 768, 1024, 512, 511, 1), (2, 4, 1024, 300, 150, 1),
+                                (64, 256, 512, 300, 150, 1), (5, 3, 4100, 700, 350, 1)]:
         S = lib.dwconv_bwd_weight_slices(B, C, L, K, p, dt)
         n = lib.dwconv_bwd_weight_workspace_bytes(B, C, L, K, p, dt)
         assert S >= 1 and n >= S * C * K * 4 and n % 16 == 0
