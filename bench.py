@@ -38,6 +38,12 @@ def parse_args():
                     help="instead of a listed workload: any shape, e.g. --shape 32 256 4096 256 255 f32 "
                          "(filters N(0, 1/K); no stored traffic figure; combine with --no-cpu-baseline for large K)")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets")
+    ap.add_argument("--min-warm-s", type=float, default=1.0,
+                    help="keep warming up (whole steps, beyond --warmup) until this much wall time has been spent on "
+                         "warm-up steps: a short run must not time the part's clock ramp (0 = exactly --warmup steps)")
+    ap.add_argument("--trace-steps", type=int, default=16,
+                    help="per-step event times of the first N steps after set-up, reported as first_steps_us "
+                         "(they are warm-up steps; nothing is hidden: the ramp shows here)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-roof", action="store_true",
                     help="instead of the benchmark, time plain device copies of 128 MiB .. 1 GiB (what a streaming "
@@ -170,12 +176,48 @@ def main():
             binding.dwconv_bwd_weight_finalize(s["ws"], wl.B, wl.C, wl.L, K, p, tdt, out=s["dw"])
         if ev: ev[4].record()
 
+    fused_on = bool(binding.dwconv_bwd_is_fused(wl.B, wl.C, wl.L, K, p, code))
+
+    def step_fused(s, ev=None):
+        if ev: ev[0].record()
+        binding.dwconv_fwd(s["x"], s["w"], p, out=s["y"])
+        if ev: ev[1].record()
+        binding.dwconv_bwd(s["dy"], s["x"], s["w"], p, workspace=s["ws"], out_dx=s["dx"], out_dw=s["dw"])
+        if ev: ev[2].record()
+
+    def new_events(n, k):
+        return [[torch.cuda.Event(enable_timing=True) for _ in range(k)] for _ in range(n)]
+
     # One plain device copy of a known size (x -> y of set 0) before anything is timed: under
     # rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate those counters.
     sets[0]["y"].copy_(sets[0]["x"])
-    for i in range(args.warmup):
-        step(sets[i % args.sets])
+    # Set-up, not warm-up: every kernel of the step is launched once on every buffer set, so that code objects are
+    # loaded, the library's per-kernel occupancy and LDS-attribute queries are done and every page is touched.
+    for s in sets:
+        step(s)
+        if fused_on:
+            step_fused(s)
     torch.cuda.synchronize()
+
+    # Warm-up: the first `trace_steps` steps carry one event pair each (their times are reported as first_steps_us,
+    # so a clock ramp after an idle period shows in the line instead of hiding in the mean); then whole steps until
+    # both `warmup` steps and `min_warm_s` seconds of warm-up have run.
+    n_trace = max(0, args.trace_steps)
+    tev = new_events(n_trace, 2)
+    t_warm0 = time.perf_counter()
+    for i in range(n_trace):
+        tev[i][0].record(); step(sets[i % args.sets]); tev[i][1].record()
+    torch.cuda.synchronize()
+    first_steps_us = [round(1e3 * e[0].elapsed_time(e[1]), 1) for e in tev]
+    warm_done = n_trace
+    chunk = max(1, min(64, args.warmup if args.warmup > 0 else 16))
+    while warm_done < args.warmup or (time.perf_counter() - t_warm0) < args.min_warm_s:
+        n = chunk if warm_done >= args.warmup else min(chunk, args.warmup - warm_done)
+        for i in range(n):
+            step(sets[(warm_done + i) % args.sets])
+        torch.cuda.synchronize()
+        warm_done += n
+    warm_seconds = time.perf_counter() - t_warm0
 
     # timed region 1: exactly `steps` steps back to back (the headline number)
     start = torch.cuda.Event(enable_timing=True); end = torch.cuda.Event(enable_timing=True)
@@ -188,27 +230,27 @@ def main():
     ms_per_step = start.elapsed_time(end) / args.steps
 
     # timed region 2: the same steps with HIP events between the launches, for per-kernel durations
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    # (at least 50 of them, so that median and minimum mean something on a short run)
+    n_ev = max(args.steps, 50)
+    evs = new_events(n_ev, 5)
     torch.cuda.synchronize()
-    for i in range(args.steps):
+    for i in range(n_ev):
         step(sets[i % args.sets], evs[i])
     torch.cuda.synchronize()
     names = ["fwd", "dx", "dw_partial", "dw_finalize"]
-    us = {n: 1e3 * sum(e[k].elapsed_time(e[k + 1]) for e in evs) / args.steps for k, n in enumerate(names)}
+    samples = {n: sorted(1e3 * e[k].elapsed_time(e[k + 1]) for e in evs) for k, n in enumerate(names)}
     if single:
-        us["dw_finalize"] = 0.0          # no second stage: "dw_partial" is the whole weight-gradient kernel
+        samples["dw_finalize"] = [0.0] * n_ev          # no second stage: "dw_partial" is the whole weight-gradient kernel
+    us = {n: sum(v) / len(v) for n, v in samples.items()}
+    us_median = {n: v[len(v) // 2] for n, v in samples.items()}
+    us_min = {n: v[0] for n, v in samples.items()}
+    step_samples = sorted(1e3 * e[0].elapsed_time(e[4]) for e in evs)
 
     # the same step with the fused backward call (reads dY once: 5 tensor passes instead of 6); reported beside
     # the headline number against its own algorithmic bytes, never as `value`
     fused = None
-    if binding.dwconv_bwd_is_fused(wl.B, wl.C, wl.L, K, p, code):
-        def step_fused(s, ev=None):
-            if ev: ev[0].record()
-            binding.dwconv_fwd(s["x"], s["w"], p, out=s["y"])
-            if ev: ev[1].record()
-            binding.dwconv_bwd(s["dy"], s["x"], s["w"], p, workspace=s["ws"], out_dx=s["dx"], out_dw=s["dw"])
-            if ev: ev[2].record()
-        for i in range(args.warmup):
+    if fused_on:
+        for i in range(max(args.warmup, 8)):
             step_fused(sets[i % args.sets])
         torch.cuda.synchronize()
         f0 = torch.cuda.Event(enable_timing=True); f1 = torch.cuda.Event(enable_timing=True)
@@ -218,13 +260,15 @@ def main():
         f1.record()
         torch.cuda.synchronize()
         fused_ms = f0.elapsed_time(f1) / args.steps
-        fevs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-        for i in range(args.steps):
+        fevs = new_events(n_ev, 3)
+        for i in range(n_ev):
             step_fused(sets[i % args.sets], fevs[i])
         torch.cuda.synchronize()
+        fb = sorted(1e3 * e[1].elapsed_time(e[2]) for e in fevs)
         fused = {"us_per_step": round(fused_ms * 1e3, 2),
-                 "fwd_us": round(1e3 * sum(e[0].elapsed_time(e[1]) for e in fevs) / args.steps, 2),
-                 "bwd_us": round(1e3 * sum(e[1].elapsed_time(e[2]) for e in fevs) / args.steps, 2)}
+                 "fwd_us": round(1e3 * sum(e[0].elapsed_time(e[1]) for e in fevs) / n_ev, 2),
+                 "bwd_us": round(sum(fb) / n_ev, 2), "bwd_us_median": round(fb[n_ev // 2], 2),
+                 "bwd_us_min": round(fb[0], 2)}
 
     es = wl.elem_size
     step_bytes = algorithmic_bytes(wl.B, wl.C, wl.L, K, es, "step")
@@ -245,6 +289,13 @@ def main():
                    "step_algorithmic_bytes": step_bytes, "path_algorithmic_bytes": path_bytes,
                    "path_flops_in_range": flops, "path_flops_dense": dense_flops(wl.B, wl.C, wl.L, K)},
         "paths_us": {n: round(v, 2) for n, v in us.items()},
+        "paths_us_median": {n: round(v, 2) for n, v in us_median.items()},
+        "paths_us_min": {n: round(v, 2) for n, v in us_min.items()},
+        "step_us_from_events": {"mean": round(sum(step_samples) / len(step_samples), 2),
+                                "median": round(step_samples[len(step_samples) // 2], 2),
+                                "min": round(step_samples[0], 2), "samples": len(step_samples)},
+        "warmup_steps_run": warm_done, "warmup_seconds": round(warm_seconds, 3),
+        "first_steps_us": first_steps_us,
         "paths_gbps": {"fwd": round(path_bytes / us["fwd"] / 1e3, 1), "dx": round(path_bytes / us["dx"] / 1e3, 1),
                        "dw": round(path_bytes / (us["dw_partial"] + us["dw_finalize"]) / 1e3, 1)},
         "paths_frac_of_hbm_peak": {"fwd": round(path_bytes / us["fwd"] / 1e3 / HBM_PEAK_GBPS, 4),

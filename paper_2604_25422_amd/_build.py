@@ -28,9 +28,9 @@ def dependencies():
     return sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + [os.path.join(HERE, "..", "include", "dwconv.h")]
 
 
-def build(verbose: bool = False, extra_flags=(), jobs: int | None = None) -> str:
-    """Always recompiles: every translation unit to an object file (side by side), then one link.
-    Returns the path of the shared library."""
+def build(verbose: bool = False, extra_flags=(), jobs: int | None = None, incremental: bool = False) -> str:
+    """Every translation unit to an object file (side by side), then one link.  Recompiles everything unless
+    `incremental` (then only units older than their source or any header).  Returns the path of the shared library."""
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -38,8 +38,13 @@ def build(verbose: bool = False, extra_flags=(), jobs: int | None = None) -> str
     srcs = sources()
     objs = [os.path.join(OBJ_DIR, os.path.basename(p)[:-4] + ".o") for p in srcs]
 
+    headers = sorted(glob.glob(os.path.join(CSRC, "*.h"))) + [os.path.join(HERE, "..", "include", "dwconv.h")]
+    newest_header = max(os.path.getmtime(h) for h in headers)
+
     def compile_one(pair):
         src, obj = pair
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            return
         cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -64,4 +69,5 @@ def is_stale() -> bool:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, incremental="--incremental" in sys.argv))

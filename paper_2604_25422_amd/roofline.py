@@ -1,4 +1,4 @@
-"""Roofline bookkeeping and the parity metric (no operator arithmetic).
+"""Roofline bookkeeping (no operator arithmetic).
 
 Operation counts follow the paper's roofline construction (Sec. III-G,
 eqs. (flops_fwd_bwdin), (flops_bwdk), (roofline_metrics)); the byte counts are
@@ -7,7 +7,6 @@ written once.
 """
 from __future__ import annotations
 
-import numpy as np
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3    # dense fp32 matrix
@@ -39,18 +38,6 @@ def in_range_flops(B, C, L, K, pad_left):
     for j in range(K):
         taps += max(0, L - abs(j - pad_left))
     return 2 * B * C * taps
-
-
-def normalised_error(got, ref, ref_abs, floor=2.0 ** -100):
-    """max_i |got_i - ref_i| / max(sum_i|terms|, floor).  Returns (err, argmax)."""
-    got = np.asarray(got, dtype=np.float64)
-    ref = np.asarray(ref, dtype=np.float64)
-    den = np.maximum(np.asarray(ref_abs, dtype=np.float64), floor)
-    e = np.abs(got - ref) / den
-    if not np.all(np.isfinite(got)):
-        return float("inf"), int(np.argmin(np.isfinite(got).ravel()))
-    i = int(np.argmax(e))
-    return float(e.ravel()[i]), i
 
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, FETCH_SIZE

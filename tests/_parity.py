@@ -4,8 +4,19 @@ import numpy as np
 import torch
 
 from paper_2604_25422_amd import binding
-from paper_2604_25422_amd.roofline import normalised_error
 from paper_2604_25422_amd.workloads import as_f32_numpy
+
+def normalised_error(got, ref, ref_abs, floor=2.0 ** -100):
+    """max_i |got_i - ref_i| / max(sum_i|terms|, floor).  Returns (err, argmax)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.maximum(np.asarray(ref_abs, dtype=np.float64), floor)
+    e = np.abs(got - ref) / den
+    if not np.all(np.isfinite(got)):
+        return float("inf"), int(np.argmin(np.isfinite(got).ravel()))
+    i = int(np.argmax(e))
+    return float(e.ravel()[i]), i
+
 
 # max |gpu - oracle| / sum|terms| allowed per path
 TOL = {("f32", "fwd"): 1e-5, ("f32", "dx"): 1e-5, ("f32", "dw"): 1e-4,

@@ -8,7 +8,7 @@ import torch
 
 from _parity import TOL
 from paper_2604_25422_amd import binding, workloads
-from paper_2604_25422_amd.roofline import normalised_error
+from _parity import normalised_error
 from paper_2604_25422_amd.workloads import as_f32_numpy
 
 pytestmark = pytest.mark.gpu

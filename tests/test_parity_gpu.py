@@ -173,7 +173,7 @@ def test_inputs_are_not_written_and_outputs_are_overwritten():
 
 def test_runs_on_a_non_default_stream(oracle_mod):
     from paper_2604_25422_amd import binding
-    from paper_2604_25422_amd.roofline import normalised_error
+    from _parity import normalised_error
     B, C, L, K, p = 2, 4, 777, 12, 11
     x = seeded((B, C, L), 5, torch.float32); w = seeded((C, K), 6, torch.float32)
     st = torch.cuda.Stream()
@@ -236,7 +236,7 @@ BWD = [
 @pytest.mark.parametrize("B,C,L,K,p,dtype,fused", BWD)
 def test_fused_backward(oracle_mod, B, C, L, K, p, dtype, fused):
     from paper_2604_25422_amd import binding
-    from paper_2604_25422_amd.roofline import normalised_error
+    from _parity import normalised_error
     from paper_2604_25422_amd.workloads import as_f32_numpy
     print(f"case bwd {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
     code = binding.F32 if dtype == "f32" else binding.BF16
@@ -294,7 +294,7 @@ def test_random_shapes(oracle_mod, B, C, L, K, p, dtype):
     dx_sep = binding.dwconv_bwd_input(dyd, wd, p)
     torch.cuda.synchronize()
     assert torch.equal(dx, dx_sep)
-    from paper_2604_25422_amd.roofline import normalised_error
+    from _parity import normalised_error
     from paper_2604_25422_amd.workloads import as_f32_numpy
     ref, ra = oracle_mod.bwd_weight(as_f32_numpy(x), as_f32_numpy(dy), K, p)
     e, i = normalised_error(dw.float().cpu().numpy().astype(np.float64), ref, ra)
