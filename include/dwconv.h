@@ -60,7 +60,8 @@ enum dwconv_status {
     DWCONV_ERR_DTYPE     = 4,  /* dtype is not a dwconv_dtype                      */
     DWCONV_ERR_WORKSPACE = 5,  /* workspace NULL, too small or not 16-byte aligned */
     DWCONV_ERR_ALIGN     = 6,  /* a tensor pointer is not element-aligned          */
-    DWCONV_ERR_LAUNCH    = 7   /* HIP reported an error when launching             */
+    DWCONV_ERR_LAUNCH    = 7,  /* HIP reported an error when launching             */
+    DWCONV_ERR_SCRATCH   = 8   /* dwconv_bwd_weight_noalloc: shape needs more than the built-in scratch */
 };
 
 /*
@@ -110,13 +111,30 @@ DWCONV_API int dwconv_bwd_weight_partial(const void *x, const void *dy,
                               int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
 /*
- * Stage 2 of the weight gradient (Sec. IV-C/D: "second reduction stage"):
+ * Stage 2 of the weight gradient (Sec. IV-C/D):
  *     dw[c,j] = sum_{s=0}^{S-1} part[s,c,j], in increasing s.
  * Reads the fp32 partials stage 1 left in `workspace`, writes dw [C,K] in
  * `dtype`.  Shape arguments must equal those given to stage 1.
  */
 DWCONV_API int dwconv_bwd_weight_finalize(const void *workspace, size_t workspace_bytes, void *dw,
                                int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/*
+ * dwconv_bwd_weight for callers that cannot allocate device memory or carry a workspace around: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels, same bits in dw.  The partial sums go to an array inside the library's device code
+ * (dwconv_noalloc_scratch_bytes() = 16 MiB per GPU the library runs on, held until the process ends); a shape whose
+ * dwconv_bwd_weight_workspace_bytes(...) exceeds that returns DWCONV_ERR_SCRATCH and launches nothing (every
+ * benchmark shape fits; C*K*4 bytes per slice is what counts).  The call allocates and frees nothing.  Its first call
+ * on a device looks the array's address up (hipGetSymbolAddress), so make that call outside a capture.  All calls on
+ * one GPU share the one array: calls that overlap in time on different streams race; on one stream they are ordered.
+ * The array keeps the previous call's contents; the kernels overwrite or clear what they read.
+ */
+DWCONV_API int dwconv_bwd_weight_noalloc(const void *x, const void *dy, void *dw,
+                              int B, int C, int L, int K, int pad_left, int dtype, void *stream);
+
+/* Size in bytes of the built-in scratch dwconv_bwd_weight_noalloc uses. */
+DWCONV_API size_t dwconv_noalloc_scratch_bytes(void);
 
 /*
  * Both gradients of the backward pass in one call: dx as dwconv_bwd_input, dw as dwconv_bwd_weight.

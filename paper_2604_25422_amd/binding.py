@@ -23,6 +23,7 @@ SYMBOLS = (
     "dwconv_fwd", "dwconv_bwd_input", "dwconv_bwd_weight", "dwconv_bwd_weight_partial",
     "dwconv_bwd_weight_finalize", "dwconv_bwd_weight_slices", "dwconv_bwd_weight_single_pass",
     "dwconv_bwd_weight_workspace_bytes", "dwconv_bwd", "dwconv_bwd_is_fused",
+    "dwconv_bwd_weight_noalloc", "dwconv_noalloc_scratch_bytes",
     "dwconv_status_string", "dwconv_version",
 )
 
@@ -62,6 +63,10 @@ def lib():
         l.dwconv_bwd_weight_single_pass.restype = i
         l.dwconv_bwd_weight_workspace_bytes.argtypes = shape
         l.dwconv_bwd_weight_workspace_bytes.restype = sz
+        l.dwconv_bwd_weight_noalloc.argtypes = [vp, vp, vp] + shape + [vp]
+        l.dwconv_bwd_weight_noalloc.restype = i
+        l.dwconv_noalloc_scratch_bytes.argtypes = []
+        l.dwconv_noalloc_scratch_bytes.restype = sz
         l.dwconv_status_string.argtypes = [i]
         l.dwconv_status_string.restype = ctypes.c_char_p
         l.dwconv_version.argtypes = []
@@ -173,6 +178,25 @@ def dwconv_bwd_weight(x, dy, K: int, pad_left: int, workspace=None, out=None) ->
     dw = torch.empty((C, K), dtype=x.dtype, device=x.device) if out is None else _dev2(out, "out", C)
     _check(lib().dwconv_bwd_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), workspace.data_ptr(), nbytes,
                                    B, C, L, int(K), int(pad_left), _dtype_code(x), _stream()))
+    return dw
+
+
+def dwconv_noalloc_scratch_bytes() -> int:
+    return int(lib().dwconv_noalloc_scratch_bytes())
+
+
+def dwconv_bwd_weight_noalloc(x, dy, K: int, pad_left: int, out: torch.Tensor) -> torch.Tensor:
+    """dwconv_bwd_weight without a workspace: partial sums go to the library's built-in scratch; `out` is the
+    caller's [C, K] tensor (the call allocates nothing, so it cannot make one)."""
+    _dev3(x, "x"); _dev3(dy, "dy")
+    if dy.shape != x.shape or dy.dtype != x.dtype:
+        raise ValueError("x and dy must match")
+    B, C, L = x.shape
+    dw = _dev2(out, "out", C)
+    if dw.shape[1] != K or dw.dtype != x.dtype:
+        raise ValueError("out must be [C, K] of x's dtype")
+    _check(lib().dwconv_bwd_weight_noalloc(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), B, C, L, int(K), int(pad_left),
+                                           _dtype_code(x), _stream()))
     return dw
 
 

@@ -4,9 +4,39 @@
 #include "dwconv_host.hip.h"
 #include "dwconv_valu.hip.h"
 
+// Partial sums of the weight gradient for callers that cannot hand over a workspace (dwconv_bwd_weight_noalloc):
+// one array per GPU, living in the code object's data segment until the process ends.  In host code the name below
+// is only a handle for hipGetSymbolAddress; kernels get the device address that call returns.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace dwhost {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 101;   // 0.1.1
+
+// Device address of `scratch` on the current device (looked up once per device and kept).
+int scratch_pointer(void **out)
+{
+    static std::mutex mu;
+    static std::map<int, void *> per_device;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return DWCONV_ERR_LAUNCH;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = per_device.find(dev);
+    if (it == per_device.end()) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return DWCONV_ERR_LAUNCH;
+        }
+        it = per_device.emplace(dev, ptr).first;
+    }
+    *out = it->second;
+    return DWCONV_OK;
+}
 
 int check_shape(int B, int C, int L, int K, int pad, int dtype)
 {
@@ -243,6 +273,7 @@ DwPlan plan_dw(const Shape &s)
     if (p.lk_table) {
         p.longk = true;
         p.S = 2;
+        p.S_fused = 2;                                     // (no fused kernel for long filters: nothing needs more slices)
         p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
         p.valu_items_per_slice = p.items_per_slice;
     }
@@ -356,6 +387,24 @@ int dwconv_bwd_weight(const void *x, const void *dy, void *dw, void *workspace, 
     return launch_dw_finalize<bf16_t>(part, dw, s, p, st);
 }
 
+int dwconv_bwd_weight_noalloc(const void *x, const void *dy, void *dw, int B, int C, int L, int K, int pad_left,
+                              int dtype, void *stream)
+{
+    if (!x || !dy || !dw) return DWCONV_ERR_NULL;
+    int rc = check_dw_shape(B, C, L, K, pad_left, dtype);
+    if (rc != DWCONV_OK) return rc;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(x, es) || !aligned_to(dy, es) || !aligned_to(dw, es)) return DWCONV_ERR_ALIGN;
+    const Shape s{B, C, L, K, pad_left, dtype};
+    if (dw_workspace_bytes(s, plan_dw(s)) > kScratchBytes) return DWCONV_ERR_SCRATCH;
+    void *ptr = nullptr;
+    rc = scratch_pointer(&ptr);
+    if (rc != DWCONV_OK) return rc;
+    return dwconv_bwd_weight(x, dy, dw, ptr, kScratchBytes, B, C, L, K, pad_left, dtype, stream);
+}
+
+size_t dwconv_noalloc_scratch_bytes(void) { return kScratchBytes; }
+
 int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx, void *dw, void *workspace,
                size_t workspace_bytes, int B, int C, int L, int K, int pad_left, int dtype, void *stream)
 {
@@ -432,6 +481,8 @@ const char *dwconv_status_string(int status)
     case DWCONV_ERR_WORKSPACE: return "workspace is NULL, smaller than dwconv_bwd_weight_workspace_bytes() or not 16-byte aligned";
     case DWCONV_ERR_ALIGN: return "a tensor pointer is not aligned to its element size";
     case DWCONV_ERR_LAUNCH: return "HIP reported an error at kernel launch";
+    case DWCONV_ERR_SCRATCH: return "this shape needs more partial-sum space than the library's built-in scratch holds "
+                                    "(dwconv_noalloc_scratch_bytes()): use dwconv_bwd_weight with a workspace";
     default: return "unknown status";
     }
 }

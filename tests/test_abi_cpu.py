@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_status_strings(lib):
     assert lib.dwconv_version() >= 100
     seen = set()
-    for code in range(0, 8):
+    for code in range(0, 9):
         s = lib.dwconv_status_string(code).decode()
         assert s and s not in seen
         seen.add(s)
@@ -174,3 +174,23 @@ def test_workloads_are_seeded_and_shaped():
     assert w3.shape == (4, 8192) and float(w3[:, 0].min()) == 1.0 and float(w3.abs().max()) <= 1.0
     w4 = workloads.make_filter(workloads.WORKLOADS[4])
     assert w4.dtype == torch.bfloat16
+
+
+def test_noalloc_argument_validation(lib):
+    """The allocation-free weight gradient validates like dwconv_bwd_weight and turns away shapes whose partial
+    sums do not fit the built-in scratch, all before any HIP call."""
+    f = lib.dwconv_bwd_weight_noalloc
+    cap = lib.dwconv_noalloc_scratch_bytes()
+    assert cap == 16 << 20
+    assert f(None, P, P, 2, 3, 100, 5, 2, 0, None) == 1
+    assert f(P, P, None, 2, 3, 100, 5, 2, 0, None) == 1
+    assert f(P, P, P, 2, 3, 100, 0, 0, 0, None) == 2
+    assert f(P, P, P, 2, 3, 100, 5, 5, 0, None) == 3
+    assert f(P, P, P, 2, 3, 100, 5, 2, 7, None) == 4
+    assert f(P + 1, P, P, 2, 3, 100, 5, 2, 0, None) == 6
+    assert lib.dwconv_bwd_weight_workspace_bytes(1, 512, 8192, 8192, 8191, 0) > cap
+    assert f(P, P, P, 1, 512, 8192, 8192, 8191, 0, None) == 8
+    # every benchmark shape fits
+    for shape in ((4, 64, 1024, 16, 15, 0), (32, 256, 4096, 64, 63, 0), (64, 512, 2048, 7, 3, 0),
+                  (8, 256, 8192, 8192, 8191, 0), (128, 768, 1024, 32, 31, 1), (16384, 128, 48, 48, 24, 0)):
+        assert 0 < lib.dwconv_bwd_weight_workspace_bytes(*shape) <= cap, shape
