@@ -34,6 +34,13 @@
  *     launches nothing.  Return value: a DWCONV_* status, DWCONV_OK (0) on
  *     success.  The library never throws and never aborts.
  *   - K = 1 and K > L are legal.  B*C*L must fit 2^40 elements.
+ *   - Non-finite inputs.  The zero padding of x~ is a value that gets multiplied, not a term that is skipped, and
+ *     the matrix-core kernels also multiply the zero taps that fill their 16 x 16 filter blocks.  An Inf or NaN at
+ *     x[b,c,u] (dy[b,c,u] for the input gradient) therefore makes non-finite the outputs the definition gives it
+ *     and possibly, as NaN, outputs of the same row up to 63 positions further on either side, the last 63 positions
+ *     of row (b-1,c) and the first 63 of row (b+1,c); an Inf or NaN in w[c,:] may reach every output of channel c.
+ *     In the weight gradient a non-finite x or dy of channel c may reach every dw[c,:].  No other channel is ever
+ *     touched, and finite inputs never produce a NaN that the definition does not produce.
  */
 #ifndef DWCONV_H
 #define DWCONV_H

@@ -18,6 +18,21 @@ def normalised_error(got, ref, ref_abs, floor=2.0 ** -100):
     return float(e.ravel()[i]), i
 
 
+def normalised_error_rows(got, ref, ref_abs, floor=2.0 ** -100):
+    """normalised_error over the leading axis in slabs (same value; bounded temporaries for 1e8-element tensors)."""
+    worst, at = 0.0, 0
+    n = got.shape[0]
+    per = int(np.prod(got.shape[1:]))
+    step = max(1, (1 << 24) // max(per, 1))
+    for a in range(0, n, step):
+        e, i = normalised_error(got[a:a + step], ref[a:a + step], ref_abs[a:a + step], floor)
+        if e > worst or not np.isfinite(e):
+            worst, at = e, a * per + i
+        if not np.isfinite(e):
+            break
+    return worst, at
+
+
 # max |gpu - oracle| / sum|terms| allowed per path
 TOL = {("f32", "fwd"): 1e-5, ("f32", "dx"): 1e-5, ("f32", "dw"): 1e-4,
        ("bf16", "fwd"): 2e-2, ("bf16", "dx"): 2e-2, ("bf16", "dw"): 2e-2}
@@ -26,6 +41,30 @@ TOL = {("f32", "fwd"): 1e-5, ("f32", "dx"): 1e-5, ("f32", "dw"): 1e-4,
 def seeded(shape, seed, dtype):
     g = torch.Generator(device="cpu"); g.manual_seed(seed)
     return torch.randn(shape, generator=g, dtype=torch.float32).to(dtype).contiguous()
+
+
+def small_ints(shape, seed, lim, dtype):
+    """Seeded integers in [-lim, lim] (exact in fp32 and bf16 for lim <= 256): every product and every partial sum
+    of the operator is then an integer, exact in fp32 up to 2^24 whatever the order of summation."""
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    return torch.randint(-lim, lim + 1, shape, generator=g, dtype=torch.int32).to(dtype).contiguous()
+
+
+def to_device(t, offset=0):
+    """A device copy of t; with offset > 0 a view that starts `offset` elements into a larger allocation, so that
+    its base pointer is aligned to the element size only."""
+    if offset == 0:
+        return t.cuda()
+    buf = torch.empty(t.numel() + offset + 8, dtype=t.dtype, device="cuda")
+    v = buf[offset:offset + t.numel()].view(t.shape)
+    v.copy_(t)
+    return v
+
+
+def empty_device(shape, dtype, offset=0):
+    n = int(np.prod(shape))
+    buf = torch.empty(n + offset + 8, dtype=dtype, device="cuda")
+    return buf[offset:offset + n].view(shape)
 
 
 def gpu_all(x, w, dy, p):

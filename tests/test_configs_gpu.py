@@ -1,17 +1,85 @@
-"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
-Where the oracle cannot finish the whole tensor in seconds, sampled rows (fwd, dX) and
-sampled channels (dW) are checked one by one: rows and channels are independent, so the
-oracle evaluates exactly the sampled outputs of the full-size problem."""
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times: every
+output of every listed workload against the oracle, once on the workload's own seeded inputs
+(tolerance) and once on small-integer inputs of the same shape (bit for bit).  The mid-size odd
+shapes at the end sample rows (fwd, dX) and channels (dW): rows and channels are independent,
+so the oracle evaluates exactly the sampled outputs of the full-size problem."""
 import numpy as np
 import pytest
 import torch
 
-from _parity import TOL
+from _parity import TOL, normalised_error_rows, small_ints
 from paper_2604_25422_amd import binding, workloads
 from _parity import normalised_error
 from paper_2604_25422_amd.workloads import as_f32_numpy
 
 pytestmark = pytest.mark.gpu
+
+
+def run_whole(oracle, wl, ints=False):
+    """Every output of the full-size problem against the oracle: within the tolerance on the workload's own
+    inputs, bit for bit on small-integer inputs of the same shape (exact in fp32 in any order of summation)."""
+    tdt = workloads.torch_dtype(wl)
+    B, C, L, K, p = wl.B, wl.C, wl.L, wl.K, wl.pad_left
+    if ints:
+        assert 9 * B * L < 2 ** 24
+        x = small_ints((B, C, L), 7100 + wl.index, 3, tdt); w = small_ints((C, K), 8100 + wl.index, 3, tdt)
+        dy = small_ints((B, C, L), 9100 + wl.index, 3, tdt)
+    else:
+        inp = workloads.make_inputs(wl)
+        x, w, dy = inp["x"], inp["w"], inp["dy"]
+    xd, wd, dyd = x.cuda(), w.cuda(), dy.cuda()
+    y = binding.dwconv_fwd(xd, wd, p)
+    dx = binding.dwconv_bwd_input(dyd, wd, p)
+    ws = binding.new_workspace(xd, K, p)
+    dw = binding.dwconv_bwd_weight(xd, dyd, K, p, workspace=ws)
+    dx_f, dw_f = binding.dwconv_bwd(dyd, xd, wd, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dx_f, dx), "fused backward: dx differs from the separate path"
+    del dx_f
+    # the fp32 partial sums (stage 1 alone): their ordered sum is what stage 2 rounds to the storage type
+    ws.fill_(0xFF)
+    binding.dwconv_bwd_weight_partial(xd, dyd, K, p, workspace=ws)
+    S = binding.dwconv_bwd_weight_slices(B, C, L, K, p, binding.F32 if wl.dtype == "f32" else binding.BF16)
+    part = ws.view(torch.float32)[: S * C * K].view(S, C, K)
+    seq = torch.zeros(C, K, device="cuda")
+    for s in range(S):
+        seq = seq + part[s]
+    torch.cuda.synchronize()
+    assert torch.equal(seq.to(tdt), dw), "dwconv_bwd_weight is not the ordered sum of the stage-1 slices"
+    seq = seq.cpu().numpy()
+    del xd, dyd, ws, part
+    xn, wn, dyn = as_f32_numpy(x), as_f32_numpy(w), as_f32_numpy(dy)
+    errs = {}
+
+    def compare(name, got, ref, ra):
+        if ints:
+            assert np.all(np.abs(ref) < 2.0 ** 24)
+            exp = torch.from_numpy(ref).to(torch.float32).to(got.dtype)
+            g = got.cpu()
+            assert torch.equal(g, exp), (f"{wl.name} {name}: {(g != exp).sum().item()} of {exp.numel()} values differ "
+                                         f"from the exact result, first at flat index {(g != exp).flatten().nonzero()[0].item()}")
+            errs[name] = 0.0
+        else:
+            g = got.float().cpu().numpy()
+            e, i = normalised_error_rows(g, ref, ra)
+            errs[name] = e
+            assert e <= TOL[(wl.dtype, name.split("_")[0])], (wl.name, name, e, i)
+            assert np.all(g[ra == 0] == 0), f"{wl.name} {name}: non-zero output where no term exists"
+
+    r, ra = oracle.fwd(xn, wn, p); compare("fwd", y, r, ra); del y, r, ra
+    r, ra = oracle.bwd_input(dyn, wn, p); compare("dx", dx, r, ra); del dx, r, ra
+    r, ra = oracle.bwd_weight(xn, dyn, K, p)
+    compare("dw", dw, r, ra)
+    compare("dw_fused", dw_f, r, ra)
+    # the unrounded fp32 sums at the fp32 bound, whatever the storage type
+    if ints:
+        assert np.array_equal(seq.astype(np.float64), r), f"{wl.name}: fp32 partial sums differ from the exact result"
+    else:
+        e, i = normalised_error(seq, r, ra)
+        errs["dw_partials_f32"] = e
+        assert e <= TOL[("f32", "dw")], (wl.name, "fp32 partial sums", e, i)
+    print(wl.name, "ints" if ints else "normal", {k: f"{v:.2e}" for k, v in errs.items()}, "whole tensors", flush=True)
+    return errs
 
 
 def run_full_size(oracle, wl, n_rows, n_chans, seed=0):
@@ -58,44 +126,16 @@ def run_full_size(oracle, wl, n_rows, n_chans, seed=0):
     return errs
 
 
-def test_cfg0_small_whole(oracle_mod):
-    run_full_size(oracle_mod, workloads.WORKLOADS[0], 10 ** 9, 10 ** 9)
+# every listed workload, whole tensors: 0 small, 1 headline, 2 short filter, 3 long filter, 4 bf16, 5 the paper's own
+# shape, 6 / 7 the 128-tap filters, 8 the long filter on bf16 storage
+@pytest.mark.parametrize("index", range(len(workloads.WORKLOADS)))
+def test_workload_whole_tensors(oracle_mod, index):
+    run_whole(oracle_mod, workloads.WORKLOADS[index])
 
 
-def test_cfg1_headline_full_size(oracle_mod):
-    run_full_size(oracle_mod, workloads.WORKLOADS[1], 1024, 32)
-
-
-def test_cfg2_short_filter_full_size(oracle_mod):
-    run_full_size(oracle_mod, workloads.WORKLOADS[2], 4096, 64)
-
-
-def test_cfg3_long_filter_full_size(oracle_mod):
-    run_full_size(oracle_mod, workloads.WORKLOADS[3], 48, 6)
-
-
-def test_cfg4_bf16_full_size(oracle_mod):
-    run_full_size(oracle_mod, workloads.WORKLOADS[4], 4096, 48)
-
-
-def test_paper_shape_full_size(oracle_mod):
-    # the shape the paper measures (Sec. V): many short rows, sixteen rows to a matrix tile
-    run_full_size(oracle_mod, workloads.WORKLOADS[5], 8192, 16)
-
-
-def test_mid_filter_full_size(oracle_mod):
-    # a filter of 128 taps at the headline geometry: nine block offsets on the register-resident kernels
-    run_full_size(oracle_mod, workloads.WORKLOADS[6], 512, 16)
-
-
-def test_long_filter_bf16_full_size(oracle_mod):
-    # the long-filter configuration on bf16 storage: the bf16 matrix-instruction long-filter kernels
-    run_full_size(oracle_mod, workloads.WORKLOADS[8], 48, 6)
-
-
-def test_mid_filter_bf16_full_size(oracle_mod):
-    # the same 128 taps on bf16 storage: nine block offsets on the bf16 matrix-instruction kernels
-    run_full_size(oracle_mod, workloads.WORKLOADS[7], 512, 16)
+@pytest.mark.parametrize("index", range(len(workloads.WORKLOADS)))
+def test_workload_whole_tensors_exact_on_integers(oracle_mod, index):
+    run_whole(oracle_mod, workloads.WORKLOADS[index], ints=True)
 
 
 @pytest.mark.parametrize("B,C,L,K,p,dtype", [

@@ -1,0 +1,126 @@
+"""Exact parity: on small-integer inputs every product and every partial sum of the operator (Sec. IV-A
+eqs. (dwconv), (dx_def) read as the adjoint, (dk_def)) is an integer below 2^24, hence exact in fp32 in ANY order
+of summation, on the matrix cores as on the vector ALU.  The HIP path must then equal the fp64 oracle bit for bit
+over the whole tensor: one dropped, doubled or misplaced term anywhere fails, which a tolerance on random data
+cannot promise for a sum of 10^5 terms.  bf16 outputs are the exact sum rounded once to nearest-even, so they must
+equal the oracle's value rounded the same way; the fp32 partial sums of the bf16 weight gradient (Sec. IV-C/D, the
+intermediate tensor) are compared unrounded.
+
+Also here: the same comparison on tensors whose base pointers are aligned to the element size only (views one
+element into an allocation), which takes every dispatch class to its generic kernels with a plan sized for the
+matrix-core ones."""
+import numpy as np
+import pytest
+import torch
+
+from _parity import empty_device, small_ints, to_device
+from paper_2604_25422_amd import binding
+from paper_2604_25422_amd.workloads import as_f32_numpy
+
+pytestmark = pytest.mark.gpu
+
+LIM = 3      # inputs in [-3, 3]: |term| <= 9, so a sum of B*L <= 1.8e6 terms stays below 2^24
+
+
+def _expected(ref, tdt):
+    """What the storage type holds for an exact integer result: the value itself (fp32), or its one rounding (bf16)."""
+    assert np.all(np.abs(ref) < 2.0 ** 24) and np.all(ref == np.rint(ref)), "the case is not exact in fp32"
+    return torch.from_numpy(ref).to(torch.float32).to(tdt)
+
+
+def _same(name, got, ref, tdt, what):
+    exp = _expected(ref, tdt)
+    got = got.cpu()
+    if not torch.equal(got, exp):
+        bad = (got != exp).nonzero()
+        i = tuple(int(v) for v in bad[0])
+        raise AssertionError(f"{what} {name}: {bad.shape[0]} of {exp.numel()} values differ, first at {i}: "
+                             f"gpu {got[i].item()!r} expected {exp[i].item()!r}")
+
+
+def run_exact(oracle, B, C, L, K, p, dtype, seed=0, offset=0, fused=True, two_stage=True):
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    code = binding.F32 if dtype == "f32" else binding.BF16
+    what = f"{dtype} B{B} C{C} L{L} K{K} p{p} offset {offset}"
+    assert 9 * B * L < 2 ** 24
+    x = small_ints((B, C, L), 7000 + seed, LIM, tdt)
+    w = small_ints((C, K), 8000 + seed, LIM, tdt)
+    dy = small_ints((B, C, L), 9000 + seed, LIM, tdt)
+    xn, wn, dyn = as_f32_numpy(x), as_f32_numpy(w), as_f32_numpy(dy)
+    y_ref, _ = oracle.fwd(xn, wn, p)
+    dx_ref, _ = oracle.bwd_input(dyn, wn, p)
+    dw_ref, _ = oracle.bwd_weight(xn, dyn, K, p)
+    xd, wd, dyd = to_device(x, offset), to_device(w, offset), to_device(dy, offset)
+    y = binding.dwconv_fwd(xd, wd, p, out=empty_device((B, C, L), tdt, offset))
+    dx = binding.dwconv_bwd_input(dyd, wd, p, out=empty_device((B, C, L), tdt, offset))
+    ws = binding.new_workspace(xd, K, p)
+    dw = binding.dwconv_bwd_weight(xd, dyd, K, p, workspace=ws, out=empty_device((C, K), tdt, offset))
+    torch.cuda.synchronize()
+    _same("fwd", y, y_ref, tdt, what)
+    _same("dx", dx, dx_ref, tdt, what)
+    _same("dw", dw, dw_ref, tdt, what)
+    if two_stage:
+        # the intermediate tensor of the two-stage reduction: fp32 whatever the storage type, its slices add up
+        # (exactly, here) to the gradient, and stage 2 gives the same bits as the one-call form
+        ws.fill_(0xFF)
+        binding.dwconv_bwd_weight_partial(xd, dyd, K, p, workspace=ws)
+        S = binding.dwconv_bwd_weight_slices(B, C, L, K, p, code)
+        part = ws.view(torch.float32)[: S * C * K].view(S, C, K)
+        total = part.double().sum(dim=0).cpu().numpy()
+        assert np.array_equal(total, dw_ref), f"{what}: the fp32 partial sums do not add up to the oracle's dw"
+        dw2 = binding.dwconv_bwd_weight_finalize(ws, B, C, L, K, p, tdt, out=empty_device((C, K), tdt, offset))
+        torch.cuda.synchronize()
+        assert torch.equal(dw2, dw), f"{what}: stage 1 + stage 2 differ from dwconv_bwd_weight"
+    if fused:
+        dxf, dwf = binding.dwconv_bwd(dyd, xd, wd, p, workspace=ws, out_dx=empty_device((B, C, L), tdt, offset),
+                                      out_dw=empty_device((C, K), tdt, offset))
+        torch.cuda.synchronize()
+        _same("dx (dwconv_bwd)", dxf, dx_ref, tdt, what)
+        _same("dw (dwconv_bwd)", dwf, dw_ref, tdt, what)
+
+
+# One or more shapes per dispatch class (B, C, L, K, pad_left), each run on fp32 and bf16 storage.
+CLASSES = [
+    # generic vector-ALU kernels: K < 3, rows that are not a multiple of 4
+    (3, 2, 33, 1, 0), (2, 3, 101, 2, 1), (2, 5, 257, 7, 3), (2, 4, 1025, 16, 8), (1, 3, 2050, 9, 4), (1, 2, 41, 100, 99),
+    # register-resident Toeplitz operands, two to six block offsets, ragged last segment, several segments per wave
+    (2, 3, 600, 64, 63), (1, 2, 4100, 64, 32), (3, 7, 336, 31, 30), (7, 9, 3000, 48, 24), (2, 2, 2060, 66, 0),
+    (6, 10, 5000, 40, 11), (2, 4, 1024, 3, 1),
+    # seven to sixteen block offsets
+    (3, 5, 2064, 100, 99), (5, 2, 3072, 128, 127), (2, 3, 1032, 226, 100), (3, 4, 2064, 160, 159), (7, 2, 1024, 161, 80),
+    # weight gradient in two, three and four launches over the block offsets
+    (3, 4, 1024, 256, 255), (2, 2, 3000, 482, 481), (2, 3, 2048, 700, 350), (3, 2, 1024, 994, 993),
+    # long filters: rows and filter in LDS
+    (3, 2, 256, 200, 100), (2, 3, 512, 512, 511), (2, 1, 1000, 2500, 1200), (1, 2, 4096, 4096, 4095), (21, 2, 1024, 600, 599),
+    # short rows: sixteen rows per tile (with channel pairs), rows of five to eight blocks, virtual rows
+    (40, 6, 48, 48, 24), (100, 3, 48, 48, 0), (17, 3, 16, 16, 15), (33, 2, 80, 48, 24), (130, 2, 128, 31, 15),
+    (70, 256, 48, 48, 24), (300, 12, 200, 31, 15), (64, 2, 512, 64, 63), (50, 3, 132, 16, 15),
+    # one workgroup per channel: the weight gradient as a single kernel
+    (9, 256, 3900, 64, 63), (4, 512, 4096, 7, 3), (11, 768, 1032, 20, 0),
+]
+
+
+@pytest.mark.parametrize("B,C,L,K,p", CLASSES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_every_dispatch_class(oracle_mod, dtype, B, C, L, K, p):
+    print(f"case exact {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    run_exact(oracle_mod, B, C, L, K, p, dtype, seed=B + 3 * C + 5 * L + 7 * K)
+
+
+# Base pointers aligned to the element size only: x, w, dy and every output start one element into their buffers.
+@pytest.mark.parametrize("B,C,L,K,p", CLASSES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_on_element_aligned_views(oracle_mod, dtype, B, C, L, K, p):
+    print(f"case exact offset view {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    run_exact(oracle_mod, B, C, L, K, p, dtype, seed=1 + B + 3 * C + 5 * L + 7 * K, offset=1)
+
+
+# ... and views that keep 8-byte but not 16-byte alignment (the long-filter launchers take those)
+@pytest.mark.parametrize("B,C,L,K,p,dtype,offset", [
+    (2, 3, 512, 512, 511, "f32", 2), (2, 3, 512, 512, 511, "bf16", 4), (2, 3, 600, 64, 63, "f32", 2),
+    (7, 9, 3000, 48, 24, "bf16", 4), (40, 6, 48, 48, 24, "f32", 2), (40, 6, 48, 48, 24, "bf16", 2),
+    (9, 256, 3900, 64, 63, "f32", 3), (3, 4, 1024, 256, 255, "bf16", 3),
+])
+def test_exact_on_partly_aligned_views(oracle_mod, B, C, L, K, p, dtype, offset):
+    print(f"case exact offset {offset} {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    run_exact(oracle_mod, B, C, L, K, p, dtype, seed=5, offset=offset)
