@@ -1,0 +1,170 @@
+// Forward / input gradient (Sec. IV-A eq. (dwconv) and its adjoint), fp32 storage, rows brought from memory
+// straight into LDS.
+//
+// The contraction is that of corr_mfma_kernel (Y[n][r] = sum_d Toep_d[r][q] X[n + d][q] on v_mfma_f32_16x16x4_f32,
+// Toeplitz operands in registers); what differs is how a segment reaches the matrix cores.  Buffer loads with the
+// LDS bit write 16 bytes per lane into consecutive LDS slots: no staging registers, no copy through the vector ALU,
+// zeros outside the row from the hardware range check.  The wave's window (1024 + 16 (ND - 1) positions) is refilled
+// IN PLACE: a segment is processed in four quarters of 256 outputs; quarter i reads 16-blocks 16 i .. 16 i + 14 + ND,
+// so after it the floats [256 i, 256 i + 256) are dead and the loads of the NEXT segment for them are issued at
+// once.  The loads of a segment are therefore in flight for three quarters of an iteration on average instead of for
+// the matrix phase alone, and a wave needs 4.5 KiB of LDS and no prefetch registers.
+// Loads of a segment in issue order: r0 r1 r2 r3 (1 KiB each), then two 4-byte-per-lane tail loads ta tb.  The
+// vector-memory counter retires in order, so "everything quarter i reads has landed" is one constant s_waitcnt;
+// the stores share the counter and only make a wait stricter.
+// The four 16-byte granules of every 16-block are permuted in LDS (granule g of block nb sits at
+// g ^ ((nb >> 1) & 3)), which keeps the strided 16-byte operand reads conflict-free without padding; the
+// permutation is applied on the memory side, each lane fetching the granule that belongs in its LDS slot.
+#pragma once
+#include "dwconv_bwd_fused.hip.h"
+
+namespace dwconv {
+
+// (loads without the non-temporal hint: the weight-gradient call of the same step reads these rows again)
+__device__ __forceinline__ void buffer_load_x4_to_lds_keep(uintx4 rsrc, int byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void buffer_load_x1_to_lds_keep(uintx4 rsrc, int byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
+}
+
+constexpr int kCorrDirectWin = kSegLen + 128;      // floats per wave: 1024 + two 64-float tail loads
+
+template <int ND>
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_direct_kernel(
+    const float *__restrict__ in, const float *__restrict__ f, float *__restrict__ out, const CorrGeom g,
+    const RowsMap /* short rows take the register-staged kernel */)
+{
+    static_assert(ND >= 2 && 16 * (ND - 1) <= 128, "window tail is two 64-float loads");
+    constexpr int XW = kSegLen + 16 * (ND - 1);    // floats of the window that are ever read
+    __shared__ __align__(16) float s_in[kCorrWavesPerBlock][kCorrDirectWin];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i16 = lane & 15, k4 = lane >> 4;
+
+    const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    int row = __builtin_amdgcn_readfirstlane(wg / g.segs_per_row);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(wg % g.segs_per_row);
+    int c = __builtin_amdgcn_readfirstlane(row % g.C);
+    if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
+
+    float *sg = s_in[wave];                            // sg[swz_pos(i)] = in~[t0 + 16 dmin + i]
+    const unsigned lds_g = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) void *)sg);
+
+    // Toeplitz operands: A[d][v] (lane (r, k)) = f_eff[16 (dmin + d) + 4k + v - r + pad]
+    float A[ND][4];
+    auto load_filter = [&](int ch) {
+        const float *f_c = f + (size_t)ch * (size_t)g.K;
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int j = 16 * (g.dmin + d) + 4 * k4 + v - i16 + g.pad;
+                const bool ok = j >= 0 && j < g.K;
+                const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
+                const float a = f_c[jc];
+                A[d][v] = ok ? a : 0.f;
+            }
+    };
+    // operand of lane (block i16, group k4) for offset d: granule k4 of window block 16 i + i16 + d (i: the quarter)
+    const float *gx[ND];
+#pragma unroll
+    for (int d = 0; d < ND; ++d) gx[d] = sg + 16 * (i16 + d) + 4 * (k4 ^ (((i16 + d) >> 1) & 3));
+    // memory-side offsets (floats inside the window) of what belongs in the lane's LDS slot
+    const int fo_g = 4 * (4 * (lane >> 2) + ((lane & 3) ^ ((lane >> 3) & 3)));
+    int fo_gt[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int slot = kSegLen + 64 * h + lane;
+        const int nb = slot >> 4, gp = (slot >> 2) & 3, e = slot & 3;
+        const int fg = 16 * nb + 4 * (gp ^ ((nb >> 1) & 3)) + e;
+        fo_gt[h] = fg < XW ? fg : -1;
+    }
+
+    // resource of the segment the next loads belong to (wave-uniform); empty past the last segment
+    uintx4 rg;
+    int g_shift;                 // negative when the window starts before the row: added to the lane offsets
+    auto aim = [&](int prow, int pseg) {
+        if (prow < g.rows) {
+            const int v0 = 4 * (pseg * kSegLen + 16 * g.dmin);
+            g_shift = v0 < 0 ? v0 : 0;
+            rg = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, v0 > 0 ? v0 : 0);
+        } else {
+            g_shift = 0;
+            rg = uintx4{0u, 0u, 0u, kBufferFlags};
+        }
+    };
+    auto load_region = [&](auto ic) {       // i = 0..3
+        constexpr int i = decltype(ic)::value;
+        buffer_load_x4_to_lds_keep(rg, 4 * fo_g + (1024 * i + g_shift), lds_g + 1024u * (unsigned)i);
+    };
+    auto load_tails = [&]() {
+        buffer_load_x1_to_lds_keep(rg, fo_gt[0] >= 0 ? 4 * fo_gt[0] + g_shift : kOutOfRow, lds_g + 4096u);
+        buffer_load_x1_to_lds_keep(rg, fo_gt[1] >= 0 ? 4 * fo_gt[1] + g_shift : kOutOfRow, lds_g + 4096u + 256u);
+    };
+
+    // The loads of the first segment go out first, the filter loads of the first channel right behind them: the wait
+    // the compiler places in front of the first use of a filter value then covers both (one memory round trip at the
+    // start of a wave instead of two).
+    aim(row, seg);
+    static_for<0, 4>([&](auto ic) { load_region(ic); });
+    load_tails();
+    load_filter(c);
+    int cur_c = c;
+
+    for (;;) {
+        int seg_n = seg + g.step_seg;
+        const int carry = seg_n >= g.segs_per_row ? 1 : 0;
+        seg_n -= carry ? g.segs_per_row : 0;
+        const int row_n = row + g.step_rows + carry;
+        int c_n = c + g.step_c + carry;
+        c_n -= c_n >= g.C ? g.C : 0;
+        c_n -= c_n >= g.C ? g.C : 0;
+        float *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+        const bool whole = (seg + 1) * kSegLen <= g.L;
+        const int t_seg = seg * kSegLen;
+        aim(row_n, seg_n);
+        if (c != cur_c) {
+            load_filter(c);
+            cur_c = c;
+        }
+
+        static_for<0, 4>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            // six loads per segment (r0 r1 r2 r3 ta tb); before quarter i everything up to r_{i+1} (i < 3) or all of
+            // them has landed; i loads of the next segment have been issued since
+            constexpr int need = i < 3 ? i + 1 : 5;
+            wait_vmcnt_at_most<(5 - need) + i>();
+            float4 bv[ND];
+#pragma unroll
+            for (int d = 0; d < ND; ++d) bv[d] = *reinterpret_cast<const float4 *>(gx[d] + 256 * i);
+            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int d = 0; d < ND; ++d) {
+                acc = mfma16x16x4(A[d][0], bv[d].x, acc);
+                acc = mfma16x16x4(A[d][1], bv[d].y, acc);
+                acc = mfma16x16x4(A[d][2], bv[d].z, acc);
+                acc = mfma16x16x4(A[d][3], bv[d].w, acc);
+            }
+            // region i of the window is dead: refill it for the next segment
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            load_region(ic);
+            if constexpr (i == 3) load_tails();
+            // store tile i: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3
+            const int lt = 256 * i + 16 * i16 + 4 * k4;
+            if (whole || t_seg + lt + 3 < g.L)
+                st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+        });
+        if (row_n >= g.rows) break;
+        row = row_n; seg = seg_n; c = c_n;
+    }
+    // nothing may land in LDS after the wave has gone
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+}  // namespace dwconv

@@ -20,6 +20,7 @@
 #include "dwconv_longk.hip.h"
 #include "dwconv_mfma.hip.h"
 #include "dwconv_rowbatch.hip.h"
+#include "dwconv_corr_direct.hip.h"
 
 namespace dwhost {
 

@@ -46,8 +46,9 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
     const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
     // One resident round of waves, each walking segments wave, wave + n_waves, ...
-    auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po) -> int {
-        const long long resident = corr_wave_slots(kernel, kThreads);
+    auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po, long long slot_cap = kTargetWaves) -> int {
+        long long resident = corr_wave_slots(kernel, kThreads);
+        if (resident > slot_cap) resident = slot_cap;
         long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
         if (spw < 1) spw = 1;
         long long waves = (total_segs + spw - 1) / spw;
@@ -190,13 +191,31 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     }
     const T *pi = static_cast<const T *>(in), *pf = static_cast<const T *>(f);
     T *po = static_cast<T *>(out);
-    switch (nd) {
-    case 2: return launch(dwconv::corr_mfma_kernel<T, 2, false>, pi, pf, po);
-    case 3: return launch(dwconv::corr_mfma_kernel<T, 3, false>, pi, pf, po);
-    case 4: return launch(dwconv::corr_mfma_kernel<T, 4, false>, pi, pf, po);
-    case 5: return launch(dwconv::corr_mfma_kernel<T, 5, false>, pi, pf, po);
-    case 6: return launch(dwconv::corr_mfma_kernel<T, 6, false>, pi, pf, po);
-    default: break;
+    if constexpr (std::is_same<T, float>::value) {
+        // fp32, two to six block offsets: rows straight into LDS, refilled in place.  Fewer wave slots than a full
+        // resident round: a launch is the time its bytes take plus a fill and a drain that grow with the bytes in
+        // flight (B32 C256 L4096: K = 7 93 us with 8 waves per compute unit, 96 us with 12 or 16; K = 64 51.4 / 50.8 /
+        // 50.9 us with 8 / 12 / 16, the matrix pipe wanting more than two waves per SIMD there)
+        const long long cap = (long long)kComputeUnits * (nd <= 3 ? 8 : 12);
+        switch (nd) {
+        case 2: return launch(dwconv::corr_direct_kernel<2>, pi, pf, po, cap);
+        case 3: return launch(dwconv::corr_direct_kernel<3>, pi, pf, po, cap);
+        case 4: return launch(dwconv::corr_direct_kernel<4>, pi, pf, po, cap);
+        case 5: return launch(dwconv::corr_direct_kernel<5>, pi, pf, po, cap);
+        case 6: return launch(dwconv::corr_direct_kernel<6>, pi, pf, po, cap);
+        default: break;
+        }
+    }
+    if constexpr (!std::is_same<T, float>::value) {
+        // (bf16 rows that are not whole 16-byte granules: widened to fp32 on the way into LDS)
+        switch (nd) {
+        case 2: return launch(dwconv::corr_mfma_kernel<T, 2, false>, pi, pf, po);
+        case 3: return launch(dwconv::corr_mfma_kernel<T, 3, false>, pi, pf, po);
+        case 4: return launch(dwconv::corr_mfma_kernel<T, 4, false>, pi, pf, po);
+        case 5: return launch(dwconv::corr_mfma_kernel<T, 5, false>, pi, pf, po);
+        case 6: return launch(dwconv::corr_mfma_kernel<T, 6, false>, pi, pf, po);
+        default: break;
+        }
     }
     if constexpr (std::is_same<T, float>::value) {
         switch (nd) {
