@@ -17,6 +17,7 @@
 // permutation is applied on the memory side, each lane fetching the granule that belongs in its LDS slot.
 #pragma once
 #include "dwconv_bwd_fused.hip.h"
+#include "dwconv_bwd_fused_bf16.hip.h"
 
 namespace dwconv {
 
@@ -159,6 +160,132 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             const int lt = 256 * i + 16 * i16 + 4 * k4;
             if (whole || t_seg + lt + 3 < g.L)
                 st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+        });
+        if (row_n >= g.rows) break;
+        row = row_n; seg = seg_n; c = c_n;
+    }
+    // nothing may land in LDS after the wave has gone
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// bf16 storage (rows of whole 16-byte granules, L % 8 == 0): the same in-place scheme on v_mfma_f32_16x16x16_bf16 with
+// the raw bf16 window in LDS (2 bytes per position: a wave needs 2.25 KiB).  The window layout is that of the dY
+// window of bwd_fused_bf16_kernel (bf16_dy_pos: blocks permuted inside groups of four, the 16-byte halves of a block
+// swapped when bit 3 of the block index is set), which keeps the 8-byte operand reads of sixteen consecutive blocks
+// conflict-free.  Loads of a segment in issue order: g0 g1 (512 positions each), gt (128-position tail, two positions
+// per lane); 256-position chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt; positions [0, 512) are dead
+// after chunk 1, the rest after chunk 3.
+template <int ND>
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_direct_bf16_kernel(
+    const bf16_t *__restrict__ in, const bf16_t *__restrict__ f, bf16_t *__restrict__ out, const CorrGeom g,
+    const RowsMap /* short rows are an fp32 path */)
+{
+    static_assert(ND >= 2 && 16 * (ND - 1) <= 128, "window tail is one 128-element load");
+    constexpr int XWE = kSegLen + 16 * (ND - 1);   // elements of the window that are ever read
+    __shared__ __align__(16) short s_in[kCorrWavesPerBlock][kBf16FusedWin];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int i16 = lane & 15, kg = lane >> 4;
+
+    const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    int row = __builtin_amdgcn_readfirstlane(wg / g.segs_per_row);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(wg % g.segs_per_row);
+    int c = __builtin_amdgcn_readfirstlane(row % g.C);
+    if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
+
+    const short *sg = s_in[wave];
+    const unsigned lds_g = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) const void *)sg);
+
+    // Toeplitz operands: A[d][e] (lane (r, kg)) = f_eff[16 (dmin + d) + 4 kg + e - r + pad]
+    shortx4 A[ND];
+    auto load_filter = [&](int ch) {
+        const bf16_t *f_c = f + (size_t)ch * (size_t)g.K;
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = 16 * (g.dmin + d) + 4 * kg + e - i16 + g.pad;
+                const bool ok = j >= 0 && j < g.K;
+                const int jc = ok ? (g.reverse ? (g.K - 1 - j) : j) : 0;
+                const uint16_t bits = f_c[jc].bits;
+                A[d][e] = ok ? (short)bits : (short)0;
+            }
+    };
+    const short *gx[ND];            // operand: elements 4 kg .. 4 kg + 3 of window block i16 + d (the chunk in the immediate offset)
+#pragma unroll
+    for (int d = 0; d < ND; ++d) gx[d] = sg + bf16_dy_pos(i16 + d, 4 * kg);
+    // memory side of the loads (bytes): what belongs in the lane's LDS slot
+    const int pb = lane >> 1;                                           // position block of the lane's 16-byte granule
+    const int off_g = 32 * bf16_block_pos(pb) + 16 * ((lane & 1) ^ ((pb >> 3) & 1));
+    const int tnb = 64 + bf16_block_pos(lane >> 3);                     // tail: LDS elements 1024 + 2 lane, + 1
+    const int te = 2 * (lane & 7);
+    const int tail_g = 16 * tnb + 4 * ((te >> 2) ^ (2 * ((tnb >> 3) & 1))) + (te & 3);
+    const int off_gt = tail_g < XWE ? 2 * tail_g : kOutOfRow;
+
+    uintx4 rg;
+    int g_shift;
+    auto aim = [&](int prow, int pseg) {
+        if (prow < g.rows) {
+            const int v0 = 2 * (pseg * kSegLen + 16 * g.dmin);
+            g_shift = v0 < 0 ? v0 : 0;
+            rg = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, v0 > 0 ? v0 : 0);
+        } else {
+            g_shift = 0;
+            rg = uintx4{0u, 0u, 0u, kBufferFlags};
+        }
+    };
+    auto load_half = [&](auto hc) {
+        constexpr int h = decltype(hc)::value;
+        buffer_load_x4_to_lds_keep(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
+    };
+    auto load_tail = [&]() {
+        buffer_load_x1_to_lds_keep(rg, off_gt == kOutOfRow ? kOutOfRow : off_gt + g_shift, lds_g + 2048u);
+    };
+
+    aim(row, seg);
+    load_half(std::integral_constant<int, 0>{});
+    load_half(std::integral_constant<int, 1>{});
+    load_tail();
+    load_filter(c);
+    int cur_c = c;
+
+    for (;;) {
+        int seg_n = seg + g.step_seg;
+        const int carry = seg_n >= g.segs_per_row ? 1 : 0;
+        seg_n -= carry ? g.segs_per_row : 0;
+        const int row_n = row + g.step_rows + carry;
+        int c_n = c + g.step_c + carry;
+        c_n -= c_n >= g.C ? g.C : 0;
+        c_n -= c_n >= g.C ? g.C : 0;
+        bf16_t *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+        const bool whole = (seg + 1) * kSegLen <= g.L;
+        const int t_seg = seg * kSegLen;
+        aim(row_n, seg_n);
+        if (c != cur_c) {
+            load_filter(c);
+            cur_c = c;
+        }
+        static_for<0, 4>([&](auto cc) {
+            constexpr int c4 = decltype(cc)::value;
+            // three loads per segment (g0 g1 gt); one load of the next segment is out after chunk 1
+            constexpr int need = c4 == 0 ? 0 : (c4 < 3 ? 1 : 2), issued = c4 >= 2 ? 1 : 0;
+            wait_vmcnt_at_most<(2 - need) + issued>();
+            shortx4 bv[ND];
+#pragma unroll
+            for (int d = 0; d < ND; ++d) bv[d] = *reinterpret_cast<const shortx4 *>(gx[d] + 256 * c4);
+            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int d = 0; d < ND; ++d) acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A[d], bv[d], acc, 0, 0, 0);
+            if constexpr (c4 == 1 || c4 == 3) {
+                // half c4 / 2 of the window is dead: refill it for the next segment
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                load_half(std::integral_constant<int, c4 / 2>{});
+                if constexpr (c4 == 3) load_tail();
+            }
+            // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the chunk
+            const int lt = 256 * c4 + 16 * i16 + 4 * kg;
+            if (whole || t_seg + lt + 3 < g.L) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;
