@@ -198,7 +198,8 @@ DwPlan plan_dw(const Shape &s)
     }
     long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) && (s.L % 4) == 0 && s.L <= kMfmaMaxL;
+    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) && ((s.L % 4) == 0 || ragged_rows_ok(s, nd)) &&
+                            s.L <= kMfmaMaxL;
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
     // waves takes a whole channel: no slices, no second stage.
     p.wpb = dwconv::kWavesPerBlock;
@@ -206,7 +207,11 @@ DwPlan plan_dw(const Shape &s)
     p.dw_nc = 1;
     if (mfma_shape && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) && s.C % kComputeUnits == 0 &&
         s.C / kComputeUnits <= 3) {
-        const int wpb = 16 / (s.C / kComputeUnits);
+        int wpb = 16 / (s.C / kComputeUnits);
+        // short filters leave the matrix pipe idle, and what then counts is how many bytes the chip has in flight:
+        // two rows of 4 KiB per wave are enough with 8 to 12 waves per compute unit (B64 C512 L2048 K7: 82 us against
+        // 87 us with 16 waves; bf16 B128 C768 L1024 K32: 59.6 against 60.8 us)
+        if (nd <= 3 && s.C / kComputeUnits >= 2) wpb = 4;
         // (sixteen-row units of rows longer than 48 positions need more LDS than sixteen waves have)
         const bool fits = (!p.rows.batch || dwconv::rb_dw_lds_bytes(s.L, nd, wpb, 1) <= kMaxLdsBytes) &&
                           (nd <= kMfmaMaxND || dwconv::dw_direct_lds_bytes(nd, wpb) <= kMaxLdsBytes);
@@ -444,8 +449,9 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
     if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type, L % 4 == 0
     if (dtype == DWCONV_BF16 && p.rows.on) return 0;
-    return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && (L % (dtype == DWCONV_BF16 ? 8 : 4)) == 0 &&
-            L <= kMfmaMaxL) ? 1 : 0;
+    const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_ok(s, nd) : true)))
+                                               : ((L % 4) == 0 || ragged_rows_ok(s, nd));
+    return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && rows_fit && L <= kMfmaMaxL) ? 1 : 0;
 }
 
 int dwconv_bwd_weight_single_pass(int B, int C, int L, int K, int pad_left, int dtype)

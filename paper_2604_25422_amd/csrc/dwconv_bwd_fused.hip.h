@@ -230,8 +230,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
                 const int e = rows_element(rm, t_seg + lt);         // the four outputs are in one row or in one gap
                 if (e >= 0) st_elem4_stream(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]));
             } else {
-                if (whole || t_seg + lt + 3 < L)
-                    st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, L);
             }
         });
         b = b_n; seg = seg_n;

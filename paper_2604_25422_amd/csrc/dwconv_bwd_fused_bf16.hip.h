@@ -183,7 +183,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
             }
             // ---- store tile c4: lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
-            if (whole || t_seg + lt + 3 < L) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, L);
         });
         b = b_n; seg = seg_n;
     }

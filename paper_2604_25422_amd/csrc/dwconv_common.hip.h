@@ -57,4 +57,18 @@ __device__ __forceinline__ void st_elem4_stream(bf16_t *p, float4 v)
     __builtin_nontemporal_store(u, reinterpret_cast<nt_uintx2 *>(p));
 }
 
+// Four consecutive outputs at positions t .. t + 3 of a row of L positions, the last group of a row possibly
+// partial (rows whose length is not a multiple of four): whole groups as one streaming store, the rest by element.
+template <typename T>
+__device__ __forceinline__ void st_elem4_stream_upto(T *p, float4 v, int t, int L)
+{
+    if (t + 3 < L) {
+        st_elem4_stream(p, v);
+    } else {
+        if (t < L) st_elem(p, v.x);
+        if (t + 1 < L) st_elem(p + 1, v.y);
+        if (t + 2 < L) st_elem(p + 2, v.z);
+    }
+}
+
 }  // namespace dwconv

@@ -158,8 +158,8 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             if constexpr (i == 3) load_tails();
             // store tile i: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3
             const int lt = 256 * i + 16 * i16 + 4 * k4;
-            if (whole || t_seg + lt + 3 < g.L)
-                st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;
@@ -285,7 +285,8 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             }
             // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the chunk
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
-            if (whole || t_seg + lt + 3 < g.L) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;

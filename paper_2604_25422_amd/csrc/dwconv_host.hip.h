@@ -63,6 +63,17 @@ inline int mfma_max_nd_dw(const Shape &s)
     }
     return kMfmaMaxND;
 }
+// Rows that are not whole 16-byte granules (fp32 lengths that are not multiples of four, tensors whose base is only
+// element-aligned; bf16: even lengths that are not multiples of eight).  The kernels that bring rows straight into
+// LDS take them when every row starts on a dword: their loads are range-checked per dword, so a granule that
+// straddles the end of its row is completed with zeros, and the last outputs of a row are stored by element.  Two to
+// six block offsets, and rows long enough that 1024-position segments are not mostly padding.
+constexpr int kRaggedMinL = 768;
+inline bool ragged_rows_ok(const Shape &s, int nd)
+{
+    return s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && s.L >= kRaggedMinL &&
+           (s.dtype == DWCONV_F32 || (s.L % 2) == 0);
+}
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 

@@ -102,12 +102,18 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     if (p.longk) return -1;
     if (p.rows.batch) return launch_bwd_rowbatch<T>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
     if (s.dtype == DWCONV_BF16 && p.rows.on) return -1;      // bf16 virtual rows: the two separate kernels
-    // bf16: whole 16-byte granules of 8 elements
-    if (s.dtype == DWCONV_BF16 && (s.L % 8) != 0) return -1;
+    // bf16: rows that start on a dword
+    if (s.dtype == DWCONV_BF16 && (s.L % 2) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
-    if (!aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || s.L > kMfmaMaxL) return -1;
+    // whole 16-byte granules; otherwise rows that start on a dword (see ragged_rows_ok), ordinary rows only
+    const bool granular = (s.L % (s.dtype == DWCONV_BF16 ? 8 : 4)) == 0 && aligned_to(x, 16) && aligned_to(dy, 16) && aligned_to(dx, 16);
+    if (!granular) {
+        const bool short_ok = s.dtype == DWCONV_BF16 && (s.L % 4) == 0;      // (bf16 rows in granules of four: any ordinary length)
+        if ((!short_ok && !ragged_rows_ok(s, nd)) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4))
+            return -1;
+    }
     void *direct = (p.single && p.S == 1) ? dw_out : nullptr;
     int rc = -1;
     switch (nd) {

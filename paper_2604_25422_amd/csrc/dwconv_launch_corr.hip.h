@@ -27,8 +27,10 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
 {
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
-    if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || s.L > kMfmaMaxL) return -1;
+    // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
+    const bool granular = (s.L % 4) == 0 && aligned_to(in, 4 * sizeof(T)) && aligned_to(out, 4 * sizeof(T));
+    if (!granular && (!ragged_rows_ok(s, nd) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
     // block offsets the long-filter kernel takes too (fp32 eleven to sixteen, bf16 seven to sixteen): only where rows
     // fill their 1024-position segments to three quarters (shorter rows do less work on the long-filter kernel,
     // which contracts in-row block pairs only)
@@ -71,6 +73,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         return launch_status();
     };
     const RowsPlan rp = plan_rows(s);
+    if (!granular && (rp.on || rp.batch)) return -1;       // (short rows of a tensor that is only element-aligned)
     if (rp.batch) {
         // rows of at most 128 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
         dwconv::RowBatchGeom rg;
@@ -166,7 +169,8 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     }
     if constexpr (sizeof(T) == 2) {
         // bf16 storage: the bf16 matrix instruction when 16-byte granules of 8 elements line up
-        if ((s.L % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
+        const bool whole8 = (s.L % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16);
+        if (whole8 || (nd <= kMfmaMaxND && (s.L % 2) == 0 && aligned_to(in, 4) && aligned_to(out, 4))) {
             const bf16_t *pi = static_cast<const bf16_t *>(in), *pf = static_cast<const bf16_t *>(f);
             bf16_t *po = static_cast<bf16_t *>(out);
             {
@@ -182,6 +186,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                 default: break;
                 }
             }
+            if (!whole8) return -1;
             switch (nd) {
             case 7: return launch(dwconv::corr_mfma_bf16_kernel<7>, pi, pf, po);
             case 8: return launch(dwconv::corr_mfma_bf16_kernel<8>, pi, pf, po);
@@ -214,8 +219,9 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         default: break;
         }
     }
+    if (!granular) return -1;
     if constexpr (!std::is_same<T, float>::value) {
-        // (bf16 rows that are not whole 16-byte granules: widened to fp32 on the way into LDS)
+        // (bf16 rows of odd length in whole granules of four: widened to fp32 on the way into LDS)
         switch (nd) {
         case 2: return launch(dwconv::corr_mfma_kernel<T, 2, false>, pi, pf, po);
         case 3: return launch(dwconv::corr_mfma_kernel<T, 3, false>, pi, pf, po);

@@ -83,8 +83,8 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const T *>(x),
                            static_cast<const T *>(dy), part, static_cast<T *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin,
                            p.tiles_per_row, p.rows.map);
-    } else if ((s.L % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
-        // bf16 rows of whole 16-byte granules: raw rows straight into LDS, bf16 matrix instruction
+    } else if ((s.L % 2) == 0 && aligned_to(x, 4) && aligned_to(dy, 4)) {
+        // bf16 rows that start on a dword: raw rows straight into LDS, bf16 matrix instruction
         auto kernel = dwconv::dw_partial_bf16_kernel<ND, W>;
         constexpr size_t lds = dwconv::dw_bf16_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
@@ -124,8 +124,10 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || (s.L % 4) != 0 || s.L > kMfmaMaxL) return -1;
-    if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T))) return -1;
+    if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || s.L > kMfmaMaxL) return -1;
+    // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
+    const bool granular = (s.L % 4) == 0 && aligned_to(x, 4 * sizeof(T)) && aligned_to(dy, 4 * sizeof(T));
+    if (!granular && (!ragged_rows_ok(s, nd) || p.rows.on || p.rows.batch || !aligned_to(x, 4) || !aligned_to(dy, 4))) return -1;
     if constexpr (std::is_same<T, float>::value) {
         if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
     } else {

@@ -132,7 +132,11 @@ def test_single_pass_query(lib):
     assert f(4, 64, 1024, 16, 15, 0) == 1            # ... but at most four segments per wave: launch-bound, one kernel
     assert f(8, 256, 8192, 8192, 8191, 0) == 0       # long filter: two zero-filled slices
     assert f(1, 256, 1024, 16, 15, 0) == 1           # a single segment per channel: one kernel as well
-    assert f(32, 256, 4098, 64, 63, 0) == 0          # row length not a multiple of 4
+    assert f(32, 256, 4098, 64, 63, 0) == 1          # row length not a multiple of 4: rows still start on a dword
+    assert f(32, 256, 4098, 128, 127, 0) == 0        # ... but only up to six block offsets
+    assert f(128, 768, 1026, 32, 31, 1) == 1 and f(128, 768, 1025, 32, 31, 1) == 0      # bf16: even lengths
+    assert lib.dwconv_bwd_is_fused(32, 256, 4098, 64, 63, 0) == 1 and lib.dwconv_bwd_is_fused(32, 256, 4097, 64, 63, 1) == 0
+    assert lib.dwconv_bwd_is_fused(4, 8, 500, 64, 63, 0) == 1 and lib.dwconv_bwd_is_fused(4, 8, 502, 64, 63, 0) == 0
     # seventeen to thirty-two block offsets: two launches over halves of the offsets, each into its own slices,
     # so an even number of slices and never one kernel - also for small problems, in either storage type
     S226, S256 = lib.dwconv_bwd_weight_slices(32, 256, 4096, 226, 225, 0), lib.dwconv_bwd_weight_slices(32, 256, 4096, 256, 255, 0)

@@ -95,6 +95,10 @@ CLASSES = [
     # short rows: sixteen rows per tile (with channel pairs), rows of five to eight blocks, virtual rows
     (40, 6, 48, 48, 24), (100, 3, 48, 48, 0), (17, 3, 16, 16, 15), (33, 2, 80, 48, 24), (130, 2, 128, 31, 15),
     (70, 256, 48, 48, 24), (300, 12, 200, 31, 15), (64, 2, 512, 64, 63), (50, 3, 132, 16, 15),
+    # rows that are not whole 16-byte granules on the kernels that load rows straight into LDS (fp32: any length from
+    # 768 positions; bf16: even lengths), ragged last segments, rows that end one, two and three positions into a granule
+    (2, 3, 2050, 64, 63), (3, 5, 4097, 31, 15), (2, 4, 1026, 7, 3), (3, 2, 1027, 66, 0), (5, 3, 769, 16, 15), (2, 2, 3075, 48, 24),
+    (4, 256, 2049, 64, 63), (3, 2, 1030, 33, 16), (2, 3, 5001, 20, 19),
     # one workgroup per channel: the weight gradient as a single kernel
     (9, 256, 3900, 64, 63), (4, 512, 4096, 7, 3), (11, 768, 1032, 20, 0),
 ]
