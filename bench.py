@@ -310,15 +310,23 @@ def main():
     tflops = flops / us[dom] / 1e6
     mfma_peak = MFMA_F32_PEAK_TFLOPS if wl.dtype == "f32" else MFMA_BF16_PEAK_TFLOPS
     mfma_frac = tflops / mfma_peak
-    traffic = measured_traffic(args.workload, dom)
+    # HBM bytes per launch of the dominant kernel from the committed counter summary, if one exists and the kernel's
+    # sources have not changed since (a stale figure is withheld)
+    tm = measured_traffic(args.workload, dom)
+    traffic = tm[0] if tm and not tm[2] else None
+    traffic_note = ({"profile": tm[1], "stale": tm[2]} if tm else None)
     if hbm_frac >= mfma_frac:
         out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                            "unit": "GB/s", "frac": round(hbm_frac, 4), "traffic": traffic,
-                           "kernel_us": round(us[dom], 2), "algorithmic_bytes": path_bytes}
+                           "traffic_from": traffic_note, "kernel_us": round(us[dom], 2),
+                           "kernel_us_median": round(us_median[dom], 2), "kernel_us_min": round(us_min[dom], 2),
+                           "algorithmic_bytes": path_bytes}
     else:
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": round(tflops, 2), "peak": mfma_peak,
                            "unit": "TFLOP/s", "frac": round(mfma_frac, 4), "traffic": traffic,
-                           "kernel_us": round(us[dom], 2), "algorithmic_flops": flops}
+                           "traffic_from": traffic_note, "kernel_us": round(us[dom], 2),
+                           "kernel_us_median": round(us_median[dom], 2), "kernel_us_min": round(us_min[dom], 2),
+                           "algorithmic_flops": flops}
     if fused:
         n_elems = wl.B * wl.C * wl.L
         fused_step_bytes = (5 * n_elems + 3 * wl.C * K) * es        # fwd 2N + CK, fused backward 3N + 2CK
@@ -328,7 +336,8 @@ def main():
         fused["bwd_gbps"] = round(fused_bwd_bytes / (fused["bwd_us"] * 1e-6) / 1e9, 1)
         fused["bwd_frac_of_hbm_peak"] = round(fused["bwd_gbps"] / HBM_PEAK_GBPS, 4)
         fused["speedup_vs_three_calls"] = round(ms_per_step * 1e3 / fused["us_per_step"], 3)
-        fused["bwd_traffic"] = measured_traffic(args.workload, "bwd_fused")
+        tb = measured_traffic(args.workload, "bwd_fused")
+        fused["bwd_traffic"] = tb[0] if tb and not tb[2] else None
         out["fused_backward"] = fused
     # the achievable ceiling beside the published peak: a plain device copy of 1 GiB, which nothing caches
     del sets

@@ -275,6 +275,25 @@ DwPlan plan_dw(const Shape &s)
         p.lk_wgs = (nd + per_wg - 1) / per_wg;
         p.lk_table = longk_dw_table(s, p.lk_wgs, &p.lk_gd);
     }
+    p.manypass = false;
+    if (!p.lk_table && nd > mfma_max_nd_dw(s) && s.dtype == DWCONV_F32 && (s.L % 4) == 0 && s.L >= kRaggedMinL &&
+        s.L <= kMfmaMaxL && !p.rows.on) {
+        // filters (or rows) too long for the long-filter kernel's LDS: the register-resident kernel, sixteen block
+        // offsets per launch, every launch adding the taps it owns to one of two zero-filled sets of slices
+        p.manypass = true;
+        p.single = false;
+        p.wpb = dwconv::kWavesPerBlock;
+        p.passes = (nd + kMfmaMaxNDDw - 1) / kMfmaMaxNDDw;
+        long long sp = (kTargetWaves / p.wpb + s.C - 1) / s.C;       // workgroups per channel and launch
+        const long long all_items = (long long)s.B * (((long long)s.L + kDwTT - 1) / kDwTT);
+        if (sp > (all_items + p.wpb - 1) / p.wpb) sp = (all_items + p.wpb - 1) / p.wpb;
+        if (sp < 1) sp = 1;
+        p.S = (int)(2 * sp);
+        p.S_fused = p.S;
+        p.tiles_per_row = (int)(((long long)s.L + kDwTT - 1) / kDwTT);
+        p.valu_items_per_slice = (int)((all_items + p.S - 1) / p.S);
+        p.items_per_slice = p.valu_items_per_slice;
+    }
     if (p.lk_table) {
         p.longk = true;
         p.S = 2;

@@ -108,11 +108,15 @@ constexpr size_t dw_direct_lds_bytes(int ND, int W) { return (size_t)W * (size_t
 // ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap); B is then 1 and segs_per_row the
 // number of segments of the virtual row.
 // [j0, j1): the taps this launch owns, at most dw_direct_row_floats(ND) of them (0, K unless the block offsets of the
-// filter are split over two launches); the other taps of its slices are written as zeros.
+// filter are split over several launches); the other taps of its slices are written as zeros, or, with own_only set,
+// left alone (filters with hundreds of block offsets: dozens of launches share two zero-filled sets of slices).
+// seg0: the first 1024-position segment of every row this launch walks (segs_per_row of them): a launch over offsets
+// far from lag 0 skips the segments whose x window lies outside the row.
 template <int ND, int W, bool ROWS>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_kernel(
     const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, float *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, const RowsMap rm, int j0, int j1)
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, const RowsMap rm, int j0, int j1, int seg0,
+    int own_only)
 {
     constexpr int XW = kSegLen + 16 * ND;          // staged x window (floats)
     constexpr int NGX = XW / 4;                    // its 16-byte granules: 4 full loads and a tail
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
                 // batches are walked from the last to the first: the input-gradient call that usually runs just
                 // before this one walks them upwards, so its last rows of dY are still in the last-level cache
                 const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
-                const int t0 = pseg * kSegLen;
+                const int t0 = (seg0 + pseg) * kSegLen;
                 const int u0 = 4 * (t0 + 16 * dmin);
                 x_shift = u0 < 0 ? u0 : 0;
                 // (a window that starts past the end of the row - possible when dmin > 0, the second of two passes
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     static_assert(WREG >= ((16 * ND + 15) * 17 + 3) / 4 * 4, "diagonal image fits the wave's region");
     dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, j0, j1, pad, dmin);
     __syncthreads();
-    for (int j = tid; j < K; j += 64 * W) {
+    for (int j = own_only ? j0 + tid : tid; j < (own_only ? j1 : K); j += 64 * W) {
         float sum = 0.f;
         if (j >= j0 && j < j1) {
 #pragma unroll

@@ -161,6 +161,8 @@ struct DwPlan {
     std::shared_ptr<const dwconv::LongKDwTable> lk_table;   // which offsets every wave slot owns
     int S;                 // partial slices per coefficient (all passes together)
     int passes;            // launches of the stage-1 kernel, each over part of the block offsets into S / passes slices
+    bool manypass;         // filters beyond the long-filter kernel's LDS: `passes` launches of sixteen offsets into TWO
+                           // zero-filled sets of S / 2 slices (even launches the first set, odd launches the second)
     RowsPlan rows;         // short rows: stage 1 walks the virtual row of a channel
     int wpb;               // waves per block of the matrix-core stage-1 kernels
     int dw_nc;             // short rows, sixteen-row units: channels per block of the stage-1 kernel (1 or 2)

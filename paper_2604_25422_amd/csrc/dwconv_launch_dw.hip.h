@@ -65,14 +65,14 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
             hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                                static_cast<const float *>(x), static_cast<const float *>(dy), part,
                                static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map, 0,
-                               s.K);
+                               s.K, 0, 0);
         } else {
             auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
             if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
             hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                                static_cast<const float *>(x), static_cast<const float *>(dy), part,
                                static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map,
-                               0, s.K);
+                               0, s.K, 0, 0);
         }
     } else if (p.rows.on) {
         // bf16 short rows (longer than 64 positions): the virtual row of a channel, widened to fp32 through registers
@@ -124,6 +124,14 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
+    if (p.manypass) {
+        if constexpr (std::is_same<T, float>::value) {
+            if (!aligned_to(x, 16) || !aligned_to(dy, 16)) return -1;
+            return launch_dw_partial_wide_f32(x, dy, part, nullptr, s, p, dmin, nd, st);
+        } else {
+            return -1;
+        }
+    }
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(x, 4 * sizeof(T)) && aligned_to(dy, 4 * sizeof(T));

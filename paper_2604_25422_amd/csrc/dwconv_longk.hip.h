@@ -158,6 +158,126 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_kernel(const T *__re
 }
 
 // ------------------------------------------------------------------------------------------------
+// Filters or rows beyond what LDS holds whole (K or L above 8192): the same kernel in tiles.
+// A workgroup owns one PIECE of 4096 outputs of a row pair and walks the filter in CHUNKS of 4096 taps.  For chunk ck
+// the operator restricted to taps [4096 ck, 4096 ck + 4096) is the operator of a 4096-tap filter with pad
+// pad - 4096 ck (any integer: the block offsets that can hold one of its taps follow from the same inequalities),
+// and its contribution to the piece needs the input window of 4096 + 4096 + 30 positions that those offsets reach:
+// both are staged (the filter chunk with zero margins, so that the taps of the neighbouring chunks inside its edge
+// blocks count as zeros here; the window with zeros outside the row), the sixteen waves add the chunk's
+// contribution to the accumulators of their tile (256 outputs x 2 rows), and the next chunk is staged.  A chunk whose
+// window misses the row is skipped, so a causal filter costs its triangle, not the square.
+constexpr int kLkTilePiece = 4096;                       // outputs per workgroup and row
+constexpr int kLkTileChunk = 4096;                       // taps staged at a time
+constexpr int kLkTileWinBlocks = kLkTilePiece / 16 + kLkTileChunk / 16 + 4;    // 16-blocks of a staged window (516)
+
+struct LongKTileGeom {
+    int B, C, L, K;
+    int pad;        // effective pad of this correlation
+    int reverse;    // filter index reversed (input gradient)
+    int NB;         // 16-blocks per row, ceil(L / 16)
+    int NP;         // pieces per row
+    int NCK;        // filter chunks
+};
+inline size_t longk_tiled_lds_bytes()
+{
+    return sizeof(float) * ((size_t)(kLkTileChunk + 2 * kLkWMargin) + (size_t)kLkRows * kLkTileWinBlocks * kLdsBlockStride);
+}
+
+template <typename T>
+__global__ __launch_bounds__(64 * kLkWaves) void corr_longk_tiled_kernel(const T *__restrict__ in, const T *__restrict__ f,
+                                                                          T *__restrict__ out, const LongKTileGeom g)
+{
+    extern __shared__ __align__(16) float lkt_smem[];
+    constexpr int FWT = kLkTileChunk + 2 * kLkWMargin;
+    constexpr int XR = kLkTileWinBlocks * kLdsBlockStride;
+    float *fw = lkt_smem;                                    // fw[kLkWMargin + jj] = tap 4096 ck + jj, zero outside the chunk
+    float *xr = lkt_smem + FWT;                              // two staged windows
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int t = __builtin_amdgcn_readfirstlane(tid >> 6);     // the wave's tile of the piece
+    const int i16 = lane & 15;
+    const int k4 = lane >> 4;
+    const int c = blockIdx.x;
+    const int a = g.NP - 1 - (int)(blockIdx.y % (unsigned)g.NP);     // piece (the dear ones of a causal filter first)
+    const int b0 = 2 * (int)(blockIdx.y / (unsigned)g.NP);
+    const int n0 = (kLkTilePiece / 16) * a + 16 * t;                 // row block of the tile's first output block
+    const T *f_c = f + (size_t)c * (size_t)g.K;
+
+    floatx4 tot0 = floatx4{0.f, 0.f, 0.f, 0.f}, tot1 = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int ck = 0; ck < g.NCK; ++ck) {
+        const int klen = min(kLkTileChunk, g.K - ck * kLkTileChunk);
+        const int padc = g.pad - ck * kLkTileChunk;
+        // block offsets that can hold a tap of the chunk (arithmetic shifts: floor division)
+        const int dminc = -((padc + 15) >> 4), dmaxc = (klen - padc + 14) >> 4;
+        const int wlo = (kLkTilePiece / 16) * a + dminc;             // row block of window block 0
+        const int nwb = kLkTilePiece / 16 + (dmaxc - dminc);         // window blocks
+        if (wlo + nwb - 1 < 0 || wlo >= g.NB) continue;              // the window misses the row (block-uniform)
+        __syncthreads();                                             // everyone is done with the previous chunk
+        for (int i = tid; i < FWT; i += 64 * kLkWaves) {
+            const int jj = i - kLkWMargin;
+            float v = 0.f;
+            if (jj >= 0 && jj < klen) {
+                const int j = ck * kLkTileChunk + jj;
+                v = ld_elem(f_c + (g.reverse ? (g.K - 1 - j) : j));
+            }
+            fw[i] = v;
+        }
+        for (int rb = 0; rb < kLkRows; ++rb) {
+            float *xrow = xr + rb * XR;
+            const int b = b0 + rb;
+            const T *in_row = in + ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            for (int gi = tid; gi < nwb * 4; gi += 64 * kLkWaves) {
+                const int m = wlo + (gi >> 2);
+                const int u = 16 * m + 4 * (gi & 3);
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (b < g.B && m >= 0 && u + 3 < g.L) v = ld_elem4(in_row + u);
+                *reinterpret_cast<float4 *>(xrow + (gi >> 2) * kLdsBlockStride + (gi & 3) * 4) = v;
+            }
+        }
+        __syncthreads();
+        // offsets for which some block n0 + j + d of the tile lies inside the row
+        const int dlo = max(dminc, -(n0 + 15));
+        const int dhi = min(dmaxc, g.NB - 1 - n0);
+        if (dlo <= dhi && b0 < g.B) {
+            // A: lane (r = i16, k4) reads chunk tap 16 d + 4 k4 + v - r + padc;  B: lane (j = i16, k4) reads window block 16 t + j + d - dminc
+            const float *ap = fw + kLkWMargin + 16 * dlo + 4 * k4 - i16 + padc;
+            const float *bp = xr + (16 * t + i16 + (dlo - dminc)) * kLdsBlockStride + 4 * k4;
+            for (int d0 = dlo; d0 <= dhi; d0 += kLkFold) {
+                const int n = min(kLkFold, dhi - d0 + 1);
+                floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                for (int i = 0; i < n; ++i) {
+                    const float a0 = ap[0], a1 = ap[1], a2 = ap[2], a3 = ap[3];
+                    const float4 x0 = *reinterpret_cast<const float4 *>(bp);
+                    const float4 x1 = *reinterpret_cast<const float4 *>(bp + XR);
+                    acc0 = mfma16x16x4(a0, x0.x, acc0);
+                    acc1 = mfma16x16x4(a0, x1.x, acc1);
+                    acc0 = mfma16x16x4(a1, x0.y, acc0);
+                    acc1 = mfma16x16x4(a1, x1.y, acc1);
+                    acc0 = mfma16x16x4(a2, x0.z, acc0);
+                    acc1 = mfma16x16x4(a2, x1.z, acc1);
+                    acc0 = mfma16x16x4(a3, x0.w, acc0);
+                    acc1 = mfma16x16x4(a3, x1.w, acc1);
+                    ap += 16;
+                    bp += kLdsBlockStride;
+                }
+                tot0 += acc0;
+                tot1 += acc1;
+            }
+        }
+    }
+    // lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3 of the tile
+    const int to = 16 * n0 + 16 * i16 + 4 * k4;
+    if (b0 < g.B && to + 3 < g.L) {
+        T *o0 = out + ((size_t)b0 * (size_t)g.C + (size_t)c) * (size_t)g.L + to;
+        st_elem4(o0, make_float4(tot0[0], tot0[1], tot0[2], tot0[3]));
+        if (b0 + 1 < g.B) st_elem4(o0 + (size_t)g.C * (size_t)g.L, make_float4(tot1[0], tot1[1], tot1[2], tot1[3]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // The same correlation for bf16 storage on the bf16 matrix instruction (v_mfma_f32_16x16x16_bf16): one
 // instruction covers a whole block offset of one row (products of two bf16 are exact in fp32, sums fp32, one
 // rounding at the store), so per offset a wave issues kLkRows instructions instead of 4 kLkRows.

@@ -40,21 +40,46 @@ def in_range_flops(B, C, L, K, pad_left):
     return 2 * B * C * taps
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, FETCH_SIZE
-# scaled by 2.00 and WRITE_SIZE by 1.00: what the same counters read for a plain 128 MiB device copy).
-# Keyed by (workload index, kernel); the figures and the commands are in the text summaries under profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    (1, "fwd"): 262325 * 1024, (1, "dx"): 262325 * 1024, (1, "dw_partial"): 268418 * 1024, (1, "bwd_fused"): 407515 * 1024,
-    (2, "fwd"): 525294 * 1024, (2, "dx"): 525294 * 1024, (2, "dw_partial"): 539684 * 1024, (2, "bwd_fused"): 831299 * 1024,
-    (3, "fwd"): 163881 * 1024, (3, "dx"): 163881 * 1024, (3, "dw_partial"): 271351 * 1024,
-    (4, "fwd"): 393355 * 1024, (4, "dx"): 393355 * 1024, (4, "dw_partial"): 396139 * 1024, (4, "bwd_fused"): 598836 * 1024,
-    (8, "fwd"): 69698 * 1024, (8, "dx"): 69698 * 1024, (8, "dw_partial"): 188048 * 1024,
-    (7, "fwd"): 393537 * 1024, (7, "dx"): 393537 * 1024, (7, "dw_partial"): 394072 * 1024,
-    (6, "fwd"): 262396 * 1024, (6, "dx"): 262396 * 1024, (6, "dw_partial"): 273273 * 1024,
-    (5, "fwd"): 786611 * 1024, (5, "dx"): 786611 * 1024, (5, "dw_partial"): 786934 * 1024, (5, "bwd_fused"): 1234118 * 1024,
-}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE come from the text summaries under
+# profiles/: every summary carries, per kernel, one line of the form
+#     TRAFFIC workload=<index> kernel=<fwd|dx|dw_partial|bwd_fused> bytes=<n> sources=<a.h,b.h> digest=<12 hex digits>
+# where digest is kernel_sources_digest(sources) at the time of the counter run.  A figure whose digest no longer
+# matches the sources is stale and is not reported.
+import glob
+import hashlib
+import os
+import re
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_PROFILES = os.path.join(_HERE, "..", "profiles")
+_TRAFFIC_RE = re.compile(r"TRAFFIC workload=(-?\d+) kernel=(\w+) bytes=(\d+) sources=([\w.,]+) digest=([0-9a-f]{12})")
+
+
+def kernel_sources_digest(sources):
+    """First 12 hex digits of the SHA-1 over the named files of csrc/ (sorted by name)."""
+    h = hashlib.sha1()
+    for name in sorted(sources):
+        with open(os.path.join(_CSRC, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:12]
 
 
 def measured_traffic(workload_index, kernel):
-    """HBM bytes per launch from the committed rocprofv3 summaries, or None where none was taken."""
-    return MEASURED_TRAFFIC_BYTES.get((workload_index, kernel))
+    """(bytes per launch, profile file name, stale?) from the committed rocprofv3 summaries; None where none was taken."""
+    for path in sorted(glob.glob(os.path.join(_PROFILES, "*.md"))):
+        with open(path) as f:
+            text = f.read()
+        for m in _TRAFFIC_RE.finditer(text):
+            if int(m.group(1)) == workload_index and m.group(2) == kernel:
+                try:
+                    fresh = kernel_sources_digest(m.group(4).split(",")) == m.group(5)
+                except OSError:
+                    fresh = False
+                return int(m.group(3)), os.path.basename(path), not fresh
+    return None
+
+
+if __name__ == "__main__":
+    import sys
+    print(kernel_sources_digest(sys.argv[1:]))

@@ -47,6 +47,9 @@ SMALL = [
     (21, 2, 1024, 600, 599), (11, 2, 2048, 900, 450), (37, 1, 512, 700, 0),
     # thirty-three to forty-eight block offsets: the weight gradient in three passes
     (2, 3, 2048, 700, 350), (2, 2, 3000, 513, 0), (40, 8, 1024, 530, 529), (3, 2, 1024, 738, 737),
+    # filters or rows beyond 8192: tiled long-filter forward / input gradient, many-launch weight gradient
+    (1, 2, 9000, 300, 299), (1, 1, 16384, 16384, 16383), (2, 1, 12000, 9000, 4000), (3, 1, 8200, 8200, 0),
+    (1, 2, 9000, 900, 899), (1, 1, 32768, 20000, 19999),
     # matrix-core kernels at row lengths that are multiples of 4 but not of 8, 16 or 64
     (2, 3, 1004, 32, 31), (3, 2, 36, 16, 15), (2, 2, 2060, 64, 63), (1, 5, 44, 7, 3),
 ]
