@@ -44,6 +44,11 @@ def parse_args():
     ap.add_argument("--trace-steps", type=int, default=16,
                     help="per-step event times of the first N steps after set-up, reported as first_steps_us "
                          "(they are warm-up steps; nothing is hidden: the ramp shows here)")
+    ap.add_argument("--data", choices=("workload", "zeros"), default="workload",
+                    help="zeros: all-zero x, w and dY (same work; the part draws less power, so the shader clock the "
+                         "kernels sustain on real data can be told from the clock-free time; no parity meaning)")
+    ap.add_argument("--sample-clocks", action="store_true",
+                    help="sample `rocm-smi --showclocks` while the timed region runs and report the shader clock seen")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-roof", action="store_true",
                     help="instead of the benchmark, time plain device copies of 128 MiB .. 1 GiB (what a streaming "
@@ -142,6 +147,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     inputs = workloads.make_inputs(wl)
+    if args.data == "zeros":
+        inputs = {k: torch.zeros_like(v) for k, v in inputs.items()}
     K, p = wl.K, wl.pad_left
 
     sets = []
@@ -220,6 +227,26 @@ def main():
     warm_seconds = time.perf_counter() - t_warm0
 
     # timed region 1: exactly `steps` steps back to back (the headline number)
+    clocks = []
+    sampler = None
+    if args.sample_clocks:
+        import re
+        import subprocess
+        import threading
+        stop_sampling = threading.Event()
+
+        def sample():
+            while not stop_sampling.is_set():
+                try:
+                    o = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5).stdout
+                    m = re.search(r"sclk clock level:.*?\((\d+)Mhz\)", o)
+                    if m:
+                        clocks.append(int(m.group(1)))
+                except Exception:
+                    pass
+                time.sleep(0.02)
+        sampler = threading.Thread(target=sample, daemon=True)
+        sampler.start()
     start = torch.cuda.Event(enable_timing=True); end = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     start.record()
@@ -228,6 +255,9 @@ def main():
     end.record()
     torch.cuda.synchronize()
     ms_per_step = start.elapsed_time(end) / args.steps
+    if sampler:
+        stop_sampling.set()
+        sampler.join()
 
     # timed region 2: the same steps with HIP events between the launches, for per-kernel durations
     # (at least 50 of them, so that median and minimum mean something on a short run)
@@ -294,6 +324,9 @@ def main():
         "step_us_from_events": {"mean": round(sum(step_samples) / len(step_samples), 2),
                                 "median": round(step_samples[len(step_samples) // 2], 2),
                                 "min": round(step_samples[0], 2), "samples": len(step_samples)},
+        "input_values": args.data,
+        "sclk_mhz_during_timed_steps": ({"samples": len(clocks), "min": min(clocks), "median": sorted(clocks)[len(clocks) // 2],
+                                         "max": max(clocks)} if clocks else None),
         "warmup_steps_run": warm_done, "warmup_seconds": round(warm_seconds, 3),
         "first_steps_us": first_steps_us,
         "paths_gbps": {"fwd": round(path_bytes / us["fwd"] / 1e3, 1), "dx": round(path_bytes / us["dx"] / 1e3, 1),
