@@ -19,6 +19,30 @@ HIPCC_FLAGS = [
 ]
 OBJ_DIR = os.path.join(HERE, "_build")     # object files of the translation units (not tracked)
 
+# Kernels that prefetch into registers with loads the compiler does not track (inline assembly, one manual
+# s_waitcnt before the registers are read): a spill or scratch copy of such a register between the load and the
+# wait would read it before the data has arrived, so these kernels must not use scratch memory at all.
+UNTRACKED_PREFETCH_KERNELS = ("corr_mfma_kernel", "corr_mfma_bf16_kernel", "corr_rowbatch_kernel", "dw_rowbatch_kernel",
+                              "bwd_rowbatch_kernel")
+VALIDATED_HIPCC = "7.2"       # ROCm release whose hipcc these kernels were checked with
+
+
+def check_no_scratch(remarks: str, unit: str):
+    """Parse -Rpass-analysis=kernel-resource-usage output; raise if a kernel with untracked prefetch uses scratch."""
+    import re
+    name = None
+    bad = []
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name and int(m.group(1)) > 0 and any(k in name for k in UNTRACKED_PREFETCH_KERNELS):
+            bad.append((name, int(m.group(1))))
+    if bad:
+        raise RuntimeError(f"{unit}: kernels with untracked register prefetch must not spill, but use scratch: {bad}")
+
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
@@ -34,6 +58,13 @@ def build(verbose: bool = False, extra_flags=(), jobs: int | None = None, increm
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    try:
+        ver = subprocess.run([hipcc, "--version"], capture_output=True, text=True).stdout
+        if f"HIP version: {VALIDATED_HIPCC}" not in ver:
+            print(f"warning: kernels with untracked register prefetch were validated with hipcc {VALIDATED_HIPCC}; "
+                  f"this is\n{ver.splitlines()[0] if ver else 'unknown'}", flush=True)
+    except OSError:
+        pass
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = sources()
     objs = [os.path.join(OBJ_DIR, os.path.basename(p)[:-4] + ".o") for p in srcs]
@@ -45,10 +76,17 @@ def build(verbose: bool = False, extra_flags=(), jobs: int | None = None, increm
         src, obj = pair
         if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
             return
-        cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-c", src, "-o", obj]
+        cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
+        r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+        other = [ln for ln in r.stderr.splitlines() if "[-Rpass-analysis=kernel-resource-usage]" not in ln and
+                 "is not a recognized feature for this target" not in ln]
+        if other and (verbose or r.returncode != 0):
+            print("\n".join(other), flush=True)
+        if r.returncode != 0:
+            raise subprocess.CalledProcessError(r.returncode, cmd)
+        check_no_scratch(r.stderr, os.path.basename(src))
 
     if jobs is None:
         jobs = max(1, min(len(srcs), os.cpu_count() or 1, 8))

@@ -92,19 +92,29 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16 storage only")
 
 
-def _dev3(t: torch.Tensor, name: str):
+def _on_current_device(t: torch.Tensor, name: str):
+    """The library enqueues on the current stream of the current device: every tensor must live there."""
     if not t.is_cuda:
         raise ValueError(f"{name} must be a GPU tensor")
+    if t.device.index != torch.cuda.current_device():
+        raise ValueError(f"{name} is on {t.device}, the current device is cuda:{torch.cuda.current_device()}")
+
+
+def _dev3(t: torch.Tensor, name: str):
+    _on_current_device(t, name)
     if t.dim() != 3 or not t.is_contiguous():
         raise ValueError(f"{name} must be a contiguous [B, C, L] tensor")
     return t
 
 
-def _dev2(t: torch.Tensor, name: str, C: int):
-    if not t.is_cuda:
-        raise ValueError(f"{name} must be a GPU tensor")
+def _dev2(t: torch.Tensor, name: str, C: int, K: int | None = None, dtype=None):
+    _on_current_device(t, name)
     if t.dim() != 2 or not t.is_contiguous() or t.shape[0] != C:
         raise ValueError(f"{name} must be a contiguous [C, K] tensor")
+    if K is not None and t.shape[1] != K:
+        raise ValueError(f"{name} must have {K} columns, has {t.shape[1]}")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, is {t.dtype}")
     return t
 
 
@@ -166,7 +176,8 @@ def _dw_args(x, dy, K, pad_left, workspace):
         raise ValueError("x and dy must match")
     if workspace is None:
         workspace = new_workspace(x, K, pad_left)
-    if not workspace.is_cuda or not workspace.is_contiguous():
+    _on_current_device(workspace, "workspace")
+    if not workspace.is_contiguous():
         raise ValueError("workspace must be a contiguous GPU tensor")
     return workspace, workspace.numel() * workspace.element_size()
 
@@ -175,7 +186,7 @@ def dwconv_bwd_weight(x, dy, K: int, pad_left: int, workspace=None, out=None) ->
     """dw[c,j] = sum_b sum_t dy[b,c,t] x~[b,c,t+j-pad_left]  (Sec. IV-A eq. (dk_def)); both stages."""
     workspace, nbytes = _dw_args(x, dy, K, pad_left, workspace)
     B, C, L = x.shape
-    dw = torch.empty((C, K), dtype=x.dtype, device=x.device) if out is None else _dev2(out, "out", C)
+    dw = torch.empty((C, K), dtype=x.dtype, device=x.device) if out is None else _dev2(out, "out", C, int(K), x.dtype)
     _check(lib().dwconv_bwd_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), workspace.data_ptr(), nbytes,
                                    B, C, L, int(K), int(pad_left), _dtype_code(x), _stream()))
     return dw
@@ -192,9 +203,7 @@ def dwconv_bwd_weight_noalloc(x, dy, K: int, pad_left: int, out: torch.Tensor) -
     if dy.shape != x.shape or dy.dtype != x.dtype:
         raise ValueError("x and dy must match")
     B, C, L = x.shape
-    dw = _dev2(out, "out", C)
-    if dw.shape[1] != K or dw.dtype != x.dtype:
-        raise ValueError("out must be [C, K] of x's dtype")
+    dw = _dev2(out, "out", C, int(K), x.dtype)
     _check(lib().dwconv_bwd_weight_noalloc(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), B, C, L, int(K), int(pad_left),
                                            _dtype_code(x), _stream()))
     return dw
@@ -205,11 +214,11 @@ def dwconv_bwd(dy, x, w, pad_left: int, workspace=None, out_dx=None, out_dw=None
     K = int(w.shape[1])
     workspace, nbytes = _dw_args(x, dy, K, pad_left, workspace)
     B, C, L = x.shape
-    wd = _dev2(w, "w", C)
-    dx = torch.empty_like(dy) if out_dx is None else out_dx
-    dw = torch.empty((C, K), dtype=x.dtype, device=x.device) if out_dw is None else _dev2(out_dw, "out_dw", C)
-    if dx.shape != dy.shape or dx.dtype != dy.dtype or not dx.is_cuda or not dx.is_contiguous():
-        raise ValueError("out_dx must be a contiguous device tensor shaped and typed like dy")
+    wd = _dev2(w, "w", C, K, x.dtype)
+    dx = torch.empty_like(dy) if out_dx is None else _dev3(out_dx, "out_dx")
+    dw = torch.empty((C, K), dtype=x.dtype, device=x.device) if out_dw is None else _dev2(out_dw, "out_dw", C, K, x.dtype)
+    if dx.shape != dy.shape or dx.dtype != dy.dtype:
+        raise ValueError("out_dx must be shaped and typed like dy")
     _check(lib().dwconv_bwd(dy.data_ptr(), x.data_ptr(), wd.data_ptr(), dx.data_ptr(), dw.data_ptr(),
                             workspace.data_ptr(), nbytes, B, C, L, K, int(pad_left), _dtype_code(x), _stream()))
     return dx, dw
@@ -230,7 +239,8 @@ def dwconv_bwd_weight_partial(x, dy, K: int, pad_left: int, workspace=None) -> t
 
 def dwconv_bwd_weight_finalize(workspace, B, C, L, K: int, pad_left: int, dtype: torch.dtype, out=None) -> torch.Tensor:
     """Stage 2: dw[c,j] = sum_s part[s,c,j] in increasing s (Sec. IV-C/D)."""
-    dw = torch.empty((C, K), dtype=dtype, device=workspace.device) if out is None else _dev2(out, "out", C)
+    _on_current_device(workspace, "workspace")
+    dw = torch.empty((C, K), dtype=dtype, device=workspace.device) if out is None else _dev2(out, "out", C, int(K), dtype)
     code = _dtype_code(dw)
     _check(lib().dwconv_bwd_weight_finalize(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                             dw.data_ptr(), B, C, L, int(K), int(pad_left), code, _stream()))

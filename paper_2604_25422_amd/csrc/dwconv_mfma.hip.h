@@ -188,7 +188,7 @@ template <> struct Raw4<bf16_t> {
 // ordered (virtual segment, channel), so neighbouring waves read neighbouring channels of the same batches, and
 // `row` / `seg` below then hold the virtual segment and the channel.
 template <typename T, int ND, bool ROWS>
-__global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 10 ? 2 : ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 9 ? 2 : ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
                                                                          const T *__restrict__ f, T *__restrict__ out,
                                                                          const CorrGeom g, const RowsMap rm)
 {

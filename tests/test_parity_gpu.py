@@ -339,3 +339,62 @@ def test_calls_can_be_captured_in_a_graph(B, C, L, K, p, dtype):
         torch.cuda.synchronize()
         for name, t, r in zip(("y", "dx", "dw", "dx fused", "dw fused"), (y, dx, dw, dx2, dw2), ref):
             assert torch.equal(t, r), f"replay {rep}: {name} differs from the eager call"
+
+
+def test_binding_rejects_mismatched_outputs():
+    """The marshalling layer checks what the C ABI cannot see: shapes and types of caller-supplied outputs."""
+    from paper_2604_25422_amd import binding
+    B, C, L, K, p = 2, 3, 64, 9, 4
+    x = torch.zeros((B, C, L), device="cuda"); w = torch.zeros((C, K), device="cuda")
+    with pytest.raises(ValueError):
+        binding.dwconv_bwd_weight(x, x, K, p, out=torch.zeros((C, K - 1), device="cuda"))
+    with pytest.raises(TypeError):
+        binding.dwconv_bwd_weight(x, x, K, p, out=torch.zeros((C, K), device="cuda", dtype=torch.bfloat16))
+    with pytest.raises(TypeError):
+        binding.dwconv_bwd(x, x, w.to(torch.bfloat16), p)
+    with pytest.raises(ValueError):
+        binding.dwconv_bwd(x, x, w, p, out_dw=torch.zeros((C, K + 1), device="cuda"))
+    with pytest.raises(ValueError):
+        binding.dwconv_bwd_weight_finalize(torch.zeros(1024, dtype=torch.uint8), B, C, L, K, p, torch.float32)   # host workspace
+    with pytest.raises(ValueError):
+        binding.dwconv_fwd(x.cpu(), w, p)
+
+
+def test_first_calls_of_a_process_can_be_captured():
+    """Capture WITHOUT a preceding eager call: the library's per-kernel occupancy and LDS-attribute queries then run
+    while the stream is capturing.  A fresh process, so that no kernel has been launched before."""
+    import subprocess
+    import sys
+    code = r"""
+import sys, torch
+sys.path.insert(0, %r); sys.path.insert(0, %r)
+from _parity import seeded
+from paper_2604_25422_amd import binding
+for (B, C, L, K, p, dt) in ((4, 64, 1024, 16, 15, torch.float32), (3, 5, 96, 48, 24, torch.float32),
+                            (2, 3, 512, 300, 299, torch.float32), (4, 6, 1024, 32, 31, torch.bfloat16),
+                            (2, 2, 2048, 100, 99, torch.float32)):
+    x = seeded((B, C, L), 41, dt).cuda(); w = seeded((C, K), 42, dt).cuda(); dy = seeded((B, C, L), 43, dt).cuda()
+    y = torch.empty_like(x); dx = torch.empty_like(x); dw = torch.empty_like(w); dx2 = torch.empty_like(x); dw2 = torch.empty_like(w)
+    ws = binding.new_workspace(x, K, p)
+    def step():
+        binding.dwconv_fwd(x, w, p, out=y)
+        binding.dwconv_bwd_input(dy, w, p, out=dx)
+        binding.dwconv_bwd_weight(x, dy, K, p, workspace=ws, out=dw)
+        binding.dwconv_bwd(dy, x, w, p, workspace=ws, out_dx=dx2, out_dw=dw2)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        step()
+    outs = (y, dx, dw, dx2, dw2)
+    got = []
+    for rep in range(2):
+        for t in outs: t.fill_(float("nan"))
+        torch.cuda.synchronize(); g.replay(); torch.cuda.synchronize()
+        got.append([t.clone() for t in outs])
+    step(); torch.cuda.synchronize()
+    for rep in range(2):
+        for a, b in zip(got[rep], outs):
+            assert torch.equal(a, b), (B, C, L, K, rep)
+print("CAPTURE_OK")
+""" % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0 and "CAPTURE_OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
