@@ -86,7 +86,10 @@ template <typename T>
 __device__ __forceinline__ uintx4 row_tail_resource(const T *row, int L, int start)
 {
     const unsigned long long a = reinterpret_cast<unsigned long long>(row) + (unsigned long long)start;
-    const uintx4 r = {(unsigned)a, (unsigned)(a >> 32) & 0xffffu, (unsigned)(L * (int)sizeof(T) - start), kBufferFlags};
+    // (a start at or past the end of the row gives an EMPTY resource: a negative size would wrap to a huge one, under
+    // which even the out-of-row marker offset is in range)
+    const int bytes = L * (int)sizeof(T) - start;
+    const uintx4 r = {(unsigned)a, (unsigned)(a >> 32) & 0xffffu, (unsigned)(bytes > 0 ? bytes : 0), kBufferFlags};
     return r;
 }
 
