@@ -141,16 +141,21 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             // them has landed; i loads of the next segment have been issued since
             constexpr int need = i < 3 ? i + 1 : 5;
             wait_vmcnt_at_most<(5 - need) + i>();
-            float4 bv[ND];
-#pragma unroll
-            for (int d = 0; d < ND; ++d) bv[d] = *reinterpret_cast<const float4 *>(gx[d] + 256 * i);
+            // (a quarter that lies wholly past the end of the row - the last segment of a row that is not a multiple of
+            // 1024 positions - has no outputs: its matrix work is skipped, its part of the refill is not)
+            const bool live = whole || t_seg + 256 * i < g.L;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (live) {
+                float4 bv[ND];
 #pragma unroll
-            for (int d = 0; d < ND; ++d) {
-                acc = mfma16x16x4(A[d][0], bv[d].x, acc);
-                acc = mfma16x16x4(A[d][1], bv[d].y, acc);
-                acc = mfma16x16x4(A[d][2], bv[d].z, acc);
-                acc = mfma16x16x4(A[d][3], bv[d].w, acc);
+                for (int d = 0; d < ND; ++d) bv[d] = *reinterpret_cast<const float4 *>(gx[d] + 256 * i);
+#pragma unroll
+                for (int d = 0; d < ND; ++d) {
+                    acc = mfma16x16x4(A[d][0], bv[d].x, acc);
+                    acc = mfma16x16x4(A[d][1], bv[d].y, acc);
+                    acc = mfma16x16x4(A[d][2], bv[d].z, acc);
+                    acc = mfma16x16x4(A[d][3], bv[d].w, acc);
+                }
             }
             // region i of the window is dead: refill it for the next segment
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             // store tile i: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3
             const int lt = 256 * i + 16 * i16 + 4 * k4;
             if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
-            else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
+            else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;
@@ -271,12 +276,16 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             // three loads per segment (g0 g1 gt); one load of the next segment is out after chunk 1
             constexpr int need = c4 == 0 ? 0 : (c4 < 3 ? 1 : 2), issued = c4 >= 2 ? 1 : 0;
             wait_vmcnt_at_most<(2 - need) + issued>();
-            shortx4 bv[ND];
-#pragma unroll
-            for (int d = 0; d < ND; ++d) bv[d] = *reinterpret_cast<const shortx4 *>(gx[d] + 256 * c4);
+            // (a chunk wholly past the end of the row has no outputs: its matrix work is skipped)
+            const bool live = whole || t_seg + 256 * c4 < g.L;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (live) {
+                shortx4 bv[ND];
 #pragma unroll
-            for (int d = 0; d < ND; ++d) acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A[d], bv[d], acc, 0, 0, 0);
+                for (int d = 0; d < ND; ++d) bv[d] = *reinterpret_cast<const shortx4 *>(gx[d] + 256 * c4);
+#pragma unroll
+                for (int d = 0; d < ND; ++d) acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A[d], bv[d], acc, 0, 0, 0);
+            }
             if constexpr (c4 == 1 || c4 == 3) {
                 // half c4 / 2 of the window is dead: refill it for the next segment
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -286,7 +295,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the chunk
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
             if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
-            else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
+            else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;

@@ -48,8 +48,15 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
     const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
     // One resident round of waves, each walking segments wave, wave + n_waves, ...
-    auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po, long long slot_cap = kTargetWaves) -> int {
-        long long resident = corr_wave_slots(kernel, kThreads);
+    // slot_cap: the most wave slots to use.  balance_target > 0 (the kernels that load rows straight into LDS): the
+    // number of waves is chosen among whole numbers J of batch entries per round (J * C * segments per row waves, which
+    // keeps a wave on one channel) for even loading, the one nearest balance_target among the best: every SIMD gets
+    // the same number of waves (a multiple of 1024 waves: with 2560 waves two SIMDs of a compute unit carry three
+    // waves and two carry two, and the launch takes as long as the three) and the rounds divide the batch
+    // (B32 C256 L4100 K64: 70.3 us with 2560 waves, 65.3 with 3840, 62.4 with 5120; L3000: 43.5 us with 3072).
+    auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po, long long slot_cap = kTargetWaves,
+                      long long balance_target = 0) -> int {
+        long long resident = balance_target > 0 ? resident_waves(kernel, kThreads) : corr_wave_slots(kernel, kThreads);
         if (resident > slot_cap) resident = slot_cap;
         long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
         if (spw < 1) spw = 1;
@@ -60,8 +67,24 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         if (per_b <= resident) {
             long long J = resident / per_b;
             if (J > s.B) J = s.B;
-            const long long rounds = (s.B + J - 1) / J;
-            J = (s.B + rounds - 1) / rounds;                           // same number of rounds, evened out
+            if (balance_target > 0) {
+                const long long simds = 4LL * kComputeUnits;
+                long long best_j = 1;
+                double best = -1.0;
+                for (long long j = 1; j <= J; ++j) {
+                    const long long w = j * per_b, rounds = (s.B + j - 1) / j;
+                    const double even_simd = (double)w / (double)(simds * ((w + simds - 1) / simds));
+                    const double even_rounds = (double)s.B / (double)(j * rounds);
+                    const double near = 1.0 - 0.02 * (double)(w > balance_target ? w - balance_target : balance_target - w) /
+                                                  (double)balance_target;
+                    const double score = even_simd * even_rounds * near * (w < simds * 2 ? 0.8 : 1.0);
+                    if (score > best) { best = score; best_j = j; }
+                }
+                J = best_j;
+            } else {
+                const long long rounds = (s.B + J - 1) / J;
+                J = (s.B + rounds - 1) / rounds;                       // same number of rounds, evened out
+            }
             waves = J * per_b;
         }
         const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
@@ -205,17 +228,18 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     const T *pi = static_cast<const T *>(in), *pf = static_cast<const T *>(f);
     T *po = static_cast<T *>(out);
     if constexpr (std::is_same<T, float>::value) {
-        // fp32, two to six block offsets: rows straight into LDS, refilled in place.  Fewer wave slots than a full
-        // resident round: a launch is the time its bytes take plus a fill and a drain that grow with the bytes in
-        // flight (B32 C256 L4096: K = 7 93 us with 8 waves per compute unit, 96 us with 12 or 16; K = 64 51.4 / 50.8 /
-        // 50.9 us with 8 / 12 / 16, the matrix pipe wanting more than two waves per SIMD there)
-        const long long cap = (long long)kComputeUnits * (nd <= 3 ? 8 : 12);
+        // fp32, two to six block offsets: rows straight into LDS, refilled in place.  Wave slots aimed at: fewer than a
+        // full resident round, because a launch is the time its bytes take plus a fill and a drain that grow with the
+        // bytes in flight (B32 C256 L4096: K = 7 93 us with 8 waves per compute unit, 96 us with 12 or 16; K = 64 51.4 /
+        // 50.8 / 50.9 us with 8 / 12 / 16, the matrix pipe wanting more than two waves per SIMD there); up to 20 per
+        // compute unit where that is what loads the SIMDs evenly (see `launch`)
+        const long long target = (long long)kComputeUnits * (nd <= 3 ? 8 : 14), cap = (long long)kComputeUnits * (nd <= 3 ? 12 : 20);
         switch (nd) {
-        case 2: return launch(dwconv::corr_direct_kernel<2>, pi, pf, po, cap);
-        case 3: return launch(dwconv::corr_direct_kernel<3>, pi, pf, po, cap);
-        case 4: return launch(dwconv::corr_direct_kernel<4>, pi, pf, po, cap);
-        case 5: return launch(dwconv::corr_direct_kernel<5>, pi, pf, po, cap);
-        case 6: return launch(dwconv::corr_direct_kernel<6>, pi, pf, po, cap);
+        case 2: return launch(dwconv::corr_direct_kernel<2>, pi, pf, po, cap, target);
+        case 3: return launch(dwconv::corr_direct_kernel<3>, pi, pf, po, cap, target);
+        case 4: return launch(dwconv::corr_direct_kernel<4>, pi, pf, po, cap, target);
+        case 5: return launch(dwconv::corr_direct_kernel<5>, pi, pf, po, cap, target);
+        case 6: return launch(dwconv::corr_direct_kernel<6>, pi, pf, po, cap, target);
         default: break;
         }
     }
