@@ -276,7 +276,7 @@ DwPlan plan_dw(const Shape &s)
         p.lk_table = longk_dw_table(s, p.lk_wgs, &p.lk_gd);
     }
     p.manypass = false;
-    if (!p.lk_table && nd > mfma_max_nd_dw(s) && s.dtype == DWCONV_F32 && (s.L % 4) == 0 && s.L >= kRaggedMinL &&
+    if (!p.lk_table && nd > mfma_max_nd_dw(s) && (s.L % (s.dtype == DWCONV_F32 ? 4 : 8)) == 0 && s.L >= kRaggedMinL &&
         s.L <= kMfmaMaxL && !p.rows.on) {
         // filters (or rows) too long for the long-filter kernel's LDS: the register-resident kernel, sixteen block
         // offsets per launch, every launch adding the taps it owns to one of two zero-filled sets of slices

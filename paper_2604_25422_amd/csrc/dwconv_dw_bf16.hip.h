@@ -38,8 +38,10 @@ __host__ __device__ constexpr int bf16_block_pos(int nb) { return (nb & ~3) | ((
 template <int ND, int W>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ part, bf16_t *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, int j0, int j1)
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, int j0, int j1, int seg0, int own_only)
 {
+    // seg0, own_only: as in dw_partial_direct_kernel (the first segment of every row this launch walks; write the
+    // owned taps only)
     // [j0, j1): the taps this launch owns (0, K unless the block offsets of the filter are split over two launches);
     // the other taps of its slices are written as zeros
     static_assert(ND >= 2 && 16 * ND <= 256, "the x tail is one or two 128-element loads");
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
             // batches are walked from the last to the first (the rows the input-gradient call touched last are
             // still in the last-level cache)
             const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
-            const int t0 = pseg * kSegLen;
+            const int t0 = (seg0 + pseg) * kSegLen;
             const int u0 = 2 * (t0 + 16 * dmin);
             x_shift = u0 < 0 ? u0 : 0;
             // (a window that starts past the end of the row - the second of two launches - gets an empty resource)
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     // ---- per-wave diagonal sums, then the waves of the block in wave order
     dw_wave_diagonal_sums<ND>(G, s_mem[wave], s_dw[wave], lane, j0, j1, pad, dmin);
     __syncthreads();
-    for (int j = tid; j < K; j += 64 * W) {
+    for (int j = own_only ? j0 + tid : tid; j < (own_only ? j1 : K); j += 64 * W) {
         float sum = 0.f;
         if (j >= j0 && j < j1) {
 #pragma unroll

@@ -91,7 +91,7 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
         hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                            static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part,
-                           static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, 0, s.K);
+                           static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, 0, s.K, 0, 0);
     } else {
         auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W, false>;
         constexpr size_t lds = dwconv::dw_mfma_lds_bytes(ND, W);
@@ -129,7 +129,7 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
             if (!aligned_to(x, 16) || !aligned_to(dy, 16)) return -1;
             return launch_dw_partial_wide_f32(x, dy, part, nullptr, s, p, dmin, nd, st);
         } else {
-            return -1;
+            return launch_dw_partial_wide_bf16(x, dy, part, nullptr, s, p, dmin, nd, st);
         }
     }
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || s.L > kMfmaMaxL) return -1;
