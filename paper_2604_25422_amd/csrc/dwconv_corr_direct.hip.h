@@ -49,8 +49,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int i16 = lane & 15, k4 = lane >> 4;
 
     const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    int row = __builtin_amdgcn_readfirstlane(wg / g.segs_per_row);                 // b * C + c
-    int seg = __builtin_amdgcn_readfirstlane(wg % g.segs_per_row);
+    // Two walks.  Rows of whole segments: wave w takes segments w, w + n_waves, ... of the memory order.  Rows whose last
+    // segment is ragged (g.row_walk): wave w takes rows w, w + n_waves, ... and every segment of a row in turn, waves
+    // starting at different segments - the nearly empty last segment of a row then costs every wave the same, and the
+    // number of waves does not have to be a multiple of the segments per row.
+    int row = __builtin_amdgcn_readfirstlane(g.row_walk ? wg : wg / g.segs_per_row);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(g.row_walk ? (wg + wg / g.C) % g.segs_per_row : wg % g.segs_per_row);
+    const int seg0 = seg;
     int c = __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
 
@@ -119,13 +124,20 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     int cur_c = c;
 
     for (;;) {
-        int seg_n = seg + g.step_seg;
-        const int carry = seg_n >= g.segs_per_row ? 1 : 0;
-        seg_n -= carry ? g.segs_per_row : 0;
-        const int row_n = row + g.step_rows + carry;
-        int c_n = c + g.step_c + carry;
-        c_n -= c_n >= g.C ? g.C : 0;
-        c_n -= c_n >= g.C ? g.C : 0;
+        int seg_n, row_n, c_n;
+        if (g.row_walk) {
+            seg_n = seg + 1 == g.segs_per_row ? 0 : seg + 1;
+            row_n = row + (seg_n == seg0 ? g.n_waves : 0);
+            c_n = c;
+        } else {
+            seg_n = seg + g.step_seg;
+            const int carry = seg_n >= g.segs_per_row ? 1 : 0;
+            seg_n -= carry ? g.segs_per_row : 0;
+            row_n = row + g.step_rows + carry;
+            c_n = c + g.step_c + carry;
+            c_n -= c_n >= g.C ? g.C : 0;
+            c_n -= c_n >= g.C ? g.C : 0;
+        }
         float *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
         const bool whole = (seg + 1) * kSegLen <= g.L;
         const int t_seg = seg * kSegLen;
@@ -194,8 +206,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int i16 = lane & 15, kg = lane >> 4;
 
     const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    int row = __builtin_amdgcn_readfirstlane(wg / g.segs_per_row);                 // b * C + c
-    int seg = __builtin_amdgcn_readfirstlane(wg % g.segs_per_row);
+    // Two walks.  Rows of whole segments: wave w takes segments w, w + n_waves, ... of the memory order.  Rows whose last
+    // segment is ragged (g.row_walk): wave w takes rows w, w + n_waves, ... and every segment of a row in turn, waves
+    // starting at different segments - the nearly empty last segment of a row then costs every wave the same, and the
+    // number of waves does not have to be a multiple of the segments per row.
+    int row = __builtin_amdgcn_readfirstlane(g.row_walk ? wg : wg / g.segs_per_row);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(g.row_walk ? (wg + wg / g.C) % g.segs_per_row : wg % g.segs_per_row);
+    const int seg0 = seg;
     int c = __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
 
@@ -256,13 +273,20 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     int cur_c = c;
 
     for (;;) {
-        int seg_n = seg + g.step_seg;
-        const int carry = seg_n >= g.segs_per_row ? 1 : 0;
-        seg_n -= carry ? g.segs_per_row : 0;
-        const int row_n = row + g.step_rows + carry;
-        int c_n = c + g.step_c + carry;
-        c_n -= c_n >= g.C ? g.C : 0;
-        c_n -= c_n >= g.C ? g.C : 0;
+        int seg_n, row_n, c_n;
+        if (g.row_walk) {
+            seg_n = seg + 1 == g.segs_per_row ? 0 : seg + 1;
+            row_n = row + (seg_n == seg0 ? g.n_waves : 0);
+            c_n = c;
+        } else {
+            seg_n = seg + g.step_seg;
+            const int carry = seg_n >= g.segs_per_row ? 1 : 0;
+            seg_n -= carry ? g.segs_per_row : 0;
+            row_n = row + g.step_rows + carry;
+            c_n = c + g.step_c + carry;
+            c_n -= c_n >= g.C ? g.C : 0;
+            c_n -= c_n >= g.C ? g.C : 0;
+        }
         bf16_t *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
         const bool whole = (seg + 1) * kSegLen <= g.L;
         const int t_seg = seg * kSegLen;

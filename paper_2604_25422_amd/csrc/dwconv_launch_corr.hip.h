@@ -45,6 +45,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     g.C = s.C; g.L = s.L; g.K = s.K; g.rows = (int)rows;
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
     g.segs_per_row = (int)segs_per_row;
+    g.row_walk = 0;
     constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
     const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
     // One resident round of waves, each walking segments wave, wave + n_waves, ...
@@ -54,16 +55,23 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     // the same number of waves (a multiple of 1024 waves: with 2560 waves two SIMDs of a compute unit carry three
     // waves and two carry two, and the launch takes as long as the three) and the rounds divide the batch
     // (B32 C256 L4100 K64: 70.3 us with 2560 waves, 65.3 with 3840, 62.4 with 5120; L3000: 43.5 us with 3072).
+    // row_walk (the kernels that have it, rows whose last segment is ragged): a wave owns whole rows of one channel, J * C
+    // waves; the light last segments are then spread evenly over the waves and the segments per row drop out of the
+    // wave count (fwd, B32 C256 L8196: K16 127 -> 114 us, K64 128 -> 124 us; bf16 B128 C768 L1026 K32 128 -> 115 us; within
+    // the noise where the segments per row already divided the chip evenly, e.g. B32 C256 L4100 K64 63 us).  What a
+    // nearly empty segment still costs is one exposed memory round trip: nothing to compute while the next window loads.
     auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po, long long slot_cap = kTargetWaves,
-                      long long balance_target = 0) -> int {
+                      long long balance_target = 0, bool row_walk = false) -> int {
         long long resident = balance_target > 0 ? resident_waves(kernel, kThreads) : corr_wave_slots(kernel, kThreads);
         if (resident > slot_cap) resident = slot_cap;
         long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
         if (spw < 1) spw = 1;
         long long waves = (total_segs + spw - 1) / spw;
+        row_walk = row_walk && (s.L % dwconv::kSegLen) != 0 && s.C <= resident && balance_target > 0;
         // A whole number of batch entries per round where one fits: the stride of the walk is then a multiple of
         // C rows, a wave stays on one channel and loads its Toeplitz operands once.
-        const long long per_b = (long long)s.C * segs_per_row;
+        const long long per_b = row_walk ? (long long)s.C : (long long)s.C * segs_per_row;
+        g.row_walk = row_walk ? 1 : 0;
         if (per_b <= resident) {
             long long J = resident / per_b;
             if (J > s.B) J = s.B;
@@ -200,12 +208,13 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                 // two to six block offsets: rows straight into LDS, refilled in place (B128 C768 L1024 K32: 72 us
                 // against 76 us through staging registers; a wave has half the bytes of an fp32 one in flight, and a
                 // full round of sixteen waves per compute unit is the fastest here)
+                const bool ragged_last = (s.L % dwconv::kSegLen) != 0;      // (then: whole rows per wave, see `launch`)
                 switch (nd) {
-                case 2: return launch(dwconv::corr_direct_bf16_kernel<2>, pi, pf, po);
-                case 3: return launch(dwconv::corr_direct_bf16_kernel<3>, pi, pf, po);
-                case 4: return launch(dwconv::corr_direct_bf16_kernel<4>, pi, pf, po);
-                case 5: return launch(dwconv::corr_direct_bf16_kernel<5>, pi, pf, po);
-                case 6: return launch(dwconv::corr_direct_bf16_kernel<6>, pi, pf, po);
+                case 2: return launch(dwconv::corr_direct_bf16_kernel<2>, pi, pf, po, kTargetWaves, ragged_last ? kTargetWaves : 0, true);
+                case 3: return launch(dwconv::corr_direct_bf16_kernel<3>, pi, pf, po, kTargetWaves, ragged_last ? kTargetWaves : 0, true);
+                case 4: return launch(dwconv::corr_direct_bf16_kernel<4>, pi, pf, po, kTargetWaves, ragged_last ? kTargetWaves : 0, true);
+                case 5: return launch(dwconv::corr_direct_bf16_kernel<5>, pi, pf, po, kTargetWaves, ragged_last ? kTargetWaves : 0, true);
+                case 6: return launch(dwconv::corr_direct_bf16_kernel<6>, pi, pf, po, kTargetWaves, ragged_last ? kTargetWaves : 0, true);
                 default: break;
                 }
             }
@@ -235,11 +244,11 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         // compute unit where that is what loads the SIMDs evenly (see `launch`)
         const long long target = (long long)kComputeUnits * (nd <= 3 ? 8 : 14), cap = (long long)kComputeUnits * (nd <= 3 ? 12 : 20);
         switch (nd) {
-        case 2: return launch(dwconv::corr_direct_kernel<2>, pi, pf, po, cap, target);
-        case 3: return launch(dwconv::corr_direct_kernel<3>, pi, pf, po, cap, target);
-        case 4: return launch(dwconv::corr_direct_kernel<4>, pi, pf, po, cap, target);
-        case 5: return launch(dwconv::corr_direct_kernel<5>, pi, pf, po, cap, target);
-        case 6: return launch(dwconv::corr_direct_kernel<6>, pi, pf, po, cap, target);
+        case 2: return launch(dwconv::corr_direct_kernel<2>, pi, pf, po, cap, target, true);
+        case 3: return launch(dwconv::corr_direct_kernel<3>, pi, pf, po, cap, target, true);
+        case 4: return launch(dwconv::corr_direct_kernel<4>, pi, pf, po, cap, target, true);
+        case 5: return launch(dwconv::corr_direct_kernel<5>, pi, pf, po, cap, target, true);
+        case 6: return launch(dwconv::corr_direct_kernel<6>, pi, pf, po, cap, target, true);
         default: break;
         }
     }

@@ -60,6 +60,8 @@ struct CorrGeom {
     int step_rows;      // n_waves / segs_per_row
     int step_seg;       // n_waves % segs_per_row
     int step_c;         // step_rows % C
+    int row_walk;       // kernels that load rows straight into LDS: wave w owns rows w, w + n_waves, ... (n_waves a multiple
+                        // of C) and walks all segments of a row, starting at segment (w + w / C) % segs_per_row
 };
 
 // Row access through buffer instructions.  A buffer resource describes (the tail of) ONE row

@@ -269,8 +269,9 @@ def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []
     while len(out) < n:
-        K = int(rng.choice([1, 2, 3, 5, 7, 16, 31, 32, 33, 48, 64, 66, 67, 90, 100, 128, 130, 160, 200, 226, 227, 300, 513]))
-        L = int(rng.choice([4, 12, 20, 36, 48, 52, 64, 68, 100, 128, 257, 512, 1000, 1024, 1028, 2048, 3000, 4096]))
+        K = int(rng.choice([1, 2, 3, 5, 7, 16, 31, 32, 33, 48, 64, 66, 67, 90, 100, 128, 130, 160, 200, 226, 227, 300, 513, 738, 739, 1000]))
+        L = int(rng.choice([4, 12, 20, 36, 48, 52, 64, 68, 100, 128, 257, 512, 770, 1000, 1024, 1026, 1027, 1028, 2048, 2049, 2050, 3000,
+                            3001, 4096, 4098]))
         C = int(rng.choice([1, 2, 3, 5, 8, 16, 256, 512]))
         B = int(rng.choice([1, 2, 3, 7, 16, 17, 40, 130]))
         if C >= 256:
