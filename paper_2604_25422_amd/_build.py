@@ -28,7 +28,9 @@ VALIDATED_HIPCC = "7.2"       # ROCm release whose hipcc these kernels were chec
 
 
 def check_no_scratch(remarks: str, unit: str):
-    """Parse -Rpass-analysis=kernel-resource-usage output; raise if a kernel with untracked prefetch uses scratch."""
+    """Parse -Rpass-analysis=kernel-resource-usage output; raise if a kernel with untracked prefetch uses scratch
+    memory or accumulation registers (the compiler spills vector registers to either; a register it parks there
+    between an untracked load and the manual wait would be saved before its data has arrived)."""
     import re
     name = None
     bad = []
@@ -37,11 +39,12 @@ def check_no_scratch(remarks: str, unit: str):
         if m:
             name = m.group(1)
             continue
-        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
-        if m and name and int(m.group(1)) > 0 and any(k in name for k in UNTRACKED_PREFETCH_KERNELS):
-            bad.append((name, int(m.group(1))))
+        m = re.search(r"(ScratchSize \[bytes/lane\]|AGPRs): (\d+)", line)
+        if m and name and int(m.group(2)) > 0 and any(k in name for k in UNTRACKED_PREFETCH_KERNELS):
+            bad.append((name, m.group(1), int(m.group(2))))
     if bad:
-        raise RuntimeError(f"{unit}: kernels with untracked register prefetch must not spill, but use scratch: {bad}")
+        raise RuntimeError(f"{unit}: kernels with untracked register prefetch must not spill, but use scratch memory or "
+                           f"accumulation registers: {bad}")
 
 
 def sources():
