@@ -292,19 +292,29 @@ int launch_corr_longk(const void *in, const void *f, void *out, const Shape &s, 
     const int NB = (s.L + 15) / 16;
     if (!aligned_to(in, 4 * sizeof(T)) || !aligned_to(out, 4 * sizeof(T))) return -1;
     if (s.K > dwconv::kLkMaxK || NB > dwconv::kLkMaxBlocks) {
-        // beyond what LDS holds whole: pieces of 4096 outputs, filter chunks of 4096 taps (either storage type; bf16
-        // rows are widened on the way into LDS)
+        // beyond what LDS holds whole: pieces of 4096 outputs, filter chunks of 4096 taps
         dwconv::LongKTileGeom tg;
         tg.B = s.B; tg.C = s.C; tg.L = s.L; tg.K = s.K; tg.pad = pad_eff; tg.reverse = reverse; tg.NB = NB;
         tg.NP = (s.L + dwconv::kLkTilePiece - 1) / dwconv::kLkTilePiece;
         tg.NCK = (s.K + dwconv::kLkTileChunk - 1) / dwconv::kLkTileChunk;
         const long long gy = (((long long)s.B + 1) / 2) * tg.NP;
         if (gy > 65535 || s.L > kMfmaMaxL) return -1;
-        const size_t lds = dwconv::longk_tiled_lds_bytes();
-        if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::corr_longk_tiled_kernel<T>)) return -1;
-        hipLaunchKernelGGL((dwconv::corr_longk_tiled_kernel<T>), dim3((unsigned)s.C, (unsigned)gy), dim3(64 * dwconv::kLkWaves),
-                           lds, st, static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), tg);
-        return launch_status();
+        if constexpr (sizeof(T) == 2) {
+            // bf16 storage: raw bf16 operands on the bf16 matrix instruction
+            const size_t lds = dwconv::longk_tiled_bf16_lds_bytes();
+            if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::corr_longk_tiled_bf16_kernel<>)) return -1;
+            hipLaunchKernelGGL((dwconv::corr_longk_tiled_bf16_kernel<>), dim3((unsigned)s.C, (unsigned)gy),
+                               dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const bf16_t *>(in),
+                               static_cast<const bf16_t *>(f), static_cast<bf16_t *>(out), tg);
+            return launch_status();
+        } else {
+            const size_t lds = dwconv::longk_tiled_lds_bytes();
+            if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::corr_longk_tiled_kernel<T>)) return -1;
+            hipLaunchKernelGGL((dwconv::corr_longk_tiled_kernel<T>), dim3((unsigned)s.C, (unsigned)gy),
+                               dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(in), static_cast<const T *>(f),
+                               static_cast<T *>(out), tg);
+            return launch_status();
+        }
     }
     dwconv::LongKGeom g;
     g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K;

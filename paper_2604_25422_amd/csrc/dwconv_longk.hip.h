@@ -288,7 +288,7 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_tiled_kernel(const T
 //       a mod 4 depends on the lane only: it reads copy (a mod 4) at a - (a mod 4), and a grows by 16 per offset.
 //       The copies start 64 bytes apart modulo 256, which puts the sixteen r of a read on different banks.
 constexpr int kLkBf16CopyPad = 32;         // bf16 elements: makes the stride of the copies 64 bytes modulo 256
-__host__ __device__ inline int longk_bf16_copy_elems(int K)
+__host__ __device__ constexpr int longk_bf16_copy_elems(int K)
 {
     const int n = (K + 2 * kLkWMargin + 3) & ~3;                  // taps with margins, whole 8-byte granules
     return (n + 127) / 128 * 128 + kLkBf16CopyPad;                // stride = 64 bytes mod 256
@@ -404,6 +404,107 @@ __global__ __launch_bounds__(64 * kLkWaves) void corr_longk_bf16_kernel(const bf
                     st_elem4(o0 + (size_t)g.C * (size_t)g.L, make_float4(tot1[0], tot1[1], tot1[2], tot1[3]));
             }
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 storage beyond what LDS holds whole: the tiles of corr_longk_tiled_kernel (pieces of 4096 outputs of a row pair,
+// filter chunks of 4096 taps with pad - 4096 ck) on the operands of corr_longk_bf16_kernel (four shifted copies of the
+// filter chunk, raw bf16 window blocks of 48 bytes, one v_mfma_f32_16x16x16_bf16 per block offset and row).
+inline size_t longk_tiled_bf16_lds_bytes()
+{
+    return (size_t)4 * longk_bf16_copy_elems(kLkTileChunk) * 2 + (size_t)kLkRows * kLkTileWinBlocks * kBf16BlockBytes;
+}
+
+template <int UNUSED = 0>   // (a template only so that the header can be included by several translation units)
+__global__ __launch_bounds__(64 * kLkWaves) void corr_longk_tiled_bf16_kernel(const bf16_t *__restrict__ in,
+                                                                               const bf16_t *__restrict__ f,
+                                                                               bf16_t *__restrict__ out, const LongKTileGeom g)
+{
+    extern __shared__ __align__(16) unsigned char lktb_smem[];
+    constexpr int CE = longk_bf16_copy_elems(kLkTileChunk);
+    constexpr int FW = (kLkTileChunk + 2 * kLkWMargin + 3) & ~3;
+    constexpr int XR = kLkTileWinBlocks * kBf16BlockBytes;
+    uint16_t *fwc = reinterpret_cast<uint16_t *>(lktb_smem);     // copy s at fwc + s * CE: copy_s[e] = chunk tap e + s - margin
+    unsigned char *xr = lktb_smem + (size_t)4 * CE * 2;          // two staged windows
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int t = __builtin_amdgcn_readfirstlane(tid >> 6);      // the wave's tile of the piece
+    const int i16 = lane & 15;
+    const int kg = lane >> 4;
+    const int c = blockIdx.x;
+    const int a = g.NP - 1 - (int)(blockIdx.y % (unsigned)g.NP);     // piece (the dear ones of a causal filter first)
+    const int b0 = 2 * (int)(blockIdx.y / (unsigned)g.NP);
+    const int n0 = (kLkTilePiece / 16) * a + 16 * t;                 // row block of the tile's first output block
+    const bf16_t *f_c = f + (size_t)c * (size_t)g.K;
+
+    floatx4 tot0 = floatx4{0.f, 0.f, 0.f, 0.f}, tot1 = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int ck = 0; ck < g.NCK; ++ck) {
+        const int klen = min(kLkTileChunk, g.K - ck * kLkTileChunk);
+        const int padc = g.pad - ck * kLkTileChunk;
+        const int dminc = -((padc + 15) >> 4), dmaxc = (klen - padc + 14) >> 4;     // (arithmetic shifts: floor division)
+        const int wlo = (kLkTilePiece / 16) * a + dminc;             // row block of window block 0
+        const int nwb = kLkTilePiece / 16 + (dmaxc - dminc);         // window blocks
+        if (wlo + nwb - 1 < 0 || wlo >= g.NB) continue;              // the window misses the row (block-uniform)
+        __syncthreads();                                             // everyone is done with the previous chunk
+        for (int i = tid; i < 4 * FW; i += 64 * kLkWaves) {
+            const int s = i / FW, e = i - s * FW;
+            const int jj = e + s - kLkWMargin;
+            uint16_t v = 0;
+            if (jj >= 0 && jj < klen) {
+                const int j = ck * kLkTileChunk + jj;
+                v = f_c[g.reverse ? (g.K - 1 - j) : j].bits;
+            }
+            fwc[s * CE + e] = v;
+        }
+        for (int rb = 0; rb < kLkRows; ++rb) {
+            unsigned char *xrow = xr + rb * XR;
+            const int b = b0 + rb;
+            const bf16_t *in_row = in + ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            for (int gi = tid; gi < nwb * 4; gi += 64 * kLkWaves) {
+                const int m = wlo + (gi >> 2);
+                const int u = 16 * m + 4 * (gi & 3);
+                uint2 v = make_uint2(0u, 0u);
+                if (b < g.B && m >= 0 && u + 3 < g.L) v = *reinterpret_cast<const uint2 *>(in_row + u);
+                *reinterpret_cast<uint2 *>(xrow + (gi >> 2) * kBf16BlockBytes + (gi & 3) * 8) = v;
+            }
+        }
+        __syncthreads();
+        // offsets for which some block n0 + j + d of the tile lies inside the row
+        const int dlo = max(dminc, -(n0 + 15));
+        const int dhi = min(dmaxc, g.NB - 1 - n0);
+        if (dlo <= dhi && b0 < g.B) {
+            // A: lane (r = i16, kg) needs chunk taps 16 d + 4 kg + e - r + padc, e = 0..3: copy (a0 & 3) read at a0 - (a0 & 3),
+            // a0 = margin + 4 kg - r + padc (16 d keeps a0 & 3);  B: lane (j = i16, kg) reads window block 16 t + j + d - dminc
+            const int a0 = kLkWMargin + 4 * kg - i16 + padc;
+            const int sh = a0 & 3;
+            const uint16_t *ap = fwc + sh * CE + (a0 - sh) + 16 * dlo;
+            const unsigned char *bp = xr + (16 * t + i16 + (dlo - dminc)) * kBf16BlockBytes + 8 * kg;
+            for (int d0 = dlo; d0 <= dhi; d0 += kLkFold) {
+                const int n = min(kLkFold, dhi - d0 + 1);
+                floatx4 acc0 = floatx4{0.f, 0.f, 0.f, 0.f}, acc1 = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+                for (int i = 0; i < n; ++i) {
+                    const shortx4 av = *reinterpret_cast<const shortx4 *>(ap);
+                    const shortx4 x0 = *reinterpret_cast<const shortx4 *>(bp);
+                    const shortx4 x1 = *reinterpret_cast<const shortx4 *>(bp + XR);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, x0, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, x1, acc1, 0, 0, 0);
+                    ap += 16;
+                    bp += kBf16BlockBytes;
+                }
+                tot0 += acc0;
+                tot1 += acc1;
+            }
+        }
+    }
+    // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the tile
+    const int to = 16 * n0 + 16 * i16 + 4 * kg;
+    if (b0 < g.B && to + 3 < g.L) {
+        bf16_t *o0 = out + ((size_t)b0 * (size_t)g.C + (size_t)c) * (size_t)g.L + to;
+        st_elem4(o0, make_float4(tot0[0], tot0[1], tot0[2], tot0[3]));
+        if (b0 + 1 < g.B) st_elem4(o0 + (size_t)g.C * (size_t)g.L, make_float4(tot1[0], tot1[1], tot1[2], tot1[3]));
     }
 }
 
