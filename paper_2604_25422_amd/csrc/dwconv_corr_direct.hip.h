@@ -49,13 +49,16 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int i16 = lane & 15, k4 = lane >> 4;
 
     const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    // Two walks.  Rows of whole segments: wave w takes segments w, w + n_waves, ... of the memory order.  Rows whose last
-    // segment is ragged (g.row_walk): wave w takes rows w, w + n_waves, ... and every segment of a row in turn, waves
-    // starting at different segments - the nearly empty last segment of a row then costs every wave the same, and the
-    // number of waves does not have to be a multiple of the segments per row.
-    int row = __builtin_amdgcn_readfirstlane(g.row_walk ? wg : wg / g.segs_per_row);                 // b * C + c
-    int seg = __builtin_amdgcn_readfirstlane(g.row_walk ? (wg + wg / g.C) % g.segs_per_row : wg % g.segs_per_row);
-    const int seg0 = seg;
+    // Wave n_light + w takes segments w, w + n_main, ... of the memory order (row, segment), over the first walk_segs
+    // segments of every row: at any moment the chip then reads one contiguous stretch of memory (waves that walk along
+    // rows of their own, 4096 scattered streams, measured 8 to 12 % slower).  walk_segs is all segments of a row, or all
+    // but the last when that one holds few positions: a nearly empty segment costs a wave as much as a memory round
+    // trip and would tie the number of waves to an awkward number of segments per row, so such segments go to n_light
+    // waves of their own (the first of the launch: wave w takes the last segment of rows w, w + n_light, ...).
+    const bool light = wg < g.n_light;
+    const int wm = wg - g.n_light;
+    int row = __builtin_amdgcn_readfirstlane(light ? wg : wm / g.walk_segs);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(light ? g.segs_per_row - 1 : wm % g.walk_segs);
     int c = __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
 
@@ -125,14 +128,15 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 
     for (;;) {
         int seg_n, row_n, c_n;
-        if (g.row_walk) {
-            seg_n = seg + 1 == g.segs_per_row ? 0 : seg + 1;
-            row_n = row + (seg_n == seg0 ? g.n_waves : 0);
-            c_n = c;
+        if (light) {
+            seg_n = seg;
+            row_n = row + g.n_light;
+            c_n = c + g.step_c_light;
+            c_n -= c_n >= g.C ? g.C : 0;
         } else {
             seg_n = seg + g.step_seg;
-            const int carry = seg_n >= g.segs_per_row ? 1 : 0;
-            seg_n -= carry ? g.segs_per_row : 0;
+            const int carry = seg_n >= g.walk_segs ? 1 : 0;
+            seg_n -= carry ? g.walk_segs : 0;
             row_n = row + g.step_rows + carry;
             c_n = c + g.step_c + carry;
             c_n -= c_n >= g.C ? g.C : 0;
@@ -206,13 +210,16 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int i16 = lane & 15, kg = lane >> 4;
 
     const int wg = (int)blockIdx.x * kCorrWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    // Two walks.  Rows of whole segments: wave w takes segments w, w + n_waves, ... of the memory order.  Rows whose last
-    // segment is ragged (g.row_walk): wave w takes rows w, w + n_waves, ... and every segment of a row in turn, waves
-    // starting at different segments - the nearly empty last segment of a row then costs every wave the same, and the
-    // number of waves does not have to be a multiple of the segments per row.
-    int row = __builtin_amdgcn_readfirstlane(g.row_walk ? wg : wg / g.segs_per_row);                 // b * C + c
-    int seg = __builtin_amdgcn_readfirstlane(g.row_walk ? (wg + wg / g.C) % g.segs_per_row : wg % g.segs_per_row);
-    const int seg0 = seg;
+    // Wave n_light + w takes segments w, w + n_main, ... of the memory order (row, segment), over the first walk_segs
+    // segments of every row: at any moment the chip then reads one contiguous stretch of memory (waves that walk along
+    // rows of their own, 4096 scattered streams, measured 8 to 12 % slower).  walk_segs is all segments of a row, or all
+    // but the last when that one holds few positions: a nearly empty segment costs a wave as much as a memory round
+    // trip and would tie the number of waves to an awkward number of segments per row, so such segments go to n_light
+    // waves of their own (the first of the launch: wave w takes the last segment of rows w, w + n_light, ...).
+    const bool light = wg < g.n_light;
+    const int wm = wg - g.n_light;
+    int row = __builtin_amdgcn_readfirstlane(light ? wg : wm / g.walk_segs);                 // b * C + c
+    int seg = __builtin_amdgcn_readfirstlane(light ? g.segs_per_row - 1 : wm % g.walk_segs);
     int c = __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
 
@@ -274,14 +281,15 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 
     for (;;) {
         int seg_n, row_n, c_n;
-        if (g.row_walk) {
-            seg_n = seg + 1 == g.segs_per_row ? 0 : seg + 1;
-            row_n = row + (seg_n == seg0 ? g.n_waves : 0);
-            c_n = c;
+        if (light) {
+            seg_n = seg;
+            row_n = row + g.n_light;
+            c_n = c + g.step_c_light;
+            c_n -= c_n >= g.C ? g.C : 0;
         } else {
             seg_n = seg + g.step_seg;
-            const int carry = seg_n >= g.segs_per_row ? 1 : 0;
-            seg_n -= carry ? g.segs_per_row : 0;
+            const int carry = seg_n >= g.walk_segs ? 1 : 0;
+            seg_n -= carry ? g.walk_segs : 0;
             row_n = row + g.step_rows + carry;
             c_n = c + g.step_c + carry;
             c_n -= c_n >= g.C ? g.C : 0;

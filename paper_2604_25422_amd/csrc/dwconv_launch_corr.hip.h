@@ -45,7 +45,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     g.C = s.C; g.L = s.L; g.K = s.K; g.rows = (int)rows;
     g.pad = pad_eff; g.reverse = reverse; g.dmin = dmin;
     g.segs_per_row = (int)segs_per_row;
-    g.row_walk = 0;
+    g.walk_segs = (int)segs_per_row; g.n_main = 0; g.n_light = 0; g.step_c_light = 0;
     constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
     const dwconv::RowsMap no_rows{0, 0, 0, 0, 0u, 0u};
     // One resident round of waves, each walking segments wave, wave + n_waves, ...
@@ -55,23 +55,36 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     // the same number of waves (a multiple of 1024 waves: with 2560 waves two SIMDs of a compute unit carry three
     // waves and two carry two, and the launch takes as long as the three) and the rounds divide the batch
     // (B32 C256 L4100 K64: 70.3 us with 2560 waves, 65.3 with 3840, 62.4 with 5120; L3000: 43.5 us with 3072).
-    // row_walk (the kernels that have it, rows whose last segment is ragged): a wave owns whole rows of one channel, J * C
-    // waves; the light last segments are then spread evenly over the waves and the segments per row drop out of the
-    // wave count (fwd, B32 C256 L8196: K16 127 -> 114 us, K64 128 -> 124 us; bf16 B128 C768 L1026 K32 128 -> 115 us; within
-    // the noise where the segments per row already divided the chip evenly, e.g. B32 C256 L4100 K64 63 us).  What a
-    // nearly empty segment still costs is one exposed memory round trip: nothing to compute while the next window loads.
+    // own_light_waves (the kernels that have them): a ragged last segment of at most 512 positions (two live quarters)
+    // is left out of this walk and gets waves of its own - about four per compute unit, more for short rows, a whole
+    // number of times C where C allows (they then stay on one channel), and out of the resident round, so that all waves
+    // of the launch start together.  The others then walk whole segments
+    // only, in the order and number of a shape without the ragged end (fwd, B32 C256: L4160 K16 54.9 -> 50.5 us against
+    // 48.8 us at L4096; L8196 K16 127 -> 104 us; L4100 K64 62.8 -> 58.4 us).  Where that would take more than a third of
+    // the resident waves the light segments stay in the walk.
     auto launch = [&](auto kernel, auto *pi, auto *pf, auto *po, long long slot_cap = kTargetWaves,
-                      long long balance_target = 0, bool row_walk = false) -> int {
-        long long resident = balance_target > 0 ? resident_waves(kernel, kThreads) : corr_wave_slots(kernel, kThreads);
-        if (resident > slot_cap) resident = slot_cap;
-        long long spw = (total_segs + resident - 1) / resident;      // segments per wave, rounded up
+                      long long balance_target = 0, bool own_light_waves = false) -> int {
+        const long long capacity = balance_target > 0 ? resident_waves(kernel, kThreads) : corr_wave_slots(kernel, kThreads);
+        const int last = s.L % dwconv::kSegLen;
+        long long n_light = 0;
+        if (own_light_waves && balance_target > 0 && last != 0 && last <= dwconv::kSegLen / 2 && segs_per_row >= 2) {
+            // a light segment costs its wave about a microsecond (a memory round trip), a row of the walk about
+            // 2 L sizeof(T) / 5 TB/s spread over all waves: enough light waves to be done in 0.6 of the launch
+            const long long need = (long long)(5.0e6 / (0.6 * 2.0 * (double)s.L * (double)sizeof(T))) + 1;
+            const long long want = need > 1024 ? need : 1024;
+            n_light = s.C >= want ? s.C : (long long)s.C * ((want + s.C - 1) / s.C);
+            if (n_light > rows) n_light = rows;
+            if (3 * n_light > capacity) n_light = 0;
+        }
+        const long long walk_segs = segs_per_row - (n_light > 0 ? 1 : 0);
+        const long long walk_total = rows * walk_segs;
+        long long resident = capacity - n_light < slot_cap ? capacity - n_light : slot_cap;
+        long long spw = (walk_total + resident - 1) / resident;      // segments per wave, rounded up
         if (spw < 1) spw = 1;
-        long long waves = (total_segs + spw - 1) / spw;
-        row_walk = row_walk && (s.L % dwconv::kSegLen) != 0 && s.C <= resident && balance_target > 0;
+        long long waves = (walk_total + spw - 1) / spw;
         // A whole number of batch entries per round where one fits: the stride of the walk is then a multiple of
         // C rows, a wave stays on one channel and loads its Toeplitz operands once.
-        const long long per_b = row_walk ? (long long)s.C : (long long)s.C * segs_per_row;
-        g.row_walk = row_walk ? 1 : 0;
+        const long long per_b = (long long)s.C * walk_segs;
         if (per_b <= resident) {
             long long J = resident / per_b;
             if (J > s.B) J = s.B;
@@ -95,11 +108,15 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
             }
             waves = J * per_b;
         }
-        const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
-        g.n_waves = (int)waves;
-        g.step_rows = g.n_waves / g.segs_per_row;
-        g.step_seg = g.n_waves % g.segs_per_row;
+        g.walk_segs = (int)walk_segs;
+        g.n_main = (int)waves;
+        g.n_light = (int)n_light;
+        g.step_c_light = (int)(n_light % s.C);
+        g.n_waves = (int)(waves + n_light);
+        g.step_rows = g.n_main / g.walk_segs;
+        g.step_seg = g.n_main % g.walk_segs;
         g.step_c = g.step_rows % s.C;
+        const long long blocks = (g.n_waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };

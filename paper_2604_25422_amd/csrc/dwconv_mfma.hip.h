@@ -57,11 +57,17 @@ struct CorrGeom {
     int dmin;           // first block offset
     int segs_per_row;   // segments of kSegLen outputs per row
     int n_waves;        // waves launched; wave w walks segments w, w + n_waves, ... of the memory order (row, seg)
-    int step_rows;      // n_waves / segs_per_row
-    int step_seg;       // n_waves % segs_per_row
+    int step_rows;      // n_main / walk_segs
+    int step_seg;       // n_main % walk_segs
     int step_c;         // step_rows % C
-    int row_walk;       // kernels that load rows straight into LDS: wave w owns rows w, w + n_waves, ... (n_waves a multiple
-                        // of C) and walks all segments of a row, starting at segment (w + w / C) % segs_per_row
+    // Kernels that load rows straight into LDS (the others walk all segments: walk_segs = segs_per_row, n_light = 0,
+    // n_main = n_waves).  Waves n_light .. n_waves - 1 walk the first walk_segs segments of every row (step_rows, step_seg
+    // and step_c are those of n_main over walk_segs); walk_segs is segs_per_row, or segs_per_row - 1 when the last segment
+    // holds so few positions that it gets waves of its own: wave w < n_light takes the last segment of rows w, w + n_light, ...
+    int walk_segs;
+    int n_main;
+    int n_light;
+    int step_c_light;   // n_light % C
 };
 
 // Row access through buffer instructions.  A buffer resource describes (the tail of) ONE row
