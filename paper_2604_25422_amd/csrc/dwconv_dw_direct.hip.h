@@ -222,6 +222,27 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
         seg_n -= carry ? segs_per_row : 0;
         const int b_n = b + step_b + carry;
         aim(b_n, seg_n);
+        if constexpr (!ROWS && ND <= 6) {
+            // (up to six block offsets: beyond, this second body costs the kernel registers it does not have)
+            // A last segment that holds at most 256 positions of its row (rows that are not whole segments): dY is
+            // zero beyond them, so only the first four chunks can add anything; they need x0, g0 and x1, the first three
+            // of the nine loads of this segment, which are the last nine issued.  Then all nine loads of the next
+            // segment go out in the usual order.
+            if (L - (seg0 + seg) * kSegLen <= 256) {
+                wait_vmcnt_at_most<6>();
+                static_for<0, 4>([&](auto cc) {
+                    constexpr int ch = decltype(cc)::value;
+                    const float gv = sg[64 * ch + lane];
+#pragma unroll
+                    for (int d = 0; d < ND; ++d) G[d] = mfma16x16x4(sx[64 * ch + 16 * d + lane], gv, G[d]);
+                });
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                static_for<0, 4>([&](auto ic) { load_x(ic); load_g(ic); });
+                load_x(std::integral_constant<int, 4>{});
+                b = b_n; seg = seg_n;
+                continue;
+            }
+        }
         // 64-position chunk ch, block offset d:  G_d += X[n0 + k + dmin + d][q'] * dY[n0 + k][q]
         //   A operand sx[64 ch + 16 d + lane],  B operand sg[64 ch + lane].
         // LDS reads run ahead of the matrix instructions in two small rings.

@@ -9,6 +9,8 @@ intermediate tensor) are compared unrounded.
 Also here: the same comparison on tensors whose base pointers are aligned to the element size only (views one
 element into an allocation), which takes every dispatch class to its generic kernels with a plan sized for the
 matrix-core ones."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -132,3 +134,35 @@ def test_exact_on_element_aligned_views(oracle_mod, dtype, B, C, L, K, p):
 def test_exact_on_partly_aligned_views(oracle_mod, B, C, L, K, p, dtype, offset):
     print(f"case exact offset {offset} {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
     run_exact(oracle_mod, B, C, L, K, p, dtype, seed=5, offset=offset)
+
+
+def _random_exact_shapes(n, seed):
+    """Seeded shapes around every threshold of the dispatch (block-offset counts, row-length classes, channel counts
+    that change the weight-gradient plan), each with a storage type and an element offset of the views."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([1, 2, 3, 4, 7, 8, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 66, 67, 80, 100, 127, 128, 129, 161,
+                            200, 226, 227, 256, 300, 482, 483, 512, 700, 738, 739, 994, 1000, 2000, 4096, 5000]))
+        L = int(rng.choice([1, 3, 4, 8, 16, 17, 20, 44, 48, 52, 64, 68, 96, 100, 128, 129, 132, 200, 256, 257, 500, 512, 700, 766,
+                            767, 768, 769, 770, 1000, 1023, 1024, 1025, 1026, 1027, 1028, 1100, 1280, 1536, 2047, 2048, 2049,
+                            2050, 2052, 2300, 3000, 3001, 3072, 3076, 4096, 4097, 4098, 4100, 4160, 5000, 6000, 8192, 8196, 9000]))
+        C = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16, 31, 64, 256, 257, 512, 768, 1024, 1030]))
+        B = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 33, 64, 100, 130, 300]))
+        if B * C * L > 3e6 or B * C * L * min(K, L) > 4e8 or 9 * B * L >= 2 ** 24:
+            continue
+        p = int(rng.choice([0, K // 2, K - 1, int(rng.integers(0, K))]))
+        dtype = "bf16" if rng.random() < 0.4 else "f32"
+        offset = int(rng.choice([0, 0, 0, 1, 2, 4]))
+        out.append((B, C, L, K, p, dtype, offset))
+    return out
+
+
+# DWCONV_EXACT_SWEEP_N / DWCONV_EXACT_SWEEP_SEED widen or move the sweep for a one-off soak (9000 shapes over three other
+# seeds have been run that way); the defaults are what the suite runs.
+@pytest.mark.parametrize("B,C,L,K,p,dtype,offset",
+                         _random_exact_shapes(int(os.environ.get("DWCONV_EXACT_SWEEP_N", "250")),
+                                              int(os.environ.get("DWCONV_EXACT_SWEEP_SEED", "20260425"))))
+def test_exact_random_shapes(oracle_mod, B, C, L, K, p, dtype, offset):
+    print(f"case exact random {dtype} B{B} C{C} L{L} K{K} p{p} offset {offset}", flush=True)
+    run_exact(oracle_mod, B, C, L, K, p, dtype, seed=B + 3 * C + 5 * L + 7 * K + p, offset=offset)
