@@ -301,6 +301,12 @@ DwPlan plan_dw(const Shape &s)
         p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
         p.valu_items_per_slice = p.items_per_slice;
     }
+    // the generic kernel on short rows: its items are the tiles of the virtual row of the channel
+    p.valu_rows = plan_valu_rows(s);
+    if (p.valu_rows.on) {
+        p.valu_tiles_per_row = (int)p.valu_rows.tiles;
+        p.valu_items_per_slice = (int)((p.valu_rows.tiles + p.S - 1) / p.S);
+    }
     return p;
 }
 

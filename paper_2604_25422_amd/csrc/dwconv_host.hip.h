@@ -88,6 +88,33 @@ struct RowsPlan {
 };
 RowsPlan plan_rows(const Shape &s);
 
+// The same idea for the generic vector-ALU kernels, which take any row length and alignment: short rows are walked as
+// the virtual row of their channel (pitch L + max(pad, K-1-pad), no rounding: these kernels load by element) when at
+// least two rows fit a 1024-position tile and positions and element offsets stay 32-bit (B16384 C128 L50 K48, which no
+// matrix-core kernel takes: 3.1 ms per forward with one tile per 50-position row).
+struct ValuRows {
+    bool on;
+    long long tiles;        // 1024-position tiles of the virtual row
+    dwconv::RowsMap map;
+};
+inline ValuRows plan_valu_rows(const Shape &s)
+{
+    ValuRows r;
+    r.on = false; r.tiles = 0;
+    r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
+    const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
+    const long long P = (long long)s.L + halo;
+    const long long elems = (long long)s.B * s.C * s.L;
+    if (s.B < 2 || P < 2 || 2 * P > dwconv::kSegLen || elems >= (1ll << 31)) return r;     // (P = 1: 2^32 / P + 1 is not 32-bit)
+    if (((long long)s.B * P + 2 * dwconv::kSegLen + s.K) * P >= (1ll << 32)) return r;      // (exact division by P)
+    r.on = true;
+    r.tiles = ((long long)s.B * P + dwconv::kSegLen - 1) / dwconv::kSegLen;
+    r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
+    r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
+    r.map.bytes = 0u;
+    return r;
+}
+
 constexpr long long kTargetWaves = 4096;   // 256 CUs x 16 resident waves (weight-gradient plan; shape-only)
 
 // Waves of `kernel` that are resident on the current device at once (one full round), from the
@@ -169,7 +196,8 @@ struct DwPlan {
     int S_fused;           // slices the fused backward call writes (differs from S for rows of at most 48 positions)
     bool single;           // S == 1 with one block per channel: stage 1 may write the gradient itself
     int tiles_per_row;     // segments the matrix-core kernels walk per row (per virtual row for short rows)
-    int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel (always real rows)
+    int valu_tiles_per_row, valu_items_per_slice;   // the same bookkeeping for the generic kernel
+    ValuRows valu_rows;    // short rows on the generic kernel: tiles of the virtual row of a channel
     int segs_per_wave;     // (b, segment) items a wave of the matrix-core kernels walks
     int items_per_slice;   // (b, segment) items each slice owns = wpb * segs_per_wave
 };

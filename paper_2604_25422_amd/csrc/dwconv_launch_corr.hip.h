@@ -12,12 +12,23 @@ int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, i
 {
     constexpr int R = 4, THREADS = 256, KCH = 512;
     constexpr int TILE = R * THREADS;
+    static_assert(TILE == dwconv::kSegLen, "plan_valu_rows counts tiles of this size");
+    const ValuRows vr = plan_valu_rows(s);
+    if (vr.on) {
+        // short rows: tiles of the virtual row of every channel
+        const long long blocks = (long long)s.C * vr.tiles;
+        if (blocks > 0x7fffffffLL) return DWCONV_ERR_SHAPE;
+        hipLaunchKernelGGL((dwconv::corr_valu_kernel<T, R, THREADS, KCH, true>), dim3((unsigned)blocks), dim3(THREADS), 0, st,
+                           static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), s.C, s.L, s.K,
+                           pad_eff, reverse, (int)vr.tiles, vr.map);
+        return launch_status();
+    }
     const long long tiles_per_row = ((long long)s.L + TILE - 1) / TILE;
     const long long blocks = (long long)s.B * s.C * tiles_per_row;
     if (blocks > 0x7fffffffLL) return DWCONV_ERR_SHAPE;
-    hipLaunchKernelGGL((dwconv::corr_valu_kernel<T, R, THREADS, KCH>), dim3((unsigned)blocks), dim3(THREADS), 0, st,
+    hipLaunchKernelGGL((dwconv::corr_valu_kernel<T, R, THREADS, KCH, false>), dim3((unsigned)blocks), dim3(THREADS), 0, st,
                        static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), s.C, s.L, s.K,
-                       pad_eff, reverse, (int)tiles_per_row);
+                       pad_eff, reverse, (int)tiles_per_row, dwconv::RowsMap{0, 0, 0, 0, 0u, 0u});
     return launch_status();
 }
 

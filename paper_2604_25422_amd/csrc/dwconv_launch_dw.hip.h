@@ -10,9 +10,15 @@ namespace dwhost {
 template <typename T, int KCH>
 void launch_dw_partial_valu(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st)
 {
-    hipLaunchKernelGGL((dwconv::dw_partial_valu_kernel<T, kDwThreads, kDwTT, KCH>), dim3((unsigned)s.C, (unsigned)p.S),
+    if (p.valu_rows.on) {
+        hipLaunchKernelGGL((dwconv::dw_partial_valu_kernel<T, kDwThreads, kDwTT, KCH, true>), dim3((unsigned)s.C, (unsigned)p.S),
+                           dim3(kDwThreads), 0, st, static_cast<const T *>(x), static_cast<const T *>(dy), part, 1, s.C,
+                           s.L, s.K, s.pad, p.valu_tiles_per_row, p.valu_items_per_slice, p.valu_rows.map);
+        return;
+    }
+    hipLaunchKernelGGL((dwconv::dw_partial_valu_kernel<T, kDwThreads, kDwTT, KCH, false>), dim3((unsigned)s.C, (unsigned)p.S),
                        dim3(kDwThreads), 0, st, static_cast<const T *>(x), static_cast<const T *>(dy), part, s.B, s.C,
-                       s.L, s.K, s.pad, p.valu_tiles_per_row, p.valu_items_per_slice);
+                       s.L, s.K, s.pad, p.valu_tiles_per_row, p.valu_items_per_slice, dwconv::RowsMap{0, 0, 0, 0, 0u, 0u});
 }
 
 // One stage-1 launch on the matrix cores.  dw_out != nullptr only for single-slice plans.

@@ -132,27 +132,6 @@ __device__ __forceinline__ void release_after_wait(V (&regs)[N])
     for (int i = 0; i < N; ++i) asm volatile("" : "+v"(regs[i]));
 }
 
-// Short rows.  A 1024-position segment of a row much shorter than that is mostly padding, so for short rows the
-// kernels work on the VIRTUAL row of a channel instead: its B rows (b, c), b = 0..B-1, laid end to end with pitch
-// P = L + gap, gap >= max(pad, K-1-pad) zeros, so that no tap of one row reaches into the next.  That is the same
-// operator on a longer signal; only the address of a position changes: virtual position u = b P + t maps to
-// element (b C + c) L + t when t < L and to a zero otherwise.  Positions are translated when rows are loaded
-// (each lane fetches what belongs in its LDS slot) and when outputs are stored.
-struct RowsMap {
-    int P;          // pitch of a row inside the virtual row (multiple of 4)
-    int L;          // row length
-    int CL;         // C * L: elements between row (b, c) and row (b + 1, c)
-    int Lv;         // B * P: length of the virtual row
-    unsigned M;     // floor(2^32 / P) + 1: u / P == umulhi(u, M) for 0 <= u < 2^32 / P
-    unsigned bytes; // bytes from element (0, 0, 0) to the end of the tensor (< 2^30)
-};
-// Element offset (from the channel's first row) of virtual position u, or -1 where the virtual row holds a zero.
-__device__ __forceinline__ int rows_element(const RowsMap &m, int u)
-{
-    const int b = (int)__umulhi((unsigned)u, m.M);
-    const int t = u - b * m.P;
-    return ((unsigned)u < (unsigned)m.Lv && t < m.L) ? b * m.CL + t : -1;
-}
 // Byte offset for a buffer load (out of range where the virtual row holds a zero).
 template <int ES>
 __device__ __forceinline__ int rows_byte_offset(const RowsMap &m, int u)

@@ -21,10 +21,13 @@ namespace dwconv {
 // Taps are consumed in chunks of KCH so LDS stays bounded for any K; each chunk
 // has its own accumulator that is added to the running total (bounds the length
 // of any sequential fp32 sum by KCH + K/KCH).
-template <typename T, int R, int THREADS, int KCH>
+// VROWS (short rows, see RowsMap): a tile is TILE consecutive positions of the VIRTUAL row of a channel - its B rows
+// laid end to end with zeros between them - instead of a tile of one real row that is mostly padding; blockIdx.x / tiles_per_row
+// is then the channel, and positions are translated where the window is staged and where outputs are stored.
+template <typename T, int R, int THREADS, int KCH, bool VROWS>
 __global__ __launch_bounds__(THREADS) void corr_valu_kernel(const T *__restrict__ in, const T *__restrict__ f,
                                                             T *__restrict__ out, int C, int L, int K, int pad,
-                                                            int reverse, int tiles_per_row)
+                                                            int reverse, int tiles_per_row, const RowsMap rm)
 {
     static_assert(R % 4 == 0 && KCH % 4 == 0, "vector width");
     constexpr int TILE = R * THREADS;
@@ -34,9 +37,9 @@ __global__ __launch_bounds__(THREADS) void corr_valu_kernel(const T *__restrict_
     const int tid = threadIdx.x;
     const size_t row = blockIdx.x / (unsigned)tiles_per_row;
     const int tile = blockIdx.x % (unsigned)tiles_per_row;
-    const int c = (int)(row % (size_t)C);
+    const int c = VROWS ? (int)row : (int)(row % (size_t)C);
     const int t0 = tile * TILE;
-    const T *in_row = in + row * (size_t)L;
+    const T *in_row = in + row * (size_t)L;          // VROWS: row (0, c), the first of the channel
     const T *f_c = f + (size_t)c * (size_t)K;
 
     float total[R];
@@ -54,7 +57,12 @@ __global__ __launch_bounds__(THREADS) void corr_valu_kernel(const T *__restrict_
         const int g0 = t0 + jc - pad;
         for (int i = tid; i < TILE + kc4; i += THREADS) {
             const int g = g0 + i;
-            s_in[i] = (g >= 0 && g < L) ? ld_elem(in_row + g) : 0.f;
+            if constexpr (VROWS) {
+                const int e = rows_element(rm, g);
+                s_in[i] = e >= 0 ? ld_elem(in_row + e) : 0.f;
+            } else {
+                s_in[i] = (g >= 0 && g < L) ? ld_elem(in_row + g) : 0.f;
+            }
         }
         __syncthreads();
 
@@ -88,7 +96,13 @@ __global__ __launch_bounds__(THREADS) void corr_valu_kernel(const T *__restrict_
 
     const int t = t0 + R * tid;
     T *out_row = out + row * (size_t)L;
-    if (t + R <= L && (L % 4) == 0) {
+    if constexpr (VROWS) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = rows_element(rm, t + r);
+            if (e >= 0) st_elem(out_row + e, total[r]);
+        }
+    } else if (t + R <= L && (L % 4) == 0) {
 #pragma unroll
         for (int r = 0; r < R; r += 4)
             st_elem4(out_row + t + r, make_float4(total[r], total[r + 1], total[r + 2], total[r + 3]));
@@ -103,10 +117,12 @@ __global__ __launch_bounds__(THREADS) void corr_valu_kernel(const T *__restrict_
 // grid = (C, S).  Thread (jg, tg): taps 4*jg..4*jg+3 of the current tap chunk, positions
 // [tg*SUB, (tg+1)*SUB) of each tile.  Items of a channel are (b, tile) pairs in row-major
 // order; slice s owns the contiguous range [s*per, (s+1)*per).
-template <typename T, int THREADS, int TT, int KCH>
+// VROWS (short rows, see RowsMap): the items are the tiles_per_row tiles of the virtual row of the channel (B is 1).
+template <typename T, int THREADS, int TT, int KCH, bool VROWS>
 __global__ __launch_bounds__(THREADS) void dw_partial_valu_kernel(const T *__restrict__ x, const T *__restrict__ dy,
                                                                   float *__restrict__ part, int B, int C, int L, int K,
-                                                                  int pad, int tiles_per_row, int items_per_slice)
+                                                                  int pad, int tiles_per_row, int items_per_slice,
+                                                                  const RowsMap rm)
 {
     constexpr int NJ = KCH / 4;
     constexpr int NT = THREADS / NJ;
@@ -130,16 +146,26 @@ __global__ __launch_bounds__(THREADS) void dw_partial_valu_kernel(const T *__res
         for (int it = it_begin; it < it_end; ++it) {
             const int b = it / tiles_per_row;
             const int t0 = (it % tiles_per_row) * TT;
-            const size_t row = ((size_t)b * (size_t)C + (size_t)c) * (size_t)L;
+            const size_t row = ((size_t)b * (size_t)C + (size_t)c) * (size_t)L;      // VROWS: b is 0
             __syncthreads();
             for (int i = tid; i < TT; i += THREADS) {
                 const int t = t0 + i;
-                s_dy[i] = (t < L) ? ld_elem(dy + row + t) : 0.f;
+                if constexpr (VROWS) {
+                    const int e = rows_element(rm, t);
+                    s_dy[i] = e >= 0 ? ld_elem(dy + row + e) : 0.f;
+                } else {
+                    s_dy[i] = (t < L) ? ld_elem(dy + row + t) : 0.f;
+                }
             }
             const int g0 = t0 + jc - pad;
             for (int i = tid; i < TT + KCH; i += THREADS) {
                 const int g = g0 + i;
-                s_x[i] = (g >= 0 && g < L) ? ld_elem(x + row + g) : 0.f;
+                if constexpr (VROWS) {
+                    const int e = rows_element(rm, g);
+                    s_x[i] = e >= 0 ? ld_elem(x + row + e) : 0.f;
+                } else {
+                    s_x[i] = (g >= 0 && g < L) ? ld_elem(x + row + g) : 0.f;
+                }
             }
             __syncthreads();
 
