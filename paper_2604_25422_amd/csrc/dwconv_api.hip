@@ -55,14 +55,23 @@ RowsPlan plan_rows(const Shape &s)
     r.on = false; r.batch = false; r.units = 0; r.nvs = 0;
     r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND || (s.L % 4) != 0) return r;
+    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND) return r;
     const long long es = (long long)elem_size(s.dtype);
     const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
-    const long long P = s.L + (halo + 3) / 4 * 4;
+    const long long P = (s.L + 3) / 4 * 4 + (halo + 3) / 4 * 4;
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
     if (4 * padded <= 5 * P) return r;                       // ordinary segments waste less than a quarter
     // sixteen rows per tile (either storage type): byte offsets inside a unit stay below the out-of-row marker
     const bool batch = s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30);
+    if ((s.L % 4) != 0) {
+        // rows that are not whole granules of four: the sixteen-row kernels only (rows must start on a dword: any fp32
+        // row, bf16 rows of even length)
+        if (batch && (s.dtype == DWCONV_F32 || (s.L % 2) == 0)) {
+            r.on = true; r.batch = true;
+            r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
+        }
+        return r;
+    }
     const long long elems = (long long)s.B * s.C * s.L;
     if (elems * es > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) {
         // too large for virtual rows (32-bit positions); the sixteen-row kernels have no such limit
@@ -198,15 +207,15 @@ DwPlan plan_dw(const Shape &s)
     }
     long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) && ((s.L % 4) == 0 || ragged_rows_ok(s, nd)) &&
-                            s.L <= kMfmaMaxL;
+    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) &&
+                            ((s.L % 4) == 0 || ragged_rows_ok(s, nd) || p.rows.batch) && s.L <= kMfmaMaxL;
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
     // waves takes a whole channel: no slices, no second stage.
     p.wpb = dwconv::kWavesPerBlock;
     p.single = false;
     p.dw_nc = 1;
     if (mfma_shape && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) && s.C % kComputeUnits == 0 &&
-        s.C / kComputeUnits <= 3) {
+        s.C / kComputeUnits <= 3 && !(p.rows.batch && (s.L % 4) != 0)) {
         int wpb = 16 / (s.C / kComputeUnits);
         // short filters leave the matrix pipe idle, and what then counts is how many bytes the chip has in flight:
         // two rows of 4 KiB per wave are enough with 8 to 12 waves per compute unit (B64 C512 L2048 K7: 82 us against
@@ -221,7 +230,7 @@ DwPlan plan_dw(const Shape &s)
     // launch latency: one workgroup per channel and no second launch there too.
     if (mfma_shape && !p.single && items <= 4 * dwconv::kWavesPerBlock) p.single = true;
     long long groups = s.C;                                      // blocks along the channel axis
-    if (p.rows.batch && !p.single && s.C % 2 == 0 && (s.L * (int)elem_size(s.dtype)) % 128 != 0 && s.L <= 48) {
+    if (p.rows.batch && !p.single && s.C % 2 == 0 && (s.L * (int)elem_size(s.dtype)) % 128 != 0 && s.L <= 48 && (s.L % 4) == 0) {
         // two neighbouring channels per block: rows that are not whole cache lines become pieces that are;
         // a unit is then eight rows of both channels
         p.dw_nc = 2;
@@ -472,7 +481,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const Shape s{B, C, L, K, pad_left, dtype};
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
-    if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type, L % 4 == 0
+    if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type
     if (dtype == DWCONV_BF16 && p.rows.on) return 0;
     const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_ok(s, nd) : true)))
                                                : ((L % 4) == 0 || ragged_rows_ok(s, nd));

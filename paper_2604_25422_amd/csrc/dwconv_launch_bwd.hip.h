@@ -65,7 +65,7 @@ int launch_bwd_rowbatch(const void *dy, const void *x, const void *w, void *dx, 
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
     if (s.L > dwconv::kRbBwdMaxL || nd < 2 || nd > kMfmaMaxND) return -1;
-    if (!aligned_to(x, 4 * sizeof(T)) || !aligned_to(dy, 4 * sizeof(T)) || !aligned_to(dx, 4 * sizeof(T))) return -1;
+    if (!aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4)) return -1;      // (rows that start on a dword)
     void *direct_rb = p.S_fused == 1 ? dw_out : nullptr;
     auto launch_rb = [&](auto kernel, size_t lds_rb) -> int {
         if (lds_rb > kMaxLdsBytes) return -1;
@@ -82,13 +82,24 @@ int launch_bwd_rowbatch(const void *dy, const void *x, const void *w, void *dx, 
         return m == 1 ? launch_rb(k1, lds_rb) : m == 2 ? launch_rb(k2, lds_rb) : launch_rb(k3, lds_rb);
     };
     int rc = -1;
-    switch (nd) {
-    case 2: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 2, 1>, dwconv::bwd_rowbatch_kernel<T, 2, 2>, dwconv::bwd_rowbatch_kernel<T, 2, 3>, 2); break;
-    case 3: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 3, 1>, dwconv::bwd_rowbatch_kernel<T, 3, 2>, dwconv::bwd_rowbatch_kernel<T, 3, 3>, 3); break;
-    case 4: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 4, 1>, dwconv::bwd_rowbatch_kernel<T, 4, 2>, dwconv::bwd_rowbatch_kernel<T, 4, 3>, 4); break;
-    case 5: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 5, 1>, dwconv::bwd_rowbatch_kernel<T, 5, 2>, dwconv::bwd_rowbatch_kernel<T, 5, 3>, 5); break;
-    case 6: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 6, 1>, dwconv::bwd_rowbatch_kernel<T, 6, 2>, dwconv::bwd_rowbatch_kernel<T, 6, 3>, 6); break;
-    default: break;
+    if ((s.L % 4) != 0) {
+        switch (nd) {
+        case 2: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 2, 1, true>, dwconv::bwd_rowbatch_kernel<T, 2, 2, true>, dwconv::bwd_rowbatch_kernel<T, 2, 3, true>, 2); break;
+        case 3: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 3, 1, true>, dwconv::bwd_rowbatch_kernel<T, 3, 2, true>, dwconv::bwd_rowbatch_kernel<T, 3, 3, true>, 3); break;
+        case 4: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 4, 1, true>, dwconv::bwd_rowbatch_kernel<T, 4, 2, true>, dwconv::bwd_rowbatch_kernel<T, 4, 3, true>, 4); break;
+        case 5: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 5, 1, true>, dwconv::bwd_rowbatch_kernel<T, 5, 2, true>, dwconv::bwd_rowbatch_kernel<T, 5, 3, true>, 5); break;
+        case 6: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 6, 1, true>, dwconv::bwd_rowbatch_kernel<T, 6, 2, true>, dwconv::bwd_rowbatch_kernel<T, 6, 3, true>, 6); break;
+        default: break;
+        }
+    } else {
+        switch (nd) {
+        case 2: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 2, 1, false>, dwconv::bwd_rowbatch_kernel<T, 2, 2, false>, dwconv::bwd_rowbatch_kernel<T, 2, 3, false>, 2); break;
+        case 3: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 3, 1, false>, dwconv::bwd_rowbatch_kernel<T, 3, 2, false>, dwconv::bwd_rowbatch_kernel<T, 3, 3, false>, 3); break;
+        case 4: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 4, 1, false>, dwconv::bwd_rowbatch_kernel<T, 4, 2, false>, dwconv::bwd_rowbatch_kernel<T, 4, 3, false>, 4); break;
+        case 5: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 5, 1, false>, dwconv::bwd_rowbatch_kernel<T, 5, 2, false>, dwconv::bwd_rowbatch_kernel<T, 5, 3, false>, 5); break;
+        case 6: rc = launch_m(dwconv::bwd_rowbatch_kernel<T, 6, 1, false>, dwconv::bwd_rowbatch_kernel<T, 6, 2, false>, dwconv::bwd_rowbatch_kernel<T, 6, 3, false>, 6); break;
+        default: break;
+        }
     }
     if (rc == DWCONV_OK && direct_rb) *wrote_dw = true;
     return rc;

@@ -41,7 +41,9 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(in, 4 * sizeof(T)) && aligned_to(out, 4 * sizeof(T));
-    if (!granular && (!ragged_rows_ok(s, nd) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
+    const RowsPlan rp = plan_rows(s);
+    // (the sixteen-row kernels of short rows move granules with buffer loads and stores that need dword alignment only)
+    if (!granular && ((!ragged_rows_ok(s, nd) && !rp.batch) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
     // block offsets the long-filter kernel takes too (fp32 eleven to sixteen, bf16 seven to sixteen): only where rows
     // fill their 1024-position segments to three quarters (shorter rows do less work on the long-filter kernel,
     // which contracts in-row block pairs only)
@@ -131,8 +133,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };
-    const RowsPlan rp = plan_rows(s);
-    if (!granular && (rp.on || rp.batch)) return -1;       // (short rows of a tensor that is only element-aligned)
+    if (!granular && rp.on && !rp.batch) return -1;       // (virtual rows of a tensor that is only element-aligned)
     if (rp.batch) {
         // rows of at most 128 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
         dwconv::RowBatchGeom rg;
@@ -142,7 +143,9 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         rg.n_units = rp.units;
         // two channels per wave where that makes whole cache lines of rows that are not, or at least longer pieces;
         // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
-        const int nc = (s.C % 2 == 0 && (s.L * (int)sizeof(T)) % 128 != 0 && s.L <= 48 && nd <= 5) ? 2 : 1;
+        // (two channels are one piece of 2 L elements cut into granules: rows of whole granules)
+        const int nc = (s.C % 2 == 0 && (s.L * (int)sizeof(T)) % 128 != 0 && s.L <= 48 && nd <= 5 && (s.L % 4) == 0) ? 2 : 1;
+        const bool rag = (s.L % 4) != 0;                   // rows that end inside a granule
         auto launch_batch = [&](auto kernel) -> int {
             // one resident round of waves: J per channel group, each walking units j, j + J, ...
             const long long groups = s.C / nc;
@@ -162,29 +165,29 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         };
         if (nc == 2) {
             switch (nd) {
-            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2, 3>);
-            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2, 3>);
-            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2, 3>);
-            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2, 3>);
+            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2, 3, false>);
+            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2, 3, false>);
+            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2, 3, false>);
+            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2, 3, false>);
             default: return -1;
             }
         }
         if (rg.m <= 4) {
             switch (nd) {
-            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4>);
-            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4>);
-            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4>);
-            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4>);
-            case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4>);
+            case 2: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4, false>);
+            case 3: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4, false>);
+            case 4: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4, false>);
+            case 5: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4, false>);
+            case 6: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4, false>);
             default: return -1;
             }
         }
         switch (nd) {                              // rows of five to eight blocks
-        case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8>);
-        case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8>);
-        case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8>);
-        case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8>);
-        case 6: return launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8>);
+        case 2: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8, false>);
+        case 3: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8, false>);
+        case 4: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8, false>);
+        case 5: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8, false>);
+        case 6: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8, false>);
         default: return -1;
         }
     }

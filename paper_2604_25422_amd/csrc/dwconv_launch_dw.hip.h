@@ -39,25 +39,35 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         };
         // (the kernel is compiled per number of 16-blocks of a row, not per number of block offsets)
         const int m = (s.L + 15) / 16;
+        // rows that end inside a granule: the variant with the partial-granule code, four-wave workgroups only (the plan
+        // asks for no others there)
+        auto rag_rb = [&](auto mc) -> int {
+            constexpr int MM = decltype(mc)::value;
+            if ((s.L % 4) != 0) {
+                if constexpr (W == dwconv::kWavesPerBlock) return launch_rb(dwconv::dw_rowbatch_kernel<T, MM, W, 1, true>, 1);
+                else return -1;
+            }
+            return launch_rb(dwconv::dw_rowbatch_kernel<T, MM, W, 1, false>, 1);
+        };
         if constexpr (W == dwconv::kWavesPerBlock) {
             if (p.dw_nc == 2) {
                 switch (m) {
-                case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 2>, 2);
-                case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 2>, 2);
-                case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 2>, 2);
+                case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 2, false>, 2);
+                case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 2, false>, 2);
+                case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 2, false>, 2);
                 default: return -1;
                 }
             }
         }
         switch (m) {
-        case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 1>, 1);
-        case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 1>, 1);
-        case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 1>, 1);
-        case 4: return launch_rb(dwconv::dw_rowbatch_kernel<T, 4, W, 1>, 1);
-        case 5: return launch_rb(dwconv::dw_rowbatch_kernel<T, 5, W, 1>, 1);
-        case 6: return launch_rb(dwconv::dw_rowbatch_kernel<T, 6, W, 1>, 1);
-        case 7: return launch_rb(dwconv::dw_rowbatch_kernel<T, 7, W, 1>, 1);
-        case 8: return launch_rb(dwconv::dw_rowbatch_kernel<T, 8, W, 1>, 1);
+        case 1: return rag_rb(std::integral_constant<int, 1>{});
+        case 2: return rag_rb(std::integral_constant<int, 2>{});
+        case 3: return rag_rb(std::integral_constant<int, 3>{});
+        case 4: return rag_rb(std::integral_constant<int, 4>{});
+        case 5: return rag_rb(std::integral_constant<int, 5>{});
+        case 6: return rag_rb(std::integral_constant<int, 6>{});
+        case 7: return rag_rb(std::integral_constant<int, 7>{});
+        case 8: return rag_rb(std::integral_constant<int, 8>{});
         default: return -1;
         }
     }
@@ -141,7 +151,9 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(x, 4 * sizeof(T)) && aligned_to(dy, 4 * sizeof(T));
-    if (!granular && (!ragged_rows_ok(s, nd) || p.rows.on || p.rows.batch || !aligned_to(x, 4) || !aligned_to(dy, 4))) return -1;
+    // (rows of at most 128 positions: the sixteen-row kernel needs rows that start on a dword, nothing more)
+    if (!granular && ((!ragged_rows_ok(s, nd) && !p.rows.batch) || (p.rows.on && !p.rows.batch) || !aligned_to(x, 4) || !aligned_to(dy, 4)))
+        return -1;
     if constexpr (std::is_same<T, float>::value) {
         if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
     } else {

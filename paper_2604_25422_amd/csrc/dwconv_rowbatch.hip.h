@@ -1,5 +1,8 @@
-// Short rows on the matrix cores, sixteen rows at a time (L <= 128, L % 4 == 0; fp32, or bf16 storage widened to
-// fp32 on the way into LDS: fp32 matrix instructions and sums either way, one rounding at the store).
+// Short rows on the matrix cores, sixteen rows at a time (L <= 128; fp32, or bf16 storage widened to fp32 on the way
+// into LDS: fp32 matrix instructions and sums either way, one rounding at the store).  Rows are moved in granules of
+// four elements; a row that is not whole granules (L % 4 != 0, one channel per wave) ends in a granule whose last
+// elements belong to the next row: they are replaced by zeros on the way into LDS, and on the way out only the
+// elements of the row are stored.  Rows need to start on a dword only (buffer loads; bf16: even L).
 //
 // The operator of Sec. IV-A eq. (dwconv) treats every row (b, c) on its own, and the paper's own workload
 // (Sec. V: windows of 48 steps) has rows of three 16-blocks.  The blocked-Toeplitz contraction of
@@ -66,6 +69,32 @@ __device__ __forceinline__ uintx4 rb_unit_resource(const T *base, int nr, int CL
     return r;
 }
 
+// A granule on its way into LDS: rem = 0 for a whole one, else the number of its elements (1..3) that belong to the
+// row; the others become the zeros the image holds behind the end of a row.
+template <typename T>
+__device__ __forceinline__ float4 rb_granule(typename Raw4<T>::type raw, int rem)
+{
+    float4 v = Raw4<T>::widen(raw);
+    if (rem) {
+        v.w = 0.f;
+        if (rem < 3) v.z = 0.f;
+        if (rem < 2) v.y = 0.f;
+    }
+    return v;
+}
+// ... and on its way out: whole granules as one streaming store, the last one of a ragged row by element.
+template <typename T>
+__device__ __forceinline__ void rb_store_granule(T *p, float4 v, int rem)
+{
+    if (!rem) {
+        st_elem4_stream(p, v);
+    } else {
+        st_elem(p, v.x);
+        if (rem > 1) st_elem(p + 1, v.y);
+        if (rem > 2) st_elem(p + 2, v.z);
+    }
+}
+
 // LDS image of a unit in the correlate kernel, one per wave: row r of the unit at float r * pitch; inside it the
 // NC channels the wave owns, each rounded up to whole 16-blocks (the floats between the end of a row and the end
 // of its last block stay zero).  The pitch is 4 modulo 8 floats, so the 16-byte operand reads and tile writes of
@@ -82,13 +111,14 @@ constexpr int kRbCorrWaves = 4;   // waves per block: neighbouring channels, who
 // image, channel by channel, and the tiles of a channel replace its inputs; then every lane swaps its granules of
 // the image (the lane-to-granule map of the loads): the outputs go out as whole rows (streaming stores, as in the
 // long-row kernel), the prefetched inputs of the next unit come in.
-template <typename T, int ND, int NC, int MB>
-__global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 ? 3 : kMfmaWavesPerSimd)) void corr_rowbatch_kernel(
+// RAG: rows that are not whole granules (one channel per wave; the code for the partial granule is compiled only there).
+template <typename T, int ND, int NC, int MB, bool RAG>
+__global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 || RAG ? 3 : kMfmaWavesPerSimd)) void corr_rowbatch_kernel(
     const T *__restrict__ in, const T *__restrict__ f, T *__restrict__ out, const RowBatchGeom g)
 {
     constexpr int ES = (int)sizeof(T);          // bf16 storage is widened on the way into LDS; fp32 arithmetic
     // MB: 16-blocks per row the kernel is compiled for (two channels per wave: 3, the register budget)
-    static_assert(MB >= 1 && MB <= kRbMaxBlocks && (NC == 1 || MB <= 3), "row blocks");
+    static_assert(MB >= 1 && MB <= kRbMaxBlocks && (NC == 1 || MB <= 3) && (NC == 1 || !RAG), "row blocks");
     constexpr int NLD = NC * MB;                 // 16 rows * NC * 4 MB granules over 64 lanes
     extern __shared__ __align__(16) float dyn_lds[];
     const int lane = threadIdx.x & 63;
@@ -106,10 +136,10 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 ? 3 : kMfmaWavesPerSimd)
     if (unit >= g.J) return;                    // (no workgroup barrier below)
 
     const int CL = g.C * g.L;
-    const int Lg = g.L >> 2;                    // granules per row
+    const int Lg = (g.L + 3) >> 2;              // granules per row (the last one partial when L % 4 != 0: NC is 1 then)
     const int NG = kRbRows * NC * Lg;           // granules per unit
     const int nld = (NG + 63) >> 6;             // loads per lane (wave-uniform)
-    int gl_off[NLD], img[NLD];
+    int gl_off[NLD], img[NLD];                  // img: float index in the image (a multiple of 4) + elements of a partial granule
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int gi = lane + 64 * i;
@@ -117,7 +147,7 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 ? 3 : kMfmaWavesPerSimd)
         const int h = (NC > 1 && cg >= Lg) ? 1 : 0;
         static_assert(NC <= 2, "one or two channels per wave");
         gl_off[i] = gi < NG ? ES * (r * CL + 4 * cg) : kOutOfRow;
-        img[i] = gi < NG ? r * Lo + h * Lc + 4 * (cg - h * Lg) : 0;
+        img[i] = gi < NG ? (r * Lo + h * Lc + 4 * (cg - h * Lg)) | (RAG && cg == Lg - 1 ? (g.L & 3) : 0) : 0;
     }
     for (int i = lane; i < kRbRows * Lo / 4; i += 64)
         *reinterpret_cast<float4 *>(sw + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -137,7 +167,10 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 ? 3 : kMfmaWavesPerSimd)
         release_after_wait(pre);
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
-            if (i < nld && lane + 64 * i < NG) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<T>::widen(pre[i]);
+            if (i < nld && lane + 64 * i < NG) {
+                const int rem = RAG ? (img[i] & 3) : 0;
+                *reinterpret_cast<float4 *>(sw + (img[i] - rem)) = rb_granule<T>(pre[i], rem);
+            }
     };
     prefetch(unit);
     drain();
@@ -206,9 +239,10 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 ? 3 : kMfmaWavesPerSimd)
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
                 if (i < nld && lane + 64 * i < NG) {
-                    const float4 ov = *reinterpret_cast<const float4 *>(sw + img[i]);
-                    if (more) *reinterpret_cast<float4 *>(sw + img[i]) = Raw4<T>::widen(pre[i]);
-                    if (gl_off[i] < lim) st_elem4_stream(out_u + gl_off[i] / ES, ov);
+                    const int rem = RAG ? (img[i] & 3) : 0;
+                    const float4 ov = *reinterpret_cast<const float4 *>(sw + (img[i] - rem));
+                    if (more) *reinterpret_cast<float4 *>(sw + (img[i] - rem)) = rb_granule<T>(pre[i], rem);
+                    if (gl_off[i] < lim) rb_store_granule(out_u + gl_off[i] / ES, ov, rem);
                 }
         }
         wave_lds_fence();
@@ -265,14 +299,15 @@ __device__ __forceinline__ void rb_diagonal_sums(const floatx4 (&G)[NR], int M, 
 // together, ahead of its matrix instructions.
 // dw_out == nullptr: the block's sums go to slice blockIdx.y of part; otherwise (gridDim.y == 1) they are the
 // weight gradient itself.
-template <typename T, int M, int W, int NC>
+// RAG: rows that are not whole granules (one channel per wave).
+template <typename T, int M, int W, int NC, bool RAG>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     const T *__restrict__ x, const T *__restrict__ dy, float *__restrict__ part, T *__restrict__ dw_out,
     int B, int C, int L, int K, int pad, int dmin, int nd, int n_units)
 {
     constexpr int ES = (int)sizeof(T);
     static_assert(NC == 1 || NC == 2, "one or two channels per wave");
-    static_assert(M >= 1 && M <= kRbMaxBlocks && (NC == 1 || M <= 3), "rows of at most 128 (two channels: 48) positions");
+    static_assert(M >= 1 && M <= kRbMaxBlocks && (NC == 1 || M <= 3) && (NC == 1 || !RAG), "rows of at most 128 (two channels: 48) positions");
     constexpr int RU = M > 4 ? 4 : kRbRows / NC;              // rows per unit (rb_dw_unit_rows)
     constexpr int NLD = (RU * NC * 4 * M + 63) / 64;          // 16-byte granules of a unit over 64 lanes
     constexpr int NR = 2 * M - 1;                             // relative block offsets -(M-1) .. M-1
@@ -291,17 +326,17 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     const int dmax = dmin + nd - 1;
 
     const int CL = C * L;
-    const int Lg = L >> 2;
+    const int Lg = (L + 3) >> 2;                              // (the last granule partial when L % 4 != 0: NC is 1 then)
     const int NG = RU * NC * Lg;
     const int nld = (NG + 63) >> 6;
-    int gl_off[NLD], lds_idx[NLD];
+    int gl_off[NLD], lds_idx[NLD];                            // lds_idx: float index (a multiple of 4) + elements of a partial granule
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int gi = lane + 64 * i;
         const int r = gi / (NC * Lg), cg = gi - r * (NC * Lg);
         const int h = (NC > 1 && cg >= Lg) ? 1 : 0;
         gl_off[i] = gi < NG ? ES * (r * CL + 4 * cg) : kOutOfRow;
-        lds_idx[i] = gi < NG ? r * Lp + h * Lc + 4 * (cg - h * Lg) : 0;
+        lds_idx[i] = gi < NG ? (r * Lp + h * Lc + 4 * (cg - h * Lg)) | (RAG && cg == Lg - 1 ? (L & 3) : 0) : 0;
     }
     for (int i = lane; i < 2 * RU * Lp / 4; i += 64)
         *reinterpret_cast<float4 *>(s_wave + 4 * i) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -336,8 +371,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld && lane + 64 * i < NG) {
-                *reinterpret_cast<float4 *>(sx + lds_idx[i]) = Raw4<T>::widen(px[i]);
-                *reinterpret_cast<float4 *>(sg + lds_idx[i]) = Raw4<T>::widen(pg[i]);
+                const int rem = RAG ? (lds_idx[i] & 3) : 0;
+                *reinterpret_cast<float4 *>(sx + (lds_idx[i] - rem)) = rb_granule<T>(px[i], rem);
+                *reinterpret_cast<float4 *>(sg + (lds_idx[i] - rem)) = rb_granule<T>(pg[i], rem);
             }
     };
     if (unit < n_units) {
@@ -416,8 +452,10 @@ __host__ __device__ constexpr size_t rb_bwd_lds_bytes(int L, int ND)
     return (size_t)kRbBwdWaves * (size_t)(rb_bwd_wave_floats(L, ND) + 16 * ND) * sizeof(float);
 }
 
-template <typename T, int ND, int M>
-__global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowbatch_kernel(
+// RAG: rows that are not whole granules (the masks and element stores of the partial granule cost registers this
+// kernel does not have at four waves per SIMD, so that variant runs three).
+template <typename T, int ND, int M, bool RAG>
+__global__ __launch_bounds__(64 * kRbBwdWaves, (RAG ? 3 : kMfmaWavesPerSimd)) void bwd_rowbatch_kernel(
     const T *__restrict__ dy, const T *__restrict__ x, const T *__restrict__ w, T *__restrict__ dx,
     float *__restrict__ part, T *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin, int n_units)
 {
@@ -446,16 +484,16 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
     const int dminx = -(dmin + ND - 1);
 
     const int CL = C * L;
-    const int Lg = L >> 2;
+    const int Lg = (L + 3) >> 2;                              // (the last granule partial when L % 4 != 0)
     const int NG = kRbRows * Lg;
     const int nld = (NG + 63) >> 6;
-    int gl_off[NLD], img_d[NLD], img_x[NLD];
+    int gl_off[NLD], img_d[NLD], img_x[NLD];                  // img_d: float index (a multiple of 4) + elements of a partial granule
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
         const int gi = lane + 64 * i;
         const int r = gi / Lg, cg = gi - r * Lg;
         gl_off[i] = gi < NG ? ES * (r * CL + 4 * cg) : kOutOfRow;
-        img_d[i] = gi < NG ? r * Ld + 4 * cg : 0;
+        img_d[i] = gi < NG ? (r * Ld + 4 * cg) | (RAG && cg == Lg - 1 ? (L & 3) : 0) : 0;
         img_x[i] = gi < NG ? r * Lp + 4 * cg : 0;
     }
     for (int i = lane; i < kRbRows * (Ld + Lp) / 4; i += 64)
@@ -505,8 +543,9 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld && lane + 64 * i < NG) {
-                *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<T>::widen(pd[i]);
-                *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<T>::widen(px[i]);
+                const int rem = RAG ? (img_d[i] & 3) : 0;
+                *reinterpret_cast<float4 *>(sd + (img_d[i] - rem)) = rb_granule<T>(pd[i], rem);
+                *reinterpret_cast<float4 *>(sx + img_x[i]) = rb_granule<T>(px[i], rem);
             }
         wave_lds_fence();
     }
@@ -569,12 +608,13 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, kMfmaWavesPerSimd) void bwd_rowba
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
                 if (i < nld && lane + 64 * i < NG) {
-                    const float4 ov = *reinterpret_cast<const float4 *>(sd + img_d[i]);
+                    const int rem = RAG ? (img_d[i] & 3) : 0;
+                    const float4 ov = *reinterpret_cast<const float4 *>(sd + (img_d[i] - rem));
                     if (more) {
-                        *reinterpret_cast<float4 *>(sd + img_d[i]) = Raw4<T>::widen(pd[i]);
-                        *reinterpret_cast<float4 *>(sx + img_x[i]) = Raw4<T>::widen(px[i]);
+                        *reinterpret_cast<float4 *>(sd + (img_d[i] - rem)) = rb_granule<T>(pd[i], rem);
+                        *reinterpret_cast<float4 *>(sx + img_x[i]) = rb_granule<T>(px[i], rem);
                     }
-                    if (gl_off[i] < lim) st_elem4_stream(dx_u + gl_off[i] / ES, ov);
+                    if (gl_off[i] < lim) rb_store_granule(dx_u + gl_off[i] / ES, ov, rem);
                 }
         }
         wave_lds_fence();
