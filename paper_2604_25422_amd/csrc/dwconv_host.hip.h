@@ -67,11 +67,14 @@ inline int mfma_max_nd_dw(const Shape &s)
 // element-aligned; bf16: even lengths that are not multiples of eight).  The kernels that bring rows straight into
 // LDS take them when every row starts on a dword: their loads are range-checked per dword, so a granule that
 // straddles the end of its row is completed with zeros, and the last outputs of a row are stored by element.  Two to
-// six block offsets, and rows long enough that 1024-position segments are not mostly padding.
+// six block offsets; fp32 also the register-staged forward / input-gradient kernel of seven to sixteen offsets (row
+// resources, the same range check) and the weight-gradient kernel in every number of launches; rows long enough that
+// 1024-position segments are not mostly padding.
 constexpr int kRaggedMinL = 768;
+constexpr int kRaggedMaxNDF32 = 48;        // (fp32 weight gradient in up to three launches of sixteen offsets)
 inline bool ragged_rows_ok(const Shape &s, int nd)
 {
-    return s.K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && s.L >= kRaggedMinL &&
+    return s.K >= kMfmaMinK && nd >= 2 && nd <= (s.dtype == DWCONV_F32 ? kRaggedMaxNDF32 : kMfmaMaxND) && s.L >= kRaggedMinL &&
            (s.dtype == DWCONV_F32 || (s.L % 2) == 0);
 }
 constexpr int kComputeUnits = 256;     // MI355X

@@ -283,7 +283,8 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         default: break;
         }
     }
-    if (!granular) return -1;
+    // (fp32 rows that are not whole granules: the register-staged kernel below takes them too, see ragged_rows_ok)
+    if (!granular && !std::is_same<T, float>::value) return -1;
     if constexpr (!std::is_same<T, float>::value) {
         // (bf16 rows of odd length in whole granules of four: widened to fp32 on the way into LDS)
         switch (nd) {
@@ -296,6 +297,19 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         }
     }
     if constexpr (std::is_same<T, float>::value) {
+        if ((s.L % 4) != 0) {
+            switch (nd) {
+            case 7: return launch(dwconv::corr_mfma_kernel<float, 7, false, true>, pi, pf, po);
+            case 8: return launch(dwconv::corr_mfma_kernel<float, 8, false, true>, pi, pf, po);
+            case 9: return launch(dwconv::corr_mfma_kernel<float, 9, false, true>, pi, pf, po);
+            case 10: return launch(dwconv::corr_mfma_kernel<float, 10, false, true>, pi, pf, po);
+            case 11: return launch(dwconv::corr_mfma_kernel<float, 11, false, true>, pi, pf, po);
+            case 12: return launch(dwconv::corr_mfma_kernel<float, 12, false, true>, pi, pf, po);
+            case 13: return launch(dwconv::corr_mfma_kernel<float, 13, false, true>, pi, pf, po);
+            case 14: return launch(dwconv::corr_mfma_kernel<float, 14, false, true>, pi, pf, po);
+            default: return -1;                // (fifteen and sixteen offsets: no registers left for the element stores)
+            }
+        }
         switch (nd) {
         case 7: return launch(dwconv::corr_mfma_kernel<float, 7, false>, pi, pf, po);
         case 8: return launch(dwconv::corr_mfma_kernel<float, 8, false>, pi, pf, po);

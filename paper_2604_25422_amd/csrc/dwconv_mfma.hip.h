@@ -177,8 +177,11 @@ template <> struct Raw4<bf16_t> {
 // ROWS (short rows, see RowsMap): the unit of work is a segment of the virtual row of a channel; wave slots are
 // ordered (virtual segment, channel), so neighbouring waves read neighbouring channels of the same batches, and
 // `row` / `seg` below then hold the virtual segment and the channel.
-template <typename T, int ND, bool ROWS>
-__global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 9 ? 2 : ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
+// RAG: rows that are not whole granules of four (fp32, ordinary rows): the loads need nothing (row resources, per-dword
+// range check); the last group of four outputs of a row is stored by element, which costs registers, so these
+// variants are compiled apart and run two waves per SIMD from eight block offsets.
+template <typename T, int ND, bool ROWS, bool RAG = false>
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, ((ND > 9 || (RAG && ND > 7)) ? 2 : ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
                                                                          const T *__restrict__ f, T *__restrict__ out,
                                                                          const CorrGeom g, const RowsMap rm)
 {
@@ -354,9 +357,15 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, (ND > 9 ? 2 : ND > 6 ? 3 :
                     st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
             } else {
 #pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
-                    if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
-                        st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                for (int dt = 0; dt < NDT; ++dt) {
+                    if constexpr (RAG) {       // (the last group of a row that is not whole granules: by element)
+                        st_elem4_stream_upto(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]),
+                                             seg * kSegLen + 256 * dt + lane_t, g.L);
+                    } else {
+                        if (seg * kSegLen + 256 * dt + lane_t + 3 < g.L)
+                            st_elem4_stream(out_seg + (256 * dt + lane_t), make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]));
+                    }
+                }
             }
         }
         wave_lds_fence();

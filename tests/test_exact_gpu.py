@@ -101,6 +101,9 @@ CLASSES = [
     # 768 positions; bf16: even lengths), ragged last segments, rows that end one, two and three positions into a granule
     (2, 3, 2050, 64, 63), (3, 5, 4097, 31, 15), (2, 4, 1026, 7, 3), (3, 2, 1027, 66, 0), (5, 3, 769, 16, 15), (2, 2, 3075, 48, 24),
     (4, 256, 2049, 64, 63), (3, 2, 1030, 33, 16), (2, 3, 5001, 20, 19),
+    # ... with seven to sixteen block offsets (fp32: register-staged forward, weight gradient in one to three launches)
+    (2, 3, 2050, 128, 127), (3, 2, 1027, 160, 80), (2, 2, 4098, 226, 100), (1, 3, 3001, 100, 99), (2, 2, 2050, 482, 481),
+    (2, 2, 1026, 700, 350), (2, 256, 1025, 130, 129),
     # filters or rows beyond what LDS holds whole: forward / input gradient in pieces of 4096 outputs and chunks of 4096
     # taps, the fp32 weight gradient in dozens of launches of sixteen block offsets
     (1, 2, 9000, 300, 299), (1, 1, 16384, 16384, 16383), (2, 1, 12000, 9000, 4000), (1, 2, 20000, 8192, 100),
