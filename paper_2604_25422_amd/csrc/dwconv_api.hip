@@ -483,8 +483,8 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
     if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type
     if (dtype == DWCONV_BF16 && p.rows.on) return 0;
-    const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_ok(s, nd) : true)))
-                                               : ((L % 4) == 0 || ragged_rows_ok(s, nd));
+    const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
+                                               : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && rows_fit && L <= kMfmaMaxL) ? 1 : 0;
 }
 

@@ -224,18 +224,25 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
         aim(b_n, seg_n);
         if constexpr (!ROWS && ND <= 6) {
             // (up to six block offsets: beyond, this second body costs the kernel registers it does not have)
-            // A last segment that holds at most 256 positions of its row (rows that are not whole segments): dY is
-            // zero beyond them, so only the first four chunks can add anything; they need x0, g0 and x1, the first three
-            // of the nine loads of this segment, which are the last nine issued.  Then all nine loads of the next
-            // segment go out in the usual order.
-            if (L - (seg0 + seg) * kSegLen <= 256) {
-                wait_vmcnt_at_most<6>();
-                static_for<0, 4>([&](auto cc) {
-                    constexpr int ch = decltype(cc)::value;
+            // A last segment that holds at most 768 positions of its row (rows that are not whole segments): dY is zero
+            // beyond them, so only the first 4 lr chunks can add anything, lr = 1..3 the 256-position regions that hold
+            // positions of the row; they need the loads up to x_lr (x0 g0 x1 g1 ... in issue order, the nine loads of this
+            // segment being the last nine issued).  Then all nine loads of the next segment go out in the usual order.
+            const int left = L - (seg0 + seg) * kSegLen;
+            if (left <= 3 * 256) {
+                const int lr = left <= 256 ? 1 : (left <= 512 ? 2 : 3);
+                if (lr == 1) wait_vmcnt_at_most<6>();
+                else if (lr == 2) wait_vmcnt_at_most<4>();
+                else wait_vmcnt_at_most<2>();
+#pragma unroll 1
+                for (int ch = 0; ch < 4 * lr; ++ch) {
                     const float gv = sg[64 * ch + lane];
+                    float xv[ND];
 #pragma unroll
-                    for (int d = 0; d < ND; ++d) G[d] = mfma16x16x4(sx[64 * ch + 16 * d + lane], gv, G[d]);
-                });
+                    for (int d = 0; d < ND; ++d) xv[d] = sx[64 * ch + 16 * d + lane];
+#pragma unroll
+                    for (int d = 0; d < ND; ++d) G[d] = mfma16x16x4(xv[d], gv, G[d]);
+                }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 static_for<0, 4>([&](auto ic) { load_x(ic); load_g(ic); });
                 load_x(std::integral_constant<int, 4>{});

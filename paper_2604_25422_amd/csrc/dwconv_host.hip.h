@@ -69,14 +69,18 @@ inline int mfma_max_nd_dw(const Shape &s)
 // straddles the end of its row is completed with zeros, and the last outputs of a row are stored by element.  Two to
 // six block offsets; fp32 also the register-staged forward / input-gradient kernel of seven to sixteen offsets (row
 // resources, the same range check) and the weight-gradient kernel in every number of launches; rows long enough that
-// 1024-position segments are not mostly padding.
-constexpr int kRaggedMinL = 768;
+// 1024-position segments are not mostly padding (the kernels skip what lies past the end of a row, the fused one does not).
+constexpr int kRaggedMinL = 768;           // the fused backward kernel on such rows (it contracts whole segments), many-launch dW
+constexpr int kRaggedRowsMinL = 132;       // forward / input gradient / weight gradient (they skip the quarters or regions past
+                                           // the end of a row): B4096 C128 L202 K48 798 us per step against 1343 us on the
+                                           // generic kernels; the fused kernel took 1279 us for the backward half alone
 constexpr int kRaggedMaxNDF32 = 48;        // (fp32 weight gradient in up to three launches of sixteen offsets)
 inline bool ragged_rows_ok(const Shape &s, int nd)
 {
-    return s.K >= kMfmaMinK && nd >= 2 && nd <= (s.dtype == DWCONV_F32 ? kRaggedMaxNDF32 : kMfmaMaxND) && s.L >= kRaggedMinL &&
+    return s.K >= kMfmaMinK && nd >= 2 && nd <= (s.dtype == DWCONV_F32 ? kRaggedMaxNDF32 : kMfmaMaxND) && s.L >= kRaggedRowsMinL &&
            (s.dtype == DWCONV_F32 || (s.L % 2) == 0);
 }
+inline bool ragged_rows_fused_ok(const Shape &s, int nd) { return ragged_rows_ok(s, nd) && s.L >= kRaggedMinL; }
 constexpr int kComputeUnits = 256;     // MI355X
 constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below the out-of-row marker of the buffer loads
 

@@ -122,7 +122,7 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     const bool granular = (s.L % (s.dtype == DWCONV_BF16 ? 8 : 4)) == 0 && aligned_to(x, 16) && aligned_to(dy, 16) && aligned_to(dx, 16);
     if (!granular) {
         const bool short_ok = s.dtype == DWCONV_BF16 && (s.L % 4) == 0;      // (bf16 rows in granules of four: any ordinary length)
-        if ((!short_ok && !ragged_rows_ok(s, nd)) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4))
+        if ((!short_ok && !ragged_rows_fused_ok(s, nd)) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4))
             return -1;
     }
     void *direct = (p.single && p.S == 1) ? dw_out : nullptr;
