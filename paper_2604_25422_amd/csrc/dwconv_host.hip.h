@@ -71,7 +71,7 @@ inline int mfma_max_nd_dw(const Shape &s)
 // resources, the same range check) and the weight-gradient kernel in every number of launches; rows long enough that
 // 1024-position segments are not mostly padding (the kernels skip what lies past the end of a row, the fused one does not).
 constexpr int kRaggedMinL = 768;           // the fused backward kernel on such rows (it contracts whole segments), many-launch dW
-constexpr int kRaggedRowsMinL = 132;       // forward / input gradient / weight gradient (they skip the quarters or regions past
+constexpr int kRaggedRowsMinL = 129;       // forward / input gradient / weight gradient (they skip the quarters or regions past
                                            // the end of a row): B4096 C128 L202 K48 798 us per step against 1343 us on the
                                            // generic kernels; the fused kernel took 1279 us for the backward half alone
 constexpr int kRaggedMaxNDF32 = 48;        // (fp32 weight gradient in up to three launches of sixteen offsets)
