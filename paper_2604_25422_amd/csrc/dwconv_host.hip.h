@@ -40,9 +40,16 @@ inline int launch_status()
 
 // Block offsets d of the 16-blocked Toeplitz form that can hold a tap: d in [dmin, dmax].
 inline int toeplitz_dmin(int pad) { return -((pad + 15) / 16); }
-inline int toeplitz_dmax(int K, int pad) { return (K - pad + 14) / 16; }
+// (a one-tap filter touches a single block offset; the kernels are written for two and more, so it gets a second one
+// whose taps all lie outside the filter and count as zeros)
+inline int toeplitz_dmax(int K, int pad)
+{
+    const int d = (K - pad + 14) / 16, dm = toeplitz_dmin(pad);
+    return d > dm ? d : dm + 1;
+}
 
-constexpr int kMfmaMinK = 3;      // shorter filters stay on the vector ALU
+constexpr int kMfmaMinK = 1;      // (one and two taps ran 2.4x slower on the vector-ALU kernels: B32 C256 L4096 314 us per step
+                                  // against 133 us at three taps)
 constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows
 constexpr int kMfmaMaxNDWide = 10;     // fp32 on long rows, K up to 130: whole-channel workgroups for dW still possible
 constexpr int kMfmaMaxNDDw = 16;       // fp32 on long rows, K up to 226: four-wave dW workgroups, two correlate waves per SIMD
