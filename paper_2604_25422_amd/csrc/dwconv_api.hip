@@ -55,39 +55,36 @@ RowsPlan plan_rows(const Shape &s)
     r.on = false; r.batch = false; r.units = 0; r.nvs = 0;
     r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    if (s.K < kMfmaMinK || nd < 2 || nd > kMfmaMaxND) return r;
+    if (s.K < kMfmaMinK || nd < 2) return r;
     const long long es = (long long)elem_size(s.dtype);
+    // Sixteen rows per tile (rows of at most 128 positions, either storage type): byte offsets inside a unit stay below
+    // the out-of-row marker; the offsets that count are those inside the row (rows_batch_offsets: a filter as long as
+    // the row, or longer, is no different from a short one).  Rows that are not whole granules of four must start on a
+    // dword (any fp32 row, bf16 rows of even length) and have their kernels for up to six offsets only.
+    bool batch = s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30);
+    if (batch) {
+        int bd, bn;
+        rows_batch_offsets(s.L, s.K, s.pad, &bd, &bn);
+        if ((s.L % 4) != 0) batch = bn <= kMfmaMaxND && (s.dtype == DWCONV_F32 || (s.L % 2) == 0);
+        else batch = bn <= kRbMaxND;
+    }
+    // Virtual rows (whole granules, up to six offsets): where a 1024-position segment of a row would be more than a
+    // quarter padding, and positions stay 32-bit.
     const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
     const long long P = (s.L + 3) / 4 * 4 + (halo + 3) / 4 * 4;
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
-    if (4 * padded <= 5 * P) return r;                       // ordinary segments waste less than a quarter
-    // sixteen rows per tile (either storage type): byte offsets inside a unit stay below the out-of-row marker
-    const bool batch = s.L <= dwconv::kRbMaxL && (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30);
-    if ((s.L % 4) != 0) {
-        // rows that are not whole granules of four: the sixteen-row kernels only (rows must start on a dword: any fp32
-        // row, bf16 rows of even length)
-        if (batch && (s.dtype == DWCONV_F32 || (s.L % 2) == 0)) {
-            r.on = true; r.batch = true;
-            r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
-        }
-        return r;
-    }
     const long long elems = (long long)s.B * s.C * s.L;
-    if (elems * es > (1ll << 30) || (long long)s.B * P * P >= (1ll << 32) || (long long)s.B * P >= (1ll << 31)) {
-        // too large for virtual rows (32-bit positions); the sixteen-row kernels have no such limit
-        if (batch) {
-            r.on = true; r.batch = true;
-            r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
-        }
-        return r;
+    const bool vrows = (s.L % 4) == 0 && nd <= kMfmaMaxND && 4 * padded > 5 * P && elems * es <= (1ll << 30) &&
+                       (long long)s.B * P * P < (1ll << 32) && (long long)s.B * P < (1ll << 31);
+    if (vrows) {
+        r.on = true;
+        r.nvs = (int)(((long long)s.B * P + dwconv::kSegLen - 1) / dwconv::kSegLen);
+        r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
+        r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
+        r.map.bytes = (unsigned)(elems * es);
     }
-    r.on = true;
-    r.nvs = (int)(((long long)s.B * P + dwconv::kSegLen - 1) / dwconv::kSegLen);
-    r.map.P = (int)P; r.map.L = s.L; r.map.CL = s.C * s.L; r.map.Lv = (int)(s.B * P);
-    r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
-    r.map.bytes = (unsigned)(elems * es);
     if (batch) {
-        r.batch = true;
+        r.on = true; r.batch = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
     }
     return r;
@@ -206,9 +203,13 @@ DwPlan plan_dw(const Shape &s)
         tiles = (s.B + ru - 1) / ru;
     }
     long long items = p.rows.on ? tiles : (long long)s.B * tiles;                        // per channel
-    const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
-    const bool mfma_shape = s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) &&
-                            ((s.L % 4) == 0 || ragged_rows_ok(s, nd) || p.rows.batch) && s.L <= kMfmaMaxL;
+    int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
+    if (p.rows.batch) {                                          // (the offsets inside a row are all that count there)
+        int bd;
+        rows_batch_offsets(s.L, s.K, s.pad, &bd, &nd);
+    }
+    const bool mfma_shape = p.rows.batch || (s.K >= kMfmaMinK && nd >= 2 && nd <= mfma_max_nd_dw(s) &&
+                                             ((s.L % 4) == 0 || ragged_rows_ok(s, nd)) && s.L <= kMfmaMaxL);
     // When the channels alone fill the chip evenly (C = 1, 2 or 3 per compute unit), one block of 16, 8 or 5
     // waves takes a whole channel: no slices, no second stage.
     p.wpb = dwconv::kWavesPerBlock;
@@ -278,14 +279,14 @@ DwPlan plan_dw(const Shape &s)
     p.longk = false;
     p.lk_wgs = p.lk_gd = 0;
     const int NCH = (s.L + 63) / 64;
-    if (nd > mfma_max_nd_dw(s) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
+    if (!p.rows.batch && nd > mfma_max_nd_dw(s) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
         const int per_wg = 2 * dwconv::kLkWaves * dwconv::kLkDwMaxGD;
         p.lk_wgs = (nd + per_wg - 1) / per_wg;
         p.lk_table = longk_dw_table(s, p.lk_wgs, &p.lk_gd);
     }
     p.manypass = false;
-    if (!p.lk_table && nd > mfma_max_nd_dw(s) && (s.L % (s.dtype == DWCONV_F32 ? 4 : 8)) == 0 && s.L >= kRaggedMinL &&
+    if (!p.rows.batch && !p.lk_table && nd > mfma_max_nd_dw(s) && (s.L % (s.dtype == DWCONV_F32 ? 4 : 8)) == 0 && s.L >= kRaggedMinL &&
         s.L <= kMfmaMaxL && !p.rows.on) {
         // filters (or rows) too long for the long-filter kernel's LDS: the register-resident kernel, sixteen block
         // offsets per launch, every launch adding the taps it owns to one of two zero-filled sets of slices
@@ -308,7 +309,7 @@ DwPlan plan_dw(const Shape &s)
         p.S = 2;
         p.S_fused = 2;                                     // (no fused kernel for long filters: nothing needs more slices)
         p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
-        p.valu_items_per_slice = p.items_per_slice;
+        p.valu_items_per_slice = (int)(((long long)s.B * p.valu_tiles_per_row + 1) / 2);      // (of its own items: real rows)
     }
     // the generic kernel on short rows: its items are the tiles of the virtual row of the channel
     p.valu_rows = plan_valu_rows(s);

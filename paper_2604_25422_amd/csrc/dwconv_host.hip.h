@@ -48,6 +48,20 @@ inline int toeplitz_dmax(int K, int pad)
     return d > dm ? d : dm + 1;
 }
 
+// Rows of m = ceil(L / 16) blocks: only the block offsets -(m - 1) .. m - 1 have a block pair inside the row, whatever the
+// length of the filter; at least two (the kernels' minimum; a pair outside the row is skipped).
+inline void rows_batch_offsets(int L, int K, int pad, int *dmin_out, int *nd_out)
+{
+    const int m = (L + 15) / 16;
+    int dmin = toeplitz_dmin(pad), dmax = toeplitz_dmax(K, pad);
+    if (dmin < -(m - 1)) dmin = -(m - 1);
+    if (dmax > m - 1) dmax = m - 1;
+    if (dmax < dmin + 1) dmax = dmin + 1;
+    *dmin_out = dmin;
+    *nd_out = dmax - dmin + 1;
+}
+constexpr int kRbMaxND = 15;      // sixteen-row kernels: offsets of a row of eight blocks
+
 constexpr int kMfmaMinK = 1;      // (one and two taps ran 2.4x slower on the vector-ALU kernels: B32 C256 L4096 314 us per step
                                   // against 133 us at three taps)
 constexpr int kMfmaMaxND = 6;          // fused backward, bf16, short rows

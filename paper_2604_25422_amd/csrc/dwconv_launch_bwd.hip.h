@@ -62,8 +62,8 @@ template <typename T>
 int launch_bwd_rowbatch(const void *dy, const void *x, const void *w, void *dx, float *part, void *dw_out, bool *wrote_dw,
                         const Shape &s, const DwPlan &p, hipStream_t st)
 {
-    const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
-    const int nd = dmax - dmin + 1;
+    int dmin, nd;
+    rows_batch_offsets(s.L, s.K, s.pad, &dmin, &nd);        // (rows of at most three blocks: at most five offsets)
     if (s.L > dwconv::kRbBwdMaxL || nd < 2 || nd > kMfmaMaxND) return -1;
     if (!aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4)) return -1;      // (rows that start on a dword)
     void *direct_rb = p.S_fused == 1 ? dw_out : nullptr;

@@ -32,18 +32,125 @@ int launch_corr_valu(const void *in, const void *f, void *out, const Shape &s, i
     return launch_status();
 }
 
+// Rows of at most 128 positions: sixteen rows of a channel (or of two neighbouring channels) per unit.  The block
+// offsets are cropped to those that stay inside a row of m 16-blocks (rows_batch_offsets), so a filter as long as the
+// row or longer costs the block pairs of the row and nothing else.  Returns -1 when no kernel is compiled for the case.
+// (seven to fifteen offsets: translation units of their own, dwconv_launch_corr_rows_*.hip)
+int launch_corr_rowbatch_wide_f32(dwconv::RowBatchGeom &rg, int nd, const void *in, const void *f, void *out, const Shape &s,
+                                  hipStream_t st);
+int launch_corr_rowbatch_wide_bf16(dwconv::RowBatchGeom &rg, int nd, const void *in, const void *f, void *out, const Shape &s,
+                                   hipStream_t st);
+
+// The kernels for seven and more block offsets of rows of MB blocks (MB = 4: seven offsets at most).
+template <typename T>
+int launch_corr_rowbatch_wide_t(dwconv::RowBatchGeom &rg, int nd, const void *in, const void *f, void *out, const Shape &s,
+                                hipStream_t st);
+
+template <typename T, typename Kernel>
+int launch_corr_rowbatch_kernel(Kernel kernel, dwconv::RowBatchGeom &rg, int nc, const void *in, const void *f, void *out,
+                                const Shape &s, hipStream_t st)
+{
+    // one resident round of waves: J per channel group, each walking units j, j + J, ...
+    const long long groups = s.C / nc;
+    const long long resident = corr_wave_slots(kernel, 64 * dwconv::kRbCorrWaves);
+    long long J = resident / groups;
+    if (J < 1) J = 1;
+    if (J > rg.n_units) J = rg.n_units;
+    const long long upw = (rg.n_units + J - 1) / J;
+    J = (rg.n_units + upw - 1) / upw;
+    const long long blocks = (groups * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
+    if (blocks > 0x1fffffffLL) return -1;
+    rg.J = (int)J;
+    const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L, nc) * sizeof(float);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
+                       static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), rg);
+    return launch_status();
+}
+
+template <typename T>
+int launch_corr_rowbatch_wide_t(dwconv::RowBatchGeom &rg, int nd, const void *in, const void *f, void *out, const Shape &s,
+                                hipStream_t st)
+{
+    auto go = [&](auto kernel) -> int { return launch_corr_rowbatch_kernel<T>(kernel, rg, 1, in, f, out, s, st); };
+    if (rg.m <= 4) return nd == 7 ? go(dwconv::corr_rowbatch_kernel<T, 7, 1, 4, false>) : -1;
+    switch (nd) {
+    case 7: return go(dwconv::corr_rowbatch_kernel<T, 7, 1, 8, false>);
+    case 8: return go(dwconv::corr_rowbatch_kernel<T, 8, 1, 8, false>);
+    case 9: return go(dwconv::corr_rowbatch_kernel<T, 9, 1, 8, false>);
+    case 10: return go(dwconv::corr_rowbatch_kernel<T, 10, 1, 8, false>);
+    case 11: return go(dwconv::corr_rowbatch_kernel<T, 11, 1, 8, false>);
+    case 12: return go(dwconv::corr_rowbatch_kernel<T, 12, 1, 8, false>);
+    case 13: return go(dwconv::corr_rowbatch_kernel<T, 13, 1, 8, false>);
+    case 14: return go(dwconv::corr_rowbatch_kernel<T, 14, 1, 8, false>);
+    case 15: return go(dwconv::corr_rowbatch_kernel<T, 15, 1, 8, false>);
+    default: return -1;
+    }
+}
+
+template <typename T>
+int launch_corr_rowbatch(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse,
+                         const RowsPlan &rp, hipStream_t st)
+{
+    int dmin, nd;
+    rows_batch_offsets(s.L, s.K, pad_eff, &dmin, &nd);
+    dwconv::RowBatchGeom rg;
+    rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
+    rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
+    rg.m = (s.L + 15) / 16;
+    rg.n_units = rp.units;
+    // two channels per wave where that makes whole cache lines of rows that are not, or at least longer pieces;
+    // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
+    // (two channels are one piece of 2 L elements cut into granules: rows of whole granules)
+    const int nc = (s.C % 2 == 0 && (s.L * (int)sizeof(T)) % 128 != 0 && s.L <= 48 && nd <= 5 && (s.L % 4) == 0) ? 2 : 1;
+    const bool rag = (s.L % 4) != 0;                   // rows that end inside a granule
+    auto launch_batch = [&](auto kernel) -> int { return launch_corr_rowbatch_kernel<T>(kernel, rg, nc, in, f, out, s, st); };
+    if (nd > kMfmaMaxND) {
+        if (rag) return -1;
+        if constexpr (std::is_same<T, float>::value) return launch_corr_rowbatch_wide_f32(rg, nd, in, f, out, s, st);
+        else return launch_corr_rowbatch_wide_bf16(rg, nd, in, f, out, s, st);
+    }
+    if (nc == 2) {
+        switch (nd) {
+        case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2, 3, false>);
+        case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2, 3, false>);
+        case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2, 3, false>);
+        case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2, 3, false>);
+        default: return -1;
+        }
+    }
+    if (rg.m <= 4) {
+        switch (nd) {
+        case 2: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4, false>);
+        case 3: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4, false>);
+        case 4: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4, false>);
+        case 5: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4, false>);
+        case 6: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4, false>);
+        default: return -1;
+        }
+    }
+    switch (nd) {                              // rows of five to eight blocks
+    case 2: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8, false>);
+    case 3: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8, false>);
+    case 4: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8, false>);
+    case 5: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8, false>);
+    case 6: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8, false>);
+    default: return -1;
+    }
+}
+
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
 template <typename T>
 int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
 {
     const int dmin = toeplitz_dmin(pad_eff), dmax = toeplitz_dmax(s.K, pad_eff);
     const int nd = dmax - dmin + 1;
+    const RowsPlan rp = plan_rows(s);
+    // (the sixteen-row kernels of short rows move granules with buffer loads and stores that need dword alignment only)
+    if (rp.batch) return (aligned_to(in, 4) && aligned_to(out, 4)) ? launch_corr_rowbatch<T>(in, f, out, s, pad_eff, reverse, rp, st) : -1;
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(in, 4 * sizeof(T)) && aligned_to(out, 4 * sizeof(T));
-    const RowsPlan rp = plan_rows(s);
-    // (the sixteen-row kernels of short rows move granules with buffer loads and stores that need dword alignment only)
-    if (!granular && ((!ragged_rows_ok(s, nd) && !rp.batch) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
+    if (!granular && (!ragged_rows_ok(s, nd) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
     // block offsets the long-filter kernel takes too (fp32 eleven to sixteen, bf16 seven to sixteen): only where rows
     // fill their 1024-position segments to three quarters (shorter rows do less work on the long-filter kernel,
     // which contracts in-row block pairs only)
@@ -133,64 +240,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };
-    if (!granular && rp.on && !rp.batch) return -1;       // (virtual rows of a tensor that is only element-aligned)
-    if (rp.batch) {
-        // rows of at most 128 positions: sixteen rows of a channel (or of two neighbouring channels) per unit
-        dwconv::RowBatchGeom rg;
-        rg.B = s.B; rg.C = s.C; rg.L = s.L; rg.K = s.K;
-        rg.pad = pad_eff; rg.reverse = reverse; rg.dmin = dmin;
-        rg.m = (s.L + 15) / 16;
-        rg.n_units = rp.units;
-        // two channels per wave where that makes whole cache lines of rows that are not, or at least longer pieces;
-        // rows of at most 48 positions and at most five block offsets (register budget of the kernel)
-        // (two channels are one piece of 2 L elements cut into granules: rows of whole granules)
-        const int nc = (s.C % 2 == 0 && (s.L * (int)sizeof(T)) % 128 != 0 && s.L <= 48 && nd <= 5 && (s.L % 4) == 0) ? 2 : 1;
-        const bool rag = (s.L % 4) != 0;                   // rows that end inside a granule
-        auto launch_batch = [&](auto kernel) -> int {
-            // one resident round of waves: J per channel group, each walking units j, j + J, ...
-            const long long groups = s.C / nc;
-            const long long resident = corr_wave_slots(kernel, 64 * dwconv::kRbCorrWaves);
-            long long J = resident / groups;
-            if (J < 1) J = 1;
-            if (J > rg.n_units) J = rg.n_units;
-            const long long upw = (rg.n_units + J - 1) / J;
-            J = (rg.n_units + upw - 1) / upw;
-            const long long blocks = (groups * J + dwconv::kRbCorrWaves - 1) / dwconv::kRbCorrWaves;
-            if (blocks > 0x1fffffffLL) return -1;
-            rg.J = (int)J;
-            const size_t lds = (size_t)dwconv::kRbCorrWaves * dwconv::rb_corr_wave_floats(s.L, nc) * sizeof(float);
-            hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * dwconv::kRbCorrWaves), lds, st,
-                               static_cast<const T *>(in), static_cast<const T *>(f), static_cast<T *>(out), rg);
-            return launch_status();
-        };
-        if (nc == 2) {
-            switch (nd) {
-            case 2: return launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 2, 3, false>);
-            case 3: return launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 2, 3, false>);
-            case 4: return launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 2, 3, false>);
-            case 5: return launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 2, 3, false>);
-            default: return -1;
-            }
-        }
-        if (rg.m <= 4) {
-            switch (nd) {
-            case 2: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 4, false>);
-            case 3: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 4, false>);
-            case 4: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 4, false>);
-            case 5: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 4, false>);
-            case 6: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 4, false>);
-            default: return -1;
-            }
-        }
-        switch (nd) {                              // rows of five to eight blocks
-        case 2: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 2, 1, 8, false>);
-        case 3: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 3, 1, 8, false>);
-        case 4: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 4, 1, 8, false>);
-        case 5: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 5, 1, 8, false>);
-        case 6: return rag ? launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8, true>) : launch_batch(dwconv::corr_rowbatch_kernel<T, 6, 1, 8, false>);
-        default: return -1;
-        }
-    }
+    if (!granular && rp.on) return -1;       // (virtual rows of a tensor that is only element-aligned)
     {
         // longer short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
         if (rp.on) {

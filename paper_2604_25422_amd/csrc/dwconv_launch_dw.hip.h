@@ -21,56 +21,76 @@ void launch_dw_partial_valu(const void *x, const void *dy, float *part, const Sh
                        s.L, s.K, s.pad, p.valu_tiles_per_row, p.valu_items_per_slice, dwconv::RowsMap{0, 0, 0, 0, 0u, 0u});
 }
 
+// Rows of at most 128 positions, either storage type: sixteen rows per matrix tile.  dmin / nd: the block offsets inside a
+// row (rows_batch_offsets); the kernel is compiled per number of 16-blocks of a row, not per number of offsets.
+template <typename T, int W>
+int launch_dw_rowbatch_w(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p, int dmin,
+                         int nd, hipStream_t st)
+{
+    // rows of at most 128 positions, either storage type: sixteen rows per matrix tile
+    auto launch_rb = [&](auto kernel, int nc) -> int {
+        const size_t lds_rb = dwconv::rb_dw_lds_bytes(s.L, nd, W, nc);
+        if (lds_rb > kMaxLdsBytes) return -1;
+        if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(s.C / nc), (unsigned)p.S), dim3(64 * W), lds_rb, st,
+                           static_cast<const T *>(x), static_cast<const T *>(dy), part, static_cast<T *>(dw_out), s.B,
+                           s.C, s.L, s.K, s.pad, dmin, nd, p.tiles_per_row);
+        return launch_status();
+    };
+    // (the kernel is compiled per number of 16-blocks of a row, not per number of block offsets)
+    const int m = (s.L + 15) / 16;
+    // rows that end inside a granule: the variant with the partial-granule code, four-wave workgroups only (the plan
+    // asks for no others there)
+    auto rag_rb = [&](auto mc) -> int {
+        constexpr int MM = decltype(mc)::value;
+        if ((s.L % 4) != 0) {
+            if constexpr (W == dwconv::kWavesPerBlock) return launch_rb(dwconv::dw_rowbatch_kernel<T, MM, W, 1, true>, 1);
+            else return -1;
+        }
+        return launch_rb(dwconv::dw_rowbatch_kernel<T, MM, W, 1, false>, 1);
+    };
+    if constexpr (W == dwconv::kWavesPerBlock) {
+        if (p.dw_nc == 2) {
+            switch (m) {
+            case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 2, false>, 2);
+            case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 2, false>, 2);
+            case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 2, false>, 2);
+            default: return -1;
+            }
+        }
+    }
+    switch (m) {
+    case 1: return rag_rb(std::integral_constant<int, 1>{});
+    case 2: return rag_rb(std::integral_constant<int, 2>{});
+    case 3: return rag_rb(std::integral_constant<int, 3>{});
+    case 4: return rag_rb(std::integral_constant<int, 4>{});
+    case 5: return rag_rb(std::integral_constant<int, 5>{});
+    case 6: return rag_rb(std::integral_constant<int, 6>{});
+    case 7: return rag_rb(std::integral_constant<int, 7>{});
+    case 8: return rag_rb(std::integral_constant<int, 8>{});
+    default: return -1;
+    }
+}
+
+template <typename T>
+int launch_dw_rowbatch(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p, hipStream_t st)
+{
+    int dmin, nd;
+    rows_batch_offsets(s.L, s.K, s.pad, &dmin, &nd);
+    switch (p.wpb) {
+    case 4: return launch_dw_rowbatch_w<T, 4>(x, dy, part, dw_out, s, p, dmin, nd, st);
+    case 5: return launch_dw_rowbatch_w<T, 5>(x, dy, part, dw_out, s, p, dmin, nd, st);
+    case 8: return launch_dw_rowbatch_w<T, 8>(x, dy, part, dw_out, s, p, dmin, nd, st);
+    case 16: return launch_dw_rowbatch_w<T, 16>(x, dy, part, dw_out, s, p, dmin, nd, st);
+    default: return -1;
+    }
+}
+
 // One stage-1 launch on the matrix cores.  dw_out != nullptr only for single-slice plans.
 template <typename T, int ND, int W>
 int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
                                int dmin, hipStream_t st)
 {
-    if (p.rows.batch) {
-        // rows of at most 128 positions, either storage type: sixteen rows per matrix tile
-        auto launch_rb = [&](auto kernel, int nc) -> int {
-            const size_t lds_rb = dwconv::rb_dw_lds_bytes(s.L, ND, W, nc);
-            if (lds_rb > kMaxLdsBytes) return -1;
-            if (lds_rb > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-            hipLaunchKernelGGL(kernel, dim3((unsigned)(s.C / nc), (unsigned)p.S), dim3(64 * W), lds_rb, st,
-                               static_cast<const T *>(x), static_cast<const T *>(dy), part, static_cast<T *>(dw_out), s.B,
-                               s.C, s.L, s.K, s.pad, dmin, ND, p.tiles_per_row);
-            return launch_status();
-        };
-        // (the kernel is compiled per number of 16-blocks of a row, not per number of block offsets)
-        const int m = (s.L + 15) / 16;
-        // rows that end inside a granule: the variant with the partial-granule code, four-wave workgroups only (the plan
-        // asks for no others there)
-        auto rag_rb = [&](auto mc) -> int {
-            constexpr int MM = decltype(mc)::value;
-            if ((s.L % 4) != 0) {
-                if constexpr (W == dwconv::kWavesPerBlock) return launch_rb(dwconv::dw_rowbatch_kernel<T, MM, W, 1, true>, 1);
-                else return -1;
-            }
-            return launch_rb(dwconv::dw_rowbatch_kernel<T, MM, W, 1, false>, 1);
-        };
-        if constexpr (W == dwconv::kWavesPerBlock) {
-            if (p.dw_nc == 2) {
-                switch (m) {
-                case 1: return launch_rb(dwconv::dw_rowbatch_kernel<T, 1, W, 2, false>, 2);
-                case 2: return launch_rb(dwconv::dw_rowbatch_kernel<T, 2, W, 2, false>, 2);
-                case 3: return launch_rb(dwconv::dw_rowbatch_kernel<T, 3, W, 2, false>, 2);
-                default: return -1;
-                }
-            }
-        }
-        switch (m) {
-        case 1: return rag_rb(std::integral_constant<int, 1>{});
-        case 2: return rag_rb(std::integral_constant<int, 2>{});
-        case 3: return rag_rb(std::integral_constant<int, 3>{});
-        case 4: return rag_rb(std::integral_constant<int, 4>{});
-        case 5: return rag_rb(std::integral_constant<int, 5>{});
-        case 6: return rag_rb(std::integral_constant<int, 6>{});
-        case 7: return rag_rb(std::integral_constant<int, 7>{});
-        case 8: return rag_rb(std::integral_constant<int, 8>{});
-        default: return -1;
-        }
-    }
     if constexpr (std::is_same<T, float>::value) {
         // fp32 rows go from memory straight into LDS
         constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
@@ -140,6 +160,8 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
 {
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
     const int nd = dmax - dmin + 1;
+    // (rows of at most 128 positions: the sixteen-row kernel needs rows that start on a dword, nothing more)
+    if (p.rows.batch) return (aligned_to(x, 4) && aligned_to(dy, 4)) ? launch_dw_rowbatch<T>(x, dy, part, dw_out, s, p, st) : -1;
     if (p.manypass) {
         if constexpr (std::is_same<T, float>::value) {
             if (!aligned_to(x, 16) || !aligned_to(dy, 16)) return -1;
@@ -151,9 +173,7 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(x, 4 * sizeof(T)) && aligned_to(dy, 4 * sizeof(T));
-    // (rows of at most 128 positions: the sixteen-row kernel needs rows that start on a dword, nothing more)
-    if (!granular && ((!ragged_rows_ok(s, nd) && !p.rows.batch) || (p.rows.on && !p.rows.batch) || !aligned_to(x, 4) || !aligned_to(dy, 4)))
-        return -1;
+    if (!granular && (!ragged_rows_ok(s, nd) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4))) return -1;
     if constexpr (std::is_same<T, float>::value) {
         if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
     } else {

@@ -44,9 +44,12 @@ __host__ __device__ constexpr int rb_dw_wave_floats(int L, int ND, int NC)
     const int diag = ((16 * ND + 15) * 17 + 3) / 4 * 4;
     return stage > diag ? stage : diag;
 }
+// Taps the nd block offsets of a kernel can reach: 16 nd + 15 (all K of them when the offsets cover the filter; with
+// the offsets cropped to those inside a row, a window [j0, j1) of a longer filter: the other taps are zero).
+__host__ __device__ constexpr int rb_tap_floats(int ND) { return 16 * ND + 16; }
 __host__ __device__ constexpr size_t rb_dw_lds_bytes(int L, int ND, int W, int NC)
 {
-    return (size_t)W * (size_t)(rb_dw_wave_floats(L, ND, NC) + NC * 16 * ND) * sizeof(float);
+    return (size_t)W * (size_t)(rb_dw_wave_floats(L, ND, NC) + NC * rb_tap_floats(ND)) * sizeof(float);
 }
 
 struct RowBatchGeom {
@@ -113,7 +116,7 @@ constexpr int kRbCorrWaves = 4;   // waves per block: neighbouring channels, who
 // long-row kernel), the prefetched inputs of the next unit come in.
 // RAG: rows that are not whole granules (one channel per wave; the code for the partial granule is compiled only there).
 template <typename T, int ND, int NC, int MB, bool RAG>
-__global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 || RAG ? 3 : kMfmaWavesPerSimd)) void corr_rowbatch_kernel(
+__global__ __launch_bounds__(64 * kRbCorrWaves, (ND > 9 ? 2 : (MB > 4 || RAG || ND > 6) ? 3 : kMfmaWavesPerSimd)) void corr_rowbatch_kernel(
     const T *__restrict__ in, const T *__restrict__ f, T *__restrict__ out, const RowBatchGeom g)
 {
     constexpr int ES = (int)sizeof(T);          // bf16 storage is widened on the way into LDS; fp32 arithmetic
@@ -251,6 +254,15 @@ __global__ __launch_bounds__(64 * kRbCorrWaves, (MB > 4 || RAG ? 3 : kMfmaWavesP
     }
 }
 
+// First and one-past-last tap that the block offsets dmin .. dmin + nd - 1 reach: j = 16 d + q' - q + pad.
+__host__ __device__ constexpr int rb_tap_j0(int pad, int dmin) { return pad + 16 * dmin - 15 > 0 ? pad + 16 * dmin - 15 : 0; }
+__host__ __device__ constexpr int rb_tap_j1(int K, int pad, int dmin, int nd)
+{
+    const int e = pad + 16 * (dmin + nd - 1) + 16;
+    const int j0 = rb_tap_j0(pad, dmin);
+    return e < j0 ? j0 : (e < K ? e : K);
+}
+
 // Diagonal sums of accumulators that are indexed by the RELATIVE block offset rel = mi - mo = e - (M - 1)
 // (the run-time counterpart of dw_wave_diagonal_sums: which offsets exist, dmin .. dmax, is known at run time only).
 // sw: the wave's LDS region, at least ((16 nd + 15) * 17 + 3) / 4 * 4 floats; dw_wave[j], j < K, receives the sums.
@@ -273,7 +285,9 @@ __device__ __forceinline__ void rb_diagonal_sums(const floatx4 (&G)[NR], int M, 
         }
     }
     wave_lds_fence();
-    for (int j = lane; j < K; j += 64) {
+    // taps the offsets reach: j0 .. j1 - 1 (rb_tap_window), dw_wave[j - j0]
+    const int j0 = rb_tap_j0(pad, dmin), j1 = rb_tap_j1(K, pad, dmin, nd);
+    for (int j = j0 + lane; j < j1; j += 64) {
         const int jl = j - pad - 16 * dmin + 15;
         float sum = 0.f;
         if (jl >= 0 && jl < rows) {
@@ -283,7 +297,7 @@ __device__ __forceinline__ void rb_diagonal_sums(const floatx4 (&G)[NR], int M, 
 #pragma unroll
             for (int i = 0; i < 16; ++i) sum += t[i];
         }
-        dw_wave[j] = sum;
+        dw_wave[j - j0] = sum;
     }
 }
 
@@ -411,17 +425,21 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_rowbatch_kernel(
     }
 
     // ---- per-wave diagonal sums, then the waves of the block in wave order
+    const int TF = rb_tap_floats(nd);
 #pragma unroll
     for (int h = 0; h < NC; ++h) {
-        rb_diagonal_sums<NR>(G[h], M, s_wave, s_dw + (wave * NC + h) * (16 * nd), lane, K, pad, dmin, nd);
+        rb_diagonal_sums<NR>(G[h], M, s_wave, s_dw + (wave * NC + h) * TF, lane, K, pad, dmin, nd);
         wave_lds_fence();
     }
     __syncthreads();
+    const int j0 = rb_tap_j0(pad, dmin), j1 = rb_tap_j1(K, pad, dmin, nd);      // (the other taps of a longer filter are zero)
     for (int e = tid; e < NC * K; e += 64 * W) {
         const int h = e / K, j = e - h * K;
         float sum = 0.f;
+        if (j >= j0 && j < j1) {
 #pragma unroll
-        for (int w = 0; w < W; ++w) sum += s_dw[(w * NC + h) * (16 * nd) + j];
+            for (int w = 0; w < W; ++w) sum += s_dw[(w * NC + h) * TF + (j - j0)];
+        }
         const size_t o = (size_t)(c0 + h) * (size_t)K + (size_t)j;
         if (dw_out) st_elem(dw_out + o, sum);
         else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = sum;
@@ -449,7 +467,7 @@ __host__ __device__ constexpr int rb_bwd_wave_floats(int L, int ND)
 constexpr int kRbBwdWaves = 4;
 __host__ __device__ constexpr size_t rb_bwd_lds_bytes(int L, int ND)
 {
-    return (size_t)kRbBwdWaves * (size_t)(rb_bwd_wave_floats(L, ND) + 16 * ND) * sizeof(float);
+    return (size_t)kRbBwdWaves * (size_t)(rb_bwd_wave_floats(L, ND) + rb_tap_floats(ND)) * sizeof(float);
 }
 
 // RAG: rows that are not whole granules (the masks and element stores of the partial granule cost registers this
@@ -474,7 +492,7 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, (RAG ? 3 : kMfmaWavesPerSimd)) vo
     const int c = kRbBwdWaves * (int)blockIdx.x + wave;
     if (c >= C) return;                                       // (no workgroup barrier below)
     float *s_wave = dyn_lds + wave * wreg;
-    float *s_dw = dyn_lds + kRbBwdWaves * wreg + wave * (16 * ND);
+    float *s_dw = dyn_lds + kRbBwdWaves * wreg + wave * rb_tap_floats(ND);
     constexpr int m = M;
     const int Ld = 16 * m + 4;                                // pitch of the dY image
     const int Lp = rb_dw_pitch(L, 1);                         // pitch of the x image
@@ -624,10 +642,12 @@ __global__ __launch_bounds__(64 * kRbBwdWaves, (RAG ? 3 : kMfmaWavesPerSimd)) vo
     // ---- diagonal sums of this wave's accumulators: its slice of the partial sums
     rb_diagonal_sums<NR>(G, M, s_wave, s_dw, lane, K, pad, dmin, ND);
     wave_lds_fence();
+    const int j0 = rb_tap_j0(pad, dmin), j1 = rb_tap_j1(K, pad, dmin, ND);      // (the other taps of a longer filter are zero)
     for (int j = lane; j < K; j += 64) {
         const size_t o = (size_t)c * (size_t)K + (size_t)j;
-        if (dw_out) st_elem(dw_out + o, s_dw[j]);
-        else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = s_dw[j];
+        const float v = (j >= j0 && j < j1) ? s_dw[j - j0] : 0.f;
+        if (dw_out) st_elem(dw_out + o, v);
+        else part[(size_t)blockIdx.y * (size_t)C * (size_t)K + o] = v;
     }
 }
 

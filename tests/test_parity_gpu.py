@@ -234,7 +234,8 @@ BWD = [
     (2, 2, 48, 48, 24, "bf16", True), (3, 2, 4096, 66, 65, "bf16", True), (40, 256, 1024, 64, 63, "bf16", True),
     (100, 6, 44, 31, 15, "bf16", True), (37, 3, 60, 20, 10, "bf16", False), (70, 256, 48, 48, 24, "bf16", True),
     (20, 4, 128, 16, 15, "bf16", False), (20, 4, 128, 16, 15, "f32", False), (20, 4, 132, 16, 15, "f32", True),
-    (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", True),
+    (1, 2, 40, 100, 99, "f32", True), (3, 2, 33, 1, 0, "f32", True), (100, 6, 48, 200, 100, "f32", True), (40, 3, 96, 96, 48, "f32", False),
+    (60, 4, 44, 500, 499, "bf16", True),
 ]
 
 
