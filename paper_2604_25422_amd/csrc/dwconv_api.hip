@@ -278,6 +278,7 @@ DwPlan plan_dw(const Shape &s)
     // long filters: offsets are split over waves instead, partials land in exactly two slices
     p.longk = false;
     p.lk_wgs = p.lk_gd = 0;
+    p.lk_rs = 1; p.lk_bper = s.B;
     const int NCH = (s.L + 63) / 64;
     if (!p.rows.batch && nd > mfma_max_nd_dw(s) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
@@ -306,10 +307,23 @@ DwPlan plan_dw(const Shape &s)
     }
     if (p.lk_table) {
         p.longk = true;
-        p.S = 2;
-        p.S_fused = 2;                                     // (no fused kernel for long filters: nothing needs more slices)
-        p.items_per_slice = (int)((items + 1) / 2);        // the generic kernel, if it has to run, uses two slices too
-        p.valu_items_per_slice = (int)(((long long)s.B * p.valu_tiles_per_row + 1) / 2);      // (of its own items: real rows)
+        // Workgroups: channels x groups of offsets.  Where that is fewer than two per compute unit (few channels, or rows
+        // so short that the offsets fit one workgroup) the batch is cut into slices too, each with its own two slices
+        // of partial sums (B78125 C1 L256 K700: one workgroup walked the whole batch, 112 ms; B128 C128 L4096 K4096: 128
+        // workgroups on 256 compute units).  At most 128, at least one pair of rows each, workspace at most 64 MiB.
+        long long rs = (2LL * kComputeUnits + (long long)s.C * p.lk_wgs - 1) / ((long long)s.C * p.lk_wgs);
+        if (rs > 128) rs = 128;
+        if (rs > (s.B + dwconv::kLkRows - 1) / dwconv::kLkRows) rs = (s.B + dwconv::kLkRows - 1) / dwconv::kLkRows;
+        while (rs > 1 && 2 * rs * (long long)s.C * s.K * (long long)sizeof(float) > (64ll << 20)) --rs;
+        if (rs < 1) rs = 1;
+        long long bper = ((s.B + rs - 1) / rs + dwconv::kLkRows - 1) / dwconv::kLkRows * dwconv::kLkRows;
+        rs = (s.B + bper - 1) / bper;
+        p.lk_rs = (int)rs;
+        p.lk_bper = (int)bper;
+        p.S = (int)(2 * rs);
+        p.S_fused = p.S;                                   // (no fused kernel for long filters: nothing needs more slices)
+        p.items_per_slice = (int)((items + p.S - 1) / p.S);       // the generic kernel, if it has to run, uses the same slices
+        p.valu_items_per_slice = (int)(((long long)s.B * p.valu_tiles_per_row + p.S - 1) / p.S);      // (of its own items: real rows)
     }
     // the generic kernel on short rows: its items are the tiles of the virtual row of the channel
     p.valu_rows = plan_valu_rows(s);

@@ -213,6 +213,7 @@ struct DwPlan {
     DwKernel kernel;
     bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
     int lk_wgs, lk_gd;     // its workgroups per channel, largest group of offsets (accumulators per group)
+    int lk_rs, lk_bper;    // its batch slices (each with two slices of partial sums of its own) and batch entries per slice
     std::shared_ptr<const dwconv::LongKDwTable> lk_table;   // which offsets every wave slot owns
     int S;                 // partial slices per coefficient (all passes together)
     int passes;            // launches of the stage-1 kernel, each over part of the block offsets into S / passes slices

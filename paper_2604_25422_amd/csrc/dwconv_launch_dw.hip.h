@@ -193,9 +193,9 @@ template <typename T, int GD>
 int launch_dw_longk_gd(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p,
                        const dwconv::LongKDwGeom &g, hipStream_t st)
 {
-    // both slices start at zero: a group stores only the taps it owns
+    // all slices start at zero: a group stores only the taps it owns
     auto fill = [&]() {
-        const size_t n = (size_t)2 * (size_t)s.C * (size_t)s.K;
+        const size_t n = (size_t)p.S * (size_t)s.C * (size_t)s.K;
         size_t fill_blocks = (n + 256 * 8 - 1) / (256 * 8);
         if (fill_blocks > 65536) fill_blocks = 65536;
         hipLaunchKernelGGL(dwconv::fill_zero_kernel<>, dim3((unsigned)fill_blocks), dim3(256), 0, st, part, n);
@@ -205,14 +205,14 @@ int launch_dw_longk_gd(const void *x, const void *dy, float *part, const Shape &
         const size_t lds = dwconv::longk_dw_bf16_lds_bytes(s.L);
         if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::dw_longk_bf16_kernel<GD>)) return -1;
         fill();
-        hipLaunchKernelGGL((dwconv::dw_longk_bf16_kernel<GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
+        hipLaunchKernelGGL((dwconv::dw_longk_bf16_kernel<GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs, (unsigned)p.lk_rs),
                            dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const bf16_t *>(x),
                            static_cast<const bf16_t *>(dy), part, g, *p.lk_table);
     } else {
         const size_t lds = dwconv::longk_dw_lds_bytes(s.L, g.NCH);
         if (lds > kMaxLdsBytes || !allow_large_lds(dwconv::dw_longk_kernel<T, GD>)) return -1;
         fill();
-        hipLaunchKernelGGL((dwconv::dw_longk_kernel<T, GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs),
+        hipLaunchKernelGGL((dwconv::dw_longk_kernel<T, GD>), dim3((unsigned)s.C, (unsigned)p.lk_wgs, (unsigned)p.lk_rs),
                            dim3(64 * dwconv::kLkWaves), lds, st, static_cast<const T *>(x), static_cast<const T *>(dy),
                            part, g, *p.lk_table);
     }
@@ -228,6 +228,8 @@ int launch_dw_partial_longk(const void *x, const void *dy, float *part, const Sh
     g.B = s.B; g.C = s.C; g.L = s.L; g.K = s.K; g.pad = s.pad;
     g.dmin = toeplitz_dmin(s.pad); g.dmax = toeplitz_dmax(s.K, s.pad);
     g.NCH = (s.L + 63) / 64;
+    g.bper = p.lk_bper;
+    if (p.S != 2 * p.lk_rs) return -1;
     switch (p.lk_gd) {
     case 1: return launch_dw_longk_gd<T, 1>(x, dy, part, s, p, g, st);
     case 2: return launch_dw_longk_gd<T, 2>(x, dy, part, s, p, g, st);

@@ -528,6 +528,9 @@ struct LongKDwGeom {
     int B, C, L, K, pad;
     int dmin, dmax;
     int NCH;        // 64-position chunks per row
+    int bper;       // batch entries per batch slice (a multiple of the rows staged together): workgroup (c, y, z) walks
+                    // entries z * bper .. and writes the slices 2 z and 2 z + 1, so that few channels or few offsets
+                    // still fill the chip
 };
 
 // Which offsets a wave slot owns.  The block offsets dmin..dmax are cut into contiguous groups of 1..9 offsets
@@ -621,13 +624,14 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
         G1[i] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int b0 = 0; b0 < g.B; b0 += kLkRows) {
+    const int b_begin = (int)blockIdx.z * g.bper, b_end = min(g.B, b_begin + g.bper);
+    for (int b0 = b_begin; b0 < b_end; b0 += kLkRows) {
         __syncthreads();
         for (int rb = 0; rb < kLkRows; ++rb) {
             const int b = b0 + rb;
             float *xrow = sx + rb * XW;
             float *grow = sg + rb * GW;
-            const size_t row = ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            const size_t row = ((size_t)(b < b_end ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
             for (int i = tid; i < 2 * kLkDwMargin; i += 64 * kLkWaves)
                 xrow[i < kLkDwMargin ? i : g.L + i] = 0.f;
             for (int gi0 = tid; gi0 < g.NCH * 16; gi0 += 64 * kLkWaves) {
@@ -637,7 +641,7 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
                 asm volatile("" : "+v"(gi));
                 const int u = 4 * gi;
                 float4 vx = make_float4(0.f, 0.f, 0.f, 0.f), vg = vx;
-                if (b < g.B && u + 3 < g.L) {
+                if (b < b_end && u + 3 < g.L) {
                     vx = ld_elem4(x + row + u);
                     vg = ld_elem4(dy + row + u);
                 }
@@ -685,7 +689,7 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_kernel(const T *__r
             wave_lds_fence();
         }
         const int ntap = 16 * (db[k] - da[k]) + 31;
-        float *dst = part + ((size_t)(grp[k] & 1) * (size_t)g.C + (size_t)c) * (size_t)g.K;
+        float *dst = part + ((size_t)(2 * (int)blockIdx.z + (grp[k] & 1)) * (size_t)g.C + (size_t)c) * (size_t)g.K;
         for (int i = lane; i < ntap; i += 64) {
             const int j = 16 * da[k] + (i - 15) + g.pad;
             if (j >= 0 && j < g.K) dst[j] = tap[i];
@@ -803,12 +807,13 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const b
     for (int i = tid; i < kLkRows * ROWB / 16; i += 64 * kLkWaves)
         *reinterpret_cast<uint4 *>(lkb_dw_smem + 16 * i) = make_uint4(0u, 0u, 0u, 0u);
 
-    for (int b0 = 0; b0 < g.B; b0 += kLkRows) {
+    const int b_begin = (int)blockIdx.z * g.bper, b_end = min(g.B, b_begin + g.bper);
+    for (int b0 = b_begin; b0 < b_end; b0 += kLkRows) {
         __syncthreads();
         for (int rb = 0; rb < kLkRows; ++rb) {
             const int b = b0 + rb;
             unsigned char *x0 = lkb_dw_smem + rb * ROWB, *gt = x0 + 2 * XC;
-            const size_t row = ((size_t)(b < g.B ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
+            const size_t row = ((size_t)(b < b_end ? b : 0) * (size_t)g.C + (size_t)c) * (size_t)g.L;
 #pragma unroll 1
             for (int gi0 = tid; gi0 < NB * 4; gi0 += 64 * kLkWaves) {
                 // (the addresses below are recomputed from gi every time: kept as induction variables they would
@@ -817,7 +822,7 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const b
                 asm volatile("" : "+v"(gi));
                 const int u = 4 * gi;
                 uint2 vx = make_uint2(0u, 0u), vg = vx;
-                if (b < g.B && u + 3 < g.L) {
+                if (b < b_end && u + 3 < g.L) {
                     vx = *reinterpret_cast<const uint2 *>(x + row + u);
                     vg = *reinterpret_cast<const uint2 *>(dy + row + u);
                 }
@@ -880,7 +885,7 @@ __global__ __launch_bounds__(64 * kLkWaves, 4) void dw_longk_bf16_kernel(const b
             wave_lds_fence();
         }
         const int ntap = 16 * (db[k] - da[k]) + 31;
-        float *dst = part + ((size_t)(grp[k] & 1) * (size_t)g.C + (size_t)c) * (size_t)g.K;
+        float *dst = part + ((size_t)(2 * (int)blockIdx.z + (grp[k] & 1)) * (size_t)g.C + (size_t)c) * (size_t)g.K;
         for (int i = lane; i < ntap; i += 64) {
             const int j = 16 * da[k] + (i - 15) + g.pad;
             if (j >= 0 && j < g.K) dst[j] = tap[i];
