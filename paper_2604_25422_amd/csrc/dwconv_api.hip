@@ -68,13 +68,13 @@ RowsPlan plan_rows(const Shape &s)
         if ((s.L % 4) != 0) batch = bn <= kMfmaMaxND && (s.dtype == DWCONV_F32 || (s.L % 2) == 0);
         else batch = bn <= kRbMaxND;
     }
-    // Virtual rows (whole granules, up to six offsets): where a 1024-position segment of a row would be more than a
+    // Virtual rows (whole granules; up to six offsets, fp32 sixteen): where a 1024-position segment of a row would be more than a
     // quarter padding, and positions stay 32-bit.
     const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
     const long long P = (s.L + 3) / 4 * 4 + (halo + 3) / 4 * 4;
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
     const long long elems = (long long)s.B * s.C * s.L;
-    const bool vrows = (s.L % 4) == 0 && nd <= kMfmaMaxND && 4 * padded > 5 * P && elems * es <= (1ll << 30) &&
+    const bool vrows = (s.L % 4) == 0 && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND) && 4 * padded > 5 * P && elems * es <= (1ll << 30) &&
                        (long long)s.B * P * P < (1ll << 32) && (long long)s.B * P < (1ll << 31);
     if (vrows) {
         r.on = true;
@@ -216,7 +216,7 @@ DwPlan plan_dw(const Shape &s)
     p.single = false;
     p.dw_nc = 1;
     if (mfma_shape && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDWide : kMfmaMaxND) && s.C % kComputeUnits == 0 &&
-        s.C / kComputeUnits <= 3 && !(p.rows.batch && (s.L % 4) != 0)) {
+        s.C / kComputeUnits <= 3 && !(p.rows.batch && (s.L % 4) != 0) && !(p.rows.on && !p.rows.batch && nd > kMfmaMaxND)) {
         int wpb = 16 / (s.C / kComputeUnits);
         // short filters leave the matrix pipe idle, and what then counts is how many bytes the chip has in flight:
         // two rows of 4 KiB per wave are enough with 8 to 12 waves per compute unit (B64 C512 L2048 K7: 82 us against

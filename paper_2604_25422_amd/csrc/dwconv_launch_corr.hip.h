@@ -138,6 +138,41 @@ int launch_corr_rowbatch(const void *in, const void *f, void *out, const Shape &
     }
 }
 
+// One launch of a forward / input-gradient kernel on the virtual rows of the channels (short rows, see RowsMap): slots
+// ordered (virtual segment, channel).
+template <typename T, typename Kernel>
+int launch_corr_vrows_kernel(Kernel kernel, dwconv::CorrGeom g, const RowsPlan &rp, const void *in, const void *f, void *out,
+                             const Shape &s, hipStream_t st)
+{
+    constexpr int kThreads = 64 * dwconv::kCorrWavesPerBlock;
+    const long long total = (long long)rp.nvs * s.C;
+    if (total > 0x3fffffffLL) return -1;
+    g.rows = rp.nvs;
+    g.segs_per_row = s.C;
+    const long long resident = corr_wave_slots(kernel, kThreads);
+    long long spw = (total + resident - 1) / resident;
+    if (spw < 1) spw = 1;
+    long long waves = (total + spw - 1) / spw;
+    if (s.C <= resident) {                                // whole virtual segments per round: channel fixed
+        long long J = resident / s.C;
+        if (J > rp.nvs) J = rp.nvs;
+        const long long rounds = (rp.nvs + J - 1) / J;
+        J = (rp.nvs + rounds - 1) / rounds;
+        waves = J * s.C;
+    }
+    const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
+    g.n_waves = (int)waves;
+    g.step_rows = g.n_waves / g.segs_per_row;
+    g.step_seg = g.n_waves % g.segs_per_row;
+    g.step_c = 0;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, static_cast<const T *>(in),
+                       static_cast<const T *>(f), static_cast<T *>(out), g, rp.map);
+    return launch_status();
+}
+// (fp32, seven to sixteen block offsets on virtual rows: a translation unit of its own, dwconv_launch_corr_rows_f32.hip)
+int launch_corr_vrows_wide_f32(const dwconv::CorrGeom &g, const RowsPlan &rp, int nd, const void *in, const void *f, void *out,
+                               const Shape &s, hipStream_t st);
+
 // Returns -1 when the shape or the pointers do not fit the matrix-core kernel.
 template <typename T>
 int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st)
@@ -154,7 +189,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     // block offsets the long-filter kernel takes too (fp32 eleven to sixteen, bf16 seven to sixteen): only where rows
     // fill their 1024-position segments to three quarters (shorter rows do less work on the long-filter kernel,
     // which contracts in-row block pairs only)
-    if (nd >= longk_corr_min_nd(s.dtype) &&
+    if (!rp.on && nd >= longk_corr_min_nd(s.dtype) &&
         4ll * s.L < 3ll * (((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen))
         return -1;
     const long long rows = (long long)s.B * s.C;
@@ -244,39 +279,17 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     {
         // longer short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
         if (rp.on) {
-            const long long total = (long long)rp.nvs * s.C;
-            if (total > 0x3fffffffLL) return -1;
-            g.rows = rp.nvs;
-            g.segs_per_row = s.C;
-            auto launch_rows = [&](auto kernel) -> int {
-                const long long resident = corr_wave_slots(kernel, kThreads);
-                long long spw = (total + resident - 1) / resident;
-                if (spw < 1) spw = 1;
-                long long waves = (total + spw - 1) / spw;
-                if (s.C <= resident) {                                // whole virtual segments per round: channel fixed
-                    long long J = resident / s.C;
-                    if (J > rp.nvs) J = rp.nvs;
-                    const long long rounds = (rp.nvs + J - 1) / J;
-                    J = (rp.nvs + rounds - 1) / rounds;
-                    waves = J * s.C;
-                }
-                const long long blocks = (waves + dwconv::kCorrWavesPerBlock - 1) / dwconv::kCorrWavesPerBlock;
-                g.n_waves = (int)waves;
-                g.step_rows = g.n_waves / g.segs_per_row;
-                g.step_seg = g.n_waves % g.segs_per_row;
-                g.step_c = 0;
-                hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, static_cast<const T *>(in),
-                                   static_cast<const T *>(f), static_cast<T *>(out), g, rp.map);
-                return launch_status();
-            };
+            auto launch_rows = [&](auto kernel) -> int { return launch_corr_vrows_kernel<T>(kernel, g, rp, in, f, out, s, st); };
             switch (nd) {
             case 2: return launch_rows(dwconv::corr_mfma_kernel<T, 2, true>);
             case 3: return launch_rows(dwconv::corr_mfma_kernel<T, 3, true>);
             case 4: return launch_rows(dwconv::corr_mfma_kernel<T, 4, true>);
             case 5: return launch_rows(dwconv::corr_mfma_kernel<T, 5, true>);
             case 6: return launch_rows(dwconv::corr_mfma_kernel<T, 6, true>);
-            default: return -1;
+            default: break;
             }
+            if constexpr (std::is_same<T, float>::value) return launch_corr_vrows_wide_f32(g, rp, nd, in, f, out, s, st);
+            return -1;
         }
     }
     if constexpr (sizeof(T) == 2) {

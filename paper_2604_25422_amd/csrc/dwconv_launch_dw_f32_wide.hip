@@ -31,11 +31,31 @@ int launch_dw_partial_wide_ndw(const void *x, const void *dy, float *part, void 
         return launch_status();
     }
 }
+// Short rows: the same kernel on the virtual row of a channel (four-wave workgroups, the filter's offsets in one launch).
+template <int ND>
+int launch_dw_partial_wide_rows(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
+                                int dmin, hipStream_t st)
+{
+    constexpr int W = 4;
+    constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
+    if constexpr (lds > kMaxLdsBytes) {
+        return -1;
+    } else {
+        if (p.wpb != W || p.passes != 1) return -1;
+        auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const float *>(x),
+                           static_cast<const float *>(dy), part, static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin,
+                           p.tiles_per_row, p.rows.map, 0, s.K, 0, 0);
+        return launch_status();
+    }
+}
+
 template <int ND>
 int launch_dw_partial_wide_nd(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
                               int dmin, hipStream_t st)
 {
-    if (p.rows.on) return -1;
+    if (p.rows.on) return launch_dw_partial_wide_rows<ND>(x, dy, part, dw_out, s, p, dmin, st);
     if constexpr (ND > kMfmaMaxNDWide) {
         // eleven to sixteen block offsets: four-wave workgroups only (the plan never asks for more)
         return p.wpb == 4 ? launch_dw_partial_wide_ndw<ND, 4>(x, dy, part, dw_out, s, p, dmin, st) : -1;

@@ -181,7 +181,7 @@ template <> struct Raw4<bf16_t> {
 // range check); the last group of four outputs of a row is stored by element, which costs registers, so these
 // variants are compiled apart and run two waves per SIMD from eight block offsets.
 template <typename T, int ND, bool ROWS, bool RAG = false>
-__global__ __launch_bounds__(64 * kCorrWavesPerBlock, ((ND > 9 || (RAG && ND > 7)) ? 2 : ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
+__global__ __launch_bounds__(64 * kCorrWavesPerBlock, ((ND > 9 || ((RAG || ROWS) && ND > 7)) ? 2 : ND > 6 ? 3 : kMfmaWavesPerSimd)) void corr_mfma_kernel(const T *__restrict__ in,
                                                                          const T *__restrict__ f, T *__restrict__ out,
                                                                          const CorrGeom g, const RowsMap rm)
 {

@@ -97,6 +97,8 @@ CLASSES = [
     # short rows: sixteen rows per tile (with channel pairs), rows of five to eight blocks, virtual rows
     (40, 6, 48, 48, 24), (100, 3, 48, 48, 0), (17, 3, 16, 16, 15), (33, 2, 80, 48, 24), (130, 2, 128, 31, 15),
     (70, 256, 48, 48, 24), (300, 12, 200, 31, 15), (64, 2, 512, 64, 63), (50, 3, 132, 16, 15),
+    # longer short rows (virtual rows) with seven to sixteen block offsets
+    (20, 3, 256, 100, 99), (9, 2, 384, 160, 80), (6, 4, 512, 226, 0), (12, 256, 200, 130, 129), (7, 3, 640, 200, 100),
     # ... filters as long as such rows or longer (only the block offsets inside a row count: up to fifteen)
     (40, 6, 96, 96, 48), (33, 3, 128, 128, 127), (20, 4, 128, 128, 64), (17, 2, 64, 100, 50), (50, 3, 112, 300, 150),
     (100, 2, 48, 1000, 500), (30, 256, 96, 96, 95), (9, 2, 16, 64, 0), (35, 4, 80, 80, 0), (18, 5, 128, 4000, 2000),
