@@ -113,6 +113,18 @@ int corr_entry(const void *in, const void *f, void *out, int B, int C, int L, in
 // work; the cap is searched so that at most two groups per slot suffice and the busiest slot is as light as
 // possible; groups go to slots heaviest first, each to the least loaded slot that still has room.  The result
 // depends on (L, K, pad, slots) only and is cached.
+// Block offsets of the filter that have a block pair inside a row of ceil(L / 16) blocks (at least one).
+static void longk_dw_offsets(const Shape &s, int *dmin_out, int *dmax_out)
+{
+    const int nb = (s.L + 15) / 16;
+    int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
+    if (dmin < -(nb - 1)) dmin = -(nb - 1);
+    if (dmax > nb - 1) dmax = nb - 1;
+    if (dmax < dmin) dmax = dmin;
+    *dmin_out = dmin;
+    *dmax_out = dmax;
+}
+
 std::shared_ptr<const dwconv::LongKDwTable> longk_dw_table(const Shape &s, int wgs, int *max_group)
 {
     struct Entry { std::shared_ptr<const dwconv::LongKDwTable> table; int max_group; };
@@ -123,7 +135,9 @@ std::shared_ptr<const dwconv::LongKDwTable> longk_dw_table(const Shape &s, int w
     auto it = cache.find(key);
     if (it != cache.end()) { *max_group = it->second.max_group; return it->second.table; }
 
-    const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);
+    // (only the block offsets that have a block pair inside a row: a filter longer than the row has offsets that reach nothing)
+    int dmin, dmax;
+    longk_dw_offsets(s, &dmin, &dmax);
     const int NCH = (s.L + 63) / 64;
     const int nslots = wgs * dwconv::kLkWaves;
     auto fdiv = [](int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); };
@@ -283,7 +297,9 @@ DwPlan plan_dw(const Shape &s)
     if (!p.rows.batch && nd > mfma_max_nd_dw(s) && s.K <= dwconv::kLkMaxK && (s.L % 4) == 0 && (s.L + 15) / 16 <= dwconv::kLkMaxBlocks &&
         dwconv::longk_dw_lds_bytes(s.L, NCH) <= kMaxLdsBytes) {
         const int per_wg = 2 * dwconv::kLkWaves * dwconv::kLkDwMaxGD;
-        p.lk_wgs = (nd + per_wg - 1) / per_wg;
+        int lk_dmin, lk_dmax;
+        longk_dw_offsets(s, &lk_dmin, &lk_dmax);
+        p.lk_wgs = (lk_dmax - lk_dmin + 1 + per_wg - 1) / per_wg;
         p.lk_table = longk_dw_table(s, p.lk_wgs, &p.lk_gd);
     }
     p.manypass = false;
