@@ -146,8 +146,9 @@ DWCONV_API size_t dwconv_noalloc_scratch_bytes(void);
 /*
  * Both gradients of the backward pass in one call: dx as dwconv_bwd_input, dw as dwconv_bwd_weight.
  * The paper names kernel fusion as the remaining lever for the backward path (Sec. VI): for filters of the
- * register-resident class (dwconv_bwd_is_fused(...) == 1: K up to about 66, fp32 with L % 4 == 0 or bf16 with L % 8 == 0,
- * 16-byte aligned tensors; not rows of 52 to 128 positions, not bf16 short rows above that) one
+ * register-resident class (dwconv_bwd_is_fused(...) == 1: up to six 16-position block offsets, i.e. K up to about 66, or
+ * any K on rows of at most 48 positions; rows that start on a 4-byte boundary - from 768 positions when they are not
+ * whole 16-byte granules; not rows of 52 to 128 positions, not bf16 rows of 132 to about 800 positions) one
  * kernel reads dy once and produces dx and the stage-1 sums of dw (5 tensor passes over memory per
  * forward + backward step instead of 6); every other shape or type runs the two separate paths one after the
  * other.  dy, x [B,C,L] in; w [C,K] in; dx [B,C,L] out; dw [C,K] out; workspace as for dwconv_bwd_weight.
@@ -158,7 +159,7 @@ DWCONV_API int dwconv_bwd(const void *dy, const void *x, const void *w, void *dx
                void *workspace, size_t workspace_bytes,
                int B, int C, int L, int K, int pad_left, int dtype, void *stream);
 
-/* 1 when dwconv_bwd runs the fused kernel for this shape (given 16-byte aligned tensors); 0 otherwise. */
+/* 1 when dwconv_bwd runs the fused kernel for this shape (given tensors aligned as it needs: 16 bytes always do); 0 otherwise. */
 DWCONV_API int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype);
 
 /* Number S of partial slices per coefficient stage 1 writes for this shape; 0 on bad arguments. */
