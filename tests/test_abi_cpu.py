@@ -143,9 +143,12 @@ def test_single_pass_query(lib):
     assert S256 == 2 * S226 and f(32, 256, 4096, 256, 255, 0) == 0
     assert f(2, 4, 1024, 300, 150, 0) == 0 and lib.dwconv_bwd_weight_slices(2, 4, 1024, 300, 150, 0) == 2
     assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 256, 255, 1) == S256
-    # bf16: up to four launches (up to 64 offsets), fp32 up to three (48); beyond, the long-filter kernel (two slices)
+    # bf16: up to four launches (up to 64 offsets), fp32 up to three (48); beyond, the long-filter kernel: two slices per
+    # batch slice (one batch slice where channels x offset groups already fill the chip, as on the benchmark shape)
     assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 994, 993, 1) == 2 * S256
-    assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 994, 993, 0) == 2
+    assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 994, 993, 0) == 4
+    assert lib.dwconv_bwd_weight_slices(8, 256, 8192, 8192, 8191, 0) == 2
+    assert lib.dwconv_bwd_weight_slices(1000, 1, 256, 700, 350, 0) == 250       # one channel: 125 batch slices of eight rows
     assert 2 * lib.dwconv_bwd_weight_slices(32, 256, 4096, 600, 599, 0) == 3 * S256
     # ... but not for rows that fill less than three quarters of their segments (long-filter kernel: two slices)
     assert lib.dwconv_bwd_weight_slices(64, 256, 512, 300, 150, 0) == 2 and f(64, 256, 512, 300, 150, 0) == 0
