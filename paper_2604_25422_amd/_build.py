@@ -23,7 +23,7 @@ OBJ_DIR = os.path.join(HERE, "_build")     # object files of the translation uni
 # s_waitcnt before the registers are read): a spill or scratch copy of such a register between the load and the
 # wait would read it before the data has arrived, so these kernels must not use scratch memory at all.
 UNTRACKED_PREFETCH_KERNELS = ("corr_mfma_kernel", "corr_mfma_bf16_kernel", "corr_rowbatch_kernel", "dw_rowbatch_kernel",
-                              "bwd_rowbatch_kernel")
+                              "bwd_rowbatch_kernel", "corr_rowtall_kernel", "dw_rowtall_kernel")
 VALIDATED_HIPCC = "7.2"       # ROCm release whose hipcc these kernels were checked with
 
 

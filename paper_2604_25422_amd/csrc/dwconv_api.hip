@@ -52,7 +52,7 @@ int check_shape(int B, int C, int L, int K, int pad, int dtype)
 RowsPlan plan_rows(const Shape &s)
 {
     RowsPlan r;
-    r.on = false; r.batch = false; r.units = 0; r.nvs = 0;
+    r.on = false; r.batch = false; r.tall = false; r.units = 0; r.nvs = 0;
     r.map = dwconv::RowsMap{0, 0, 0, 0, 0u, 0u};
     const int nd = toeplitz_dmax(s.K, s.pad) - toeplitz_dmin(s.pad) + 1;
     if (s.K < kMfmaMinK || nd < 2) return r;
@@ -85,6 +85,17 @@ RowsPlan plan_rows(const Shape &s)
     }
     if (batch) {
         r.on = true; r.batch = true;
+        r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
+    }
+    // Rows of nine to thirty-two blocks with more block offsets than the virtual-row kernels take (filters of the order
+    // of the row length): sixteen rows per tile with the filter window and the unit in LDS.
+    const int m = (s.L + 15) / 16;
+    // (bf16 up to twenty blocks: beyond, the long-filter kernels on the bf16 matrix instruction are faster - B1016 C128 L516
+    // K516 882 us per step there against 1389 us here at L = 512; fp32 2068 against 1373 us)
+    if (!batch && !vrows && (s.L % 4) == 0 && m >= dwconv::kRtMinBlocks &&
+        m <= (s.dtype == DWCONV_F32 ? dwconv::kRtMaxBlocks : 20) &&
+        (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30)) {
+        r.tall = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
     }
     return r;
@@ -341,6 +352,28 @@ DwPlan plan_dw(const Shape &s)
         p.items_per_slice = (int)((items + p.S - 1) / p.S);       // the generic kernel, if it has to run, uses the same slices
         p.valu_items_per_slice = (int)(((long long)s.B * p.valu_tiles_per_row + p.S - 1) / p.S);      // (of its own items: real rows)
     }
+    p.tall_windows = 0;
+    if (p.rows.tall) {
+        // windows of fifteen relative block offsets (grid z), each with S / windows slices over units of four rows: about two
+        // workgroups per compute unit
+        int bd, bn;
+        rows_batch_offsets(s.L, s.K, s.pad, &bd, &bn);
+        const long long nwin = (bn + dwconv::kRtWindow - 1) / dwconv::kRtWindow;
+        const long long units = (s.B + 3) / 4;
+        long long su = (2LL * kComputeUnits + (long long)s.C * nwin - 1) / ((long long)s.C * nwin);
+        const long long su_max = (units + dwconv::kRtWaves - 1) / dwconv::kRtWaves;
+        if (su > su_max) su = su_max;
+        if (su > 4096) su = 4096;
+        if (su < 1) su = 1;
+        p.tall_windows = (int)nwin;
+        p.longk = false; p.lk_table = nullptr; p.manypass = false; p.single = false; p.passes = 1;
+        p.wpb = dwconv::kRtWaves;
+        p.S = (int)(su * nwin);
+        p.S_fused = p.S;
+        p.tiles_per_row = (int)units;
+        p.items_per_slice = (int)((units + su - 1) / su);
+        p.valu_items_per_slice = (int)(((long long)s.B * p.valu_tiles_per_row + p.S - 1) / p.S);
+    }
     // the generic kernel on short rows: its items are the tiles of the virtual row of the channel
     p.valu_rows = plan_valu_rows(s);
     if (p.valu_rows.on) {
@@ -513,6 +546,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
     if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type
+    if (p.rows.tall) return 0;
     if (dtype == DWCONV_BF16 && p.rows.on) return 0;
     const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
                                                : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));

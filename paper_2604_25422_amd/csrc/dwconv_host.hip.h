@@ -20,6 +20,7 @@
 #include "dwconv_longk.hip.h"
 #include "dwconv_mfma.hip.h"
 #include "dwconv_rowbatch.hip.h"
+#include "dwconv_rowtall.hip.h"
 #include "dwconv_corr_direct.hip.h"
 
 namespace dwhost {
@@ -110,6 +111,8 @@ constexpr int kMfmaMaxL = 1 << 27;      // byte offsets inside a row stay below 
 struct RowsPlan {
     bool on;
     bool batch;             // rows of at most 128 positions: sixteen rows of a channel per matrix tile instead
+    bool tall;              // rows of 132 to 512 positions with more block offsets than the virtual-row kernels take: sixteen
+                            // rows per tile with filter and unit in LDS (dwconv_rowtall.hip.h); `on` stays false
     int units;              // batch: groups of sixteen rows per channel
     int nvs;                // 1024-position segments of the virtual row
     dwconv::RowsMap map;
@@ -213,6 +216,7 @@ struct DwPlan {
     DwKernel kernel;
     bool longk;            // shape fits the long-filter matrix-core kernel (two zero-filled slices)
     int lk_wgs, lk_gd;     // its workgroups per channel, largest group of offsets (accumulators per group)
+    int tall_windows;      // rows.tall: windows of fifteen relative block offsets (grid z), S / tall_windows slices each
     int lk_rs, lk_bper;    // its batch slices (each with two slices of partial sums of its own) and batch entries per slice
     std::shared_ptr<const dwconv::LongKDwTable> lk_table;   // which offsets every wave slot owns
     int S;                 // partial slices per coefficient (all passes together)
@@ -237,6 +241,11 @@ constexpr int kDwThreads = 256;
 DwPlan plan_dw(const Shape &s);
 
 // Launch entry points of the per-path units.  A return value of -1 (fused backward only) means "does not apply".
+// Rows of 132 to 512 positions with long filters (RowsPlan::tall; units of their own: dwconv_launch_rowtall_*.hip).
+int launch_corr_rowtall_f32(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st);
+int launch_corr_rowtall_bf16(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st);
+int launch_dw_rowtall_f32(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st);
+int launch_dw_rowtall_bf16(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, hipStream_t st);
 int launch_corr_f32(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st);
 int launch_corr_bf16(const void *in, const void *f, void *out, const Shape &s, int pad_eff, int reverse, hipStream_t st);
 int launch_dw_partial_f32(const void *x, const void *dy, float *part, void *dw_out, bool *wrote_dw, const Shape &s,

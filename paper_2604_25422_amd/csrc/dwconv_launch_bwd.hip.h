@@ -112,6 +112,7 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     *wrote_dw = false;
     if (p.longk) return -1;
     if (p.rows.batch) return launch_bwd_rowbatch<T>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
+    if (p.rows.tall) return -1;                              // (two launches)
     if (s.dtype == DWCONV_BF16 && p.rows.on) return -1;      // bf16 virtual rows: the two separate kernels
     // bf16: rows that start on a dword
     if (s.dtype == DWCONV_BF16 && (s.L % 2) != 0) return -1;

@@ -182,6 +182,11 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     const RowsPlan rp = plan_rows(s);
     // (the sixteen-row kernels of short rows move granules with buffer loads and stores that need dword alignment only)
     if (rp.batch) return (aligned_to(in, 4) && aligned_to(out, 4)) ? launch_corr_rowbatch<T>(in, f, out, s, pad_eff, reverse, rp, st) : -1;
+    if (rp.tall) {
+        if (!aligned_to(in, 4) || !aligned_to(out, 4)) return -1;
+        if constexpr (std::is_same<T, float>::value) return launch_corr_rowtall_f32(in, f, out, s, pad_eff, reverse, st);
+        else return launch_corr_rowtall_bf16(in, f, out, s, pad_eff, reverse, st);
+    }
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(in, 4 * sizeof(T)) && aligned_to(out, 4 * sizeof(T));

@@ -162,6 +162,11 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
     const int nd = dmax - dmin + 1;
     // (rows of at most 128 positions: the sixteen-row kernel needs rows that start on a dword, nothing more)
     if (p.rows.batch) return (aligned_to(x, 4) && aligned_to(dy, 4)) ? launch_dw_rowbatch<T>(x, dy, part, dw_out, s, p, st) : -1;
+    if (p.rows.tall) {
+        if (!aligned_to(x, 4) || !aligned_to(dy, 4)) return -1;
+        if constexpr (std::is_same<T, float>::value) return launch_dw_rowtall_f32(x, dy, part, s, p, st);
+        else return launch_dw_rowtall_bf16(x, dy, part, s, p, st);
+    }
     if (p.manypass) {
         if constexpr (std::is_same<T, float>::value) {
             if (!aligned_to(x, 16) || !aligned_to(dy, 16)) return -1;

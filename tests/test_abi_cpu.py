@@ -148,10 +148,10 @@ def test_single_pass_query(lib):
     assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 994, 993, 1) == 2 * S256
     assert lib.dwconv_bwd_weight_slices(32, 256, 4096, 994, 993, 0) == 4
     assert lib.dwconv_bwd_weight_slices(8, 256, 8192, 8192, 8191, 0) == 2
-    assert lib.dwconv_bwd_weight_slices(1000, 1, 256, 700, 350, 0) == 250       # one channel: 125 batch slices of eight rows
+    assert lib.dwconv_bwd_weight_slices(1000, 1, 1024, 2000, 1000, 0) == 250    # one channel: 125 batch slices of eight rows
     assert 2 * lib.dwconv_bwd_weight_slices(32, 256, 4096, 600, 599, 0) == 3 * S256
     # ... but not for rows that fill less than three quarters of their segments (long-filter kernel: two slices per batch slice)
-    assert lib.dwconv_bwd_weight_slices(64, 256, 512, 300, 150, 0) == 4 and f(64, 256, 512, 300, 150, 0) == 0
+    assert lib.dwconv_bwd_weight_slices(64, 256, 640, 300, 150, 0) == 4 and f(64, 256, 640, 300, 150, 0) == 0
     assert f(0, 256, 4096, 64, 63, 0) == 0           # bad shape
 
 

@@ -99,6 +99,11 @@ CLASSES = [
     (70, 256, 48, 48, 24), (300, 12, 200, 31, 15), (64, 2, 512, 64, 63), (50, 3, 132, 16, 15),
     # longer short rows (virtual rows) with seven to sixteen block offsets
     (20, 3, 256, 100, 99), (9, 2, 384, 160, 80), (6, 4, 512, 226, 0), (12, 256, 200, 130, 129), (7, 3, 640, 200, 100),
+    # rows of nine to thirty-two blocks with filters of the order of the row length: sixteen rows per tile, filter in LDS
+    (20, 3, 256, 256, 255), (9, 2, 512, 512, 256), (33, 4, 160, 160, 80), (5, 3, 384, 700, 350), (18, 2, 144, 1000, 999),
+    (7, 256, 192, 192, 191), (4, 2, 512, 2048, 1024), (70, 5, 132, 300, 0), (3, 2, 500, 500, 499),
+    # ... with batches long enough that every wave walks several units
+    (130, 256, 192, 192, 191), (70, 64, 256, 300, 150), (600, 8, 160, 160, 80),
     # ... filters as long as such rows or longer (only the block offsets inside a row count: up to fifteen)
     (40, 6, 96, 96, 48), (33, 3, 128, 128, 127), (20, 4, 128, 128, 64), (17, 2, 64, 100, 50), (50, 3, 112, 300, 150),
     (100, 2, 48, 1000, 500), (30, 256, 96, 96, 95), (9, 2, 16, 64, 0), (35, 4, 80, 80, 0), (18, 5, 128, 4000, 2000),
