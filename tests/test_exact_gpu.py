@@ -179,3 +179,21 @@ def _random_exact_shapes(n, seed):
 def test_exact_random_shapes(oracle_mod, B, C, L, K, p, dtype, offset):
     print(f"case exact random {dtype} B{B} C{C} L{L} K{K} p{p} offset {offset}", flush=True)
     run_exact(oracle_mod, B, C, L, K, p, dtype, seed=B + 3 * C + 5 * L + 7 * K + p, offset=offset)
+
+
+# Shapes large enough that every wave of the short-row kernels walks several units (or virtual segments): the loops that
+# prefetch the next unit while the current one is contracted only run there.
+SEVERAL_UNITS = [
+    (640, 256, 96, 96, 48),        # sixteen-row kernels, seven and more block offsets
+    (700, 256, 48, 48, 24),        # ... the paper's row length (two channels per wave)
+    (400, 256, 200, 130, 129),     # virtual rows, nine block offsets
+    (40, 256, 1027, 160, 80),      # ordinary rows that are not whole granules, eleven block offsets
+    (300, 256, 256, 256, 255),     # rows of sixteen blocks, filter in LDS
+]
+
+
+@pytest.mark.parametrize("B,C,L,K,p", SEVERAL_UNITS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_when_waves_walk_several_units(oracle_mod, dtype, B, C, L, K, p):
+    print(f"case exact several units {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    run_exact(oracle_mod, B, C, L, K, p, dtype, seed=3 + B + 3 * C + 5 * L + 7 * K)
