@@ -545,7 +545,9 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     const Shape s{B, C, L, K, pad_left, dtype};
     const DwPlan p = plan_dw(s);
     const int nd = toeplitz_dmax(K, pad_left) - toeplitz_dmin(pad_left) + 1;
-    if (p.rows.batch) return L <= dwconv::kRbBwdMaxL ? 1 : 0;      // sixteen rows per tile: either storage type
+    // sixteen rows per tile, either storage type (its workgroups own four neighbouring channels: with fewer, most of
+    // their waves would idle and the two separate kernels are faster - B416666 C1 L48 K33: 298 against 120 us)
+    if (p.rows.batch) return (L <= dwconv::kRbBwdMaxL && C >= dwconv::kRbBwdWaves) ? 1 : 0;
     if (p.rows.tall) return 0;
     if (dtype == DWCONV_BF16 && p.rows.on) return 0;
     const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))

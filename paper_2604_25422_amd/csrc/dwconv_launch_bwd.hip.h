@@ -64,7 +64,7 @@ int launch_bwd_rowbatch(const void *dy, const void *x, const void *w, void *dx, 
 {
     int dmin, nd;
     rows_batch_offsets(s.L, s.K, s.pad, &dmin, &nd);        // (rows of at most three blocks: at most five offsets)
-    if (s.L > dwconv::kRbBwdMaxL || nd < 2 || nd > kMfmaMaxND) return -1;
+    if (s.L > dwconv::kRbBwdMaxL || nd < 2 || nd > kMfmaMaxND || s.C < dwconv::kRbBwdWaves) return -1;
     if (!aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4)) return -1;      // (rows that start on a dword)
     void *direct_rb = p.S_fused == 1 ? dw_out : nullptr;
     auto launch_rb = [&](auto kernel, size_t lds_rb) -> int {
