@@ -71,7 +71,10 @@ RowsPlan plan_rows(const Shape &s)
     // Virtual rows (whole granules; up to six offsets, fp32 sixteen): where a 1024-position segment of a row would be more than a
     // quarter padding, and positions stay 32-bit.
     const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
-    const long long P = (s.L + 3) / 4 * 4 + (halo + 3) / 4 * 4;
+    // (pitch: whole granules of four; bf16 of eight, so that the kernels that load 16 bytes per lane apply to rows of whole
+    // 16-byte granules)
+    const long long gr = s.dtype == DWCONV_F32 ? 4 : 8;
+    const long long P = (s.L + 3) / 4 * 4 + (halo + gr - 1) / gr * gr + ((s.dtype != DWCONV_F32 && (s.L % 8) == 4) ? 4 : 0);
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
     const long long elems = (long long)s.B * s.C * s.L;
     const bool vrows = (s.L % 4) == 0 && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND) && 4 * padded > 5 * P && elems * es <= (1ll << 30) &&

@@ -196,10 +196,14 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 // conflict-free.  Loads of a segment in issue order: g0 g1 (512 positions each), gt (128-position tail, two positions
 // per lane); 256-position chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt; positions [0, 512) are dead
 // after chunk 1, the rest after chunk 3.
-template <int ND>
+// ROWS: short rows, the unit of work is a segment of the virtual row of a channel (see RowsMap; pitch and row length
+// multiples of 8, so that a 16-byte granule lies in one row or in one gap): the walk's "row" is the virtual segment, its
+// "segment" the channel (walk_segs = segs_per_row = C), every lane translates the position of its granule on the memory
+// side of the loads, and the outputs of a group of four go to their row or nowhere.
+template <int ND, bool ROWS = false>
 __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_direct_bf16_kernel(
     const bf16_t *__restrict__ in, const bf16_t *__restrict__ f, bf16_t *__restrict__ out, const CorrGeom g,
-    const RowsMap /* short rows are an fp32 path */)
+    const RowsMap rm)
 {
     static_assert(ND >= 2 && 16 * (ND - 1) <= 128, "window tail is one 128-element load");
     constexpr int XWE = kSegLen + 16 * (ND - 1);   // elements of the window that are ever read
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int wm = wg - g.n_light;
     int row = __builtin_amdgcn_readfirstlane(light ? wg : wm / g.walk_segs);                 // b * C + c
     int seg = __builtin_amdgcn_readfirstlane(light ? g.segs_per_row - 1 : wm % g.walk_segs);
-    int c = __builtin_amdgcn_readfirstlane(row % g.C);
+    int c = ROWS ? seg : __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
 
     const short *sg = s_in[wave];
@@ -254,8 +258,18 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 
     uintx4 rg;
     int g_shift;
+    int vg0 = 0;            // ROWS: virtual position of the first element of the window
     auto aim = [&](int prow, int pseg) {
-        if (prow < g.rows) {
+        if constexpr (ROWS) {
+            g_shift = 0;
+            if (prow < g.rows) {
+                vg0 = prow * kSegLen + 16 * g.dmin;
+                const unsigned long long a0 = reinterpret_cast<unsigned long long>(in + (size_t)pseg * (size_t)g.L);
+                rg = uintx4{(unsigned)a0, (unsigned)(a0 >> 32) & 0xffffu, rm.bytes - (unsigned)(pseg * g.L) * 2u, kBufferFlags};
+            } else {
+                rg = uintx4{0u, 0u, 0u, kBufferFlags};
+            }
+        } else if (prow < g.rows) {
             const int v0 = 2 * (pseg * kSegLen + 16 * g.dmin);
             g_shift = v0 < 0 ? v0 : 0;
             rg = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, v0 > 0 ? v0 : 0);
@@ -266,10 +280,16 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     };
     auto load_half = [&](auto hc) {
         constexpr int h = decltype(hc)::value;
-        buffer_load_x4_to_lds_keep(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
+        if constexpr (ROWS)
+            buffer_load_x4_to_lds_keep(rg, rows_byte_offset<2>(rm, vg0 + (off_g >> 1) + 512 * h), lds_g + 1024u * (unsigned)h);
+        else
+            buffer_load_x4_to_lds_keep(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
     };
     auto load_tail = [&]() {
-        buffer_load_x1_to_lds_keep(rg, off_gt == kOutOfRow ? kOutOfRow : off_gt + g_shift, lds_g + 2048u);
+        if constexpr (ROWS)
+            buffer_load_x1_to_lds_keep(rg, off_gt == kOutOfRow ? kOutOfRow : rows_byte_offset<2>(rm, vg0 + (off_gt >> 1)), lds_g + 2048u);
+        else
+            buffer_load_x1_to_lds_keep(rg, off_gt == kOutOfRow ? kOutOfRow : off_gt + g_shift, lds_g + 2048u);
     };
 
     aim(row, seg);
@@ -294,10 +314,12 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             c_n = c + g.step_c + carry;
             c_n -= c_n >= g.C ? g.C : 0;
             c_n -= c_n >= g.C ? g.C : 0;
+            if constexpr (ROWS) c_n = seg_n;
         }
-        bf16_t *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
-        const bool whole = (seg + 1) * kSegLen <= g.L;
-        const int t_seg = seg * kSegLen;
+        bf16_t *out_seg = ROWS ? out + (size_t)c * (size_t)g.L                         // (ROWS: the channel's first row)
+                               : out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+        const bool whole = ROWS ? false : (seg + 1) * kSegLen <= g.L;
+        const int t_seg = ROWS ? row * kSegLen : seg * kSegLen;
         aim(row_n, seg_n);
         if (c != cur_c) {
             load_filter(c);
@@ -309,7 +331,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             constexpr int need = c4 == 0 ? 0 : (c4 < 3 ? 1 : 2), issued = c4 >= 2 ? 1 : 0;
             wait_vmcnt_at_most<(2 - need) + issued>();
             // (a chunk wholly past the end of the row has no outputs: its matrix work is skipped)
-            const bool live = whole || t_seg + 256 * c4 < g.L;
+            const bool live = ROWS || whole || t_seg + 256 * c4 < g.L;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
             if (live) {
                 shortx4 bv[ND];
@@ -326,8 +348,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             }
             // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the chunk
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
-            if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
-            else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
+            if constexpr (ROWS) {
+                const int e = rows_element(rm, t_seg + lt);         // four outputs: one row or one gap
+                if (e >= 0) st_elem4_stream(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            } else {
+                if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
+            }
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;

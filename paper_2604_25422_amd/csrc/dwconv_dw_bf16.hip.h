@@ -35,10 +35,14 @@ constexpr size_t dw_bf16_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(
 // position of logical 16-block nb inside the staged windows
 __host__ __device__ constexpr int bf16_block_pos(int nb) { return (nb & ~3) | ((nb & 3) ^ ((nb >> 2) & 3)); }
 
-template <int ND, int W>
+// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap; pitch and row length multiples of 8, so
+// that a 16-byte granule lies in one row or in one gap); B is then 1 and segs_per_row the number of segments of the
+// virtual row.  Every lane translates the position of its granule on the memory side of the loads.
+template <int ND, int W, bool ROWS = false>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_kernel(
     const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy, float *__restrict__ part, bf16_t *__restrict__ dw_out,
-    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, int j0, int j1, int seg0, int own_only)
+    int B, int C, int L, int K, int pad, int dmin, int segs_per_row, int j0, int j1, int seg0, int own_only,
+    const RowsMap rm)
 {
     // seg0, own_only: as in dw_partial_direct_kernel (the first segment of every row this launch walks; write the
     // owned taps only)
@@ -99,8 +103,25 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
 
     uintx4 rx, rg;
     int x_shift;        // negative when the x window starts before the row: added to the lane offsets
+    int vx0 = 0, vg0 = 0;   // ROWS: virtual positions of the first elements of the two windows
     auto aim = [&](int pb, int pseg) {
-        if (pb < B) {
+        if constexpr (ROWS) {
+            x_shift = 0;
+            if (pb < B) {
+                // (virtual segments are walked downwards, like the batches below)
+                const int t0 = (segs_per_row - 1 - pseg) * kSegLen;
+                vx0 = t0 + 16 * dmin;
+                vg0 = t0;
+                const unsigned nbytes = rm.bytes - (unsigned)(c * L) * 2u;
+                const unsigned long long ax0 = reinterpret_cast<unsigned long long>(x + (size_t)c * (size_t)L);
+                const unsigned long long ag0 = reinterpret_cast<unsigned long long>(dy + (size_t)c * (size_t)L);
+                rx = uintx4{(unsigned)ax0, (unsigned)(ax0 >> 32) & 0xffffu, nbytes, kBufferFlags};
+                rg = uintx4{(unsigned)ag0, (unsigned)(ag0 >> 32) & 0xffffu, nbytes, kBufferFlags};
+            } else {
+                rx = uintx4{0u, 0u, 0u, kBufferFlags};
+                rg = rx;
+            }
+        } else if (pb < B) {
             // batches are walked from the last to the first (the rows the input-gradient call touched last are
             // still in the last-level cache)
             const size_t row = ((size_t)(B - 1 - pb) * (size_t)C + (size_t)c) * (size_t)L;
@@ -118,12 +139,22 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     };
     auto load_half = [&](auto hc) {         // x_h then g_h
         constexpr int h = decltype(hc)::value;
-        buffer_load_x4_to_lds(rx, off_main + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
-        buffer_load_x4_to_lds(rg, off_main + 1024 * h, lds_g + 1024u * (unsigned)h);
+        if constexpr (ROWS) {
+            const int e = (off_main >> 1) + 512 * h;        // the lane's granule: elements e .. e + 7 of the windows
+            buffer_load_x4_to_lds(rx, rows_byte_offset<2>(rm, vx0 + e), lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rg, rows_byte_offset<2>(rm, vg0 + e), lds_g + 1024u * (unsigned)h);
+        } else {
+            buffer_load_x4_to_lds(rx, off_main + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rg, off_main + 1024 * h, lds_g + 1024u * (unsigned)h);
+        }
+    };
+    auto tail_offset = [&](int t) {
+        if constexpr (ROWS) return off_tail[t] == kOutOfRow ? kOutOfRow : rows_byte_offset<2>(rm, vx0 + (off_tail[t] >> 1));
+        else return off_tail[t] + x_shift;
     };
     auto load_tail = [&]() {
-        buffer_load_x1_to_lds(rx, off_tail[0] + x_shift, lds_x + 2048u);
-        if constexpr (NT > 1) buffer_load_x1_to_lds(rx, off_tail[NT - 1] + x_shift, lds_x + 2048u + 256u);
+        buffer_load_x1_to_lds(rx, tail_offset(0), lds_x + 2048u);
+        if constexpr (NT > 1) buffer_load_x1_to_lds(rx, tail_offset(NT - 1), lds_x + 2048u + 256u);
     };
 
     aim(b, seg);

@@ -110,6 +110,17 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                                static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map,
                                0, s.K, 0, 0);
         }
+    } else if (p.rows.on && (s.L % 8) == 0 && (p.rows.map.P % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
+        // bf16 short rows of whole 16-byte granules: the virtual row of a channel on the bf16 matrix instruction, raw rows
+        // straight into LDS (B4096 C128 L200 K48: 247 -> 88 us against the widening kernel below)
+        auto kernel = dwconv::dw_partial_bf16_kernel<ND, W, true>;
+        constexpr size_t lds = dwconv::dw_bf16_lds_bytes(ND, W);
+        static_assert(lds <= kMaxLdsBytes, "LDS budget");
+        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                           static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part,
+                           static_cast<bf16_t *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, 0, s.K, 0, 0,
+                           p.rows.map);
     } else if (p.rows.on) {
         // bf16 short rows (longer than 64 positions): the virtual row of a channel, widened to fp32 through registers
         auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W, true>;
@@ -127,7 +138,8 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
         if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
         hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
                            static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part,
-                           static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, 0, s.K, 0, 0);
+                           static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, 0, s.K, 0, 0,
+                           dwconv::RowsMap{0, 0, 0, 0, 0u, 0u});
     } else {
         auto kernel = dwconv::dw_partial_mfma_kernel<T, ND, W, false>;
         constexpr size_t lds = dwconv::dw_mfma_lds_bytes(ND, W);

@@ -26,7 +26,7 @@ int launch_dw_partial_wide_bf16_nd(const void *x, const void *dy, float *part, v
     if (slices < 0) slices = p.S / p.passes;
     hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)slices), dim3(64 * W), lds, st,
                        static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dy), part, static_cast<bf16_t *>(dw_out),
-                       s.B, s.C, s.L, s.K, s.pad, dmin, nseg, j0, j1, seg0, own_only);
+                       s.B, s.C, s.L, s.K, s.pad, dmin, nseg, j0, j1, seg0, own_only, dwconv::RowsMap{0, 0, 0, 0, 0u, 0u});
     return launch_status();
 }
 

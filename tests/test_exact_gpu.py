@@ -187,6 +187,7 @@ SEVERAL_UNITS = [
     (640, 256, 96, 96, 48),        # sixteen-row kernels, seven and more block offsets
     (700, 256, 48, 48, 24),        # ... the paper's row length (two channels per wave)
     (400, 256, 200, 130, 129),     # virtual rows, nine block offsets
+    (400, 256, 200, 48, 24),       # virtual rows, five block offsets (bf16: raw rows straight into LDS)
     (40, 256, 1027, 160, 80),      # ordinary rows that are not whole granules, eleven block offsets
     (300, 256, 256, 256, 255),     # rows of sixteen blocks, filter in LDS
 ]
