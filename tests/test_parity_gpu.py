@@ -309,7 +309,9 @@ def test_random_shapes(oracle_mod, B, C, L, K, p, dtype):
 
 
 @pytest.mark.parametrize("B,C,L,K,p,dtype", [(4, 64, 1024, 16, 15, "f32"), (3, 5, 96, 48, 24, "f32"),
-                                              (2, 3, 512, 300, 299, "f32"), (4, 6, 1024, 32, 31, "bf16")])
+                                              (2, 3, 512, 300, 299, "f32"), (4, 6, 1024, 32, 31, "bf16"),
+                                              (6, 8, 256, 256, 255, "f32"), (40, 8, 96, 96, 48, "bf16"),
+                                              (3, 2, 1024, 2000, 1000, "f32"), (9, 4, 200, 48, 24, "bf16")])
 def test_calls_can_be_captured_in_a_graph(B, C, L, K, p, dtype):
     """Every entry point only enqueues kernels (no allocation, no synchronisation, no memset nodes), so a step can
     be captured once and replayed; replays, with eager work in between, give the bits of the eager calls."""
