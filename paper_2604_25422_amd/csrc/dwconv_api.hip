@@ -406,6 +406,13 @@ template <typename T>
 int launch_dw_finalize(const float *part, void *dw, const Shape &s, const DwPlan &p, hipStream_t st)
 {
     const size_t CK = (size_t)s.C * (size_t)s.K;
+    if (p.S >= 32 && CK <= 16 * 2048) {
+        // many slices of few coefficients: the slices in parallel (same order of the sum)
+        const size_t nb = (CK + 15) / 16;
+        hipLaunchKernelGGL((dwconv::dw_finalize_many_kernel<T>), dim3((unsigned)nb), dim3(256), 0, st, part,
+                           static_cast<T *>(dw), p.S, CK);
+        return launch_status();
+    }
     const size_t blocks = (CK + 255) / 256;
     if (blocks > 0x7fffffffull) return DWCONV_ERR_SHAPE;
     hipLaunchKernelGGL((dwconv::dw_finalize_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, st, part,

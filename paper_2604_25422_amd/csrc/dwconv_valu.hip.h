@@ -223,4 +223,37 @@ __global__ __launch_bounds__(256) void dw_finalize_kernel(const float *__restric
     st_elem(dw + i, sum);
 }
 
+// The same sum, in the same order, for many slices of few coefficients (few channels: the slices are what fills the
+// chip in stage 1).  One thread per coefficient would wait a memory round trip for every four slices (B6666 C1 L3000 K7,
+// 1000 slices: 61 us); here 256 threads bring 128 slices of sixteen coefficients into LDS at a time, and the threads
+// that own the coefficients add them in slice order.
+template <typename T>
+__global__ __launch_bounds__(256) void dw_finalize_many_kernel(const float *__restrict__ part, T *__restrict__ dw, int S,
+                                                               size_t CK)
+{
+    constexpr int NI = 16, TS = 16, U = 8, SB = TS * U;
+    __shared__ float buf[SB][NI + 1];
+    const int ti = threadIdx.x % NI, ts = threadIdx.x / NI;
+    const size_t i = (size_t)blockIdx.x * NI + ti;
+    const bool ok = i < CK;
+    float sum = 0.f;
+    for (int s0 = 0; s0 < S; s0 += SB) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int sl = s0 + ts + TS * u;
+            v[u] = (ok && sl < S) ? part[(size_t)sl * CK + i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) buf[ts + TS * u][ti] = v[u];
+        __syncthreads();
+        if (ts == 0) {
+            const int n = S - s0 < SB ? S - s0 : SB;
+            for (int k = 0; k < n; ++k) sum += buf[k][ti];
+        }
+        __syncthreads();
+    }
+    if (ts == 0 && ok) st_elem(dw + i, sum);
+}
+
 }  // namespace dwconv
