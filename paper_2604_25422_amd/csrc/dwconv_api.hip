@@ -77,7 +77,11 @@ RowsPlan plan_rows(const Shape &s)
     const long long P = (s.L + 3) / 4 * 4 + (halo + gr - 1) / gr * gr + ((s.dtype != DWCONV_F32 && (s.L % 8) == 4) ? 4 : 0);
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
     const long long elems = (long long)s.B * s.C * s.L;
-    const bool vrows = (s.L % 4) == 0 && nd <= (s.dtype == DWCONV_F32 ? kMfmaMaxNDDw : kMfmaMaxND) && 4 * padded > 5 * P && elems * es <= (1ll << 30) &&
+    // (seven to sixteen offsets, fp32: only while the gaps stay below half a row - with a filter as long as the row half of
+    // the virtual row is gap, and the tall-row kernels below do better: B3200 C128 L160 K160 fwd 354 us here)
+    const bool vrows = (s.L % 4) == 0 &&
+                       (nd <= kMfmaMaxND || (s.dtype == DWCONV_F32 && nd <= kMfmaMaxNDDw && 2 * P <= 3 * (long long)s.L)) &&
+                       4 * padded > 5 * P && elems * es <= (1ll << 30) &&
                        (long long)s.B * P * P < (1ll << 32) && (long long)s.B * P < (1ll << 31);
     if (vrows) {
         r.on = true;
