@@ -1,92 +1,9 @@
-// Weight-gradient stage-1 kernels, fp32, filters of 67 to 226 taps (a unit of its own: these are the largest
-// fully unrolled kernels of the library).
-#include "dwconv_host.hip.h"
+// Weight-gradient stage 1, fp32, filters of 67 taps and more on the register-resident kernel: one launch (seven to sixteen
+// block offsets), two or three (up to forty-eight), or the many-launch form (beyond what the long-filter kernel's LDS holds).
+// The kernels themselves are compiled in dwconv_launch_dw_f32_wide_{w4,multi,rows}.hip.
+#include "dwconv_launch_dw_wide.hip.h"
 
 namespace dwhost {
-
-// fp32, seven to sixteen block offsets (K up to 226): the LDS-direct kernel on ordinary rows.
-// seg0 / nseg: the segments of every row the launch walks; slices: workgroups per channel; own_only: write the
-// taps the launch owns and nothing else (see dw_partial_direct_kernel).
-template <int ND, int W>
-int launch_dw_partial_wide_ndw(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
-                               int dmin, hipStream_t st, int seg0 = 0, int nseg = -1, int slices = -1, int own_only = 0)
-{
-    constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
-    if constexpr (lds > kMaxLdsBytes) {
-        return -1;
-    } else {
-        auto kernel = dwconv::dw_partial_direct_kernel<ND, W, false>;
-        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-        // the taps this launch owns: those its ND offsets can reach (all K of them when they cover the filter)
-        int j0 = 16 * dmin + s.pad - 15, j1 = 16 * (dmin + ND - 1) + s.pad + 16;
-        j0 = j0 < 0 ? 0 : (j0 > s.K ? s.K : j0);
-        j1 = j1 < j0 ? j0 : (j1 > s.K ? s.K : j1);
-        if (j1 - j0 > dwconv::dw_direct_row_floats(ND)) return -1;
-        if (nseg < 0) nseg = p.tiles_per_row;
-        if (slices < 0) slices = p.S / p.passes;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)slices), dim3(64 * W), lds, st,
-                           static_cast<const float *>(x), static_cast<const float *>(dy), part,
-                           static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, nseg, p.rows.map, j0, j1, seg0,
-                           own_only);
-        return launch_status();
-    }
-}
-// Short rows: the same kernel on the virtual row of a channel (four-wave workgroups, the filter's offsets in one launch).
-template <int ND>
-int launch_dw_partial_wide_rows(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
-                                int dmin, hipStream_t st)
-{
-    constexpr int W = 4;
-    constexpr size_t lds = dwconv::dw_direct_lds_bytes(ND, W);
-    if constexpr (lds > kMaxLdsBytes) {
-        return -1;
-    } else {
-        if (p.wpb != W || p.passes != 1) return -1;
-        auto kernel = dwconv::dw_partial_direct_kernel<ND, W, true>;
-        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st, static_cast<const float *>(x),
-                           static_cast<const float *>(dy), part, static_cast<float *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin,
-                           p.tiles_per_row, p.rows.map, 0, s.K, 0, 0);
-        return launch_status();
-    }
-}
-
-template <int ND>
-int launch_dw_partial_wide_nd(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
-                              int dmin, hipStream_t st)
-{
-    if (p.rows.on) return launch_dw_partial_wide_rows<ND>(x, dy, part, dw_out, s, p, dmin, st);
-    if constexpr (ND > kMfmaMaxNDWide) {
-        // eleven to sixteen block offsets: four-wave workgroups only (the plan never asks for more)
-        return p.wpb == 4 ? launch_dw_partial_wide_ndw<ND, 4>(x, dy, part, dw_out, s, p, dmin, st) : -1;
-    } else {
-        switch (p.wpb) {
-        case 4: return launch_dw_partial_wide_ndw<ND, 4>(x, dy, part, dw_out, s, p, dmin, st);
-        case 5: return launch_dw_partial_wide_ndw<ND, 5>(x, dy, part, dw_out, s, p, dmin, st);
-        case 8: return launch_dw_partial_wide_ndw<ND, 8>(x, dy, part, dw_out, s, p, dmin, st);
-        case 16: return launch_dw_partial_wide_ndw<ND, 16>(x, dy, part, dw_out, s, p, dmin, st);
-        default: return -1;
-        }
-    }
-}
-
-// One launch of the many-pass form: n (nine to sixteen) offsets from d_lo, segments [seg0, seg0 + nseg) of every row.
-int launch_dw_manypass_one(const void *x, const void *dy, float *part, const Shape &s, const DwPlan &p, int d_lo, int n,
-                           int seg0, int nseg, hipStream_t st)
-{
-    const int sl = p.S / 2;
-    switch (n) {
-    case 9: return launch_dw_partial_wide_ndw<9, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 10: return launch_dw_partial_wide_ndw<10, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 11: return launch_dw_partial_wide_ndw<11, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 12: return launch_dw_partial_wide_ndw<12, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 13: return launch_dw_partial_wide_ndw<13, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 14: return launch_dw_partial_wide_ndw<14, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 15: return launch_dw_partial_wide_ndw<15, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    case 16: return launch_dw_partial_wide_ndw<16, 4>(x, dy, part, nullptr, s, p, d_lo, st, seg0, nseg, sl, 1);
-    default: return -1;
-    }
-}
 
 int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void *dw_out, const Shape &s, const DwPlan &p,
                                int dmin, int nd, hipStream_t st)
@@ -114,8 +31,9 @@ int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void 
             long long seg_hi = hi < 0 ? -1 : hi / 1024;
             if (seg_hi > segs - 1) seg_hi = segs - 1;
             if (seg_lo > seg_hi) continue;                              // its taps stay zero
-            const int rc = launch_dw_manypass_one(x, dy, part + (size_t)(i & 1) * set_floats, s, p, d_lo, n, (int)seg_lo,
-                                                  (int)(seg_hi - seg_lo + 1), st);
+            // (one launch of the many-launch form: n offsets from d_lo, these segments of every row, the owned taps only)
+            const int rc = launch_dw_wide_w4_f32(n, x, dy, part + (size_t)(i & 1) * set_floats, nullptr, s, p, d_lo, st, (int)seg_lo,
+                                                 (int)(seg_hi - seg_lo + 1), sl, 1);
             if (rc != DWCONV_OK) return rc == -1 ? DWCONV_ERR_LAUNCH : rc;
         }
         return launch_status();
@@ -135,19 +53,10 @@ int launch_dw_partial_wide_f32(const void *x, const void *dy, float *part, void 
         }
         return DWCONV_OK;
     }
-    switch (nd) {
-    case 7: return launch_dw_partial_wide_nd<7>(x, dy, part, dw_out, s, p, dmin, st);
-    case 8: return launch_dw_partial_wide_nd<8>(x, dy, part, dw_out, s, p, dmin, st);
-    case 9: return launch_dw_partial_wide_nd<9>(x, dy, part, dw_out, s, p, dmin, st);
-    case 10: return launch_dw_partial_wide_nd<10>(x, dy, part, dw_out, s, p, dmin, st);
-    case 11: return launch_dw_partial_wide_nd<11>(x, dy, part, dw_out, s, p, dmin, st);
-    case 12: return launch_dw_partial_wide_nd<12>(x, dy, part, dw_out, s, p, dmin, st);
-    case 13: return launch_dw_partial_wide_nd<13>(x, dy, part, dw_out, s, p, dmin, st);
-    case 14: return launch_dw_partial_wide_nd<14>(x, dy, part, dw_out, s, p, dmin, st);
-    case 15: return launch_dw_partial_wide_nd<15>(x, dy, part, dw_out, s, p, dmin, st);
-    case 16: return launch_dw_partial_wide_nd<16>(x, dy, part, dw_out, s, p, dmin, st);
-    default: return -1;
-    }
+    if (nd < 7 || nd > kMfmaMaxNDDw) return -1;
+    if (p.rows.on) return launch_dw_wide_rows_f32(nd, x, dy, part, dw_out, s, p, dmin, st);
+    if (p.wpb == 4) return launch_dw_wide_w4_f32(nd, x, dy, part, dw_out, s, p, dmin, st, 0, -1, -1, 0);
+    return launch_dw_wide_multi_f32(nd, x, dy, part, dw_out, s, p, dmin, st);
 }
 
 }  // namespace dwhost
