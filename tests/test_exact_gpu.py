@@ -198,3 +198,29 @@ SEVERAL_UNITS = [
 def test_exact_when_waves_walk_several_units(oracle_mod, dtype, B, C, L, K, p):
     print(f"case exact several units {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
     run_exact(oracle_mod, B, C, L, K, p, dtype, seed=3 + B + 3 * C + 5 * L + 7 * K)
+
+
+def _random_large_shapes(n, seed):
+    """Seeded shapes of 3 to 25 million elements: every wave walks several units, segments or virtual segments."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([1, 3, 7, 16, 33, 48, 64, 66, 100, 128, 160, 226, 256, 300]))
+        L = int(rng.choice([16, 48, 50, 64, 96, 100, 128, 130, 160, 200, 256, 320, 384, 500, 512, 516, 768, 1000, 1024, 1026,
+                            2048, 4096, 4098, 8192]))
+        C = int(rng.choice([4, 16, 64, 128, 256, 257, 512, 768]))
+        B = int(rng.choice([2, 8, 32, 100, 256, 700, 2000]))
+        N = B * C * L
+        if N < 3e6 or N > 2.5e7 or N * min(K, L) > 2.5e9 or 9 * B * L >= 2 ** 24:
+            continue
+        p = int(rng.choice([0, K // 2, K - 1]))
+        out.append((B, C, L, K, p, "bf16" if rng.random() < 0.4 else "f32"))
+    return out
+
+
+# (1200 such shapes over two other seeds have been run as a one-off soak: DWCONV_LARGE_SWEEP_N / _SEED)
+@pytest.mark.parametrize("B,C,L,K,p,dtype", _random_large_shapes(int(os.environ.get("DWCONV_LARGE_SWEEP_N", "40")),
+                                                                 int(os.environ.get("DWCONV_LARGE_SWEEP_SEED", "20260425"))))
+def test_exact_random_large_shapes(oracle_mod, B, C, L, K, p, dtype):
+    print(f"case exact random large {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
+    run_exact(oracle_mod, B, C, L, K, p, dtype, seed=B + 3 * C + 5 * L + 7 * K + p)
