@@ -99,7 +99,10 @@ RowsPlan plan_rows(const Shape &s)
     const int m = (s.L + 15) / 16;
     // (bf16 up to twenty blocks: beyond, the long-filter kernels on the bf16 matrix instruction are faster - B1016 C128 L516
     // K516 882 us per step there against 1389 us here at L = 512; fp32 2068 against 1373 us)
-    if (!batch && !vrows && (s.L % 4) == 0 && m >= dwconv::kRtMinBlocks &&
+    // (rows that are not whole granules: they must start on a dword - any fp32 length, bf16 even lengths)
+    const bool tall_rag = (s.L % 4) != 0 && nd > kMfmaMaxND && (s.dtype == DWCONV_F32 || (s.L % 2) == 0);      // (up to six offsets:
+                                                                     // the kernels that load rows straight into LDS)
+    if (!batch && !vrows && ((s.L % 4) == 0 || tall_rag) && s.L > dwconv::kRbMaxL && m >= dwconv::kRtMinBlocks &&
         m <= (s.dtype == DWCONV_F32 ? dwconv::kRtMaxBlocks : 20) &&
         (long long)dwconv::kRbRows * s.C * s.L * es < (1ll << 30)) {
         r.tall = true;

@@ -16,7 +16,7 @@ dwconv::RowTallGeom rowtall_geom(const Shape &s, int pad, int reverse)
     g.dmin = dmin; g.dmax = dmin + nd - 1;
     g.m = (s.L + 15) / 16;
     g.n_units = 0; g.J = 0; g.win = 0;
-    g.lg_recip = (unsigned)((1ull << 32) / (unsigned long long)(s.L / 4)) + 1u;
+    g.lg_recip = (unsigned)((1ull << 32) / (unsigned long long)((s.L + 3) / 4)) + 1u;
     return g;
 }
 

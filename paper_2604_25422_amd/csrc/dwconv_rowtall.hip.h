@@ -1,5 +1,7 @@
-// Rows of 132 to 512 positions with filters of the order of the row length, sixteen rows at a time (fp32, or bf16
-// storage widened to fp32 on the way into LDS; L % 4 == 0).
+// Rows of 129 to 512 positions with filters of the order of the row length, sixteen rows at a time (fp32, or bf16
+// storage widened to fp32 on the way into LDS).  Rows need to start on a dword only (bf16: even L): a last granule of
+// four that holds elements of the next row gets zeros in their place on the way into LDS, and the last group of
+// outputs of such a row is stored by element (see dwconv_rowbatch.hip.h).
 //
 // The sixteen-row formulation of dwconv_rowbatch.hip.h (Sec. IV-A eqs. (dwconv), (dk_def): the sixteen columns of a
 // matrix tile are sixteen ROWS (b, c) of one channel at the same block position, and only block pairs inside the row
@@ -32,7 +34,7 @@ struct RowTallGeom {
     int n_units;        // correlate: ceil(B / 16); weight gradient: ceil(B / 4)
     int J;              // correlate: waves per channel, wave (c, j) walks units j, j + J, ...
     int win;            // weight gradient: relative block offsets per window (at most kRtWindow; the windows are of equal size)
-    unsigned lg_recip;  // floor(2^32 / (L / 4)) + 1: granule index -> (row of the unit, granule of the row)
+    unsigned lg_recip;  // floor(2^32 / ceil(L / 4)) + 1: granule index -> (row of the unit, granule of the row)
 };
 
 __host__ __device__ constexpr int rt_corr_pitch(int m) { return 16 * m + 4; }
@@ -80,7 +82,8 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void corr_rowtall_kernel(const T 
     wave_lds_fence();
 
     const int CL = g.C * g.L;
-    const int Lg = g.L >> 2;                    // granules per row
+    const int Lg = (g.L + 3) >> 2;              // granules per row (the last one partial when L % 4 != 0)
+    const int rem_last = g.L & 3;
     const int NG = kRbRows * Lg;                // granules per unit
     const float *a_lane = fw + 16 * (g.m - 1) + 4 * k4 - i16 + 15;
     const float *sp = sw + i16 * Lo + 4 * k4;
@@ -103,14 +106,15 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void corr_rowtall_kernel(const T 
                     const int gi = g0 + 64 * i + lane;
                     const int row = (int)__umulhi((unsigned)gi, g.lg_recip);
                     const int cg = gi - row * Lg;
-                    idx[i] = gi < NG ? row * Lo + 4 * cg : -1;
+                    // (low bits of idx: elements of a partial last granule, as in the sixteen-row kernels)
+                    idx[i] = gi < NG ? ((row * Lo + 4 * cg) | (cg == Lg - 1 ? rem_last : 0)) : -1;
                     pre[i] = Raw4<T>::load(r, gi < NG ? ES * (row * CL + 4 * cg) : kOutOfRow);
                 }
                 wait_untracked_loads();
                 release_after_wait(pre);
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    if (idx[i] >= 0) *reinterpret_cast<float4 *>(sw + idx[i]) = Raw4<T>::widen(pre[i]);
+                    if (idx[i] >= 0) *reinterpret_cast<float4 *>(sw + (idx[i] & ~3)) = rb_granule<T>(pre[i], idx[i] & 3);
             }
         }
         wave_lds_fence();
@@ -150,8 +154,8 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void corr_rowtall_kernel(const T 
                 if (mi <= mi_hi) mf(A0, B0, acc);
                 acc += acc2;
             }
-            if (row_ok && 16 * mo + 4 * k4 < g.L)
-                st_elem4_stream(out_lane + 16 * mo, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            if (row_ok)
+                st_elem4_stream_upto(out_lane + 16 * mo, make_float4(acc[0], acc[1], acc[2], acc[3]), 16 * mo + 4 * k4, g.L);
         }
         wave_lds_fence();       // (the image is rewritten by the next unit's loads)
     }
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void dw_rowtall_kernel(const T *_
     wave_lds_fence();
 
     const int CL = g.C * g.L;
-    const int Lg = g.L >> 2;
+    const int Lg = (g.L + 3) >> 2;              // (the last granule of a row partial when L % 4 != 0)
     const int NG = RU * Lg;                     // granules of a unit, per tensor
     const int nld = (NG + 63) >> 6;             // loads per lane (wave-uniform)
     int gl_off[NLD], idx[NLD];
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void dw_rowtall_kernel(const T *_
         const int row = (int)__umulhi((unsigned)gi, g.lg_recip);
         const int cg = gi - row * Lg;
         gl_off[i] = gi < NG ? ES * (row * CL + 4 * cg) : kOutOfRow;
-        idx[i] = gi < NG ? row * Lp + 4 * cg : -1;
+        idx[i] = gi < NG ? ((row * Lp + 4 * cg) | (cg == Lg - 1 ? (g.L & 3) : 0)) : -1;      // (low bits: see corr_rowtall_kernel)
     }
     const int stride = (int)gridDim.y * kRtWaves;
     int unit = (int)blockIdx.y * kRtWaves + wave;
@@ -245,8 +249,8 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void dw_rowtall_kernel(const T *_
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (i < nld && idx[i] >= 0) {
-                *reinterpret_cast<float4 *>(sx + idx[i]) = Raw4<T>::widen(px[i]);
-                *reinterpret_cast<float4 *>(sg + idx[i]) = Raw4<T>::widen(pg[i]);
+                *reinterpret_cast<float4 *>(sx + (idx[i] & ~3)) = rb_granule<T>(px[i], idx[i] & 3);
+                *reinterpret_cast<float4 *>(sg + (idx[i] & ~3)) = rb_granule<T>(pg[i], idx[i] & 3);
             }
     };
     const float *xrow = sx + k4 * Lp + i16;     // lane (q' = i16, row k4): x[row][16 mi + q']

@@ -102,6 +102,8 @@ CLASSES = [
     # rows of nine to thirty-two blocks with filters of the order of the row length: sixteen rows per tile, filter in LDS
     (20, 3, 256, 256, 255), (9, 2, 512, 512, 256), (33, 4, 160, 160, 80), (5, 3, 384, 700, 350), (18, 2, 144, 1000, 999),
     (7, 256, 192, 192, 191), (4, 2, 512, 2048, 1024), (70, 5, 132, 300, 0), (3, 2, 500, 500, 499),
+    # ... rows that are not whole granules of four
+    (33, 4, 130, 100, 0), (20, 3, 257, 256, 255), (9, 2, 510, 512, 256), (18, 2, 150, 1000, 999), (40, 5, 203, 130, 64),
     # ... with batches long enough that every wave walks several units
     (130, 256, 192, 192, 191), (70, 64, 256, 300, 150), (600, 8, 160, 160, 80),
     # ... filters as long as such rows or longer (only the block offsets inside a row count: up to fifteen)
