@@ -124,36 +124,25 @@ __global__ __launch_bounds__(64 * kRtWaves, 2) void corr_rowtall_kernel(const T 
         for (int mo = 0; mo < g.m; ++mo) {
             const int mi_lo = mo + g.dmin > 0 ? mo + g.dmin : 0;
             const int mi_hi = mo + g.dmax < g.m - 1 ? mo + g.dmax : g.m - 1;
-            // Two chains of dependent matrix instructions (even and odd input blocks, added at the end), and the LDS
-            // operands of the next block pair are read before the matrix instructions of the current one are issued
-            // (reads past the last pair are clamped to it: harmless, and no branch inside the loop).
+            // (two chains of dependent matrix instructions, even and odd input blocks, added at the end; reading the next
+            // pair's operands ahead by hand, or advancing the addresses by pointer increments, measured no faster)
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
-            auto ld = [&](int mi, float (&a)[4], float4 &b) {
+            auto pair = [&](int mi, floatx4 &a) {
                 const float *ap = a_lane + 16 * (mi - mo);
-                a[0] = ap[0]; a[1] = ap[1]; a[2] = ap[2]; a[3] = ap[3];
-                b = *reinterpret_cast<const float4 *>(sp + 16 * mi);
+                const float a0 = ap[0], a1 = ap[1], a2 = ap[2], a3 = ap[3];
+                const float4 cur = *reinterpret_cast<const float4 *>(sp + 16 * mi);
+                a = mfma16x16x4(a0, cur.x, a);
+                a = mfma16x16x4(a1, cur.y, a);
+                a = mfma16x16x4(a2, cur.z, a);
+                a = mfma16x16x4(a3, cur.w, a);
             };
-            auto mf = [&](const float (&a)[4], const float4 &b, floatx4 &d) {
-                d = mfma16x16x4(a[0], b.x, d);
-                d = mfma16x16x4(a[1], b.y, d);
-                d = mfma16x16x4(a[2], b.z, d);
-                d = mfma16x16x4(a[3], b.w, d);
-            };
-            if (mi_lo <= mi_hi) {
-                float A0[4], A1[4];
-                float4 B0, B1;
-                int mi = mi_lo;
-                ld(mi, A0, B0);
-                while (mi + 1 <= mi_hi) {
-                    ld(mi + 1, A1, B1);
-                    mf(A0, B0, acc);
-                    ld(mi + 2 <= mi_hi ? mi + 2 : mi_hi, A0, B0);
-                    mf(A1, B1, acc2);
-                    mi += 2;
-                }
-                if (mi <= mi_hi) mf(A0, B0, acc);
-                acc += acc2;
+            int mi = mi_lo;
+            for (; mi + 1 <= mi_hi; mi += 2) {
+                pair(mi, acc);
+                pair(mi + 1, acc2);
             }
+            if (mi <= mi_hi) pair(mi, acc);
+            acc += acc2;
             if (row_ok)
                 st_elem4_stream_upto(out_lane + 16 * mo, make_float4(acc[0], acc[1], acc[2], acc[3]), 16 * mo + 4 * k4, g.L);
         }
