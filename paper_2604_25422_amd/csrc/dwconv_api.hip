@@ -566,7 +566,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     // their waves would idle and the two separate kernels are faster - B416666 C1 L48 K33: 298 against 120 us)
     if (p.rows.batch) return (L <= dwconv::kRbBwdMaxL && C >= dwconv::kRbBwdWaves) ? 1 : 0;
     if (p.rows.tall) return 0;
-    if (dtype == DWCONV_BF16 && p.rows.on) return 0;
+    if (dtype == DWCONV_BF16 && p.rows.on && ((L % 8) != 0 || (p.rows.map.P % 8) != 0)) return 0;
     const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
                                                : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && rows_fit && L <= kMfmaMaxL) ? 1 : 0;

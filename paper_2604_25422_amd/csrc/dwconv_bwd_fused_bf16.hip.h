@@ -16,6 +16,11 @@
 // A segment is four 256-position chunks: chunk c4 = dX tile c4, then dW chunk c4.  Elements [0, 512) of both
 // windows are dead after chunk 1, the rest after chunk 3; loads of a segment in issue order: x0 g0 x1 g1 xt gt
 // (xt, gt: 128-element tails, two elements per lane).  Needs L % 8 == 0 and 16-byte aligned tensors.
+//
+// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap; pitch and row length multiples of 8, so
+// that a 16-byte granule lies in one row or in one gap); B is then 1 and segs_per_row the number of segments of the
+// virtual row.  Every lane translates the position of its granule on the memory side of the loads, and the position of
+// its four outputs at the stores.
 #pragma once
 #include "dwconv_dw_bf16.hip.h"
 
@@ -38,11 +43,11 @@ __host__ __device__ constexpr int bf16_dy_pos(int nb, int i)
     return 16 * bf16_block_pos(nb) + 4 * ((i >> 2) ^ (2 * ((nb >> 3) & 1))) + (i & 3);
 }
 
-template <int ND, int W>
+template <int ND, int W, bool ROWS = false>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kernel(
     const bf16_t *__restrict__ dy, const bf16_t *__restrict__ x, const bf16_t *__restrict__ f, bf16_t *__restrict__ dx,
     float *__restrict__ part, bf16_t *__restrict__ dw_out, int B, int C, int L, int K, int pad, int dmin,
-    int segs_per_row)
+    int segs_per_row, const RowsMap rm)
 {
     static_assert(ND >= 2 && 16 * ND <= 128, "window tails are one 128-element load each");
     constexpr int XWE = kSegLen + 16 * ND;         // elements of either window that are ever read
@@ -111,8 +116,24 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
 
     uintx4 rx, rg;
     int x_shift, g_shift;       // negative when a window starts before the row: added to the lane offsets
+    int vx0 = 0, vg0 = 0;       // ROWS: virtual positions of the first elements of the two windows
     auto aim = [&](int pbat, int pseg) {
-        if (pbat < B) {
+        if constexpr (ROWS) {
+            x_shift = g_shift = 0;
+            if (pbat < B) {
+                const int t0 = pseg * kSegLen;
+                vx0 = t0 + 16 * dmin;
+                vg0 = t0 + 16 * dmin_x;
+                const unsigned nbytes = rm.bytes - (unsigned)(c * L) * 2u;
+                const unsigned long long ax0 = reinterpret_cast<unsigned long long>(x + (size_t)c * (size_t)L);
+                const unsigned long long ag0 = reinterpret_cast<unsigned long long>(dy + (size_t)c * (size_t)L);
+                rx = uintx4{(unsigned)ax0, (unsigned)(ax0 >> 32) & 0xffffu, nbytes, kBufferFlags};
+                rg = uintx4{(unsigned)ag0, (unsigned)(ag0 >> 32) & 0xffffu, nbytes, kBufferFlags};
+            } else {
+                rx = uintx4{0u, 0u, 0u, kBufferFlags};
+                rg = rx;
+            }
+        } else if (pbat < B) {
             const size_t row = ((size_t)pbat * (size_t)C + (size_t)c) * (size_t)L;
             const int t0 = pseg * kSegLen;
             const int u0 = 2 * (t0 + 16 * dmin), v0 = 2 * (t0 + 16 * dmin_x);
@@ -128,12 +149,22 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
     };
     auto load_half = [&](auto hc) {         // x_h then g_h
         constexpr int h = decltype(hc)::value;
-        buffer_load_x4_to_lds(rx, off_x + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
-        buffer_load_x4_to_lds(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
+        if constexpr (ROWS) {
+            // the lane's granules: elements e .. e + 7 of the windows
+            buffer_load_x4_to_lds(rx, rows_byte_offset<2>(rm, vx0 + (off_x >> 1) + 512 * h), lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rg, rows_byte_offset<2>(rm, vg0 + (off_g >> 1) + 512 * h), lds_g + 1024u * (unsigned)h);
+        } else {
+            buffer_load_x4_to_lds(rx, off_x + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
+        }
+    };
+    auto tail_offset = [&](int off, int v0, int shift) {
+        if constexpr (ROWS) return off == kOutOfRow ? kOutOfRow : rows_byte_offset<2>(rm, v0 + (off >> 1));
+        else return off == kOutOfRow ? kOutOfRow : off + shift;
     };
     auto load_tails = [&]() {               // xt gt
-        buffer_load_x1_to_lds(rx, off_xt == kOutOfRow ? kOutOfRow : off_xt + x_shift, lds_x + 2048u);
-        buffer_load_x1_to_lds(rg, off_gt == kOutOfRow ? kOutOfRow : off_gt + g_shift, lds_g + 2048u);
+        buffer_load_x1_to_lds(rx, tail_offset(off_xt, vx0, x_shift), lds_x + 2048u);
+        buffer_load_x1_to_lds(rg, tail_offset(off_gt, vg0, g_shift), lds_g + 2048u);
     };
 
     aim(b, seg);
@@ -146,8 +177,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
         const int carry = seg_n >= segs_per_row ? 1 : 0;
         seg_n -= carry ? segs_per_row : 0;
         const int b_n = b + step_b + carry;
-        bf16_t *out_seg = dx + ((size_t)b * (size_t)C + (size_t)c) * (size_t)L + (size_t)(seg * kSegLen);   // wave-uniform
-        const bool whole = (seg + 1) * kSegLen <= L;
+        bf16_t *out_seg = ROWS ? dx + (size_t)c * (size_t)L                                                  // wave-uniform
+                               : dx + ((size_t)b * (size_t)C + (size_t)c) * (size_t)L + (size_t)(seg * kSegLen);
+        const bool whole = !ROWS && (seg + 1) * kSegLen <= L;
         const int t_seg = seg * kSegLen;
         aim(b_n, seg_n);
         // loads of this segment: x0 g0 x1 g1 xt gt.  Chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt;
@@ -183,8 +215,13 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
             }
             // ---- store tile c4: lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
-            if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
-            else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, L);
+            if constexpr (ROWS) {
+                const int eo = rows_element(rm, t_seg + lt);        // the four outputs are in one row or in one gap
+                if (eo >= 0) st_elem4_stream(out_seg + eo, make_float4(acc[0], acc[1], acc[2], acc[3]));
+            } else {
+                if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, L);
+            }
         });
         b = b_n; seg = seg_n;
     }

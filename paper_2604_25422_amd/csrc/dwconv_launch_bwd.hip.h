@@ -13,14 +13,23 @@ int launch_bwd_fused_ndw(const void *dy, const void *x, const void *w, void *dx,
                          const Shape &s, const DwPlan &p, int dmin, hipStream_t st)
 {
     if constexpr (std::is_same<T, bf16_t>::value) {
-        auto kernel = dwconv::bwd_fused_bf16_kernel<ND, W>;
         constexpr size_t lds = dwconv::bwd_fused_bf16_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
-        if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
-                           static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(w),
-                           static_cast<bf16_t *>(dx), part, static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin,
-                           p.tiles_per_row);
+        if (p.rows.on) {
+            auto kernel = dwconv::bwd_fused_bf16_kernel<ND, W, true>;
+            if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                               static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(w),
+                               static_cast<bf16_t *>(dx), part, static_cast<bf16_t *>(dw_out), 1, s.C, s.L, s.K, s.pad, dmin,
+                               p.tiles_per_row, p.rows.map);
+        } else {
+            auto kernel = dwconv::bwd_fused_bf16_kernel<ND, W, false>;
+            if (lds > 64 * 1024 && !allow_large_lds(kernel)) return -1;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)s.C, (unsigned)p.S), dim3(64 * W), lds, st,
+                               static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(w),
+                               static_cast<bf16_t *>(dx), part, static_cast<bf16_t *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin,
+                               p.tiles_per_row, p.rows.map);
+        }
         return launch_status();
     } else {
     constexpr size_t lds = dwconv::bwd_fused_lds_bytes(ND, W);
@@ -113,7 +122,10 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     if (p.longk) return -1;
     if (p.rows.batch) return launch_bwd_rowbatch<T>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
     if (p.rows.tall) return -1;                              // (two launches)
-    if (s.dtype == DWCONV_BF16 && p.rows.on) return -1;      // bf16 virtual rows: the two separate kernels
+    // bf16 virtual rows: rows and pitch of whole 16-byte granules (otherwise the two separate kernels)
+    if (s.dtype == DWCONV_BF16 && p.rows.on &&
+        ((s.L % 8) != 0 || (p.rows.map.P % 8) != 0 || !aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)))
+        return -1;
     // bf16: rows that start on a dword
     if (s.dtype == DWCONV_BF16 && (s.L % 2) != 0) return -1;
     const int dmin = toeplitz_dmin(s.pad), dmax = toeplitz_dmax(s.K, s.pad);

@@ -230,12 +230,15 @@ BWD = [
     (2, 5, 257, 7, 3, "f32", False), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", True), (3, 5, 1004, 32, 16, "bf16", True), (3, 5, 1006, 32, 16, "bf16", True), (3, 5, 1007, 32, 16, "bf16", False),
     (2, 3, 2050, 64, 63, "f32", True), (3, 2, 1025, 7, 3, "f32", True), (2, 2, 4099, 48, 24, "f32", True), (2, 2, 770, 31, 0, "f32", True),
     (2, 2, 766, 31, 0, "f32", False),
-    (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", False), (10, 768, 1024, 32, 31, "bf16", True),
+    (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", True), (10, 768, 1024, 32, 31, "bf16", True),
     (2, 2, 48, 48, 24, "bf16", False), (3, 2, 4096, 66, 65, "bf16", True), (40, 256, 1024, 64, 63, "bf16", True),
     (100, 6, 44, 31, 15, "bf16", True), (37, 3, 60, 20, 10, "bf16", False), (70, 256, 48, 48, 24, "bf16", True),
     (20, 4, 128, 16, 15, "bf16", False), (20, 4, 128, 16, 15, "f32", False), (20, 4, 132, 16, 15, "f32", True),
     (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", False), (100, 6, 48, 200, 100, "f32", True), (40, 3, 96, 96, 48, "f32", False),
     (60, 4, 44, 500, 499, "bf16", True),
+    # bf16 virtual rows: fused when rows and pitch are whole 16-byte granules
+    (40, 6, 200, 48, 24, "bf16", True), (30, 5, 196, 33, 16, "bf16", False), (7, 3, 520, 66, 65, "bf16", True),
+    (64, 8, 136, 20, 19, "bf16", True), (600, 16, 200, 48, 47, "bf16", True), (25, 3, 264, 7, 3, "bf16", True),
 ]
 
 
