@@ -90,6 +90,11 @@ RowsPlan plan_rows(const Shape &s)
         r.map.M = (unsigned)((1ull << 32) / (unsigned long long)P) + 1u;
         r.map.bytes = (unsigned)(elems * es);
     }
+    // bf16 rows of 64 to 128 positions in whole 16-byte granules: the virtual-row kernels bring the raw bf16 rows straight
+    // into LDS for the bf16 matrix instruction, while the sixteen-row kernels widen them to fp32 in registers (B8192 C128
+    // L128 K48: 542 -> 313 us per step, L96: 528 -> 366, L64: 462 -> 346; at 48 positions and below the sixteen-row kernels
+    // win, 416 against 525 us)
+    if (batch && vrows && s.dtype == DWCONV_BF16 && s.L >= 64 && (s.L % 8) == 0 && (P % 8) == 0) batch = false;
     if (batch) {
         r.on = true; r.batch = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
