@@ -94,7 +94,7 @@ RowsPlan plan_rows(const Shape &s)
     // into LDS for the bf16 matrix instruction, while the sixteen-row kernels widen them to fp32 in registers (B8192 C128
     // L128 K48: 542 -> 313 us per step, L96: 528 -> 366, L64: 462 -> 346; at 48 positions and below the sixteen-row kernels
     // win, 416 against 525 us)
-    if (batch && vrows && s.dtype == DWCONV_BF16 && s.L >= 64 && (s.L % 8) == 0 && (P % 8) == 0) batch = false;
+    if (batch && vrows && s.dtype == DWCONV_BF16 && s.L >= 64 && (s.L % 4) == 0 && (P % 8) == 0) batch = false;
     if (batch) {
         r.on = true; r.batch = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;
@@ -571,7 +571,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     // their waves would idle and the two separate kernels are faster - B416666 C1 L48 K33: 298 against 120 us)
     if (p.rows.batch) return (L <= dwconv::kRbBwdMaxL && C >= dwconv::kRbBwdWaves) ? 1 : 0;
     if (p.rows.tall) return 0;
-    if (dtype == DWCONV_BF16 && p.rows.on && ((L % 8) != 0 || (p.rows.map.P % 8) != 0)) return 0;
+    if (dtype == DWCONV_BF16 && p.rows.on && ((L % 4) != 0 || (p.rows.map.P % 8) != 0)) return 0;
     const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
                                                : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && rows_fit && L <= kMfmaMaxL) ? 1 : 0;

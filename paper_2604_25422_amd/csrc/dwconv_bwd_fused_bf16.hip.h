@@ -17,8 +17,9 @@
 // windows are dead after chunk 1, the rest after chunk 3; loads of a segment in issue order: x0 g0 x1 g1 xt gt
 // (xt, gt: 128-element tails, two elements per lane).  Needs L % 8 == 0 and 16-byte aligned tensors.
 //
-// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap; pitch and row length multiples of 8, so
-// that a 16-byte granule lies in one row or in one gap); B is then 1 and segs_per_row the number of segments of the
+// ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap; pitch a multiple of 8 and row length a
+// multiple of 4, so that a 16-byte granule lies in one row or in one gap, or holds the last four elements of a row, in
+// which case its upper half is cleared in LDS once it has landed: rows_granule8_byte_offset); B is then 1 and segs_per_row the number of segments of the
 // virtual row.  Every lane translates the position of its granule on the memory side of the loads, and the position of
 // its four outputs at the stores.
 #pragma once
@@ -147,12 +148,16 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
             rg = rx;
         }
     };
+    // ROWS, rows of 8 n + 4 elements: which of the lane's granules x0 g0 x1 g1 end in the middle (rows_granule8_byte_offset)
+    bool half_next[4] = {false, false, false, false}, half_cur[4] = {false, false, false, false};
     auto load_half = [&](auto hc) {         // x_h then g_h
         constexpr int h = decltype(hc)::value;
         if constexpr (ROWS) {
             // the lane's granules: elements e .. e + 7 of the windows
-            buffer_load_x4_to_lds(rx, rows_byte_offset<2>(rm, vx0 + (off_x >> 1) + 512 * h), lds_x + 1024u * (unsigned)h);
-            buffer_load_x4_to_lds(rg, rows_byte_offset<2>(rm, vg0 + (off_g >> 1) + 512 * h), lds_g + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rx, rows_granule8_byte_offset(rm, vx0 + (off_x >> 1) + 512 * h, half_next[2 * h]),
+                                  lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rg, rows_granule8_byte_offset(rm, vg0 + (off_g >> 1) + 512 * h, half_next[2 * h + 1]),
+                                  lds_g + 1024u * (unsigned)h);
         } else {
             buffer_load_x4_to_lds(rx, off_x + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
             buffer_load_x4_to_lds(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
@@ -182,12 +187,21 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
         const bool whole = !ROWS && (seg + 1) * kSegLen <= L;
         const int t_seg = seg * kSegLen;
         aim(b_n, seg_n);
+        if constexpr (ROWS) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) half_cur[i] = half_next[i];
+        }
         // loads of this segment: x0 g0 x1 g1 xt gt.  Chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt;
         // two loads of the next segment are out after chunk 1.
         static_for<0, 4>([&](auto cc) {
             constexpr int c4 = decltype(cc)::value;
             constexpr int need = c4 == 0 ? 1 : (c4 < 3 ? 3 : 5), issued = c4 >= 2 ? 2 : 0;
             wait_vmcnt_at_most<(5 - need) + issued>();
+            if constexpr (ROWS) {
+                // what has just landed: x0 and g0 before chunk 0, x1 and g1 before chunk 1
+                if constexpr (c4 == 0) { zero_upper_half(sx + 8 * lane, half_cur[0]); zero_upper_half(sg + 8 * lane, half_cur[1]); }
+                if constexpr (c4 == 1) { zero_upper_half(sx + 512 + 8 * lane, half_cur[2]); zero_upper_half(sg + 512 + 8 * lane, half_cur[3]); }
+            }
             // ---- input gradient, tile c4
             shortx4 bv[ND];
 #pragma unroll

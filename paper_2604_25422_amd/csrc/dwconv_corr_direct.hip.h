@@ -196,8 +196,9 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 // conflict-free.  Loads of a segment in issue order: g0 g1 (512 positions each), gt (128-position tail, two positions
 // per lane); 256-position chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt; positions [0, 512) are dead
 // after chunk 1, the rest after chunk 3.
-// ROWS: short rows, the unit of work is a segment of the virtual row of a channel (see RowsMap; pitch and row length
-// multiples of 8, so that a 16-byte granule lies in one row or in one gap): the walk's "row" is the virtual segment, its
+// ROWS: short rows, the unit of work is a segment of the virtual row of a channel (see RowsMap; pitch a multiple of 8 and
+// row length a multiple of 4, so that a 16-byte granule lies in one row or in one gap, or holds the last four elements of a
+// row, in which case its upper half is cleared in LDS once it has landed: rows_granule8_byte_offset): the walk's "row" is the virtual segment, its
 // "segment" the channel (walk_segs = segs_per_row = C), every lane translates the position of its granule on the memory
 // side of the loads, and the outputs of a group of four go to their row or nowhere.
 template <int ND, bool ROWS = false>
@@ -278,10 +279,12 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             rg = uintx4{0u, 0u, 0u, kBufferFlags};
         }
     };
+    bool half_next[2] = {false, false}, half_cur[2] = {false, false};   // ROWS: see rows_granule8_byte_offset
     auto load_half = [&](auto hc) {
         constexpr int h = decltype(hc)::value;
         if constexpr (ROWS)
-            buffer_load_x4_to_lds_keep(rg, rows_byte_offset<2>(rm, vg0 + (off_g >> 1) + 512 * h), lds_g + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds_keep(rg, rows_granule8_byte_offset(rm, vg0 + (off_g >> 1) + 512 * h, half_next[h]),
+                                       lds_g + 1024u * (unsigned)h);
         else
             buffer_load_x4_to_lds_keep(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
     };
@@ -325,11 +328,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             load_filter(c);
             cur_c = c;
         }
+        if constexpr (ROWS) { half_cur[0] = half_next[0]; half_cur[1] = half_next[1]; }
         static_for<0, 4>([&](auto cc) {
             constexpr int c4 = decltype(cc)::value;
             // three loads per segment (g0 g1 gt); one load of the next segment is out after chunk 1
             constexpr int need = c4 == 0 ? 0 : (c4 < 3 ? 1 : 2), issued = c4 >= 2 ? 1 : 0;
             wait_vmcnt_at_most<(2 - need) + issued>();
+            if constexpr (ROWS && c4 < 2) zero_upper_half(sg + 512 * c4 + 8 * lane, half_cur[c4]);     // g_{c4} has just landed
             // (a chunk wholly past the end of the row has no outputs: its matrix work is skipped)
             const bool live = ROWS || whole || t_seg + 256 * c4 < g.L;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};

@@ -122,9 +122,9 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     if (p.longk) return -1;
     if (p.rows.batch) return launch_bwd_rowbatch<T>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
     if (p.rows.tall) return -1;                              // (two launches)
-    // bf16 virtual rows: rows and pitch of whole 16-byte granules (otherwise the two separate kernels)
+    // bf16 virtual rows: rows of whole 8-byte granules, pitch of whole 16-byte granules (otherwise the two separate kernels)
     if (s.dtype == DWCONV_BF16 && p.rows.on &&
-        ((s.L % 8) != 0 || (p.rows.map.P % 8) != 0 || !aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)))
+        ((s.L % 4) != 0 || (p.rows.map.P % 8) != 0 || !aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)))
         return -1;
     // bf16: rows that start on a dword
     if (s.dtype == DWCONV_BF16 && (s.L % 2) != 0) return -1;

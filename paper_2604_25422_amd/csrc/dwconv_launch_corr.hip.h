@@ -289,7 +289,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
             if constexpr (sizeof(T) == 2) {
                 // bf16 rows of whole 16-byte granules: raw rows straight into LDS, bf16 matrix instruction (B4096 C128 L200
                 // K48: 186 -> 104 us against the widening kernel below)
-                if ((s.L % 8) == 0 && (rp.map.P % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
+                if ((s.L % 4) == 0 && (rp.map.P % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
                     switch (nd) {
                     case 2: return launch_rows(dwconv::corr_direct_bf16_kernel<2, true>);
                     case 3: return launch_rows(dwconv::corr_direct_bf16_kernel<3, true>);

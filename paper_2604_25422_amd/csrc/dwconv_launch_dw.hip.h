@@ -110,7 +110,7 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                                static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map,
                                0, s.K, 0, 0);
         }
-    } else if (p.rows.on && (s.L % 8) == 0 && (p.rows.map.P % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
+    } else if (p.rows.on && (s.L % 4) == 0 && (p.rows.map.P % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
         // bf16 short rows of whole 16-byte granules: the virtual row of a channel on the bf16 matrix instruction, raw rows
         // straight into LDS (B4096 C128 L200 K48: 247 -> 88 us against the widening kernel below)
         auto kernel = dwconv::dw_partial_bf16_kernel<ND, W, true>;

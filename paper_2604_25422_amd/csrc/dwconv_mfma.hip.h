@@ -140,6 +140,25 @@ __device__ __forceinline__ int rows_byte_offset(const RowsMap &m, int u)
     return e >= 0 ? ES * e : kOutOfRow;
 }
 
+// The same for a 16-byte granule of eight 2-byte elements that starts at virtual position u (a multiple of 8; pitch a
+// multiple of 8, row length a multiple of 4).  A row of 8 n + 4 elements ends in the middle of its last granule: the load
+// then brings the first four elements of the next row in memory where the virtual row holds zeros; `half` says so, and
+// the lane clears the upper 8 bytes of its LDS slot once the load has landed (zero_upper_half).
+__device__ __forceinline__ int rows_granule8_byte_offset(const RowsMap &m, int u, bool &half)
+{
+    const int b = (int)__umulhi((unsigned)u, m.M);
+    const int t = u - b * m.P;
+    const bool in = (unsigned)u < (unsigned)m.Lv && t < m.L;
+    half = in && t + 8 > m.L;
+    return in ? 2 * (b * m.CL + t) : kOutOfRow;
+}
+// Clear bytes 8..15 of a 16-byte LDS slot (lanes with `half` set).  Ordinary LDS store: it stays behind the wait that
+// precedes it and ahead of the operand reads that follow it in program order.
+__device__ __forceinline__ void zero_upper_half(const short *slot, bool half)
+{
+    if (half) *reinterpret_cast<uint2 *>(const_cast<short *>(slot) + 4) = make_uint2(0u, 0u);
+}
+
 // Raw bits of 4 consecutive elements (a "granule").
 template <typename T> struct Raw4;
 template <> struct Raw4<float> {
