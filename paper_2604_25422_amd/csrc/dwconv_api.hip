@@ -71,15 +71,15 @@ RowsPlan plan_rows(const Shape &s)
     // Virtual rows (whole granules; up to six offsets, fp32 sixteen): where a 1024-position segment of a row would be more than a
     // quarter padding, and positions stay 32-bit.
     const long long halo = s.pad > s.K - 1 - s.pad ? s.pad : s.K - 1 - s.pad;
-    // (pitch: whole granules of four; bf16 of eight, so that the kernels that load 16 bytes per lane apply to rows of whole
-    // 16-byte granules)
+    // (pitch: whole granules of four; bf16 of eight - rows AND gaps - so that the kernels that load 16 bytes per lane apply;
+    // a bf16 row of even length that is not a multiple of eight ends inside its last granule, see rows_granule8_byte_offset)
     const long long gr = s.dtype == DWCONV_F32 ? 4 : 8;
-    const long long P = (s.L + 3) / 4 * 4 + (halo + gr - 1) / gr * gr + ((s.dtype != DWCONV_F32 && (s.L % 8) == 4) ? 4 : 0);
+    const long long P = (s.L + gr - 1) / gr * gr + (halo + gr - 1) / gr * gr;
     const long long padded = ((long long)s.L + dwconv::kSegLen - 1) / dwconv::kSegLen * dwconv::kSegLen;
     const long long elems = (long long)s.B * s.C * s.L;
     // (seven to sixteen offsets, fp32: only while the gaps stay below half a row - with a filter as long as the row half of
     // the virtual row is gap, and the tall-row kernels below do better: B3200 C128 L160 K160 fwd 354 us here)
-    const bool vrows = (s.L % 4) == 0 &&
+    const bool vrows = (s.L % (s.dtype == DWCONV_F32 ? 4 : 2)) == 0 &&
                        (nd <= kMfmaMaxND || (s.dtype == DWCONV_F32 && nd <= kMfmaMaxNDDw && 2 * P <= 3 * (long long)s.L)) &&
                        4 * padded > 5 * P && elems * es <= (1ll << 30) &&
                        (long long)s.B * P * P < (1ll << 32) && (long long)s.B * P < (1ll << 31);
@@ -571,9 +571,10 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     // their waves would idle and the two separate kernels are faster - B416666 C1 L48 K33: 298 against 120 us)
     if (p.rows.batch) return (L <= dwconv::kRbBwdMaxL && C >= dwconv::kRbBwdWaves) ? 1 : 0;
     if (p.rows.tall) return 0;
-    if (dtype == DWCONV_BF16 && p.rows.on && ((L % 4) != 0 || (p.rows.map.P % 8) != 0)) return 0;
-    const bool rows_fit = dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
-                                               : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));
+    if (dtype == DWCONV_BF16 && p.rows.on && !p.rows.batch && ((L % 2) != 0 || (p.rows.map.P % 8) != 0)) return 0;
+    const bool rows_fit = (dtype == DWCONV_BF16 && p.rows.on) ? true      // (virtual rows of even length, checked above)
+                          : dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
+                                                 : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && rows_fit && L <= kMfmaMaxL) ? 1 : 0;
 }
 

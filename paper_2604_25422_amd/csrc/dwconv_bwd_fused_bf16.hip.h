@@ -18,8 +18,8 @@
 // (xt, gt: 128-element tails, two elements per lane).  Needs L % 8 == 0 and 16-byte aligned tensors.
 //
 // ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap; pitch a multiple of 8 and row length a
-// multiple of 4, so that a 16-byte granule lies in one row or in one gap, or holds the last four elements of a row, in
-// which case its upper half is cleared in LDS once it has landed: rows_granule8_byte_offset); B is then 1 and segs_per_row the number of segments of the
+// row length even: a 16-byte granule lies in one row or in one gap, or holds the last two, four or six elements of a row, in
+// which case the rest of it is cleared in LDS once it has landed: rows_granule8_byte_offset); B is then 1 and segs_per_row the number of segments of the
 // virtual row.  Every lane translates the position of its granule on the memory side of the loads, and the position of
 // its four outputs at the stores.
 #pragma once
@@ -148,15 +148,15 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
             rg = rx;
         }
     };
-    // ROWS, rows of 8 n + 4 elements: which of the lane's granules x0 g0 x1 g1 end in the middle (rows_granule8_byte_offset)
-    bool half_next[4] = {false, false, false, false}, half_cur[4] = {false, false, false, false};
+    // ROWS: elements of the lane's granules x0 g0 x1 g1 that belong to a row which ends inside them (rows_granule8_byte_offset)
+    int live_next[4] = {8, 8, 8, 8}, live_cur[4] = {8, 8, 8, 8};
     auto load_half = [&](auto hc) {         // x_h then g_h
         constexpr int h = decltype(hc)::value;
         if constexpr (ROWS) {
             // the lane's granules: elements e .. e + 7 of the windows
-            buffer_load_x4_to_lds(rx, rows_granule8_byte_offset(rm, vx0 + (off_x >> 1) + 512 * h, half_next[2 * h]),
+            buffer_load_x4_to_lds(rx, rows_granule8_byte_offset(rm, vx0 + (off_x >> 1) + 512 * h, live_next[2 * h]),
                                   lds_x + 1024u * (unsigned)h);
-            buffer_load_x4_to_lds(rg, rows_granule8_byte_offset(rm, vg0 + (off_g >> 1) + 512 * h, half_next[2 * h + 1]),
+            buffer_load_x4_to_lds(rg, rows_granule8_byte_offset(rm, vg0 + (off_g >> 1) + 512 * h, live_next[2 * h + 1]),
                                   lds_g + 1024u * (unsigned)h);
         } else {
             buffer_load_x4_to_lds(rx, off_x + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
         aim(b_n, seg_n);
         if constexpr (ROWS) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) half_cur[i] = half_next[i];
+            for (int i = 0; i < 4; ++i) live_cur[i] = live_next[i];
         }
         // loads of this segment: x0 g0 x1 g1 xt gt.  Chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt;
         // two loads of the next segment are out after chunk 1.
@@ -199,8 +199,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
             wait_vmcnt_at_most<(5 - need) + issued>();
             if constexpr (ROWS) {
                 // what has just landed: x0 and g0 before chunk 0, x1 and g1 before chunk 1
-                if constexpr (c4 == 0) { zero_upper_half(sx + 8 * lane, half_cur[0]); zero_upper_half(sg + 8 * lane, half_cur[1]); }
-                if constexpr (c4 == 1) { zero_upper_half(sx + 512 + 8 * lane, half_cur[2]); zero_upper_half(sg + 512 + 8 * lane, half_cur[3]); }
+                if constexpr (c4 == 0) { zero_slot_tail(sx + 8 * lane, live_cur[0]); zero_slot_tail(sg + 8 * lane, live_cur[1]); }
+                if constexpr (c4 == 1) { zero_slot_tail(sx + 512 + 8 * lane, live_cur[2]); zero_slot_tail(sg + 512 + 8 * lane, live_cur[3]); }
             }
             // ---- input gradient, tile c4
             shortx4 bv[ND];
@@ -230,8 +230,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_bf16_kern
             // ---- store tile c4: lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
             if constexpr (ROWS) {
-                const int eo = rows_element(rm, t_seg + lt);        // the four outputs are in one row or in one gap
-                if (eo >= 0) st_elem4_stream(out_seg + eo, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                int n;
+                const int eo = rows_element_group(rm, t_seg + lt, n);   // four outputs: one row, one gap, or the end of a row
+                if (eo >= 0) st_rows_group(out_seg + eo, make_float4(acc[0], acc[1], acc[2], acc[3]), n);
             } else {
                 if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
                 else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, L);

@@ -197,8 +197,8 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
 // per lane); 256-position chunk 0 needs g0, chunks 1 and 2 need g1, chunk 3 needs gt; positions [0, 512) are dead
 // after chunk 1, the rest after chunk 3.
 // ROWS: short rows, the unit of work is a segment of the virtual row of a channel (see RowsMap; pitch a multiple of 8 and
-// row length a multiple of 4, so that a 16-byte granule lies in one row or in one gap, or holds the last four elements of a
-// row, in which case its upper half is cleared in LDS once it has landed: rows_granule8_byte_offset): the walk's "row" is the virtual segment, its
+// row length even: a 16-byte granule lies in one row or in one gap, or holds the last two, four or six elements of a row,
+// in which case the rest of it is cleared in LDS once it has landed: rows_granule8_byte_offset): the walk's "row" is the virtual segment, its
 // "segment" the channel (walk_segs = segs_per_row = C), every lane translates the position of its granule on the memory
 // side of the loads, and the outputs of a group of four go to their row or nowhere.
 template <int ND, bool ROWS = false>
@@ -279,11 +279,11 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             rg = uintx4{0u, 0u, 0u, kBufferFlags};
         }
     };
-    bool half_next[2] = {false, false}, half_cur[2] = {false, false};   // ROWS: see rows_granule8_byte_offset
+    int live_next[2] = {8, 8}, live_cur[2] = {8, 8};   // ROWS: see rows_granule8_byte_offset
     auto load_half = [&](auto hc) {
         constexpr int h = decltype(hc)::value;
         if constexpr (ROWS)
-            buffer_load_x4_to_lds_keep(rg, rows_granule8_byte_offset(rm, vg0 + (off_g >> 1) + 512 * h, half_next[h]),
+            buffer_load_x4_to_lds_keep(rg, rows_granule8_byte_offset(rm, vg0 + (off_g >> 1) + 512 * h, live_next[h]),
                                        lds_g + 1024u * (unsigned)h);
         else
             buffer_load_x4_to_lds_keep(rg, off_g + (1024 * h + g_shift), lds_g + 1024u * (unsigned)h);
@@ -328,13 +328,13 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             load_filter(c);
             cur_c = c;
         }
-        if constexpr (ROWS) { half_cur[0] = half_next[0]; half_cur[1] = half_next[1]; }
+        if constexpr (ROWS) { live_cur[0] = live_next[0]; live_cur[1] = live_next[1]; }
         static_for<0, 4>([&](auto cc) {
             constexpr int c4 = decltype(cc)::value;
             // three loads per segment (g0 g1 gt); one load of the next segment is out after chunk 1
             constexpr int need = c4 == 0 ? 0 : (c4 < 3 ? 1 : 2), issued = c4 >= 2 ? 1 : 0;
             wait_vmcnt_at_most<(2 - need) + issued>();
-            if constexpr (ROWS && c4 < 2) zero_upper_half(sg + 512 * c4 + 8 * lane, half_cur[c4]);     // g_{c4} has just landed
+            if constexpr (ROWS && c4 < 2) zero_slot_tail(sg + 512 * c4 + 8 * lane, live_cur[c4]);     // g_{c4} has just landed
             // (a chunk wholly past the end of the row has no outputs: its matrix work is skipped)
             const bool live = ROWS || whole || t_seg + 256 * c4 < g.L;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -354,8 +354,9 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             // lane (block j = i16, row group kg) owns outputs 16 j + 4 kg + 0..3 of the chunk
             const int lt = 256 * c4 + 16 * i16 + 4 * kg;
             if constexpr (ROWS) {
-                const int e = rows_element(rm, t_seg + lt);         // four outputs: one row or one gap
-                if (e >= 0) st_elem4_stream(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                int n;
+                const int e = rows_element_group(rm, t_seg + lt, n);    // four outputs: one row, one gap, or the end of a row
+                if (e >= 0) st_rows_group(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]), n);
             } else {
                 if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
                 else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);

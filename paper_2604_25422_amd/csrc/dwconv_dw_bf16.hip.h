@@ -36,8 +36,8 @@ constexpr size_t dw_bf16_lds_bytes(int ND, int W) { return (size_t)W * (size_t)(
 __host__ __device__ constexpr int bf16_block_pos(int nb) { return (nb & ~3) | ((nb & 3) ^ ((nb >> 2) & 3)); }
 
 // ROWS: short rows, the wave walks the virtual row of its channel (see RowsMap; pitch a multiple of 8 and row length a
-// multiple of 4, so that a 16-byte granule lies in one row or in one gap, or holds the last four elements of a row, in
-// which case its upper half is cleared in LDS once it has landed: rows_granule8_byte_offset); B is then 1 and segs_per_row the number of segments of the
+// row length even: a 16-byte granule lies in one row or in one gap, or holds the last two, four or six elements of a row, in
+// which case the rest of it is cleared in LDS once it has landed: rows_granule8_byte_offset); B is then 1 and segs_per_row the number of segments of the
 // virtual row.  Every lane translates the position of its granule on the memory side of the loads.
 template <int ND, int W, bool ROWS = false>
 __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_kernel(
@@ -138,14 +138,14 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
             rg = rx;
         }
     };
-    // ROWS, rows of 8 n + 4 elements: which of the lane's granules x0 g0 x1 g1 end in the middle (rows_granule8_byte_offset)
-    bool half_next[4] = {false, false, false, false}, half_cur[4] = {false, false, false, false};
+    // ROWS: elements of the lane's granules x0 g0 x1 g1 that belong to a row which ends inside them (rows_granule8_byte_offset)
+    int live_next[4] = {8, 8, 8, 8}, live_cur[4] = {8, 8, 8, 8};
     auto load_half = [&](auto hc) {         // x_h then g_h
         constexpr int h = decltype(hc)::value;
         if constexpr (ROWS) {
             const int e = (off_main >> 1) + 512 * h;        // the lane's granule: elements e .. e + 7 of the windows
-            buffer_load_x4_to_lds(rx, rows_granule8_byte_offset(rm, vx0 + e, half_next[2 * h]), lds_x + 1024u * (unsigned)h);
-            buffer_load_x4_to_lds(rg, rows_granule8_byte_offset(rm, vg0 + e, half_next[2 * h + 1]), lds_g + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rx, rows_granule8_byte_offset(rm, vx0 + e, live_next[2 * h]), lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds(rg, rows_granule8_byte_offset(rm, vg0 + e, live_next[2 * h + 1]), lds_g + 1024u * (unsigned)h);
         } else {
             buffer_load_x4_to_lds(rx, off_main + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
             buffer_load_x4_to_lds(rg, off_main + 1024 * h, lds_g + 1024u * (unsigned)h);
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
         aim(b_n, seg_n);
         if constexpr (ROWS) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) half_cur[i] = half_next[i];
+            for (int i = 0; i < 4; ++i) live_cur[i] = live_next[i];
         }
         // 256-position chunk c4 (x blocks 16 c4 .. 16 c4 + 15 + ND + 2): before it, load number need(c4) of this
         // segment has landed
@@ -184,9 +184,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
             wait_vmcnt_at_most<(NLOADS - 1 - need) + issued>();
             if constexpr (ROWS) {
                 // what has just landed: x0 and g0 before chunk 0, x1 before chunk 1, g1 before chunk 2
-                if constexpr (c4 == 0) { zero_upper_half(sx + 8 * lane, half_cur[0]); zero_upper_half(sg + 8 * lane, half_cur[1]); }
-                if constexpr (c4 == 1) zero_upper_half(sx + 512 + 8 * lane, half_cur[2]);
-                if constexpr (c4 == 2) zero_upper_half(sg + 512 + 8 * lane, half_cur[3]);
+                if constexpr (c4 == 0) { zero_slot_tail(sx + 8 * lane, live_cur[0]); zero_slot_tail(sg + 8 * lane, live_cur[1]); }
+                if constexpr (c4 == 1) zero_slot_tail(sx + 512 + 8 * lane, live_cur[2]);
+                if constexpr (c4 == 2) zero_slot_tail(sg + 512 + 8 * lane, live_cur[3]);
             }
             shortx4 bq;
 #pragma unroll

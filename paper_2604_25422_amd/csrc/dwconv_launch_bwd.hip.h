@@ -122,9 +122,10 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     if (p.longk) return -1;
     if (p.rows.batch) return launch_bwd_rowbatch<T>(dy, x, w, dx, part, dw_out, wrote_dw, s, p, st);
     if (p.rows.tall) return -1;                              // (two launches)
-    // bf16 virtual rows: rows of whole 8-byte granules, pitch of whole 16-byte granules (otherwise the two separate kernels)
+    // bf16 virtual rows: rows of even length (they start on a dword), pitch of whole 16-byte granules (otherwise the two
+    // separate kernels)
     if (s.dtype == DWCONV_BF16 && p.rows.on &&
-        ((s.L % 4) != 0 || (p.rows.map.P % 8) != 0 || !aligned_to(x, 16) || !aligned_to(dy, 16) || !aligned_to(dx, 16)))
+        ((s.L % 2) != 0 || (p.rows.map.P % 8) != 0 || !aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4)))
         return -1;
     // bf16: rows that start on a dword
     if (s.dtype == DWCONV_BF16 && (s.L % 2) != 0) return -1;
@@ -135,7 +136,9 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     const bool granular = (s.L % (s.dtype == DWCONV_BF16 ? 8 : 4)) == 0 && aligned_to(x, 16) && aligned_to(dy, 16) && aligned_to(dx, 16);
     if (!granular) {
         const bool short_ok = s.dtype == DWCONV_BF16 && (s.L % 4) == 0;      // (bf16 rows in granules of four: any ordinary length)
-        if ((!short_ok && !ragged_rows_fused_ok(s, nd)) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4) || !aligned_to(dx, 4))
+        const bool rows_ok = s.dtype == DWCONV_BF16 && p.rows.on;            // (bf16 virtual rows of even length, checked above)
+        if ((!short_ok && !rows_ok && !ragged_rows_fused_ok(s, nd)) || (p.rows.on && !rows_ok) || !aligned_to(x, 4) ||
+            !aligned_to(dy, 4) || !aligned_to(dx, 4))
             return -1;
     }
     void *direct = (p.single && p.S == 1) ? dw_out : nullptr;

@@ -281,15 +281,18 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };
-    if (!granular && rp.on) return -1;       // (virtual rows of a tensor that is only element-aligned)
+    // bf16 virtual rows on the kernels that load raw rows straight into LDS: rows of even length (they start on a dword),
+    // pitch a multiple of 8
+    const bool rows_direct_bf16 = sizeof(T) == 2 && rp.on && (s.L % 2) == 0 && (rp.map.P % 8) == 0 && aligned_to(in, 4) && aligned_to(out, 4);
+    if (!granular && rp.on && !rows_direct_bf16) return -1;       // (virtual rows of a tensor that is only element-aligned)
     {
         // longer short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)
         if (rp.on) {
             auto launch_rows = [&](auto kernel) -> int { return launch_corr_vrows_kernel<T>(kernel, g, rp, in, f, out, s, st); };
             if constexpr (sizeof(T) == 2) {
-                // bf16 rows of whole 16-byte granules: raw rows straight into LDS, bf16 matrix instruction (B4096 C128 L200
-                // K48: 186 -> 104 us against the widening kernel below)
-                if ((s.L % 4) == 0 && (rp.map.P % 8) == 0 && aligned_to(in, 16) && aligned_to(out, 16)) {
+                // bf16 rows of even length: raw rows straight into LDS, bf16 matrix instruction (B4096 C128 L200
+                // K48: 186 -> 104 us against the widening kernel below, which needs whole granules of four)
+                if (rows_direct_bf16) {
                     switch (nd) {
                     case 2: return launch_rows(dwconv::corr_direct_bf16_kernel<2, true>);
                     case 3: return launch_rows(dwconv::corr_direct_bf16_kernel<3, true>);
@@ -300,6 +303,7 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
                     }
                 }
             }
+            if (!granular) return -1;             // (the kernels below move whole granules of four)
             switch (nd) {
             case 2: return launch_rows(dwconv::corr_mfma_kernel<T, 2, true>);
             case 3: return launch_rows(dwconv::corr_mfma_kernel<T, 3, true>);

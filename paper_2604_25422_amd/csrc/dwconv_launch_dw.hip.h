@@ -110,9 +110,9 @@ int launch_dw_partial_mfma_ndw(const void *x, const void *dy, float *part, void 
                                static_cast<float *>(dw_out), s.B, s.C, s.L, s.K, s.pad, dmin, p.tiles_per_row, p.rows.map,
                                0, s.K, 0, 0);
         }
-    } else if (p.rows.on && (s.L % 4) == 0 && (p.rows.map.P % 8) == 0 && aligned_to(x, 16) && aligned_to(dy, 16)) {
-        // bf16 short rows of whole 16-byte granules: the virtual row of a channel on the bf16 matrix instruction, raw rows
-        // straight into LDS (B4096 C128 L200 K48: 247 -> 88 us against the widening kernel below)
+    } else if (p.rows.on && (s.L % 2) == 0 && (p.rows.map.P % 8) == 0 && aligned_to(x, 4) && aligned_to(dy, 4)) {
+        // bf16 short rows of even length (they start on a dword): the virtual row of a channel on the bf16 matrix instruction,
+        // raw rows straight into LDS (B4096 C128 L200 K48: 247 -> 88 us against the widening kernel below)
         auto kernel = dwconv::dw_partial_bf16_kernel<ND, W, true>;
         constexpr size_t lds = dwconv::dw_bf16_lds_bytes(ND, W);
         static_assert(lds <= kMaxLdsBytes, "LDS budget");
@@ -190,7 +190,9 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd_dw(s) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(x, 4 * sizeof(T)) && aligned_to(dy, 4 * sizeof(T));
-    if (!granular && (!ragged_rows_ok(s, nd) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4))) return -1;
+    // (bf16 virtual rows of even length: launch_dw_partial_mfma_ndw takes them on the kernel that loads raw rows into LDS)
+    const bool rows_direct_bf16 = sizeof(T) == 2 && p.rows.on && (s.L % 2) == 0 && (p.rows.map.P % 8) == 0;
+    if (!granular && (!ragged_rows_ok(s, nd) || (p.rows.on && !rows_direct_bf16) || !aligned_to(x, 4) || !aligned_to(dy, 4))) return -1;
     if constexpr (std::is_same<T, float>::value) {
         if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
     } else {

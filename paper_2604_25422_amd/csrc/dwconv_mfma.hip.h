@@ -141,22 +141,52 @@ __device__ __forceinline__ int rows_byte_offset(const RowsMap &m, int u)
 }
 
 // The same for a 16-byte granule of eight 2-byte elements that starts at virtual position u (a multiple of 8; pitch a
-// multiple of 8, row length a multiple of 4).  A row of 8 n + 4 elements ends in the middle of its last granule: the load
-// then brings the first four elements of the next row in memory where the virtual row holds zeros; `half` says so, and
-// the lane clears the upper 8 bytes of its LDS slot once the load has landed (zero_upper_half).
-__device__ __forceinline__ int rows_granule8_byte_offset(const RowsMap &m, int u, bool &half)
+// multiple of 8, row length even).  A row whose length is not a multiple of 8 ends inside its last granule: the load
+// then brings the first elements of the next row in memory where the virtual row holds zeros.  `live` is the number of
+// elements of the granule that belong to the row when that is the case (2, 4 or 6), 8 otherwise; the lane clears the
+// rest of its LDS slot once the load has landed (zero_slot_tail).
+__device__ __forceinline__ int rows_granule8_byte_offset(const RowsMap &m, int u, int &live)
 {
     const int b = (int)__umulhi((unsigned)u, m.M);
     const int t = u - b * m.P;
     const bool in = (unsigned)u < (unsigned)m.Lv && t < m.L;
-    half = in && t + 8 > m.L;
+    const int left = m.L - t;
+    live = (in && left < 8) ? left : 8;
     return in ? 2 * (b * m.CL + t) : kOutOfRow;
 }
-// Clear bytes 8..15 of a 16-byte LDS slot (lanes with `half` set).  Ordinary LDS store: it stays behind the wait that
-// precedes it and ahead of the operand reads that follow it in program order.
-__device__ __forceinline__ void zero_upper_half(const short *slot, bool half)
+// Clear the dwords of a 16-byte LDS slot from element `live` on (live = 2, 4, 6; 8: nothing).  Ordinary LDS stores:
+// they stay behind the wait that precedes them and ahead of the operand reads that follow them in program order.
+__device__ __forceinline__ void zero_slot_tail(const short *slot, int live)
 {
-    if (half) *reinterpret_cast<uint2 *>(const_cast<short *>(slot) + 4) = make_uint2(0u, 0u);
+    if (live < 8) {
+        unsigned *p = reinterpret_cast<unsigned *>(const_cast<short *>(slot));
+        if (live <= 2) p[1] = 0u;
+        if (live <= 4) p[2] = 0u;
+        p[3] = 0u;
+    }
+}
+// Four consecutive outputs of a virtual row, at positions u .. u + 3 (u a multiple of 4): they lie in one row, in one gap,
+// or - rows whose length is not a multiple of four - the first n of them end a row.  Element offset of the first (from the
+// channel's first row) or -1, and n.
+__device__ __forceinline__ int rows_element_group(const RowsMap &m, int u, int &n)
+{
+    const int b = (int)__umulhi((unsigned)u, m.M);
+    const int t = u - b * m.P;
+    const bool in = (unsigned)u < (unsigned)m.Lv && t < m.L;
+    const int left = m.L - t;
+    n = left < 4 ? left : 4;
+    return in ? b * m.CL + t : -1;
+}
+template <typename T>
+__device__ __forceinline__ void st_rows_group(T *p, float4 v, int n)
+{
+    if (n == 4) {
+        st_elem4_stream(p, v);
+    } else {
+        st_elem(p, v.x);
+        if (n > 1) st_elem(p + 1, v.y);
+        if (n > 2) st_elem(p + 2, v.z);
+    }
 }
 
 // Raw bits of 4 consecutive elements (a "granule").

@@ -102,8 +102,9 @@ def test_fused_backward_argument_validation(lib):
     assert q(8, 256, 8192, 8192, 8191, 0) == 0 and q(2, 3, 101, 5, 2, 0) == 0
     assert q(2, 3, 100, 2, 1, 0) == 0 and q(0, 3, 100, 5, 2, 0) == 0
     assert q(16384, 128, 48, 48, 24, 0) == 1        # rows of at most 64 positions: sixteen rows per tile
-    # bf16 virtual rows: rows of whole 8-byte granules
-    assert q(4096, 128, 200, 48, 24, 1) == 1 and q(4096, 128, 196, 48, 24, 1) == 1 and q(4096, 128, 198, 48, 24, 1) == 0
+    # bf16 virtual rows: rows of even length
+    assert q(4096, 128, 200, 48, 24, 1) == 1 and q(4096, 128, 196, 48, 24, 1) == 1 and q(4096, 128, 198, 48, 24, 1) == 1
+    assert q(4096, 128, 199, 48, 24, 1) == 0
 
 
 def test_workspace_query_rejects_bad_shapes(lib):

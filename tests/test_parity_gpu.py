@@ -236,13 +236,16 @@ BWD = [
     (20, 4, 128, 16, 15, "bf16", True), (20, 4, 128, 16, 15, "f32", False), (20, 4, 132, 16, 15, "f32", True),
     (1, 2, 40, 100, 99, "f32", False), (3, 2, 33, 1, 0, "f32", False), (100, 6, 48, 200, 100, "f32", True), (40, 3, 96, 96, 48, "f32", False),
     (60, 4, 44, 500, 499, "bf16", True),
-    # bf16 virtual rows: fused when rows are whole 8-byte granules (a multiple of 4 positions)
+    # bf16 virtual rows: fused when rows start on a dword (even length)
     (40, 6, 200, 48, 24, "bf16", True), (30, 5, 196, 33, 16, "bf16", True), (7, 3, 520, 66, 65, "bf16", True),
     (64, 8, 136, 20, 19, "bf16", True), (600, 16, 200, 48, 47, "bf16", True), (25, 3, 264, 7, 3, "bf16", True),
     # ... from 64 positions (below: sixteen rows per tile, fused up to 48 positions only)
     (90, 5, 64, 48, 24, "bf16", True), (70, 6, 96, 33, 32, "bf16", True), (50, 3, 56, 16, 15, "bf16", False),
     (50, 3, 68, 16, 15, "bf16", True), (50, 3, 120, 66, 0, "bf16", True), (50, 3, 66, 16, 15, "bf16", False),
     (900, 16, 196, 48, 24, "bf16", True), (300, 8, 500, 64, 63, "bf16", True), (40, 4, 100, 7, 3, "bf16", True),
+    # ... and of any even length from 129 positions (a row then ends two, four or six elements into a 16-byte granule)
+    (40, 6, 198, 48, 24, "bf16", True), (30, 5, 250, 33, 16, "bf16", True), (25, 3, 130, 7, 3, "bf16", True),
+    (700, 16, 202, 48, 47, "bf16", True), (30, 5, 199, 33, 16, "bf16", False),
 ]
 
 
