@@ -150,6 +150,9 @@ def test_exact_on_element_aligned_views(oracle_mod, dtype, B, C, L, K, p):
     (2, 3, 512, 512, 511, "f32", 2), (2, 3, 512, 512, 511, "bf16", 4), (2, 3, 600, 64, 63, "f32", 2),
     (7, 9, 3000, 48, 24, "bf16", 4), (40, 6, 48, 48, 24, "f32", 2), (40, 6, 48, 48, 24, "bf16", 2),
     (9, 256, 3900, 64, 63, "f32", 3), (3, 4, 1024, 256, 255, "bf16", 3),
+    # bf16 virtual rows on tensors that are only 4-byte aligned (the kernels that load raw rows into LDS take them)
+    (300, 12, 200, 31, 15, "bf16", 2), (300, 12, 198, 31, 15, "bf16", 2), (64, 2, 508, 64, 63, "bf16", 6),
+    (50, 3, 100, 16, 15, "bf16", 2), (40, 5, 202, 48, 24, "bf16", 4),
 ])
 def test_exact_on_partly_aligned_views(oracle_mod, B, C, L, K, p, dtype, offset):
     print(f"case exact offset {offset} {dtype} B{B} C{C} L{L} K{K} p{p}", flush=True)
