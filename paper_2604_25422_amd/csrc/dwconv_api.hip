@@ -79,8 +79,11 @@ RowsPlan plan_rows(const Shape &s)
     const long long elems = (long long)s.B * s.C * s.L;
     // (seven to sixteen offsets, fp32: only while the gaps stay below half a row - with a filter as long as the row half of
     // the virtual row is gap, and the tall-row kernels below do better: B3200 C128 L160 K160 fwd 354 us here)
-    const bool vrows = (s.L % (s.dtype == DWCONV_F32 ? 4 : 2)) == 0 &&
-                       (nd <= kMfmaMaxND || (s.dtype == DWCONV_F32 && nd <= kMfmaMaxNDDw && 2 * P <= 3 * (long long)s.L)) &&
+    // (rows that end inside a 16-byte granule - fp32 lengths that are not multiples of four, bf16 even lengths that are not
+    // multiples of eight: the kernels that load rows straight into LDS, up to six offsets; bf16 rows of odd length do not
+    // start on a dword)
+    const bool vrows = (s.dtype == DWCONV_F32 ? ((s.L % 4) == 0 || nd <= kMfmaMaxND) : (s.L % 2) == 0) &&
+                       (nd <= kMfmaMaxND || (s.dtype == DWCONV_F32 && (s.L % 4) == 0 && nd <= kMfmaMaxNDDw && 2 * P <= 3 * (long long)s.L)) &&
                        4 * padded > 5 * P && elems * es <= (1ll << 30) &&
                        (long long)s.B * P * P < (1ll << 32) && (long long)s.B * P < (1ll << 31);
     if (vrows) {
@@ -572,7 +575,7 @@ int dwconv_bwd_is_fused(int B, int C, int L, int K, int pad_left, int dtype)
     if (p.rows.batch) return (L <= dwconv::kRbBwdMaxL && C >= dwconv::kRbBwdWaves) ? 1 : 0;
     if (p.rows.tall) return 0;
     if (dtype == DWCONV_BF16 && p.rows.on && !p.rows.batch && ((L % 2) != 0 || (p.rows.map.P % 8) != 0)) return 0;
-    const bool rows_fit = (dtype == DWCONV_BF16 && p.rows.on) ? true      // (virtual rows of even length, checked above)
+    const bool rows_fit = p.rows.on ? true      // (virtual rows; bf16: of even length, checked above)
                           : dtype == DWCONV_BF16 ? ((L % 8) == 0 || ((L % 2) == 0 && ((L % 4) != 0 ? ragged_rows_fused_ok(s, nd) : true)))
                                                  : ((L % 4) == 0 || ragged_rows_fused_ok(s, nd));
     return (!p.longk && K >= kMfmaMinK && nd >= 2 && nd <= kMfmaMaxND && rows_fit && L <= kMfmaMaxL) ? 1 : 0;

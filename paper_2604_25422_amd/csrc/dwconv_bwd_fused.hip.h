@@ -152,11 +152,21 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
             rg = rx;
         }
     };
+    // ROWS: floats of the lane's granules x0 g0 x1 g1 x2 g2 x3 g3 that belong to a row which ends inside them
+    // (rows_granule4_byte_offset; rows whose length is not a multiple of four)
+    // (three bits per load, packed: the kernel has no registers to spare)
+    const bool rag = ROWS && (rm.L & 3) != 0;
+    unsigned live_next = 0u, live_cur = 0u;
+    auto note_live = [&](int k, int live) { live_next |= (unsigned)live << (3 * k); };
+    auto live_of = [&](int k) { return (int)((live_cur >> (3 * k)) & 7u); };
     auto load_region = [&](auto ic) {       // x_i then g_i, i = 0..3
         constexpr int i = decltype(ic)::value;
         if constexpr (ROWS) {
-            buffer_load_x4_to_lds(rx, rows_byte_offset<4>(rm, vx0 + fo_x + 256 * i), lds_x + 1024u * (unsigned)i);
-            buffer_load_x4_to_lds(rg, rows_byte_offset<4>(rm, vg0 + fo_g + 256 * i), lds_g + 1024u * (unsigned)i);
+            int lx, lg;
+            const int ox = rows_granule4_byte_offset(rm, vx0 + fo_x + 256 * i, lx), og = rows_granule4_byte_offset(rm, vg0 + fo_g + 256 * i, lg);
+            note_live(2 * i, lx); note_live(2 * i + 1, lg);
+            buffer_load_x4_to_lds(rx, ox, lds_x + 1024u * (unsigned)i);
+            buffer_load_x4_to_lds(rg, og, lds_g + 1024u * (unsigned)i);
         } else {
             buffer_load_x4_to_lds(rx, 4 * fo_x + (1024 * i + x_shift), lds_x + 1024u * (unsigned)i);
             buffer_load_x4_to_lds(rg, 4 * fo_g + (1024 * i + g_shift), lds_g + 1024u * (unsigned)i);
@@ -188,12 +198,24 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
         const bool whole = !ROWS && (seg + 1) * kSegLen <= L;
         const int t_seg = seg * kSegLen;
         aim(b_n, seg_n);
+        if constexpr (ROWS) { live_cur = live_next; live_next = 0u; }
 
         static_for<0, 4>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             // twelve loads per segment; before quarter i everything up to g_{i+1} (i < 3) or all of them has landed
             constexpr int need = i < 3 ? 2 * i + 3 : 11;
             wait_vmcnt_at_most<(11 - need) + 2 * i>();
+            if constexpr (ROWS) {
+                // what has just landed: x0 g0 x1 g1 before quarter 0, x2 g2 before quarter 1, x3 g3 before quarter 2
+                if (rag && i == 0) {
+                    zero_slot_tail(sx + 4 * lane, live_of(0)); zero_slot_tail(sg + 4 * lane, live_of(1));
+                    zero_slot_tail(sx + 256 + 4 * lane, live_of(2)); zero_slot_tail(sg + 256 + 4 * lane, live_of(3));
+                }
+                if (rag && (i == 1 || i == 2)) {
+                    zero_slot_tail(sx + 256 * (i + 1) + 4 * lane, live_of(2 * (i + 1)));
+                    zero_slot_tail(sg + 256 * (i + 1) + 4 * lane, live_of(2 * (i + 1) + 1));
+                }
+            }
 
             // ---- input gradient, tile i: one chain of 4 ND matrix instructions
             float4 bv[ND];
@@ -227,8 +249,9 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void bwd_fused_kernel(
             // ---- store tile i: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3
             const int lt = 256 * i + 16 * i16 + 4 * k4;
             if constexpr (ROWS) {
-                const int e = rows_element(rm, t_seg + lt);         // the four outputs are in one row or in one gap
-                if (e >= 0) st_elem4_stream(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                int n;
+                const int e = rows_element_group(rm, t_seg + lt, n);    // four outputs: one row, one gap, or the end of a row
+                if (e >= 0) st_rows_group(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]), n);
             } else {
                 if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
                 else st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, L);

@@ -35,10 +35,16 @@ __device__ __forceinline__ void buffer_load_x1_to_lds_keep(uintx4 rsrc, int byte
 
 constexpr int kCorrDirectWin = kSegLen + 128;      // floats per wave: 1024 + two 64-float tail loads
 
-template <int ND>
+// ROWS: short rows whose length is not a multiple of four (those that are take the register-staged kernel), the unit of
+// work is a segment of the virtual row of a channel (see RowsMap; pitch a multiple of 4): the walk's "row" is the virtual
+// segment, its "segment" the channel (walk_segs = segs_per_row = C), every lane translates the position of its granule on
+// the memory side of the loads; the granule in which a row ends also brings elements of the next row in memory, which
+// the lane clears in LDS once the load has landed (rows_granule4_byte_offset); the outputs of a group of four go to their
+// row, as far as it reaches, or nowhere.
+template <int ND, bool ROWS = false>
 __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void corr_direct_kernel(
     const float *__restrict__ in, const float *__restrict__ f, float *__restrict__ out, const CorrGeom g,
-    const RowsMap /* short rows take the register-staged kernel */)
+    const RowsMap rm)
 {
     static_assert(ND >= 2 && 16 * (ND - 1) <= 128, "window tail is two 64-float loads");
     constexpr int XW = kSegLen + 16 * (ND - 1);    // floats of the window that are ever read
@@ -59,7 +65,7 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     const int wm = wg - g.n_light;
     int row = __builtin_amdgcn_readfirstlane(light ? wg : wm / g.walk_segs);                 // b * C + c
     int seg = __builtin_amdgcn_readfirstlane(light ? g.segs_per_row - 1 : wm % g.walk_segs);
-    int c = __builtin_amdgcn_readfirstlane(row % g.C);
+    int c = ROWS ? seg : __builtin_amdgcn_readfirstlane(row % g.C);
     if (wg >= g.n_waves || row >= g.rows) return;      // (the last block may hold spare waves)
 
     float *sg = s_in[wave];                            // sg[swz_pos(i)] = in~[t0 + 16 dmin + i]
@@ -98,8 +104,19 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     // resource of the segment the next loads belong to (wave-uniform); empty past the last segment
     uintx4 rg;
     int g_shift;                 // negative when the window starts before the row: added to the lane offsets
+    int vg0 = 0;                 // ROWS: virtual position of the first float of the window
+    int live_next[4] = {4, 4, 4, 4}, live_cur[4] = {4, 4, 4, 4};    // ROWS: see rows_granule4_byte_offset (loads r0 .. r3)
     auto aim = [&](int prow, int pseg) {
-        if (prow < g.rows) {
+        if constexpr (ROWS) {
+            g_shift = 0;
+            if (prow < g.rows) {
+                vg0 = prow * kSegLen + 16 * g.dmin;
+                const unsigned long long a0 = reinterpret_cast<unsigned long long>(in + (size_t)pseg * (size_t)g.L);
+                rg = uintx4{(unsigned)a0, (unsigned)(a0 >> 32) & 0xffffu, rm.bytes - (unsigned)(pseg * g.L) * 4u, kBufferFlags};
+            } else {
+                rg = uintx4{0u, 0u, 0u, kBufferFlags};
+            }
+        } else if (prow < g.rows) {
             const int v0 = 4 * (pseg * kSegLen + 16 * g.dmin);
             g_shift = v0 < 0 ? v0 : 0;
             rg = row_tail_resource(in + (size_t)prow * (size_t)g.L, g.L, v0 > 0 ? v0 : 0);
@@ -110,11 +127,18 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
     };
     auto load_region = [&](auto ic) {       // i = 0..3
         constexpr int i = decltype(ic)::value;
-        buffer_load_x4_to_lds_keep(rg, 4 * fo_g + (1024 * i + g_shift), lds_g + 1024u * (unsigned)i);
+        if constexpr (ROWS)
+            buffer_load_x4_to_lds_keep(rg, rows_granule4_byte_offset(rm, vg0 + fo_g + 256 * i, live_next[i]), lds_g + 1024u * (unsigned)i);
+        else
+            buffer_load_x4_to_lds_keep(rg, 4 * fo_g + (1024 * i + g_shift), lds_g + 1024u * (unsigned)i);
+    };
+    auto tail_offset = [&](int fo) {
+        if constexpr (ROWS) return fo >= 0 ? rows_byte_offset<4>(rm, vg0 + fo) : kOutOfRow;
+        else return fo >= 0 ? 4 * fo + g_shift : kOutOfRow;
     };
     auto load_tails = [&]() {
-        buffer_load_x1_to_lds_keep(rg, fo_gt[0] >= 0 ? 4 * fo_gt[0] + g_shift : kOutOfRow, lds_g + 4096u);
-        buffer_load_x1_to_lds_keep(rg, fo_gt[1] >= 0 ? 4 * fo_gt[1] + g_shift : kOutOfRow, lds_g + 4096u + 256u);
+        buffer_load_x1_to_lds_keep(rg, tail_offset(fo_gt[0]), lds_g + 4096u);
+        buffer_load_x1_to_lds_keep(rg, tail_offset(fo_gt[1]), lds_g + 4096u + 256u);
     };
 
     // The loads of the first segment go out first, the filter loads of the first channel right behind them: the wait
@@ -141,14 +165,20 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             c_n = c + g.step_c + carry;
             c_n -= c_n >= g.C ? g.C : 0;
             c_n -= c_n >= g.C ? g.C : 0;
+            if constexpr (ROWS) c_n = seg_n;
         }
-        float *out_seg = out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
-        const bool whole = (seg + 1) * kSegLen <= g.L;
-        const int t_seg = seg * kSegLen;
+        float *out_seg = ROWS ? out + (size_t)c * (size_t)g.L                          // (ROWS: the channel's first row)
+                              : out + (size_t)row * (size_t)g.L + (size_t)(seg * kSegLen);   // wave-uniform
+        const bool whole = ROWS ? false : (seg + 1) * kSegLen <= g.L;
+        const int t_seg = ROWS ? row * kSegLen : seg * kSegLen;
         aim(row_n, seg_n);
         if (c != cur_c) {
             load_filter(c);
             cur_c = c;
+        }
+        if constexpr (ROWS) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) live_cur[j] = live_next[j];
         }
 
         static_for<0, 4>([&](auto ic) {
@@ -157,9 +187,14 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             // them has landed; i loads of the next segment have been issued since
             constexpr int need = i < 3 ? i + 1 : 5;
             wait_vmcnt_at_most<(5 - need) + i>();
+            if constexpr (ROWS) {
+                // what has just landed: r0 and r1 before quarter 0, r2 before quarter 1, r3 before quarter 2
+                if constexpr (i == 0) { zero_slot_tail(sg + 4 * lane, live_cur[0]); zero_slot_tail(sg + 256 + 4 * lane, live_cur[1]); }
+                if constexpr (i == 1 || i == 2) zero_slot_tail(sg + 256 * (i + 1) + 4 * lane, live_cur[i + 1]);
+            }
             // (a quarter that lies wholly past the end of the row - the last segment of a row that is not a multiple of
             // 1024 positions - has no outputs: its matrix work is skipped, its part of the refill is not)
-            const bool live = whole || t_seg + 256 * i < g.L;
+            const bool live = ROWS || whole || t_seg + 256 * i < g.L;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
             if (live) {
                 float4 bv[ND];
@@ -179,8 +214,14 @@ __global__ __launch_bounds__(64 * kCorrWavesPerBlock, kMfmaWavesPerSimd) void co
             if constexpr (i == 3) load_tails();
             // store tile i: lane (block j = i16, row group k4) owns outputs 16 j + 4 k4 + 0..3
             const int lt = 256 * i + 16 * i16 + 4 * k4;
-            if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
-            else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
+            if constexpr (ROWS) {
+                int n;
+                const int e = rows_element_group(rm, t_seg + lt, n);    // four outputs: one row, one gap, or the end of a row
+                if (e >= 0) st_rows_group(out_seg + e, make_float4(acc[0], acc[1], acc[2], acc[3]), n);
+            } else {
+                if (whole) st_elem4_stream(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]));
+                else if (live) st_elem4_stream_upto(out_seg + lt, make_float4(acc[0], acc[1], acc[2], acc[3]), t_seg + lt, g.L);
+            }
         });
         if (row_n >= g.rows) break;
         row = row_n; seg = seg_n; c = c_n;

@@ -192,10 +192,16 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     };
     // (no immediate offsets on the x side: a window that starts before the row has negative lane offsets,
     // and the chunk loop stays one straight-line block without a second code path)
+    // ROWS, rows whose length is not a multiple of four (rag): floats of the lane's granules x0 .. x4 (fields 0 .. 4) and
+    // g0 .. g3 (fields 5 .. 8) that belong to a row which ends inside them (rows_granule4_byte_offset), three bits per load
+    const bool rag = ROWS && (rm.L & 3) != 0;
+    unsigned live_next = 0u, live_cur = 0u;
     auto load_x = [&](auto ic) {        // ic = 0..4
         constexpr int i = decltype(ic)::value;
         if constexpr (ROWS) {
-            const int off = (i < 4 || lane + 256 < NGX) ? rows_byte_offset<4>(rm, vx0 + 4 * (lane + 64 * i)) : kOutOfRow;
+            int live = 4;
+            const int off = (i < 4 || lane + 256 < NGX) ? rows_granule4_byte_offset(rm, vx0 + 4 * (lane + 64 * i), live) : kOutOfRow;
+            live_next |= (unsigned)live << (3 * i);
             buffer_load_x4_to_lds(rx, off, lds_x + 1024u * (unsigned)i);
         } else {
             if constexpr (i < 4) buffer_load_x4_to_lds(rx, off_lane + (1024 * i + x_shift), lds_x + 1024u * (unsigned)i);
@@ -204,8 +210,14 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
     };
     auto load_g = [&](auto ic) {        // ic = 0..3
         constexpr int i = decltype(ic)::value;
-        if constexpr (ROWS) buffer_load_x4_to_lds(rg, rows_byte_offset<4>(rm, vg0 + 4 * (lane + 64 * i)), lds_g + 1024u * (unsigned)i);
-        else buffer_load_x4_to_lds_imm<1024 * i>(rg, off_lane, lds_g);
+        if constexpr (ROWS) {
+            int live;
+            const int off = rows_granule4_byte_offset(rm, vg0 + 4 * (lane + 64 * i), live);
+            live_next |= (unsigned)live << (3 * (5 + i));
+            buffer_load_x4_to_lds(rg, off, lds_g + 1024u * (unsigned)i);
+        } else {
+            buffer_load_x4_to_lds_imm<1024 * i>(rg, off_lane, lds_g);
+        }
     };
 
     // first segment: all nine loads, in the order every later segment uses
@@ -248,6 +260,18 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_direct_k
                 load_x(std::integral_constant<int, 4>{});
                 b = b_n; seg = seg_n;
                 continue;
+            }
+        }
+        if constexpr (ROWS) {
+            live_cur = live_next; live_next = 0u;
+            if (rag) {
+                // rows that end inside a granule: all nine loads of this segment have to land before the elements of the
+                // next row they brought along are cleared (the waits below then find nothing left to wait for)
+                wait_vmcnt_at_most<0>();
+#pragma unroll
+                for (int i = 0; i < 5; ++i) zero_slot_tail(sx + 256 * i + 4 * lane, (int)((live_cur >> (3 * i)) & 7u));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) zero_slot_tail(sg + 256 * i + 4 * lane, (int)((live_cur >> (3 * (5 + i))) & 7u));
             }
         }
         // 64-position chunk ch, block offset d:  G_d += X[n0 + k + dmin + d][q'] * dY[n0 + k][q]

@@ -136,7 +136,7 @@ int launch_bwd_fused(const void *dy, const void *x, const void *w, void *dx, flo
     const bool granular = (s.L % (s.dtype == DWCONV_BF16 ? 8 : 4)) == 0 && aligned_to(x, 16) && aligned_to(dy, 16) && aligned_to(dx, 16);
     if (!granular) {
         const bool short_ok = s.dtype == DWCONV_BF16 && (s.L % 4) == 0;      // (bf16 rows in granules of four: any ordinary length)
-        const bool rows_ok = s.dtype == DWCONV_BF16 && p.rows.on;            // (bf16 virtual rows of even length, checked above)
+        const bool rows_ok = p.rows.on;                                      // (virtual rows; bf16: of even length, checked above)
         if ((!short_ok && !rows_ok && !ragged_rows_fused_ok(s, nd)) || (p.rows.on && !rows_ok) || !aligned_to(x, 4) ||
             !aligned_to(dy, 4) || !aligned_to(dx, 4))
             return -1;

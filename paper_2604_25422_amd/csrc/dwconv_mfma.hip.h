@@ -165,6 +165,26 @@ __device__ __forceinline__ void zero_slot_tail(const short *slot, int live)
         p[3] = 0u;
     }
 }
+// The same for fp32 rows of any length (pitch a multiple of 4): a 16-byte granule of four floats that starts at virtual
+// position u (a multiple of 4); `live` = 1, 2 or 3 when a row ends inside it, 4 otherwise.
+__device__ __forceinline__ int rows_granule4_byte_offset(const RowsMap &m, int u, int &live)
+{
+    const int b = (int)__umulhi((unsigned)u, m.M);
+    const int t = u - b * m.P;
+    const bool in = (unsigned)u < (unsigned)m.Lv && t < m.L;
+    const int left = m.L - t;
+    live = (in && left < 4) ? left : 4;
+    return in ? 4 * (b * m.CL + t) : kOutOfRow;
+}
+__device__ __forceinline__ void zero_slot_tail(const float *slot, int live)
+{
+    if (live < 4) {
+        float *p = const_cast<float *>(slot);
+        if (live <= 1) p[1] = 0.f;
+        if (live <= 2) p[2] = 0.f;
+        p[3] = 0.f;
+    }
+}
 // Four consecutive outputs of a virtual row, at positions u .. u + 3 (u a multiple of 4): they lie in one row, in one gap,
 // or - rows whose length is not a multiple of four - the first n of them end a row.  Element offset of the first (from the
 // channel's first row) or -1, and n.

@@ -140,7 +140,10 @@ def test_single_pass_query(lib):
     assert f(32, 256, 4098, 128, 127, 0) == 0        # ... but only up to six block offsets
     assert f(128, 768, 1026, 32, 31, 1) == 1 and f(128, 768, 1025, 32, 31, 1) == 0      # bf16: even lengths
     assert lib.dwconv_bwd_is_fused(32, 256, 4098, 64, 63, 0) == 1 and lib.dwconv_bwd_is_fused(32, 256, 4097, 64, 63, 1) == 0
-    assert lib.dwconv_bwd_is_fused(4, 8, 500, 64, 63, 0) == 1 and lib.dwconv_bwd_is_fused(4, 8, 502, 64, 63, 0) == 0
+    # short rows that are not whole granules: virtual rows (fp32 any length, bf16 even lengths), fused
+    assert lib.dwconv_bwd_is_fused(4, 8, 500, 64, 63, 0) == 1 and lib.dwconv_bwd_is_fused(4, 8, 502, 64, 63, 0) == 1
+    assert lib.dwconv_bwd_is_fused(4, 8, 503, 64, 63, 0) == 1 and lib.dwconv_bwd_is_fused(4, 8, 503, 64, 63, 1) == 0
+    assert lib.dwconv_bwd_is_fused(4, 8, 502, 128, 127, 0) == 0      # ... up to six block offsets
     # seventeen to thirty-two block offsets: two launches over halves of the offsets, each into its own slices,
     # so an even number of slices and never one kernel - also for small problems, in either storage type
     S226, S256 = lib.dwconv_bwd_weight_slices(32, 256, 4096, 226, 225, 0), lib.dwconv_bwd_weight_slices(32, 256, 4096, 256, 255, 0)

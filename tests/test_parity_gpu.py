@@ -227,9 +227,9 @@ BWD = [
     (70, 256, 48, 48, 24, "f32", True), (300, 4, 20, 9, 8, "f32", True), (4, 16, 4096, 64, 63, "f32", True),
     (3, 2, 2048, 66, 65, "f32", True), (2, 2, 3072, 66, 0, "f32", True), (2, 3, 2052, 40, 20, "f32", True),
     (9, 256, 3900, 64, 63, "f32", True), (4, 512, 4096, 7, 3, "f32", True), (11, 768, 1032, 20, 0, "f32", True),
-    (2, 5, 257, 7, 3, "f32", False), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", True), (3, 5, 1004, 32, 16, "bf16", True), (3, 5, 1006, 32, 16, "bf16", True), (3, 5, 1007, 32, 16, "bf16", False),
+    (2, 5, 257, 7, 3, "f32", True), (2, 2, 1500, 300, 299, "f32", False), (3, 5, 1000, 32, 16, "bf16", True), (3, 5, 1004, 32, 16, "bf16", True), (3, 5, 1006, 32, 16, "bf16", True), (3, 5, 1007, 32, 16, "bf16", False),
     (2, 3, 2050, 64, 63, "f32", True), (3, 2, 1025, 7, 3, "f32", True), (2, 2, 4099, 48, 24, "f32", True), (2, 2, 770, 31, 0, "f32", True),
-    (2, 2, 766, 31, 0, "f32", False),
+    (2, 2, 766, 31, 0, "f32", True),
     (4, 6, 1024, 32, 31, "bf16", True), (2, 3, 2056, 64, 0, "bf16", True), (10, 768, 1024, 32, 31, "bf16", True),
     (2, 2, 48, 48, 24, "bf16", False), (3, 2, 4096, 66, 65, "bf16", True), (40, 256, 1024, 64, 63, "bf16", True),
     (100, 6, 44, 31, 15, "bf16", True), (37, 3, 60, 20, 10, "bf16", False), (70, 256, 48, 48, 24, "bf16", True),
@@ -246,6 +246,9 @@ BWD = [
     # ... and of any even length from 129 positions (a row then ends two, four or six elements into a 16-byte granule)
     (40, 6, 198, 48, 24, "bf16", True), (30, 5, 250, 33, 16, "bf16", True), (25, 3, 130, 7, 3, "bf16", True),
     (700, 16, 202, 48, 47, "bf16", True), (30, 5, 199, 33, 16, "bf16", False),
+    # fp32 virtual rows of any length (a row then ends one, two or three floats into a 16-byte granule)
+    (40, 6, 198, 48, 24, "f32", True), (30, 5, 199, 33, 16, "f32", True), (25, 3, 133, 7, 3, "f32", True),
+    (700, 16, 201, 48, 47, "f32", True), (300, 8, 365, 64, 63, "f32", True), (9, 4, 131, 100, 50, "f32", False),
 ]
 
 
