@@ -92,6 +92,8 @@ inline int mfma_max_nd_dw(const Shape &s)
 // six block offsets; fp32 also the register-staged forward / input-gradient kernel of seven to sixteen offsets (row
 // resources, the same range check) and the weight-gradient kernel in every number of launches; rows long enough that
 // 1024-position segments are not mostly padding (the kernels skip what lies past the end of a row, the fused one does not).
+// Short rows of such lengths with up to six block offsets are walked as virtual rows instead (plan_rows): there the granule in
+// which a row ends is completed with zeros in LDS by the lane that loaded it.
 constexpr int kRaggedMinL = 768;           // the fused backward kernel on such rows (it contracts whole segments), many-launch dW
 constexpr int kRaggedRowsMinL = 129;       // forward / input gradient / weight gradient (they skip the quarters or regions past
                                            // the end of a row): B4096 C128 L202 K48 798 us per step against 1343 us on the
