@@ -148,8 +148,7 @@ DWCONV_API size_t dwconv_noalloc_scratch_bytes(void);
  * The paper names kernel fusion as the remaining lever for the backward path (Sec. VI): for filters of the
  * register-resident class (dwconv_bwd_is_fused(...) == 1: up to six 16-position block offsets, i.e. K up to about 66, or
  * any K on rows of at most 48 positions; rows that start on a 4-byte boundary; not fp32 rows of 52 to 128 positions,
- * and bf16 rows of 52 to about 800 positions only from 64 positions - from 129: any even length; below: multiples
- * of 4) one kernel reads dy once and produces dx and the stage-1 sums of dw (5 tensor passes over memory per
+ * and bf16 rows of 52 to about 800 positions only from 64 positions and of even length) one kernel reads dy once and produces dx and the stage-1 sums of dw (5 tensor passes over memory per
  * forward + backward step instead of 6); every other shape or type runs the two separate paths one after the
  * other.  dy, x [B,C,L] in; w [C,K] in; dx [B,C,L] out; dw [C,K] out; workspace as for dwconv_bwd_weight.
  * dx must not alias dy or x.  Results: dx equals dwconv_bwd_input's bit for bit; dw is a fixed-order sum like

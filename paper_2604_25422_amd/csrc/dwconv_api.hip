@@ -97,7 +97,7 @@ RowsPlan plan_rows(const Shape &s)
     // into LDS for the bf16 matrix instruction, while the sixteen-row kernels widen them to fp32 in registers (B8192 C128
     // L128 K48: 542 -> 313 us per step, L96: 528 -> 366, L64: 462 -> 346; at 48 positions and below the sixteen-row kernels
     // win, 416 against 525 us)
-    if (batch && vrows && s.dtype == DWCONV_BF16 && s.L >= 64 && (s.L % 4) == 0 && (P % 8) == 0) batch = false;
+    if (batch && vrows && s.dtype == DWCONV_BF16 && s.L >= 64 && (s.L % 2) == 0 && (P % 8) == 0) batch = false;
     if (batch) {
         r.on = true; r.batch = true;
         r.units = (s.B + dwconv::kRbRows - 1) / dwconv::kRbRows;

@@ -191,7 +191,12 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
     if (s.K < kMfmaMinK || nd < 2 || nd > mfma_max_nd(s.dtype) || s.L > kMfmaMaxL) return -1;
     // whole granules of four elements; otherwise only the kernels that load rows straight into LDS apply (see ragged_rows_ok)
     const bool granular = (s.L % 4) == 0 && aligned_to(in, 4 * sizeof(T)) && aligned_to(out, 4 * sizeof(T));
-    if (!granular && (!ragged_rows_ok(s, nd) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
+    // bf16 virtual rows on the kernels that load raw rows straight into LDS: rows of even length (they start on a dword),
+    // pitch a multiple of 8; fp32 virtual rows of any length on any fp32 tensor: the kernel that loads rows straight into
+    // LDS (up to six offsets)
+    const bool rows_direct_bf16 = sizeof(T) == 2 && rp.on && (s.L % 2) == 0 && (rp.map.P % 8) == 0 && aligned_to(in, 4) && aligned_to(out, 4);
+    const bool rows_direct_f32 = sizeof(T) == 4 && rp.on && nd <= kMfmaMaxND;
+    if (!granular && !rows_direct_bf16 && !rows_direct_f32 && (!ragged_rows_ok(s, nd) || !aligned_to(in, 4) || !aligned_to(out, 4))) return -1;
     // block offsets the long-filter kernel takes too (fp32 eleven to sixteen, bf16 seven to sixteen): only where rows
     // fill their 1024-position segments to three quarters (shorter rows do less work on the long-filter kernel,
     // which contracts in-row block pairs only)
@@ -281,11 +286,6 @@ int launch_corr_mfma(const void *in, const void *f, void *out, const Shape &s, i
         hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, pi, pf, po, g, no_rows);
         return launch_status();
     };
-    // bf16 virtual rows on the kernels that load raw rows straight into LDS: rows of even length (they start on a dword),
-    // pitch a multiple of 8
-    const bool rows_direct_bf16 = sizeof(T) == 2 && rp.on && (s.L % 2) == 0 && (rp.map.P % 8) == 0 && aligned_to(in, 4) && aligned_to(out, 4);
-    // fp32 virtual rows of any length on any fp32 tensor: the kernel that loads rows straight into LDS (up to six offsets)
-    const bool rows_direct_f32 = sizeof(T) == 4 && rp.on && nd <= kMfmaMaxND;
     if (!granular && rp.on && !rows_direct_bf16 && !rows_direct_f32) return -1;
     {
         // longer short rows: segments of the virtual row of a channel, slots ordered (virtual segment, channel)

@@ -194,8 +194,8 @@ int launch_dw_partial_mfma(const void *x, const void *dy, float *part, void *dw_
     // (fp32 virtual rows of any length, up to six offsets: the kernel that loads rows straight into LDS)
     const bool rows_direct_bf16 = sizeof(T) == 2 && p.rows.on && (s.L % 2) == 0 && (p.rows.map.P % 8) == 0;
     const bool rows_direct_f32 = sizeof(T) == 4 && p.rows.on && nd <= kMfmaMaxND;
-    if (!granular && (!ragged_rows_ok(s, nd) || (p.rows.on && !rows_direct_bf16 && !rows_direct_f32) || !aligned_to(x, 4) || !aligned_to(dy, 4)))
-        return -1;
+    const bool rows_direct = (rows_direct_bf16 || rows_direct_f32) && aligned_to(x, 4) && aligned_to(dy, 4);
+    if (!granular && !rows_direct && (!ragged_rows_ok(s, nd) || p.rows.on || !aligned_to(x, 4) || !aligned_to(dy, 4))) return -1;
     if constexpr (std::is_same<T, float>::value) {
         if (nd > kMfmaMaxND) return launch_dw_partial_wide_f32(x, dy, part, dw_out, s, p, dmin, nd, st);
     } else {

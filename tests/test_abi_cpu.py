@@ -98,7 +98,7 @@ def test_fused_backward_argument_validation(lib):
     q = lib.dwconv_bwd_is_fused
     assert q(32, 256, 4096, 64, 63, 0) == 1 and q(4096, 128, 196, 48, 24, 0) == 1 and q(2, 3, 200, 5, 2, 0) == 1
     assert q(128, 768, 1024, 32, 31, 1) == 1 and q(2, 3, 100, 5, 2, 1) == 1     # bf16: rows of whole 8-byte granules
-    assert q(2, 3, 102, 5, 2, 1) == 0 and q(2, 3, 60, 5, 2, 1) == 0
+    assert q(2, 3, 102, 5, 2, 1) == 1 and q(2, 3, 101, 5, 2, 1) == 0 and q(2, 3, 60, 5, 2, 1) == 0
     assert q(8, 256, 8192, 8192, 8191, 0) == 0 and q(2, 3, 101, 5, 2, 0) == 0
     assert q(2, 3, 100, 2, 1, 0) == 0 and q(0, 3, 100, 5, 2, 0) == 0
     assert q(16384, 128, 48, 48, 24, 0) == 1        # rows of at most 64 positions: sixteen rows per tile

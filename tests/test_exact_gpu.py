@@ -105,6 +105,8 @@ CLASSES = [
     # ... and of odd lengths (fp32: one to three floats of the last granule belong to the row; bf16: the vector-ALU kernels)
     (300, 12, 199, 31, 15), (64, 2, 507, 64, 63), (50, 3, 133, 16, 15), (21, 3, 773, 7, 3), (40, 5, 201, 48, 24), (33, 2, 129, 66, 0),
     (17, 4, 365, 48, 47),
+    # ... bf16 rows of 64 to 128 positions of even length
+    (90, 3, 98, 48, 24), (70, 4, 126, 31, 15), (130, 2, 66, 16, 15), (40, 5, 70, 7, 3),
     # longer short rows (virtual rows) with seven to sixteen block offsets
     (20, 3, 256, 100, 99), (9, 2, 384, 160, 80), (6, 4, 512, 226, 0), (12, 256, 200, 130, 129), (7, 3, 640, 200, 100),
     # rows of nine to thirty-two blocks with filters of the order of the row length: sixteen rows per tile, filter in LDS
@@ -205,6 +207,7 @@ SEVERAL_UNITS = [
     (600, 256, 100, 33, 16),       # ... from 64 positions on bf16 storage
     (400, 256, 198, 48, 24),       # ... rows of 4 n + 2 positions
     (400, 256, 199, 48, 24),       # ... rows of odd length (fp32 virtual rows; bf16 on the vector-ALU kernels)
+    (700, 256, 98, 48, 24),        # ... bf16 rows below 129 positions of even length
     (40, 256, 1027, 160, 80),      # ordinary rows that are not whole granules, eleven block offsets
     (300, 256, 256, 256, 255),     # rows of sixteen blocks, filter in LDS
 ]

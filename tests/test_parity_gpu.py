@@ -241,7 +241,7 @@ BWD = [
     (64, 8, 136, 20, 19, "bf16", True), (600, 16, 200, 48, 47, "bf16", True), (25, 3, 264, 7, 3, "bf16", True),
     # ... from 64 positions (below: sixteen rows per tile, fused up to 48 positions only)
     (90, 5, 64, 48, 24, "bf16", True), (70, 6, 96, 33, 32, "bf16", True), (50, 3, 56, 16, 15, "bf16", False),
-    (50, 3, 68, 16, 15, "bf16", True), (50, 3, 120, 66, 0, "bf16", True), (50, 3, 66, 16, 15, "bf16", False),
+    (50, 3, 68, 16, 15, "bf16", True), (50, 3, 120, 66, 0, "bf16", True), (50, 3, 66, 16, 15, "bf16", True), (50, 3, 62, 16, 15, "bf16", False), (70, 4, 126, 48, 24, "bf16", True),
     (900, 16, 196, 48, 24, "bf16", True), (300, 8, 500, 64, 63, "bf16", True), (40, 4, 100, 7, 3, "bf16", True),
     # ... and of any even length from 129 positions (a row then ends two, four or six elements into a 16-byte granule)
     (40, 6, 198, 48, 24, "bf16", True), (30, 5, 250, 33, 16, "bf16", True), (25, 3, 130, 7, 3, "bf16", True),
