@@ -92,4 +92,15 @@ __device__ __forceinline__ int rows_element(const RowsMap &m, int u)
     const int t = u - b * m.P;
     return ((unsigned)u < (unsigned)m.Lv && t < m.L) ? b * m.CL + t : -1;
 }
+
+// Channel of workgroup bx in a grid (C, slices) whose workgroups own one channel each.  Short rows of neighbouring
+// channels share the cache line in which one ends and the next begins, and every one of the 8 accelerator dies has an
+// L2 of its own; workgroups go to the dies round-robin by linear index, so die k gets the workgroups with bx = k
+// (mod 8) of a slice.  Give it a run of consecutive channels (C / 8 of them, one more on the first C % 8 dies): the
+// two readers of a shared line then sit behind one L2.
+__device__ __forceinline__ int die_run_channel(int bx, int C)
+{
+    const int q = C >> 3, r = C & 7, k = bx & 7, i = bx >> 3;
+    return k * q + (k < r ? k : r) + i;
+}
 }  // namespace dwconv

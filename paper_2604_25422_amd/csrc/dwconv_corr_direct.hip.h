@@ -21,18 +21,6 @@
 
 namespace dwconv {
 
-// (loads without the non-temporal hint: the weight-gradient call of the same step reads these rows again)
-__device__ __forceinline__ void buffer_load_x4_to_lds_keep(uintx4 rsrc, int byte_off, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
-}
-__device__ __forceinline__ void buffer_load_x1_to_lds_keep(uintx4 rsrc, int byte_off, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
-}
-
 constexpr int kCorrDirectWin = kSegLen + 128;      // floats per wave: 1024 + two 64-float tail loads
 
 // ROWS: short rows whose length is not a multiple of four (those that are take the register-staged kernel), the unit of

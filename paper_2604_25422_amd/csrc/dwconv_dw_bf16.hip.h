@@ -64,7 +64,11 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int i16 = lane & 15, kg = lane >> 4;
-    const int c = blockIdx.x;
+    // ROWS, rows that are not whole 128-byte cache lines: neighbouring channels behind one L2, loads without the
+    // non-temporal hint (the line a row shares with the next channel's row is then fetched once; measured on B8192 C128
+    // L136 K48: weight gradient 132 -> 107 us; rows of whole lines keep the hint, they lose without it)
+    const bool keep_lines = ROWS && ((L * 2) & 127) != 0;
+    const int c = keep_lines ? die_run_channel((int)blockIdx.x, C) : (int)blockIdx.x;
     const int stride = (int)gridDim.y * W;
     const int ws = (int)blockIdx.y * W + __builtin_amdgcn_readfirstlane(wave);
     const int step_b = stride / segs_per_row, step_seg = stride % segs_per_row;
@@ -144,8 +148,8 @@ __global__ __launch_bounds__(64 * W, kMfmaWavesPerSimd) void dw_partial_bf16_ker
         constexpr int h = decltype(hc)::value;
         if constexpr (ROWS) {
             const int e = (off_main >> 1) + 512 * h;        // the lane's granule: elements e .. e + 7 of the windows
-            buffer_load_x4_to_lds(rx, rows_granule8_byte_offset(rm, vx0 + e, live_next[2 * h]), lds_x + 1024u * (unsigned)h);
-            buffer_load_x4_to_lds(rg, rows_granule8_byte_offset(rm, vg0 + e, live_next[2 * h + 1]), lds_g + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds_sel(keep_lines, rx, rows_granule8_byte_offset(rm, vx0 + e, live_next[2 * h]), lds_x + 1024u * (unsigned)h);
+            buffer_load_x4_to_lds_sel(keep_lines, rg, rows_granule8_byte_offset(rm, vg0 + e, live_next[2 * h + 1]), lds_g + 1024u * (unsigned)h);
         } else {
             buffer_load_x4_to_lds(rx, off_main + (1024 * h + x_shift), lds_x + 1024u * (unsigned)h);
             buffer_load_x4_to_lds(rg, off_main + 1024 * h, lds_g + 1024u * (unsigned)h);

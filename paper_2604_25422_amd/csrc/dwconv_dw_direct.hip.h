@@ -42,6 +42,26 @@ __device__ __forceinline__ void buffer_load_x4_to_lds_imm(uintx4 rsrc, int byte_
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 nt lds"
                  :: "s"(lds_base), "v"(byte_off), "s"(rsrc), "n"(OFF) : "memory");
 }
+// The same loads without the non-temporal hint: the forward / input-gradient kernels (the weight-gradient call of the
+// same step reads their rows again), and the weight-gradient and fused kernels on short rows that are not whole
+// 128-byte cache lines, where the line in which one row ends and the next channel's row begins has a second reader
+// behind the same L2 (see die_run_channel).
+__device__ __forceinline__ void buffer_load_x4_to_lds_keep(uintx4 rsrc, int byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void buffer_load_x1_to_lds_keep(uintx4 rsrc, int byte_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(byte_off), "s"(rsrc) : "memory");
+}
+// One or the other (keep is wave-uniform): either way one load, so the wait counts do not depend on it.
+__device__ __forceinline__ void buffer_load_x4_to_lds_sel(bool keep, uintx4 rsrc, int byte_off, unsigned lds_base)
+{
+    if (keep) buffer_load_x4_to_lds_keep(rsrc, byte_off, lds_base);
+    else buffer_load_x4_to_lds(rsrc, byte_off, lds_base);
+}
 // s_waitcnt vmcnt(N)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_at_most()
